@@ -1,0 +1,11 @@
+"""fp64 CPU oracle of one CNN training step.  TEST INFRASTRUCTURE ONLY.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import this package.
+It shares no code with the HIP path and never imports it.  ops.py wraps the C library
+(cnnk_ref.c, direct loops in double precision); step.py chains the operators over a layer
+list by the chain rule (forward, loss, backward, SGD-momentum update).
+"""
+from . import ops
+from .step import train_step, forward_loss
+
+__all__ = ["ops", "train_step", "forward_loss"]

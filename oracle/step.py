@@ -1,0 +1,93 @@
+"""Oracle walker: one training step over a layer list, in float64.  Test infrastructure.
+
+Follows the inner loop of the paper's Algorithm 1 in its printed order: forward pass, loss,
+backward pass (chain rule through the layer list in reverse), parameter update.  A tensor
+that feeds two consumers receives the sum of both gradients; the network input (slot 0)
+receives none.
+"""
+from __future__ import annotations
+import numpy as np
+from . import ops
+
+BN_EPS = 1e-5
+BN_MOMENTUM = 0.1
+
+
+def forward_loss(net, x, labels, params, keep=None):
+    """Forward pass and loss only.  Returns (loss, fc_result, acts, saved)."""
+    acts = {0: np.asarray(x, dtype=np.float64)}
+    saved = {}
+    out = None
+    for i, L in enumerate(net.layers):
+        op = L["op"]
+        if op == "conv":
+            acts[L["y"]] = ops.conv2d_fwd(acts[L["x"]], params[L["w"]], L["stride"], L["pad"])
+        elif op == "bn":
+            res = acts[L["res"]] if L["res"] >= 0 else None
+            y, mean, invstd = ops.bn_relu_fwd(acts[L["x"]], params[L["gamma"]], params[L["beta"]],
+                                              relu=bool(L["relu"]), residual=res, eps=BN_EPS,
+                                              momentum=BN_MOMENTUM)
+            acts[L["y"]] = y
+            saved[i] = (mean, invstd)
+        elif op == "pool":
+            y, am = ops.pool_fwd(acts[L["x"]], L["mode"])
+            acts[L["y"]] = y
+            saved[i] = am
+        elif op == "add":
+            acts[L["y"]] = acts[L["a"]] + acts[L["b"]]
+        elif op == "fc_loss":
+            xin = acts[L["x"]].reshape(L["N"], L["F"])
+            out = ops.fc_softmax_xent(xin, params[L["W"]], params[L["b"]], labels)
+        else:
+            raise ValueError(op)
+    return out["loss"], out, acts, saved
+
+
+def train_step(net, x, labels, params, mom, lr=0.1, momentum=0.9, weight_decay=0.0):
+    """One step.  Returns dict(loss, pred, acts, dacts, grads, params, mom); inputs are not modified."""
+    loss, fc, acts, saved = forward_loss(net, x, labels, params)
+    grads = [None] * len(params)
+    dacts = {}
+
+    def contribute(slot, g):
+        if slot == 0:
+            return
+        dacts[slot] = g if slot not in dacts else dacts[slot] + g
+
+    for i in range(len(net.layers) - 1, -1, -1):
+        L = net.layers[i]
+        op = L["op"]
+        if op == "fc_loss":
+            grads[L["W"]] = fc["dW"]
+            grads[L["b"]] = fc["db"]
+            contribute(L["x"], fc["dx"].reshape(L["N"], 1, 1, L["F"]))
+        elif op == "pool":
+            contribute(L["x"], ops.pool_bwd(dacts[L["y"]], saved[i], acts[L["x"]].shape, L["mode"]))
+        elif op == "add":
+            contribute(L["a"], dacts[L["y"]])
+            contribute(L["b"], dacts[L["y"]])
+        elif op == "bn":
+            mean, invstd = saved[i]
+            dx, dres, dg, db = ops.bn_relu_bwd(dacts[L["y"]], acts[L["x"]], acts[L["y"]],
+                                               params[L["gamma"]], mean, invstd,
+                                               relu=bool(L["relu"]), want_dres=L["res"] >= 0)
+            grads[L["gamma"]] = dg
+            grads[L["beta"]] = db
+            contribute(L["x"], dx)
+            if L["res"] >= 0:
+                contribute(L["res"], dres)
+        elif op == "conv":
+            dy = dacts[L["y"]]
+            grads[L["w"]] = ops.conv2d_wgrad(acts[L["x"]], dy, params[L["w"]].shape, L["stride"], L["pad"])
+            if L["x"] != 0:
+                contribute(L["x"], ops.conv2d_dgrad(dy, params[L["w"]], acts[L["x"]].shape,
+                                                    L["stride"], L["pad"]))
+    new_params, new_mom = [], []
+    for p, v, g in zip(params, mom, grads):
+        w2 = np.array(p, dtype=np.float64, copy=True, order="C")
+        v2 = np.array(v, dtype=np.float64, copy=True, order="C")
+        ops.sgd_momentum(w2.reshape(-1), v2.reshape(-1), np.asarray(g).reshape(-1), lr, momentum, weight_decay)
+        new_params.append(w2)
+        new_mom.append(v2)
+    return dict(loss=loss, pred=fc["pred"], probs=fc["probs"], acts=acts, dacts=dacts, grads=grads,
+                params=new_params, mom=new_mom, saved=saved)
