@@ -1,0 +1,193 @@
+/* cnnk: one device's CNN training step (forward, loss, backward, SGD-momentum update) on gfx950.
+ *
+ * The operations are those of the inner mini-batch loop of the paper's Algorithm 1
+ * ("perform forward pass", "compute loss L(theta)", "perform backward pass", "update
+ * parameters theta = theta - eta * grad") as one data-parallel replica executes them
+ * (Section III-A, data parallelism: every device holds the whole model and processes its own
+ * share of the batch).  The model family is the image-classification CNN of Section IV-A
+ * (ResNet-style networks on 32x32 RGB inputs, 100 classes).
+ *
+ * Conventions common to every entry point
+ *  - All tensor pointers are DEVICE pointers owned by the caller; descriptors are host structs.
+ *  - The library never allocates, frees or synchronises.  Work is enqueued on `stream` (a
+ *    hipStream_t passed as void*, NULL = the default stream) and the call returns at once.
+ *  - Layout: activations NHWC; convolution weights [Cout][R][S][Cin]; FC weight [classes][F].
+ *  - dtype CNNK_F32: every tensor is float.  dtype CNNK_BF16: activations, activation gradients
+ *    and the convolution weights handed to the conv calls are bfloat16 (round to nearest even);
+ *    BN statistics and parameters, all parameter gradients, FC parameters, master weights,
+ *    momentum, logits and the loss stay float.  Accumulation is always fp32.
+ *  - Errors are return codes.  Arguments are validated on the host before anything is
+ *    enqueued: a call that returns an error other than CNNK_ERR_HIP has launched nothing.
+ *  - Outputs must not alias inputs unless stated.
+ *  - Workspace (`ws`, `ws_bytes`): scratch device memory, at least the size the matching
+ *    *_workspace_bytes query returns (may be NULL when that is 0), 256-byte aligned.
+ *    Contents are undefined on entry and on return.
+ */
+#ifndef CNNK_H
+#define CNNK_H
+#include <stddef.h>
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CNNK_OK = 0,
+  CNNK_ERR_NULL = 1,        /* a required pointer is NULL */
+  CNNK_ERR_SHAPE = 2,       /* non-positive or inconsistent sizes */
+  CNNK_ERR_UNSUPPORTED = 3, /* valid but outside the supported set */
+  CNNK_ERR_WORKSPACE = 4,   /* workspace missing or too small */
+  CNNK_ERR_HIP = 5          /* the HIP runtime refused a launch */
+} cnnk_status;
+
+typedef enum { CNNK_F32 = 0, CNNK_BF16 = 1 } cnnk_dtype;
+typedef enum { CNNK_POOL_MAX2 = 0, CNNK_POOL_GAP = 1 } cnnk_pool_mode;
+typedef enum { CNNK_PASS_FWD = 0, CNNK_PASS_DGRAD = 1, CNNK_PASS_WGRAD = 2 } cnnk_conv_pass;
+
+/* Output extent: Ho = (H + 2*pad - R)/stride + 1 (integer division), same for Wo. */
+typedef struct { int N, H, W, Cin, Cout, R, S, stride, pad; int dtype; } cnnk_conv_desc;
+typedef struct { int N, H, W, C; int dtype; float eps, momentum; int relu; } cnnk_bn_desc;
+typedef struct { int N, H, W, C; int dtype; int mode; } cnnk_pool_desc;
+typedef struct { int N, F, classes; int dtype; } cnnk_fc_desc;
+
+const char* cnnk_status_string(int status);
+/* Library version, and the code-object architecture the kernels were built for ("gfx950"). */
+const char* cnnk_version(void);
+
+/* ---- convolution (Algorithm 1: forward pass / backward pass of a conv layer) -------------- */
+
+/* Scratch bytes needed by the given pass (cnnk_conv_pass) of this convolution. */
+size_t cnnk_conv2d_workspace_bytes(const cnnk_conv_desc* d, int pass);
+
+/* y[n,ho,wo,k] = sum_{r,s,c} x[n,ho*stride+r-pad,wo*stride+s-pad,c] * w[k,r,s,c], zero padding,
+ * no bias.  x: N*H*W*Cin, w: Cout*R*S*Cin, y: N*Ho*Wo*Cout, all of d->dtype.
+ * ch_sum / ch_sumsq (both or neither; nullable): Cout floats each, receive sum_m y and
+ * sum_m y^2 over the N*Ho*Wo output positions of the fp32 accumulators (input to batch norm).
+ * Supported: R==S in {1,3}, stride in {1,2}, pad == R/2. */
+int cnnk_conv2d_fwd(const cnnk_conv_desc* d, const void* x, const void* w, void* y,
+                    float* ch_sum, float* ch_sumsq, void* ws, size_t ws_bytes, void* stream);
+
+/* dx[n,h,w,c] = sum_{k,r,s} dy[n,(h+pad-r)/stride,(w+pad-s)/stride,k] * w[k,r,s,c] over the
+ * (r,s) whose quotients are integers inside the output image.  accumulate != 0 adds the result
+ * to the existing contents of dx (a tensor with two consumers receives the sum of both
+ * gradients), otherwise dx is overwritten. */
+int cnnk_conv2d_dgrad(const cnnk_conv_desc* d, const void* dy, const void* w, void* dx,
+                      int accumulate, void* ws, size_t ws_bytes, void* stream);
+
+/* dw[k,r,s,c] = sum_{n,ho,wo} dy[n,ho,wo,k] * x[n,ho*stride+r-pad,wo*stride+s-pad,c].
+ * dw is float in both dtypes and is overwritten. */
+int cnnk_conv2d_wgrad(const cnnk_conv_desc* d, const void* x, const void* dy, float* dw,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/* ---- batch norm (+ residual) (+ ReLU) ------------------------------------------------------ */
+
+size_t cnnk_bn_workspace_bytes(const cnnk_bn_desc* d);
+
+/* Training-mode batch norm over m = N*H*W positions per channel:
+ * mean = (1/m) sum x; var = (1/m) sum (x-mean)^2; invstd = 1/sqrt(var+eps);
+ * y = act(gamma*(x-mean)*invstd + beta [+ residual]), act = max(.,0) if d->relu else identity.
+ * save_mean, save_invstd: C floats each (needed by the backward call).
+ * running_mean/var (both or neither; nullable, updated in place): r <- (1-momentum)*r +
+ * momentum*stat, with the unbiased variance var*m/(m-1).
+ * ch_sum/ch_sumsq (both or neither; nullable): per-channel sum x and sum x^2 produced by
+ * cnnk_conv2d_fwd; when given, the statistics pass over x is skipped. */
+int cnnk_bn_relu_fwd(const cnnk_bn_desc* d, const void* x, const void* residual,
+                     const float* gamma, const float* beta, void* y, float* save_mean,
+                     float* save_invstd, float* running_mean, float* running_var,
+                     const float* ch_sum, const float* ch_sumsq, void* ws, size_t ws_bytes,
+                     void* stream);
+
+/* dz = dy*[y>0] (strict; dz = dy without ReLU); dbeta = sum dz; dgamma = sum dz*xhat;
+ * dx = (gamma*invstd/m)*(m*dz - dbeta - xhat*dgamma), xhat = (x-mean)*invstd; dresidual = dz.
+ * y may be NULL when d->relu == 0; dresidual is nullable.
+ * flags bit 0: add into dx instead of overwriting; bit 1: add into dresidual. */
+int cnnk_bn_relu_bwd(const cnnk_bn_desc* d, const void* dy, const void* x, const void* y,
+                     const float* gamma, const float* save_mean, const float* save_invstd,
+                     void* dx, void* dresidual, int flags, float* dgamma, float* dbeta,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/* ---- pooling --------------------------------------------------------------------------------- */
+
+/* CNNK_POOL_MAX2: 2x2 window, stride 2, no padding (H, W even); y: N*(H/2)*(W/2)*C; argmax
+ * (one byte per output element) = 2*dr+dc of the first maximal element in (row, col) order.
+ * CNNK_POOL_GAP: y[n,c] = mean over H*W; argmax unused (may be NULL). */
+int cnnk_pool_fwd(const cnnk_pool_desc* d, const void* x, void* y, unsigned char* argmax,
+                  void* stream);
+/* MAX2: dx = dy at the recorded argmax, 0 elsewhere.  GAP: dx = dy/(H*W) everywhere.
+ * accumulate != 0 adds into dx. */
+int cnnk_pool_bwd(const cnnk_pool_desc* d, const void* dy, const unsigned char* argmax, void* dx,
+                  int accumulate, void* stream);
+
+/* ---- element-wise helpers for residual sums without a following batch norm --------------- */
+
+/* y = a + b over n elements of dtype. */
+int cnnk_add(size_t n, int dtype, const void* a, const void* b, void* y, void* stream);
+/* dst = src (accumulate == 0) or dst += src, n elements of dtype: gradient fan-out of cnnk_add. */
+int cnnk_grad_route(size_t n, int dtype, const void* src, void* dst, int accumulate, void* stream);
+
+/* ---- classifier head and loss (Algorithm 1: "compute loss L(theta)") ---------------------- */
+
+size_t cnnk_fc_workspace_bytes(const cnnk_fc_desc* d);
+
+/* z = x W^T + b; loss = (1/N) sum_n (logsumexp(z_n) - z[n,label_n]) (natural log);
+ * pred[n] = smallest j attaining max_j z[n,j]; dz = (softmax(z) - onehot)/N;
+ * dW = dz^T x; db = sum_n dz; dx = dz W.
+ * x, dx: N*F of dtype; W, dW: classes*F float; b, db: classes float; labels, pred: N int32
+ * (labels must lie in [0, classes): not checked on the device, out-of-range labels contribute
+ * a zero target); loss: 1 float; probs (nullable): N*classes float softmax output. */
+int cnnk_fc_softmax_xent(const cnnk_fc_desc* d, const void* x, const float* W, const float* b,
+                         const int* labels, float* loss, int* pred, float* probs, void* dx,
+                         float* dW, float* db, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- parameter update (Algorithm 1: theta = theta - eta * grad, with momentum) ------------ */
+
+/* g' = g + weight_decay*w; v <- momentum*v + g'; w <- w - lr*v, in place over n floats.
+ * w_bf16 (nullable): n bfloat16 values refreshed with the rounded new w. */
+int cnnk_sgd_momentum(size_t n, float* w, float* v, const float* g, void* w_bf16, float lr,
+                      float momentum, float weight_decay, void* stream);
+
+/* ---- the whole step over a layer list ------------------------------------------------------ */
+
+typedef enum { CNNK_OP_CONV = 0, CNNK_OP_BN = 1, CNNK_OP_POOL = 2, CNNK_OP_ADD = 3,
+               CNNK_OP_FC_LOSS = 4 } cnnk_op;
+
+/* One layer.  in0/in1/out are tensor-slot ids, p0/p1 parameter-slot ids, -1 = unused.
+ *   CONV: x=in0, y=out, w=p0            BN: x=in0, residual=in1, y=out, gamma=p0, beta=p1
+ *   POOL: x=in0, y=out                  ADD: a=in0, b=in1, y=out (d.pool describes the shape)
+ *   FC_LOSS: x=in0, W=p0, b=p1 (must be the last layer).
+ * Slot 0 is the network input and receives no gradient. */
+typedef struct cnnk_layer {
+  int op, in0, in1, out, p0, p1;
+  union { cnnk_conv_desc conv; cnnk_bn_desc bn; cnnk_pool_desc pool; cnnk_fc_desc fc; } d;
+} cnnk_layer;
+
+/* Caller-owned device buffers, arrays indexed by slot / parameter / layer id (host arrays of
+ * device pointers).  Element types follow the dtype rules at the top of this file. */
+typedef struct cnnk_buffers {
+  int n_slots, n_params;
+  void** act;               /* [n_slots] activations */
+  void** dact;              /* [n_slots] activation gradients; dact[0] may be NULL */
+  float** param;            /* [n_params] float master parameters (updated in place) */
+  void** param_lp;          /* [n_params] bf16 copies of conv weights (bf16 mode), else NULL */
+  float** grad;             /* [n_params] parameter gradients (overwritten) */
+  float** mom;              /* [n_params] momentum buffers (updated in place) */
+  float** bn_save;          /* [n_layers] BN layers: 2*C floats (mean, then invstd) */
+  float** bn_running;       /* [n_layers] BN layers: 2*C floats (mean, then var) or NULL */
+  unsigned char** pool_idx; /* [n_layers] MAX2 layers: one byte per output element */
+  float* probs;             /* N*classes softmax output, nullable */
+  void* ws; size_t ws_bytes;
+} cnnk_buffers;
+
+size_t cnnk_train_step_workspace_bytes(const cnnk_layer* layers, int n_layers);
+
+/* Forward over the list, loss, backward over the reversed list, then the update of every
+ * parameter, all on one stream without host synchronisation.  labels: N int32 (device);
+ * loss: 1 float (device); pred: N int32 (device).  The first gradient written to a slot in
+ * the backward pass overwrites it, later ones are added. */
+int cnnk_train_step(const cnnk_layer* layers, int n_layers, const cnnk_buffers* buf,
+                    const int* labels, float lr, float momentum, float weight_decay,
+                    float* loss, int* pred, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CNNK_H */

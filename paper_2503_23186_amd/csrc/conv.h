@@ -1,0 +1,41 @@
+// Internal interfaces between the convolution front end (conv_api.hip) and its kernel families.
+#pragma once
+#include "common.h"
+
+struct ConvGeom {
+  int N, H, W, Cin, Cout, R, S, stride, pad, Ho, Wo;
+};
+
+static inline ConvGeom make_geom(const cnnk_conv_desc* d) {
+  ConvGeom g;
+  g.N = d->N; g.H = d->H; g.W = d->W; g.Cin = d->Cin; g.Cout = d->Cout;
+  g.R = d->R; g.S = d->S; g.stride = d->stride; g.pad = d->pad;
+  g.Ho = conv_out(d->H, d->pad, d->R, d->stride);
+  g.Wo = conv_out(d->W, d->pad, d->S, d->stride);
+  return g;
+}
+
+// direct kernels (any shape, both dtypes)
+size_t conv_direct_wgrad_ws(const ConvGeom& g);
+int conv_direct_fwd(const ConvGeom& g, int dtype, const void* x, const void* w, void* y, hipStream_t st);
+int conv_direct_dgrad(const ConvGeom& g, int dtype, const void* dy, const void* w, void* dx, int accumulate,
+                      hipStream_t st);
+int conv_direct_wgrad(const ConvGeom& g, int dtype, const void* x, const void* dy, float* dw, void* ws,
+                      hipStream_t st);
+int reduce_partials(const float* part, float* out, int n, int P, hipStream_t st);
+
+// bf16 MFMA implicit-GEMM kernels
+bool conv_mfma_supported(const ConvGeom& g, int pass);
+size_t conv_mfma_ws(const ConvGeom& g, int pass, bool want_stats);
+int conv_mfma_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y, float* ch_sum,
+                  float* ch_sumsq, void* ws, hipStream_t st);
+int conv_mfma_dgrad(const ConvGeom& g, const bf16_t* dy, const bf16_t* w, bf16_t* dx, int accumulate,
+                    void* ws, hipStream_t st);
+int conv_mfma_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws,
+                    hipStream_t st);
+
+// per-channel sum / sum of squares of a tensor with C channels (used when the conv kernel
+// itself does not produce them)
+size_t channel_stats_ws(size_t m, int C);
+int channel_stats(int dtype, const void* x, size_t m, int C, float* ch_sum, float* ch_sumsq, void* ws,
+                  hipStream_t st);

@@ -1,0 +1,170 @@
+// Direct (non-MFMA) convolution kernels: the fp32 mode, and bf16 shapes the MFMA engine does
+// not take (channel counts that are not multiples of 8, e.g. the 3-channel stem).
+// One thread per output element, fp32 accumulation in a fixed order.
+#include "common.h"
+#include "conv.h"
+
+namespace {
+
+template <typename T>
+__global__ void __launch_bounds__(256) direct_fwd_kernel(ConvGeom g, const T* __restrict__ x,
+                                                         const T* __restrict__ w, T* __restrict__ y) {
+  const size_t total = (size_t)g.N * g.Ho * g.Wo * g.Cout;
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const int k = (int)(idx % g.Cout);
+  size_t m = idx / g.Cout;
+  const int wo = (int)(m % g.Wo); m /= g.Wo;
+  const int ho = (int)(m % g.Ho);
+  const int n = (int)(m / g.Ho);
+  float acc = 0.f;
+  for (int r = 0; r < g.R; ++r) {
+    const int hi = ho * g.stride + r - g.pad;
+    if (hi < 0 || hi >= g.H) continue;
+    for (int s = 0; s < g.S; ++s) {
+      const int wi = wo * g.stride + s - g.pad;
+      if (wi < 0 || wi >= g.W) continue;
+      const T* xp = x + (((size_t)n * g.H + hi) * g.W + wi) * g.Cin;
+      const T* wp = w + (((size_t)k * g.R + r) * g.S + s) * g.Cin;
+      for (int c = 0; c < g.Cin; ++c) acc = fmaf(Elem<T>::ld(xp + c), Elem<T>::ld(wp + c), acc);
+    }
+  }
+  Elem<T>::st(y + idx, acc);
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) direct_dgrad_kernel(ConvGeom g, const T* __restrict__ dy,
+                                                           const T* __restrict__ w, T* __restrict__ dx,
+                                                           int accumulate) {
+  const size_t total = (size_t)g.N * g.H * g.W * g.Cin;
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const int c = (int)(idx % g.Cin);
+  size_t m = idx / g.Cin;
+  const int wi = (int)(m % g.W); m /= g.W;
+  const int hi = (int)(m % g.H);
+  const int n = (int)(m / g.H);
+  float acc = 0.f;
+  for (int r = 0; r < g.R; ++r) {
+    const int th = hi + g.pad - r;
+    if (th < 0 || th % g.stride != 0) continue;
+    const int ho = th / g.stride;
+    if (ho >= g.Ho) continue;
+    for (int s = 0; s < g.S; ++s) {
+      const int tw = wi + g.pad - s;
+      if (tw < 0 || tw % g.stride != 0) continue;
+      const int wo = tw / g.stride;
+      if (wo >= g.Wo) continue;
+      const T* dyp = dy + (((size_t)n * g.Ho + ho) * g.Wo + wo) * g.Cout;
+      const T* wp = w + ((size_t)r * g.S + s) * g.Cin + c;
+      const size_t wk = (size_t)g.R * g.S * g.Cin;
+      for (int k = 0; k < g.Cout; ++k) acc = fmaf(Elem<T>::ld(dyp + k), Elem<T>::ld(wp + k * wk), acc);
+    }
+  }
+  if (accumulate) acc += Elem<T>::ld(dx + idx);
+  Elem<T>::st(dx + idx, acc);
+}
+
+// Partial weight gradient over the output positions [p*chunk, (p+1)*chunk) into part[p][i].
+template <typename T>
+__global__ void __launch_bounds__(256) direct_wgrad_kernel(ConvGeom g, const T* __restrict__ x,
+                                                           const T* __restrict__ dy,
+                                                           float* __restrict__ part, int chunk) {
+  const int nw = g.Cout * g.R * g.S * g.Cin;
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= nw) return;
+  const int c = i % g.Cin;
+  int t = i / g.Cin;
+  const int s = t % g.S; t /= g.S;
+  const int r = t % g.R;
+  const int k = t / g.R;
+  const long M = (long)g.N * g.Ho * g.Wo;
+  const long m0 = (long)blockIdx.y * chunk;
+  const long m1 = (m0 + chunk < M) ? m0 + chunk : M;
+  float acc = 0.f;
+  for (long m = m0; m < m1; ++m) {
+    const int wo = (int)(m % g.Wo);
+    const long q = m / g.Wo;
+    const int ho = (int)(q % g.Ho);
+    const int n = (int)(q / g.Ho);
+    const int hi = ho * g.stride + r - g.pad;
+    const int wi = wo * g.stride + s - g.pad;
+    if (hi < 0 || hi >= g.H || wi < 0 || wi >= g.W) continue;
+    acc = fmaf(Elem<T>::ld(dy + (size_t)m * g.Cout + k),
+               Elem<T>::ld(x + (((size_t)n * g.H + hi) * g.W + wi) * g.Cin + c), acc);
+  }
+  part[(size_t)blockIdx.y * nw + i] = acc;
+}
+
+__global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __restrict__ part,
+                                                              float* __restrict__ out, int n, int P) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  float acc = 0.f;
+  for (int p = 0; p < P; ++p) acc += part[(size_t)p * n + i];
+  out[i] = acc;
+}
+
+void wgrad_split(const ConvGeom& g, int* chunk, int* P) {
+  const long M = (long)g.N * g.Ho * g.Wo;
+  const long nw = (long)g.Cout * g.R * g.S * g.Cin;
+  const long out_blocks = (nw + 255) / 256;
+  long want = (2048 + out_blocks - 1) / out_blocks;
+  const long maxP = (M + 63) / 64;
+  if (want > maxP) want = maxP;
+  if (want > 4096) want = 4096;
+  if (want < 1) want = 1;
+  long ch = (M + want - 1) / want;
+  *chunk = (int)ch;
+  *P = (int)((M + ch - 1) / ch);
+}
+
+}  // namespace
+
+size_t conv_direct_wgrad_ws(const ConvGeom& g) {
+  int chunk, P;
+  wgrad_split(g, &chunk, &P);
+  return (size_t)P * g.Cout * g.R * g.S * g.Cin * sizeof(float);
+}
+
+int conv_direct_fwd(const ConvGeom& g, int dtype, const void* x, const void* w, void* y, hipStream_t st) {
+  const size_t total = (size_t)g.N * g.Ho * g.Wo * g.Cout;
+  const unsigned blocks = (unsigned)((total + 255) / 256);
+  if (dtype == CNNK_BF16)
+    direct_fwd_kernel<bf16_t><<<blocks, 256, 0, st>>>(g, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y);
+  else
+    direct_fwd_kernel<float><<<blocks, 256, 0, st>>>(g, (const float*)x, (const float*)w, (float*)y);
+  return launch_status();
+}
+
+int conv_direct_dgrad(const ConvGeom& g, int dtype, const void* dy, const void* w, void* dx, int accumulate,
+                      hipStream_t st) {
+  const size_t total = (size_t)g.N * g.H * g.W * g.Cin;
+  const unsigned blocks = (unsigned)((total + 255) / 256);
+  if (dtype == CNNK_BF16)
+    direct_dgrad_kernel<bf16_t><<<blocks, 256, 0, st>>>(g, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, accumulate);
+  else
+    direct_dgrad_kernel<float><<<blocks, 256, 0, st>>>(g, (const float*)dy, (const float*)w, (float*)dx, accumulate);
+  return launch_status();
+}
+
+int conv_direct_wgrad(const ConvGeom& g, int dtype, const void* x, const void* dy, float* dw, void* ws,
+                      hipStream_t st) {
+  int chunk, P;
+  wgrad_split(g, &chunk, &P);
+  const int nw = g.Cout * g.R * g.S * g.Cin;
+  dim3 grid((nw + 255) / 256, P);
+  float* part = (float*)ws;
+  if (dtype == CNNK_BF16)
+    direct_wgrad_kernel<bf16_t><<<grid, 256, 0, st>>>(g, (const bf16_t*)x, (const bf16_t*)dy, part, chunk);
+  else
+    direct_wgrad_kernel<float><<<grid, 256, 0, st>>>(g, (const float*)x, (const float*)dy, part, chunk);
+  if (launch_status() != CNNK_OK) return CNNK_ERR_HIP;
+  reduce_partials_kernel<<<(nw + 255) / 256, 256, 0, st>>>(part, dw, nw, P);
+  return launch_status();
+}
+
+int reduce_partials(const float* part, float* out, int n, int P, hipStream_t st) {
+  reduce_partials_kernel<<<(n + 255) / 256, 256, 0, st>>>(part, out, n, P);
+  return launch_status();
+}

@@ -1,0 +1,510 @@
+// bf16 implicit-GEMM convolution kernels on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16,
+// fp32 accumulation).  Activations NHWC, weights [Cout][R][S][Cin].
+//
+//  * igemm_kernel: forward and data-gradient.  GEMM rows are output pixels, columns are output
+//    channels, the reduction runs over (filter tap, source channel).  A tap is a (dh, dw) shift
+//    of the source image plus an index into the weight array, so the same kernel serves the
+//    forward pass (source x, shifts r-pad / s-pad, source step = stride) and the data gradient
+//    (source dy, weights transposed to [Cin][tap][Cout], one launch class per output parity so
+//    that a strided layer only visits the taps that really contribute).
+//  * wgrad_kernel: weight gradient.  GEMM rows are output channels, columns are (tap, input
+//    channel), the reduction runs over output pixels, split across workgroups; both operands
+//    arrive channel-contiguous and are transposed in registers on their way into LDS.
+#include "common.h"
+#include "conv.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kMaxTaps = 9;
+
+struct TapTable {
+  int nclass;
+  int cls_begin[5];
+  int dh[kMaxTaps], dw[kMaxTaps], widx[kMaxTaps];
+  int Hm[4], Wm[4], oh[4], ow[4];
+};
+
+struct IgemmArgs {
+  const bf16_t* src;
+  const bf16_t* wt;
+  bf16_t* dst;
+  int Nimg, Hs, Ws, Cs;  // source tensor
+  int Hd, Wd, Cd;        // destination tensor; Cd = GEMM columns
+  int T;                 // taps in the weight array: wt[Cd][T][Cs]
+  int ss, os;            // source step per sub-grid index; destination step per sub-grid index
+  int accumulate;
+  int ntiles;
+  TapTable tt;
+};
+
+template <int BM, int BN, int BK, int WM, int WN>
+__global__ void __launch_bounds__(kThreads) igemm_kernel(IgemmArgs a) {
+  constexpr int LDK = BK + 8;  // padded row (elements): conflict-free 16-byte fragment reads
+  constexpr int KC = BK / 8;
+  constexpr int RPP = kThreads / KC;  // tile rows filled per pass of the workgroup
+  constexpr int A_IT = (BM + RPP - 1) / RPP, B_IT = (BN + RPP - 1) / RPP;  // rows beyond the tile are skipped
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  constexpr int LDC = BN + 8;
+  static_assert(WM * WN == 4 && A_IT >= 1 && B_IT >= 1 && TM >= 1 && TN >= 1, "tile shape");
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem_raw);  // [2][BM][LDK]
+  bf16_t* Bs = As + 2 * BM * LDK;                    // [2][BN][LDK]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave % WM, wn = wave / WM;
+  int b = blockIdx.x;
+  const int nb = gridDim.x;
+  if ((nb & 7) == 0) b = (b & 7) * (nb >> 3) + (b >> 3);  // consecutive tiles share an XCD (and its L2)
+  const int cls = blockIdx.y;
+  const int nt = b % a.ntiles, mt = b / a.ntiles;
+  const int Hm = a.tt.Hm[cls], Wm = a.tt.Wm[cls];
+  const int M = a.Nimg * Hm * Wm;
+  if (mt * BM >= M) return;
+  const int tap0 = a.tt.cls_begin[cls], ntap = a.tt.cls_begin[cls + 1] - tap0;
+
+  const int kc = tid % KC, r0 = tid / KC;
+  int a_n[A_IT], a_h[A_IT], a_w[A_IT];
+#pragma unroll
+  for (int it = 0; it < A_IT; ++it) {
+    const int m = mt * BM + r0 + it * RPP;
+    if (m < M && r0 + it * RPP < BM) {
+      const int j = m % Wm, q = m / Wm;
+      const int i = q % Hm, n = q / Hm;
+      a_n[it] = n * a.Hs * a.Ws;
+      a_h[it] = i * a.ss;
+      a_w[it] = j * a.ss;
+    } else {
+      a_n[it] = 0; a_h[it] = -(1 << 20); a_w[it] = 0;
+    }
+  }
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int cchunks = (a.Cs + BK - 1) / BK;
+  const int nstage = ntap * cchunks;
+  uint4 ra[A_IT], rb[B_IT];
+
+  auto load_stage = [&](int s) {
+    const int t = tap0 + s / cchunks;
+    const int c = (s % cchunks) * BK + kc * 8;
+    const int dh = a.tt.dh[t], dw = a.tt.dw[t], wi = a.tt.widx[t];
+    const bool cok = c < a.Cs;
+#pragma unroll
+    for (int it = 0; it < A_IT; ++it) {
+      const int hs = a_h[it] + dh, ws = a_w[it] + dw;
+      const bool ok = cok && (unsigned)hs < (unsigned)a.Hs && (unsigned)ws < (unsigned)a.Ws;
+      ra[it] = make_uint4(0, 0, 0, 0);
+      if (ok) ra[it] = *reinterpret_cast<const uint4*>(a.src + ((size_t)(a_n[it] + hs * a.Ws + ws)) * a.Cs + c);
+    }
+#pragma unroll
+    for (int it = 0; it < B_IT; ++it) {
+      const int ch = nt * BN + r0 + it * RPP;
+      rb[it] = make_uint4(0, 0, 0, 0);
+      if (cok && ch < a.Cd && r0 + it * RPP < BN) rb[it] = *reinterpret_cast<const uint4*>(a.wt + ((size_t)ch * a.T + wi) * a.Cs + c);
+    }
+  };
+  auto store_stage = [&](int buf) {
+#pragma unroll
+    for (int it = 0; it < A_IT; ++it)
+      if (r0 + it * RPP < BM) *reinterpret_cast<uint4*>(As + (buf * BM + r0 + it * RPP) * LDK + kc * 8) = ra[it];
+#pragma unroll
+    for (int it = 0; it < B_IT; ++it)
+      if (r0 + it * RPP < BN) *reinterpret_cast<uint4*>(Bs + (buf * BN + r0 + it * RPP) * LDK + kc * 8) = rb[it];
+  };
+
+  if (nstage > 0) {
+    load_stage(0);
+    store_stage(0);
+  }
+  __syncthreads();
+  for (int s = 0; s < nstage; ++s) {
+    const int cur = s & 1;
+    if (s + 1 < nstage) load_stage(s + 1);
+    const bf16_t* Ab = As + (cur * BM + wm * TM * 32 + (lane & 31)) * LDK + (lane >> 5) * 8;
+    const bf16_t* Bb = Bs + (cur * BN + wn * TN * 32 + (lane & 31)) * LDK + (lane >> 5) * 8;
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      bf16x8_t af[TM], bfr[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const bf16x8_t*>(Ab + i * 32 * LDK + kk * 16);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bfr[j] = *reinterpret_cast<const bf16x8_t*>(Bb + j * 32 * LDK + kk * 16);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    if (s + 1 < nstage) store_stage(cur ^ 1);
+    __syncthreads();
+  }
+
+  // Epilogue: accumulators -> bf16 tile in LDS -> 16-byte coalesced rows to the destination.
+  bf16_t* Ct = reinterpret_cast<bf16_t*>(smem_raw);
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = wm * TM * 32 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        const int col = wn * TN * 32 + j * 32 + (lane & 31);
+        Ct[row * LDC + col] = f32_to_bf16(acc[i][j][r]);
+      }
+  __syncthreads();
+  const int oh = a.tt.oh[cls], ow = a.tt.ow[cls];
+  for (int idx = tid; idx < BM * (BN / 8); idx += kThreads) {
+    const int row = idx / (BN / 8), ch = idx % (BN / 8);
+    const int m = mt * BM + row, co = nt * BN + ch * 8;
+    if (m >= M || co >= a.Cd) continue;
+    const int j = m % Wm, q = m / Wm;
+    const int i = q % Hm, n = q / Hm;
+    bf16_t* dp = a.dst + (((size_t)n * a.Hd + (i * a.os + oh)) * a.Wd + (j * a.os + ow)) * a.Cd + co;
+    uint4 v = *reinterpret_cast<const uint4*>(Ct + row * LDC + ch * 8);
+    if (a.accumulate) {
+      float o[8], nw[8];
+      load8(dp, o);
+      load8(Ct + row * LDC + ch * 8, nw);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] += nw[e];
+      store8(dp, o);
+    } else {
+      *reinterpret_cast<uint4*>(dp) = v;
+    }
+  }
+}
+
+// wt[c][t][k] = w[k][t][c]
+__global__ void __launch_bounds__(256) transpose_weights_kernel(const bf16_t* __restrict__ w,
+                                                                bf16_t* __restrict__ wt, int Cout, int T,
+                                                                int Cin) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= Cout * T * Cin) return;
+  const int k = idx % Cout;
+  const int t = (idx / Cout) % T;
+  const int c = idx / (Cout * T);
+  wt[idx] = w[((size_t)k * T + t) * Cin + c];
+}
+
+// ------------------------------------------------------------------------------------------
+struct WgradArgs {
+  const bf16_t* x;
+  const bf16_t* dy;
+  float* part;  // [splits][Cout][Q]
+  int N, H, W, Cin, Cout, R, S, stride, pad, Ho, Wo;
+  int M;      // N*Ho*Wo
+  int chunk;  // output positions per split (multiple of 64)
+  int Q;      // R*S*Cin
+  int qtiles;
+};
+
+__device__ __forceinline__ int swz(int row) { return (row & 7) ^ ((row >> 3) & 7); }
+
+template <int BMK, int BNQ, int WM, int WN>
+__global__ void __launch_bounds__(kThreads) wgrad_kernel(WgradArgs a) {
+  constexpr int BKP = 64;  // output positions per stage
+  constexpr int NA = (BMK / 8) * (BKP / 8), NB = (BNQ / 8) * (BKP / 8);
+  constexpr int TM = BMK / WM / 32, TN = BNQ / WN / 32;
+  static_assert(NA + NB <= kThreads && WM * WN == 4 && TM >= 1 && TN >= 1, "tile shape");
+  __shared__ __align__(16) bf16_t At[2][BMK * BKP];
+  __shared__ __align__(16) bf16_t Bt[2][BNQ * BKP];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave % WM, wn = wave / WM;
+  const int qt = blockIdx.x % a.qtiles, kt = blockIdx.x / a.qtiles;
+  const int m_begin = blockIdx.y * a.chunk;
+  const int m_end = min(m_begin + a.chunk, a.M);
+  const int nstage = (m_end - m_begin + BKP - 1) / BKP;
+
+  // role of this thread in the staging: one 8-position x 8-channel block of dy or of x
+  const bool isA = tid < NA, isB = !isA && tid < NA + NB;
+  int oct, po;  // channel octet, position octet inside the stage
+  if (isA) { oct = tid % (BMK / 8); po = tid / (BMK / 8); }
+  else { oct = (tid - NA) % (BNQ / 8); po = (tid - NA) / (BNQ / 8); }
+  int ch0 = 0, fr = 0, fs = 0;
+  bool chan_ok = false;
+  if (isA) {
+    ch0 = kt * BMK + oct * 8;
+    chan_ok = ch0 < a.Cout;
+  } else if (isB) {
+    const int q0 = qt * BNQ + oct * 8;
+    chan_ok = q0 < a.Q;
+    const int t = q0 / a.Cin;
+    ch0 = q0 % a.Cin;
+    fr = t / a.S;
+    fs = t % a.S;
+  }
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  uint4 rg[8];
+  auto load_stage = [&](int s) {
+    const int m0 = m_begin + s * BKP + po * 8;
+#pragma unroll
+    for (int p = 0; p < 8; ++p) rg[p] = make_uint4(0, 0, 0, 0);
+    if (!chan_ok) return;
+    if (isA) {
+#pragma unroll
+      for (int p = 0; p < 8; ++p)
+        if (m0 + p < m_end) rg[p] = *reinterpret_cast<const uint4*>(a.dy + (size_t)(m0 + p) * a.Cout + ch0);
+    } else if (isB) {
+      int wo = m0 % a.Wo, q = m0 / a.Wo;
+      int ho = q % a.Ho, n = q / a.Ho;
+#pragma unroll
+      for (int p = 0; p < 8; ++p) {
+        const int hi = ho * a.stride + fr - a.pad, wi = wo * a.stride + fs - a.pad;
+        if (m0 + p < m_end && (unsigned)hi < (unsigned)a.H && (unsigned)wi < (unsigned)a.W)
+          rg[p] = *reinterpret_cast<const uint4*>(a.x + (((size_t)n * a.H + hi) * a.W + wi) * a.Cin + ch0);
+        if (++wo == a.Wo) { wo = 0; if (++ho == a.Ho) { ho = 0; ++n; } }
+      }
+    }
+  };
+  auto store_stage = [&](int buf) {
+    if (!(isA || isB)) return;
+    bf16_t* T_ = isA ? At[buf] : Bt[buf];
+    const unsigned* rw = reinterpret_cast<const unsigned*>(rg);
+#pragma unroll
+    for (int c2 = 0; c2 < 4; ++c2) {
+      uint4 lo, hi;
+      unsigned* lw = reinterpret_cast<unsigned*>(&lo);
+      unsigned* hw = reinterpret_cast<unsigned*>(&hi);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const unsigned e = rw[(2 * j) * 4 + c2], o = rw[(2 * j + 1) * 4 + c2];
+        lw[j] = (e & 0xffffu) | (o << 16);
+        hw[j] = (e >> 16) | (o & 0xffff0000u);
+      }
+      const int rl = oct * 8 + 2 * c2, rh = rl + 1;
+      *reinterpret_cast<uint4*>(T_ + rl * BKP + ((po ^ swz(rl)) << 3)) = lo;
+      *reinterpret_cast<uint4*>(T_ + rh * BKP + ((po ^ swz(rh)) << 3)) = hi;
+    }
+  };
+
+  if (nstage > 0) {
+    load_stage(0);
+    store_stage(0);
+  }
+  __syncthreads();
+  for (int s = 0; s < nstage; ++s) {
+    const int cur = s & 1;
+    if (s + 1 < nstage) load_stage(s + 1);
+#pragma unroll
+    for (int kk = 0; kk < BKP / 16; ++kk) {
+      bf16x8_t af[TM], bfr[TN];
+      const int chunk = kk * 2 + (lane >> 5);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int row = wm * TM * 32 + i * 32 + (lane & 31);
+        af[i] = *reinterpret_cast<const bf16x8_t*>(At[cur] + row * BKP + ((chunk ^ swz(row)) << 3));
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int row = wn * TN * 32 + j * 32 + (lane & 31);
+        bfr[j] = *reinterpret_cast<const bf16x8_t*>(Bt[cur] + row * BKP + ((chunk ^ swz(row)) << 3));
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    if (s + 1 < nstage) store_stage(cur ^ 1);
+    __syncthreads();
+  }
+
+  float* out = a.part + (size_t)blockIdx.y * a.Cout * a.Q;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = kt * BMK + wm * TM * 32 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        const int col = qt * BNQ + wn * TN * 32 + j * 32 + (lane & 31);
+        if (row < a.Cout && col < a.Q) out[(size_t)row * a.Q + col] = acc[i][j][r];
+      }
+}
+
+// ---------------------------------------------------------------------------- host side ----
+struct IgemmPlan {
+  int bm, bn, bk;
+};
+
+IgemmPlan plan_igemm(long maxM, int Cd, int Cs) {
+  IgemmPlan p;
+  p.bk = (Cs % 32 == 0) ? 32 : 16;
+  const long b128 = ((maxM + 127) / 128) * ((Cd + 127) / 128);
+  if (Cd > 64 && b128 >= 256) { p.bm = 128; p.bn = 128; }
+  else if (Cd <= 64 && (maxM + 255) / 256 >= 512) { p.bm = 256; p.bn = 64; }
+  else if (((maxM + 127) / 128) * ((Cd + 63) / 64) >= 256) { p.bm = 128; p.bn = 64; }
+  else { p.bm = 64; p.bn = 64; }
+  return p;
+}
+
+template <int BM, int BN, int BK, int WM, int WN>
+int launch_igemm(const IgemmArgs& a, long maxM, hipStream_t st) {
+  constexpr size_t stage_bytes = (size_t)2 * (BM + BN) * (BK + 8) * sizeof(bf16_t);
+  constexpr size_t epi_bytes = (size_t)BM * (BN + 8) * sizeof(bf16_t);
+  constexpr size_t smem = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
+  static bool attr_done = false;
+  auto kern = igemm_kernel<BM, BN, BK, WM, WN>;
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)smem) != hipSuccess)
+      return CNNK_ERR_HIP;
+    attr_done = true;
+  }
+  IgemmArgs b = a;
+  b.ntiles = (a.Cd + BN - 1) / BN;
+  const long mtiles = (maxM + BM - 1) / BM;
+  dim3 grid((unsigned)(mtiles * b.ntiles), a.tt.nclass);
+  hipLaunchKernelGGL(kern, grid, dim3(kThreads), smem, st, b);
+  return launch_status();
+}
+
+int dispatch_igemm(const IgemmArgs& a, long maxM, hipStream_t st) {
+  const IgemmPlan p = plan_igemm(maxM, a.Cd, a.Cs);
+#define CNNK_IGEMM_CASE(BM, BN, WM, WN)                                              \
+  if (p.bm == BM && p.bn == BN) {                                                    \
+    if (p.bk == 32) return launch_igemm<BM, BN, 32, WM, WN>(a, maxM, st);            \
+    return launch_igemm<BM, BN, 16, WM, WN>(a, maxM, st);                            \
+  }
+  CNNK_IGEMM_CASE(128, 128, 2, 2)
+  CNNK_IGEMM_CASE(256, 64, 4, 1)
+  CNNK_IGEMM_CASE(128, 64, 4, 1)
+  CNNK_IGEMM_CASE(64, 64, 2, 2)
+#undef CNNK_IGEMM_CASE
+  return CNNK_ERR_UNSUPPORTED;
+}
+
+void wgrad_plan(const ConvGeom& g, int* bmk, int* chunk, int* splits) {
+  const int Q = g.R * g.S * g.Cin;
+  const long M = (long)g.N * g.Ho * g.Wo;
+  *bmk = g.Cout > 64 ? 128 : 64;
+  const long tiles = (long)((g.Cout + *bmk - 1) / *bmk) * ((Q + 127) / 128);
+  long want = (768 + tiles - 1) / tiles;
+  const long maxs = (M + 255) / 256;
+  if (want > maxs) want = maxs;
+  if (want < 1) want = 1;
+  long ch = (M + want - 1) / want;
+  ch = (ch + 63) / 64 * 64;
+  *chunk = (int)ch;
+  *splits = (int)((M + ch - 1) / ch);
+}
+
+}  // namespace
+
+bool conv_mfma_supported(const ConvGeom& g, int pass) {
+  (void)pass;
+  if (g.Cin % 8 != 0 || g.Cout % 8 != 0) return false;
+  if (g.R != g.S || (g.R != 1 && g.R != 3)) return false;
+  if (g.stride < 1 || g.stride > 2) return false;
+  // 32-bit element offsets inside the kernels
+  const long e_in = (long)g.N * g.H * g.W * g.Cin, e_out = (long)g.N * g.Ho * g.Wo * g.Cout;
+  if (e_in >= (1L << 31) || e_out >= (1L << 31)) return false;
+  return true;
+}
+
+size_t conv_mfma_ws(const ConvGeom& g, int pass, bool want_stats) {
+  (void)want_stats;
+  if (pass == CNNK_PASS_DGRAD) return align_up((size_t)g.Cout * g.R * g.S * g.Cin * sizeof(bf16_t), 256);
+  if (pass == CNNK_PASS_WGRAD) {
+    int bmk, chunk, splits;
+    wgrad_plan(g, &bmk, &chunk, &splits);
+    return splits > 1 ? (size_t)splits * g.Cout * g.R * g.S * g.Cin * sizeof(float) : 0;
+  }
+  return 0;
+}
+
+int conv_mfma_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y, float* ch_sum,
+                  float* ch_sumsq, void* ws, hipStream_t st) {
+  (void)ch_sum; (void)ch_sumsq; (void)ws;
+  IgemmArgs a{};
+  a.src = x; a.wt = w; a.dst = y;
+  a.Nimg = g.N; a.Hs = g.H; a.Ws = g.W; a.Cs = g.Cin;
+  a.Hd = g.Ho; a.Wd = g.Wo; a.Cd = g.Cout;
+  a.T = g.R * g.S; a.ss = g.stride; a.os = 1; a.accumulate = 0;
+  a.tt.nclass = 1;
+  a.tt.cls_begin[0] = 0; a.tt.cls_begin[1] = g.R * g.S;
+  for (int r = 0; r < g.R; ++r)
+    for (int s = 0; s < g.S; ++s) {
+      const int t = r * g.S + s;
+      a.tt.dh[t] = r - g.pad; a.tt.dw[t] = s - g.pad; a.tt.widx[t] = t;
+    }
+  a.tt.Hm[0] = g.Ho; a.tt.Wm[0] = g.Wo; a.tt.oh[0] = 0; a.tt.ow[0] = 0;
+  return dispatch_igemm(a, (long)g.N * g.Ho * g.Wo, st);
+}
+
+int conv_mfma_dgrad(const ConvGeom& g, const bf16_t* dy, const bf16_t* w, bf16_t* dx, int accumulate,
+                    void* ws, hipStream_t st) {
+  const int T = g.R * g.S;
+  bf16_t* wt = reinterpret_cast<bf16_t*>(ws);
+  const int nw = g.Cout * T * g.Cin;
+  transpose_weights_kernel<<<(nw + 255) / 256, 256, 0, st>>>(w, wt, g.Cout, T, g.Cin);
+  if (launch_status() != CNNK_OK) return CNNK_ERR_HIP;
+  IgemmArgs a{};
+  a.src = dy; a.wt = wt; a.dst = dx;
+  a.Nimg = g.N; a.Hs = g.Ho; a.Ws = g.Wo; a.Cs = g.Cout;
+  a.Hd = g.H; a.Wd = g.W; a.Cd = g.Cin;
+  a.T = T; a.ss = 1; a.os = g.stride; a.accumulate = accumulate;
+  const int st_ = g.stride;
+  int ncls = 0, ntap = 0;
+  long maxM = 0;
+  for (int eh = 0; eh < st_; ++eh)
+    for (int ew = 0; ew < st_; ++ew) {
+      a.tt.cls_begin[ncls] = ntap;
+      for (int r = 0; r < g.R; ++r) {
+        const int th = eh + g.pad - r;
+        if (((th % st_) + st_) % st_ != 0) continue;
+        for (int s = 0; s < g.S; ++s) {
+          const int tw = ew + g.pad - s;
+          if (((tw % st_) + st_) % st_ != 0) continue;
+          // exact quotients (th, tw are multiples of the stride, possibly negative)
+          a.tt.dh[ntap] = th / st_; a.tt.dw[ntap] = tw / st_; a.tt.widx[ntap] = r * g.S + s;
+          ++ntap;
+        }
+      }
+      a.tt.Hm[ncls] = (g.H - eh + st_ - 1) / st_;
+      a.tt.Wm[ncls] = (g.W - ew + st_ - 1) / st_;
+      a.tt.oh[ncls] = eh; a.tt.ow[ncls] = ew;
+      const long m = (long)g.N * a.tt.Hm[ncls] * a.tt.Wm[ncls];
+      if (m > maxM) maxM = m;
+      ++ncls;
+    }
+  a.tt.cls_begin[ncls] = ntap;
+  a.tt.nclass = ncls;
+  return dispatch_igemm(a, maxM, st);
+}
+
+int conv_mfma_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws,
+                    hipStream_t st) {
+  int bmk, chunk, splits;
+  wgrad_plan(g, &bmk, &chunk, &splits);
+  WgradArgs a{};
+  a.x = x; a.dy = dy;
+  a.part = splits > 1 ? reinterpret_cast<float*>(ws) : dw;
+  a.N = g.N; a.H = g.H; a.W = g.W; a.Cin = g.Cin; a.Cout = g.Cout; a.R = g.R; a.S = g.S;
+  a.stride = g.stride; a.pad = g.pad; a.Ho = g.Ho; a.Wo = g.Wo;
+  a.M = g.N * g.Ho * g.Wo; a.chunk = chunk; a.Q = g.R * g.S * g.Cin;
+  a.qtiles = (a.Q + 127) / 128;
+  const int ktiles = (g.Cout + bmk - 1) / bmk;
+  dim3 grid(ktiles * a.qtiles, splits);
+  if (bmk == 128) hipLaunchKernelGGL((wgrad_kernel<128, 128, 2, 2>), grid, dim3(kThreads), 0, st, a);
+  else hipLaunchKernelGGL((wgrad_kernel<64, 128, 1, 4>), grid, dim3(kThreads), 0, st, a);
+  if (launch_status() != CNNK_OK) return CNNK_ERR_HIP;
+  if (splits > 1) return reduce_partials(a.part, dw, g.Cout * a.Q, splits, st);
+  return CNNK_OK;
+}

@@ -1,0 +1,148 @@
+// Classifier head: logits, softmax cross-entropy (mean over the batch, natural log), class
+// prediction, and the gradients of the head.  The work is tiny (N x F x classes); the kernels
+// are written for determinism: every sum has a fixed order, no atomics.
+#include "common.h"
+
+namespace {
+constexpr int kT = 256;
+constexpr int kMaxClasses = 4096;
+
+// One workgroup per sample: z = W x + b by wave-level dot products, then the softmax.
+template <typename T>
+__global__ void __launch_bounds__(kT) logits_softmax_kernel(const T* __restrict__ x, const float* __restrict__ W,
+                                                            const float* __restrict__ b,
+                                                            const int* __restrict__ labels, int N, int F, int K,
+                                                            float* __restrict__ dz, float* __restrict__ loss_n,
+                                                            int* __restrict__ pred, float* __restrict__ probs) {
+  __shared__ float z[kMaxClasses];
+  __shared__ float red[kT / 64];
+  __shared__ int redi[kT / 64];
+  const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const T* xr = x + (size_t)n * F;
+  for (int j = wave; j < K; j += kT / 64) {
+    float acc = 0.f;
+    for (int f = lane; f < F; f += 64) acc = fmaf(Elem<T>::ld(xr + f), W[(size_t)j * F + f], acc);
+    acc = wave_sum(acc);
+    if (lane == 0) z[j] = acc + b[j];
+  }
+  __syncthreads();
+  // max and its lowest index
+  float mx = -INFINITY;
+  int arg = 0x7fffffff;
+  for (int j = tid; j < K; j += kT)
+    if (z[j] > mx) { mx = z[j]; arg = j; }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float om = __shfl_xor(mx, o, 64);
+    const int oa = __shfl_xor(arg, o, 64);
+    if (om > mx || (om == mx && oa < arg)) { mx = om; arg = oa; }
+  }
+  if (lane == 0) { red[wave] = mx; redi[wave] = arg; }
+  __syncthreads();
+  mx = red[0]; arg = redi[0];
+  for (int w = 1; w < kT / 64; ++w)
+    if (red[w] > mx || (red[w] == mx && redi[w] < arg)) { mx = red[w]; arg = redi[w]; }
+  __syncthreads();
+  float se = 0.f;
+  for (int j = tid; j < K; j += kT) se += expf(z[j] - mx);
+  se = wave_sum(se);
+  if (lane == 0) red[wave] = se;
+  __syncthreads();
+  se = 0.f;
+  for (int w = 0; w < kT / 64; ++w) se += red[w];
+  const float lse = mx + logf(se);
+  const int lab = labels[n];
+  if (tid == 0) {
+    pred[n] = arg;
+    loss_n[n] = (lab >= 0 && lab < K) ? lse - z[lab] : lse;
+  }
+  const float invN = 1.f / (float)N;
+  for (int j = tid; j < K; j += kT) {
+    const float p = expf(z[j] - lse);
+    if (probs) probs[(size_t)n * K + j] = p;
+    dz[(size_t)n * K + j] = (p - (j == lab ? 1.f : 0.f)) * invN;
+  }
+}
+
+// loss = mean(loss_n); db[j] = sum_n dz[n][j]      (single workgroup, fixed order)
+__global__ void __launch_bounds__(kT) loss_db_kernel(const float* __restrict__ loss_n, const float* __restrict__ dz,
+                                                     int N, int K, float* __restrict__ loss, float* __restrict__ db) {
+  __shared__ float red[kT];
+  const int tid = threadIdx.x;
+  float s = 0.f;
+  for (int n = tid; n < N; n += kT) s += loss_n[n];
+  red[tid] = s;
+  __syncthreads();
+  for (int o = kT / 2; o > 0; o >>= 1) {
+    if (tid < o) red[tid] += red[tid + o];
+    __syncthreads();
+  }
+  if (tid == 0) loss[0] = red[0] / (float)N;
+  for (int j = tid; j < K; j += kT) {
+    float a = 0.f;
+    for (int n = 0; n < N; ++n) a += dz[(size_t)n * K + j];
+    db[j] = a;
+  }
+}
+
+// dW[j][f] = sum_n dz[n][j] * x[n][f]
+template <typename T>
+__global__ void __launch_bounds__(kT) fc_dw_kernel(const float* __restrict__ dz, const T* __restrict__ x, int N,
+                                                   int F, int K, float* __restrict__ dW) {
+  const int f = blockIdx.x * kT + threadIdx.x, j = blockIdx.y;
+  if (f >= F) return;
+  float a = 0.f;
+  for (int n = 0; n < N; ++n) a = fmaf(dz[(size_t)n * K + j], Elem<T>::ld(x + (size_t)n * F + f), a);
+  dW[(size_t)j * F + f] = a;
+}
+
+// dx[n][f] = sum_j dz[n][j] * W[j][f]
+template <typename T>
+__global__ void __launch_bounds__(kT) fc_dx_kernel(const float* __restrict__ dz, const float* __restrict__ W, int N,
+                                                   int F, int K, T* __restrict__ dx) {
+  const int f = blockIdx.x * kT + threadIdx.x, n = blockIdx.y;
+  if (f >= F) return;
+  float a = 0.f;
+  for (int j = 0; j < K; ++j) a = fmaf(dz[(size_t)n * K + j], W[(size_t)j * F + f], a);
+  Elem<T>::st(dx + (size_t)n * F + f, a);
+}
+
+int validate_fc(const cnnk_fc_desc* d) {
+  if (!d) return CNNK_ERR_NULL;
+  if (d->N <= 0 || d->F <= 0 || d->classes <= 0) return CNNK_ERR_SHAPE;
+  if (d->dtype != CNNK_F32 && d->dtype != CNNK_BF16) return CNNK_ERR_UNSUPPORTED;
+  if (d->classes > kMaxClasses || d->N > 65535) return CNNK_ERR_UNSUPPORTED;
+  return CNNK_OK;
+}
+}  // namespace
+
+extern "C" size_t cnnk_fc_workspace_bytes(const cnnk_fc_desc* d) {
+  if (validate_fc(d) != CNNK_OK) return 0;
+  return align_up(((size_t)d->N * d->classes + d->N) * sizeof(float), 256);
+}
+
+extern "C" int cnnk_fc_softmax_xent(const cnnk_fc_desc* d, const void* x, const float* W, const float* b,
+                                    const int* labels, float* loss, int* pred, float* probs, void* dx, float* dW,
+                                    float* db, void* ws, size_t ws_bytes, void* stream) {
+  int rc = validate_fc(d);
+  if (rc != CNNK_OK) return rc;
+  if (!x || !W || !b || !labels || !loss || !pred || !dx || !dW || !db) return CNNK_ERR_NULL;
+  if (!ws || ws_bytes < cnnk_fc_workspace_bytes(d)) return CNNK_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  const int N = d->N, F = d->F, K = d->classes;
+  float* dz = (float*)ws;
+  float* loss_n = dz + (size_t)N * K;
+  dim3 gw((F + kT - 1) / kT, K), gx((F + kT - 1) / kT, N);
+  if (d->dtype == CNNK_BF16) {
+    logits_softmax_kernel<bf16_t><<<N, kT, 0, st>>>((const bf16_t*)x, W, b, labels, N, F, K, dz, loss_n, pred, probs);
+    loss_db_kernel<<<1, kT, 0, st>>>(loss_n, dz, N, K, loss, db);
+    fc_dw_kernel<bf16_t><<<gw, kT, 0, st>>>(dz, (const bf16_t*)x, N, F, K, dW);
+    fc_dx_kernel<bf16_t><<<gx, kT, 0, st>>>(dz, W, N, F, K, (bf16_t*)dx);
+  } else {
+    logits_softmax_kernel<float><<<N, kT, 0, st>>>((const float*)x, W, b, labels, N, F, K, dz, loss_n, pred, probs);
+    loss_db_kernel<<<1, kT, 0, st>>>(loss_n, dz, N, K, loss, db);
+    fc_dw_kernel<float><<<gw, kT, 0, st>>>(dz, (const float*)x, N, F, K, dW);
+    fc_dx_kernel<float><<<gx, kT, 0, st>>>(dz, W, N, F, K, (float*)dx);
+  }
+  return launch_status();
+}

@@ -1,0 +1,261 @@
+// cnnk_train_step: forward over a layer list, loss, backward over the reversed list, SGD-momentum
+// update of every parameter (the inner mini-batch loop of the paper's Algorithm 1 for one
+// data-parallel replica).  Host code only: it validates the whole list first, then enqueues the
+// kernels of the other entry points on one stream, with no host synchronisation in between.
+#include <vector>
+#include "common.h"
+#include "sgd.h"
+
+namespace {
+
+struct Walk {
+  std::vector<size_t> slot_elems;   // 0 = not seen yet
+  std::vector<size_t> param_elems;
+  size_t ws = 0;
+  int dtype = -1;
+};
+
+bool set_elems(std::vector<size_t>& v, int id, size_t n) {
+  if (id < 0 || id >= (int)v.size()) return false;
+  if (v[id] == 0) { v[id] = n; return true; }
+  return v[id] == n;
+}
+
+size_t max_sz(size_t a, size_t b) { return a > b ? a : b; }
+
+// Checks every layer and gathers tensor sizes and the workspace need.  n_slots/n_params < 0:
+// sizes are unknown (workspace query), ids are only checked for being non-negative.
+int walk_layers(const cnnk_layer* L, int n, int n_slots, int n_params, Walk* w) {
+  if (!L) return CNNK_ERR_NULL;
+  if (n <= 0) return CNNK_ERR_SHAPE;
+  int max_slot = 0, max_param = 0;
+  for (int i = 0; i < n; ++i) {
+    const int ids[3] = {L[i].in0, L[i].in1, L[i].out};
+    for (int k = 0; k < 3; ++k) if (ids[k] > max_slot) max_slot = ids[k];
+    if (L[i].p0 > max_param) max_param = L[i].p0;
+    if (L[i].p1 > max_param) max_param = L[i].p1;
+  }
+  if (n_slots >= 0 && max_slot >= n_slots) return CNNK_ERR_SHAPE;
+  if (n_params >= 0 && max_param >= n_params) return CNNK_ERR_SHAPE;
+  w->slot_elems.assign(max_slot + 1, 0);
+  w->param_elems.assign(max_param + 1, 0);
+  for (int i = 0; i < n; ++i) {
+    const cnnk_layer& l = L[i];
+    int dt = -1;
+    bool ok = true;
+    switch (l.op) {
+      case CNNK_OP_CONV: {
+        const cnnk_conv_desc& d = l.d.conv;
+        int rc = cnnk_validate_conv(&d);
+        if (rc != CNNK_OK) return rc;
+        dt = d.dtype;
+        const int Ho = conv_out(d.H, d.pad, d.R, d.stride), Wo = conv_out(d.W, d.pad, d.S, d.stride);
+        ok = l.in0 >= 0 && l.out > 0 && l.p0 >= 0 &&
+             set_elems(w->slot_elems, l.in0, (size_t)d.N * d.H * d.W * d.Cin) &&
+             set_elems(w->slot_elems, l.out, (size_t)d.N * Ho * Wo * d.Cout) &&
+             set_elems(w->param_elems, l.p0, (size_t)d.Cout * d.R * d.S * d.Cin);
+        for (int p = 0; p < 3; ++p) w->ws = max_sz(w->ws, cnnk_conv2d_workspace_bytes(&d, p));
+        break;
+      }
+      case CNNK_OP_BN: {
+        const cnnk_bn_desc& d = l.d.bn;
+        const size_t e = (size_t)d.N * d.H * d.W * d.C;
+        dt = d.dtype;
+        if (d.N <= 0 || d.H <= 0 || d.W <= 0 || d.C <= 0) return CNNK_ERR_SHAPE;
+        if (d.C % 8 != 0 || d.C > 2048) return CNNK_ERR_UNSUPPORTED;
+        if (l.in0 == 0) return CNNK_ERR_UNSUPPORTED;  // batch norm directly on the network input
+        ok = l.in0 > 0 && l.out > 0 && l.p0 >= 0 && l.p1 >= 0 && set_elems(w->slot_elems, l.in0, e) &&
+             set_elems(w->slot_elems, l.out, e) && (l.in1 < 0 || set_elems(w->slot_elems, l.in1, e)) &&
+             set_elems(w->param_elems, l.p0, d.C) && set_elems(w->param_elems, l.p1, d.C);
+        w->ws = max_sz(w->ws, cnnk_bn_workspace_bytes(&d));
+        break;
+      }
+      case CNNK_OP_POOL: {
+        const cnnk_pool_desc& d = l.d.pool;
+        dt = d.dtype;
+        if (d.N <= 0 || d.H <= 0 || d.W <= 0 || d.C <= 0) return CNNK_ERR_SHAPE;
+        if (d.C % 8 != 0) return CNNK_ERR_UNSUPPORTED;
+        size_t eo;
+        if (d.mode == CNNK_POOL_MAX2) {
+          if ((d.H & 1) || (d.W & 1)) return CNNK_ERR_SHAPE;
+          eo = (size_t)d.N * (d.H / 2) * (d.W / 2) * d.C;
+        } else if (d.mode == CNNK_POOL_GAP) {
+          eo = (size_t)d.N * d.C;
+        } else {
+          return CNNK_ERR_UNSUPPORTED;
+        }
+        ok = l.in0 >= 0 && l.out > 0 && set_elems(w->slot_elems, l.in0, (size_t)d.N * d.H * d.W * d.C) &&
+             set_elems(w->slot_elems, l.out, eo);
+        break;
+      }
+      case CNNK_OP_ADD: {
+        const cnnk_pool_desc& d = l.d.pool;
+        dt = d.dtype;
+        if (d.N <= 0 || d.H <= 0 || d.W <= 0 || d.C <= 0) return CNNK_ERR_SHAPE;
+        const size_t e = (size_t)d.N * d.H * d.W * d.C;
+        ok = l.in0 >= 0 && l.in1 >= 0 && l.out > 0 && set_elems(w->slot_elems, l.in0, e) &&
+             set_elems(w->slot_elems, l.in1, e) && set_elems(w->slot_elems, l.out, e);
+        break;
+      }
+      case CNNK_OP_FC_LOSS: {
+        const cnnk_fc_desc& d = l.d.fc;
+        dt = d.dtype;
+        if (i != n - 1) return CNNK_ERR_UNSUPPORTED;
+        if (d.N <= 0 || d.F <= 0 || d.classes <= 0) return CNNK_ERR_SHAPE;
+        if (d.classes > 4096 || d.N > 65535) return CNNK_ERR_UNSUPPORTED;
+        ok = l.in0 > 0 && l.p0 >= 0 && l.p1 >= 0 && set_elems(w->slot_elems, l.in0, (size_t)d.N * d.F) &&
+             set_elems(w->param_elems, l.p0, (size_t)d.classes * d.F) && set_elems(w->param_elems, l.p1, d.classes);
+        w->ws = max_sz(w->ws, cnnk_fc_workspace_bytes(&d));
+        break;
+      }
+      default:
+        return CNNK_ERR_UNSUPPORTED;
+    }
+    if (!ok) return CNNK_ERR_SHAPE;
+    if (dt != CNNK_F32 && dt != CNNK_BF16) return CNNK_ERR_UNSUPPORTED;
+    if (w->dtype < 0) w->dtype = dt;
+    if (dt != w->dtype) return CNNK_ERR_UNSUPPORTED;
+  }
+  if (L[n - 1].op != CNNK_OP_FC_LOSS) return CNNK_ERR_UNSUPPORTED;
+  return CNNK_OK;
+}
+
+}  // namespace
+
+extern "C" size_t cnnk_train_step_workspace_bytes(const cnnk_layer* layers, int n_layers) {
+  Walk w;
+  if (walk_layers(layers, n_layers, -1, -1, &w) != CNNK_OK) return 0;
+  return align_up(w.ws, 256);
+}
+
+extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B, const int* labels, float lr,
+                               float momentum, float weight_decay, float* loss, int* pred, void* stream) {
+  if (!B || !labels || !loss || !pred) return CNNK_ERR_NULL;
+  if (!B->act || !B->dact || !B->param || !B->grad || !B->mom || !B->bn_save || !B->pool_idx) return CNNK_ERR_NULL;
+  Walk w;
+  int rc = walk_layers(L, n, B->n_slots, B->n_params, &w);
+  if (rc != CNNK_OK) return rc;
+  if (w.ws > 0 && (!B->ws || B->ws_bytes < w.ws)) return CNNK_ERR_WORKSPACE;
+  const bool bf16 = w.dtype == CNNK_BF16;
+  for (size_t s = 0; s < w.slot_elems.size(); ++s) {
+    if (w.slot_elems[s] == 0) continue;
+    if (!B->act[s] || (s != 0 && !B->dact[s])) return CNNK_ERR_NULL;
+  }
+  for (size_t p = 0; p < w.param_elems.size(); ++p) {
+    if (w.param_elems[p] == 0) continue;
+    if (!B->param[p] || !B->grad[p] || !B->mom[p]) return CNNK_ERR_NULL;
+  }
+  for (int i = 0; i < n; ++i) {
+    if (L[i].op == CNNK_OP_CONV && bf16 && (!B->param_lp || !B->param_lp[L[i].p0])) return CNNK_ERR_NULL;
+    if (L[i].op == CNNK_OP_BN && !B->bn_save[i]) return CNNK_ERR_NULL;
+    if (L[i].op == CNNK_OP_POOL && L[i].d.pool.mode == CNNK_POOL_MAX2 && !B->pool_idx[i]) return CNNK_ERR_NULL;
+  }
+  // every tensor that the backward pass reads a gradient from must receive one
+  {
+    std::vector<char> has(w.slot_elems.size(), 0);
+    for (int i = n - 1; i >= 0; --i) {
+      const cnnk_layer& l = L[i];
+      if (l.op != CNNK_OP_FC_LOSS && !has[l.out]) return CNNK_ERR_SHAPE;
+      has[l.in0] = 1;
+      if ((l.op == CNNK_OP_BN || l.op == CNNK_OP_ADD) && l.in1 >= 0) has[l.in1] = 1;
+    }
+  }
+
+  void* ws = B->ws;
+  const size_t wsb = B->ws_bytes;
+  // ---- forward pass and loss ---------------------------------------------------------------
+  for (int i = 0; i < n; ++i) {
+    const cnnk_layer& l = L[i];
+    switch (l.op) {
+      case CNNK_OP_CONV: {
+        const void* wt = bf16 ? B->param_lp[l.p0] : (const void*)B->param[l.p0];
+        rc = cnnk_conv2d_fwd(&l.d.conv, B->act[l.in0], wt, B->act[l.out], nullptr, nullptr, ws, wsb, stream);
+        break;
+      }
+      case CNNK_OP_BN: {
+        const int C = l.d.bn.C;
+        float* run = B->bn_running ? B->bn_running[i] : nullptr;
+        rc = cnnk_bn_relu_fwd(&l.d.bn, B->act[l.in0], l.in1 >= 0 ? B->act[l.in1] : nullptr, B->param[l.p0],
+                              B->param[l.p1], B->act[l.out], B->bn_save[i], B->bn_save[i] + C, run,
+                              run ? run + C : nullptr, nullptr, nullptr, ws, wsb, stream);
+        break;
+      }
+      case CNNK_OP_POOL:
+        rc = cnnk_pool_fwd(&l.d.pool, B->act[l.in0], B->act[l.out], B->pool_idx[i], stream);
+        break;
+      case CNNK_OP_ADD:
+        rc = cnnk_add(w.slot_elems[l.out], w.dtype, B->act[l.in0], B->act[l.in1], B->act[l.out], stream);
+        break;
+      case CNNK_OP_FC_LOSS:
+        rc = cnnk_fc_softmax_xent(&l.d.fc, B->act[l.in0], B->param[l.p0], B->param[l.p1], labels, loss, pred,
+                                  B->probs, B->dact[l.in0], B->grad[l.p0], B->grad[l.p1], ws, wsb, stream);
+        break;
+    }
+    if (rc != CNNK_OK) return rc;
+  }
+  // ---- backward pass ---------------------------------------------------------------------------
+  std::vector<char> written(w.slot_elems.size(), 0);
+  written[L[n - 1].in0] = 1;
+  for (int i = n - 2; i >= 0; --i) {
+    const cnnk_layer& l = L[i];
+    switch (l.op) {
+      case CNNK_OP_CONV: {
+        rc = cnnk_conv2d_wgrad(&l.d.conv, B->act[l.in0], B->dact[l.out], B->grad[l.p0], ws, wsb, stream);
+        if (rc == CNNK_OK && l.in0 != 0) {
+          const void* wt = bf16 ? B->param_lp[l.p0] : (const void*)B->param[l.p0];
+          rc = cnnk_conv2d_dgrad(&l.d.conv, B->dact[l.out], wt, B->dact[l.in0], written[l.in0], ws, wsb, stream);
+          written[l.in0] = 1;
+        }
+        break;
+      }
+      case CNNK_OP_BN: {
+        const int C = l.d.bn.C;
+        const bool res = l.in1 > 0;
+        const int flags = (written[l.in0] ? 1 : 0) | ((res && written[l.in1]) ? 2 : 0);
+        rc = cnnk_bn_relu_bwd(&l.d.bn, B->dact[l.out], B->act[l.in0], B->act[l.out], B->param[l.p0], B->bn_save[i],
+                              B->bn_save[i] + C, B->dact[l.in0], res ? B->dact[l.in1] : nullptr, flags,
+                              B->grad[l.p0], B->grad[l.p1], ws, wsb, stream);
+        written[l.in0] = 1;
+        if (res) written[l.in1] = 1;
+        break;
+      }
+      case CNNK_OP_POOL:
+        if (l.in0 != 0) {
+          rc = cnnk_pool_bwd(&l.d.pool, B->dact[l.out], B->pool_idx[i], B->dact[l.in0], written[l.in0], stream);
+          written[l.in0] = 1;
+        }
+        break;
+      case CNNK_OP_ADD: {
+        const int ins[2] = {l.in0, l.in1};
+        for (int k = 0; k < 2 && rc == CNNK_OK; ++k) {
+          if (ins[k] == 0) continue;
+          rc = cnnk_grad_route(w.slot_elems[l.out], w.dtype, B->dact[l.out], B->dact[ins[k]], written[ins[k]], stream);
+          written[ins[k]] = 1;
+        }
+        break;
+      }
+      default:
+        break;
+    }
+    if (rc != CNNK_OK) return rc;
+  }
+  // ---- parameter update -----------------------------------------------------------------------
+  SgdTable t;
+  t.count = 0;
+  for (size_t p = 0; p < w.param_elems.size(); ++p) {
+    if (w.param_elems[p] == 0) continue;
+    const int k = t.count++;
+    t.w[k] = B->param[p];
+    t.v[k] = B->mom[p];
+    t.g[k] = B->grad[p];
+    t.wlp[k] = (bf16 && B->param_lp) ? B->param_lp[p] : nullptr;
+    t.n[k] = w.param_elems[p];
+    if (t.count == kSgdMaxTensors) {
+      rc = sgd_multi(t, lr, momentum, weight_decay, (hipStream_t)stream);
+      if (rc != CNNK_OK) return rc;
+      t.count = 0;
+    }
+  }
+  if (t.count > 0) rc = sgd_multi(t, lr, momentum, weight_decay, (hipStream_t)stream);
+  return rc;
+}

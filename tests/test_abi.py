@@ -1,0 +1,86 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every symbol that
+include/cnnk.h declares, and rejects bad arguments on the host before launching anything."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def cnnk():
+    lib_path = os.path.join(ROOT, "paper_2503_23186_amd", "libcnnk.so")
+    if not os.path.exists(lib_path):
+        from paper_2503_23186_amd.build import build
+        build()
+    from paper_2503_23186_amd import cnnk as mod
+    return mod
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "cnnk.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cnnk_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(cnnk):
+    names = declared_functions()
+    assert len(names) >= 18
+    for n in names:
+        assert hasattr(cnnk.lib, n), n
+    assert sorted(cnnk.EXPORTS) == names
+    assert "gfx950" in cnnk.version()
+
+
+def test_struct_layouts_match_header(cnnk):
+    assert C.sizeof(cnnk.ConvDesc) == 40 and C.sizeof(cnnk.BnDesc) == 32
+    assert C.sizeof(cnnk.PoolDesc) == 24 and C.sizeof(cnnk.FcDesc) == 16
+    assert C.sizeof(cnnk.Layer) == 24 + 40
+
+
+def test_argument_errors_are_reported_before_any_launch(cnnk):
+    d = cnnk.conv_desc(2, 8, 8, 16, 16, 3, 3, 1, 1, cnnk.BF16)
+    with pytest.raises(cnnk.CnnkError) as e:
+        cnnk.cnnk_conv2d_fwd(d, None, None, None)
+    assert e.value.status == 1
+    bad = cnnk.conv_desc(2, 8, 8, 16, 16, 5, 5, 1, 2, cnnk.BF16)
+    with pytest.raises(cnnk.CnnkError) as e:
+        cnnk.cnnk_conv2d_fwd(bad, 256, 256, 256)
+    assert e.value.status == 3
+    neg = cnnk.conv_desc(0, 8, 8, 16, 16, 3, 3, 1, 1, cnnk.BF16)
+    with pytest.raises(cnnk.CnnkError) as e:
+        cnnk.cnnk_conv2d_wgrad(neg, 256, 256, 256)
+    assert e.value.status == 2
+    # dgrad on the MFMA path needs its workspace
+    with pytest.raises(cnnk.CnnkError) as e:
+        cnnk.cnnk_conv2d_dgrad(d, 256, 256, 256, 0, None, 0)
+    assert e.value.status == 4
+    assert cnnk.cnnk_conv2d_workspace_bytes(d, cnnk.PASS_DGRAD) >= 16 * 16 * 9 * 2
+    bn = cnnk.bn_desc(2, 4, 4, 12, cnnk.F32, 1)
+    with pytest.raises(cnnk.CnnkError) as e:
+        cnnk.cnnk_bn_relu_fwd(bn, 256, None, 256, 256, 256, 256, 256, ws=256, ws_bytes=1 << 20)
+    assert e.value.status == 3          # C must be a multiple of 8
+    pool = cnnk.pool_desc(2, 5, 4, 8, cnnk.F32, cnnk.POOL_MAX2)
+    with pytest.raises(cnnk.CnnkError) as e:
+        cnnk.cnnk_pool_fwd(pool, 256, 256, 256)
+    assert e.value.status == 2          # odd height
+    fc = cnnk.fc_desc(4, 16, 100, cnnk.F32)
+    with pytest.raises(cnnk.CnnkError) as e:
+        cnnk.cnnk_fc_softmax_xent(fc, 256, 256, 256, 256, 256, 256, None, 256, 256, 256, None, 0)
+    assert e.value.status == 4
+    assert cnnk.status_string(4).startswith("workspace")
+
+
+def test_train_step_validates_the_layer_list(cnnk):
+    import workloads as WL
+    net = WL.mini_resnet()
+    nl = len(net.layers)
+    layers = (cnnk.Layer * nl)()
+    # an all-zero list is a list of malformed convolutions
+    assert cnnk.cnnk_train_step_workspace_bytes(layers, nl) == 0
+    b = cnnk.Buffers()
+    with pytest.raises(cnnk.CnnkError) as e:
+        cnnk.cnnk_train_step(layers, nl, b, 256, 0.1, 0.9, 0.0, 256, 256)
+    assert e.value.status == 1
