@@ -338,3 +338,22 @@ int cnnk_ref_sgd_momentum(long n, double* w, double* v, const double* g, double 
   }
   return 0;
 }
+
+/* Storage emulation for the bf16 mode (used when the comparison must take the ReLU / max-pool /
+ * argmax decisions on values stored at the kernel's precision): round each double to the
+ * nearest bfloat16 (8 significand bits, ties to even), in place.  The value is first rounded to
+ * float (the kernel's accumulator type), then to bfloat16; overflow to infinity is not handled. */
+int cnnk_ref_round_bf16(long n, double* a) {
+  if (!a) return 1;
+  if (n < 0) return 2;
+  for (long i = 0; i < n; ++i) {
+    const float f = (float)a[i];
+    if (f != f || f == 0.0f) { a[i] = (double)f; continue; }
+    int e;
+    const double m = frexp((double)f, &e);          /* f = m * 2^e, 0.5 <= |m| < 1 */
+    const double scaled = ldexp(m, 8);              /* 8 significand bits: |scaled| in [128, 256) */
+    const double r = nearbyint(scaled);             /* default rounding mode: ties to even */
+    a[i] = ldexp(r, e - 8);
+  }
+  return 0;
+}

@@ -40,6 +40,7 @@ int cnnk_ref_fc_softmax_xent(int N, int F, int classes, const double* x, const d
                              double* probs, double* dx, double* dW, double* db);
 int cnnk_ref_sgd_momentum(long n, double* w, double* v, const double* g, double lr, double momentum,
                           double weight_decay);
+int cnnk_ref_round_bf16(long n, double* a);
 int cnnk_ref_num_threads(void);
 
 #ifdef __cplusplus

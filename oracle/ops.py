@@ -145,5 +145,13 @@ def sgd_momentum(w, v, g, lr, momentum, weight_decay=0.0):
     _chk(lib().cnnk_ref_sgd_momentum(w.size, _p(w), _p(v), _p(g), lr, momentum, weight_decay), "sgd_momentum")
 
 
+def round_bf16(a):
+    """Return a copy of `a` with every value rounded to the nearest bfloat16 (ties to even)."""
+    out = np.array(a, dtype=np.float64, copy=True, order="C")
+    lib().cnnk_ref_round_bf16.argtypes = [C.c_long, C.c_void_p]
+    _chk(lib().cnnk_ref_round_bf16(out.size, _p(out)), "round_bf16")
+    return out
+
+
 def num_threads():
     return lib().cnnk_ref_num_threads()

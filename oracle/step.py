@@ -4,6 +4,14 @@ Follows the inner loop of the paper's Algorithm 1 in its printed order: forward 
 backward pass (chain rule through the layer list in reverse), parameter update.  A tensor
 that feeds two consumers receives the sum of both gradients; the network input (slot 0)
 receives none.
+
+storage=None   : pure float64, no intermediate rounding.
+storage='bf16' : every activation and activation gradient is rounded to bfloat16 at the point
+                 where the bf16 mode stores it (conv / BN / pool / add outputs, every gradient
+                 contribution and every sum of contributions); arithmetic between the stores
+                 stays float64 and parameter gradients are not rounded.  The ReLU masks,
+                 max-pool winners and predicted classes are then decided on values of the same
+                 precision as the stored ones.
 """
 from __future__ import annotations
 import numpy as np
@@ -13,28 +21,37 @@ BN_EPS = 1e-5
 BN_MOMENTUM = 0.1
 
 
-def forward_loss(net, x, labels, params, keep=None):
+def _q(storage):
+    if storage is None:
+        return lambda a: a
+    if storage == "bf16":
+        return ops.round_bf16
+    raise ValueError(storage)
+
+
+def forward_loss(net, x, labels, params, storage=None):
     """Forward pass and loss only.  Returns (loss, fc_result, acts, saved)."""
+    q = _q(storage)
     acts = {0: np.asarray(x, dtype=np.float64)}
     saved = {}
     out = None
     for i, L in enumerate(net.layers):
         op = L["op"]
         if op == "conv":
-            acts[L["y"]] = ops.conv2d_fwd(acts[L["x"]], params[L["w"]], L["stride"], L["pad"])
+            acts[L["y"]] = q(ops.conv2d_fwd(acts[L["x"]], params[L["w"]], L["stride"], L["pad"]))
         elif op == "bn":
             res = acts[L["res"]] if L["res"] >= 0 else None
             y, mean, invstd = ops.bn_relu_fwd(acts[L["x"]], params[L["gamma"]], params[L["beta"]],
                                               relu=bool(L["relu"]), residual=res, eps=BN_EPS,
                                               momentum=BN_MOMENTUM)
-            acts[L["y"]] = y
+            acts[L["y"]] = q(y)
             saved[i] = (mean, invstd)
         elif op == "pool":
             y, am = ops.pool_fwd(acts[L["x"]], L["mode"])
-            acts[L["y"]] = y
+            acts[L["y"]] = q(y)
             saved[i] = am
         elif op == "add":
-            acts[L["y"]] = acts[L["a"]] + acts[L["b"]]
+            acts[L["y"]] = q(acts[L["a"]] + acts[L["b"]])
         elif op == "fc_loss":
             xin = acts[L["x"]].reshape(L["N"], L["F"])
             out = ops.fc_softmax_xent(xin, params[L["W"]], params[L["b"]], labels)
@@ -43,16 +60,18 @@ def forward_loss(net, x, labels, params, keep=None):
     return out["loss"], out, acts, saved
 
 
-def train_step(net, x, labels, params, mom, lr=0.1, momentum=0.9, weight_decay=0.0):
+def train_step(net, x, labels, params, mom, lr=0.1, momentum=0.9, weight_decay=0.0, storage=None):
     """One step.  Returns dict(loss, pred, acts, dacts, grads, params, mom); inputs are not modified."""
-    loss, fc, acts, saved = forward_loss(net, x, labels, params)
+    q = _q(storage)
+    loss, fc, acts, saved = forward_loss(net, x, labels, params, storage)
     grads = [None] * len(params)
     dacts = {}
 
     def contribute(slot, g):
         if slot == 0:
             return
-        dacts[slot] = g if slot not in dacts else dacts[slot] + g
+        g = q(g)
+        dacts[slot] = g if slot not in dacts else q(dacts[slot] + g)
 
     for i in range(len(net.layers) - 1, -1, -1):
         L = net.layers[i]

@@ -13,52 +13,105 @@ import oracle  # noqa: E402
 
 
 def run_both(net, config_id, lr=0.1, momentum=0.9, wd=0.0, steps=1, **gen):
+    """Runs the HIP step and the oracle walker(s) on the same seeded inputs.  For the bf16 mode the
+    oracle is walked twice: in pure float64, and with bf16 storage emulation (decisions such as
+    ReLU masks and pool winners taken on values of the kernel's storage precision)."""
     from paper_2503_23186_amd import StepRunner
     inp = WL.make_inputs(net, config_id, **gen)
     runner = StepRunner(net.layers, net.slots, [p["shape"] for p in net.params], net.dtype)
     runner.load(inp["x"], inp["labels"], inp["params"], inp["mom"])
-    params, mom = inp["params"], inp["mom"]
-    out = None
+    modes = [None, "bf16"] if net.dtype == "bf16" else [None]
+    outs = {}
+    state = {m: (inp["params"], inp["mom"]) for m in modes}
     for _ in range(steps):
         runner.step(lr, momentum, wd)
-        out = oracle.train_step(net, inp["x"], inp["labels"], params, mom, lr, momentum, wd)
-        params, mom = out["params"], out["mom"]
+        for m in modes:
+            outs[m] = oracle.train_step(net, inp["x"], inp["labels"], state[m][0], state[m][1], lr, momentum, wd,
+                                        storage=m)
+            state[m] = (outs[m]["params"], outs[m]["mom"])
     torch.cuda.synchronize()
-    return inp, runner, out
+    return inp, runner, outs
 
 
-def check_step(net, inp, runner, out, tol):
-    worst = {}
-    loss = runner.loss.item()
-    assert abs(loss - out["loss"]) <= tol * abs(out["loss"]), (loss, out["loss"])
-    assert torch.equal(runner.labels.cpu(), torch.from_numpy(inp["labels"]))        # labels pass through
+def l2_rel_err(got, ref):
+    return float(np.linalg.norm((got - ref).ravel()) / max(np.linalg.norm(ref.ravel()), 1e-30))
+
+
+def errors(net, runner, out):
+    """Per tensor class: worst max-norm error (max|gpu-ref| / max|ref|) and worst L2 relative error."""
+    e = {}
+
+    def upd(kind, got, ref):
+        got = got.reshape(ref.shape)
+        m, l = max_rel_err(got, ref), l2_rel_err(got, ref)
+        pm, pl = e.get(kind, (0.0, 0.0))
+        e[kind] = (max(pm, m), max(pl, l))
+
+    upd("loss", np.array([runner.loss.item()]), np.array([out["loss"]]))
     for s, a in out["acts"].items():
-        e = max_rel_err(host(runner.act[s]).reshape(a.shape), a)
-        worst["act"] = max(worst.get("act", 0), e)
-        assert e <= tol, ("act", s, e)
+        upd("act", host(runner.act[s]), a)
     for s, g in out["dacts"].items():
-        e = max_rel_err(host(runner.dact[s]).reshape(g.shape), g)
-        worst["dact"] = max(worst.get("dact", 0), e)
-        assert e <= tol, ("dact", s, e)
+        upd("dact", host(runner.dact[s]), g)
     for k, g in enumerate(out["grads"]):
-        e = max_rel_err(host(runner.grad[k]), g)
-        worst["grad"] = max(worst.get("grad", 0), e)
-        assert e <= tol, ("grad", k, net.params[k]["kind"], e)
-        e = max_rel_err(host(runner.param[k]), out["params"][k])
-        assert e <= tol, ("param", k, e)
-        e = max_rel_err(host(runner.mom[k]), out["mom"][k])
-        assert e <= tol, ("mom", k, e)
+        upd("grad", host(runner.grad[k]), g)
+        upd("param", host(runner.param[k]), out["params"][k])
+        upd("mom", host(runner.mom[k]), out["mom"][k])
+    upd("probs", host(runner.probs), out["probs"])
+    return e
+
+
+def check_step(net, inp, runner, outs, tol):
+    """fp32 mode: every tensor within `tol` (max-norm) of the float64 oracle.
+
+    bf16 mode: a free-running bf16 step and the float64 walk decide ReLU masks and pool winners on
+    values that differ by storage rounding, and at random initialisation the gradients are
+    incoherent sums, so a fraction f of flipped decisions moves a gradient by about sqrt(f) of its
+    norm whatever the implementation.  The oracle measures that floor itself: its walk with bf16
+    stores against its pure walk.  Graded here: the loss within `tol`; every tensor no farther
+    from the pure float64 result than 1.5x the oracle's own bf16-storage walk is (plus `tol`).
+    Element-wise bf16 parity of every layer on identical inputs is test_gpu_layers.py."""
+    assert torch.equal(runner.labels.cpu(), torch.from_numpy(inp["labels"]))        # labels pass through
+    for k in range(len(net.params)):
         if runner.param_lp[k] is not None:
             assert torch.equal(runner.param_lp[k], runner.param[k].to(torch.bfloat16))
-    # predicted classes: exact wherever the oracle's top-2 probability margin exceeds the tolerance
-    p = out["probs"]
+    pure = outs[None]
+    e = errors(net, runner, pure)
+    print("\n%s [%s] b%d vs float64 oracle (max-norm/L2): %s"
+          % (net.name, net.dtype, net.batch, {k: "%.1e/%.1e" % v for k, v in e.items()}))
+    p = pure["probs"]
     top2 = np.sort(p, axis=1)[:, -2:]
-    safe = (top2[:, 1] - top2[:, 0]) > 4 * tol * top2[:, 1]
     pred = runner.pred.cpu().numpy()
-    assert np.array_equal(pred[safe], out["pred"][safe])
-    assert max_rel_err(host(runner.probs), p) <= tol
-    print("%s: loss %.6f vs %.6f, worst errors %s, argmax compared on %d/%d samples"
-          % (net.name, loss, out["loss"], {k: "%.2e" % v for k, v in worst.items()}, int(safe.sum()), len(safe)))
+    if net.dtype == "f32":
+        for kind, (m, _) in e.items():
+            assert m <= tol, (kind, m)
+        safe = (top2[:, 1] - top2[:, 0]) > 4 * tol * top2[:, 1]
+    else:
+        emu = outs["bf16"]
+        floor = {}
+
+        def upd(kind, a, b):
+            m, l = max_rel_err(a, b), l2_rel_err(a, b)
+            pm, pl = floor.get(kind, (0.0, 0.0))
+            floor[kind] = (max(pm, m), max(pl, l))
+
+        for s_, a in pure["acts"].items():
+            upd("act", emu["acts"][s_], a)
+        for s_, g in pure["dacts"].items():
+            upd("dact", emu["dacts"][s_], g)
+        for k in range(len(net.params)):
+            upd("grad", emu["grads"][k], pure["grads"][k])
+            upd("param", emu["params"][k], pure["params"][k])
+            upd("mom", emu["mom"][k], pure["mom"][k])
+        upd("probs", emu["probs"], p)
+        print("%s oracle bf16-storage walk vs its pure walk (the floor): %s"
+              % (net.name, {k: "%.1e/%.1e" % v for k, v in floor.items()}))
+        assert e["loss"][0] <= tol, e["loss"]
+        for kind in floor:
+            assert e[kind][1] <= 1.5 * floor[kind][1] + tol, (kind, e[kind], floor[kind])
+            assert e[kind][0] <= 1.5 * floor[kind][0] + tol, (kind, e[kind], floor[kind])
+        safe = (top2[:, 1] - top2[:, 0]) > 4 * max(tol, e["probs"][0]) * top2[:, 1]
+    assert np.array_equal(pred[safe], pure["pred"][safe])                            # argmax: bit exact
+    print("argmax compared on %d of %d samples" % (int(safe.sum()), len(safe)))
 
 
 def test_config1_tiny_cnn_fp32():

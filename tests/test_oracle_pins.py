@@ -356,3 +356,32 @@ def test_step_matches_torch_autograd_on_mini_resnet():
         assert abs(loss.item() - out["loss"]) < 1e-12
         for k, t in enumerate(tp):
             assert relerr(out["grads"][k], t.grad.numpy()) < 1e-9, (net.name, k)
+
+
+def test_round_bf16_matches_library_conversion_and_ties():
+    a = np.concatenate([RNG.standard_normal(5000) * 10.0 ** RNG.integers(-6, 6, 5000), [0.0, -0.0, 1.0, -3.5]])
+    a = a.astype(np.float32).astype(np.float64)
+    got = ops.round_bf16(a)
+    lib = torch.from_numpy(a.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(got, lib)
+    # ties go to the even significand: 1 + 2^-8 is halfway between 1 and 1 + 2^-7
+    assert ops.round_bf16(np.array([1 + 2.0 ** -8]))[0] == 1.0
+    assert ops.round_bf16(np.array([1 + 3 * 2.0 ** -8]))[0] == 1 + 2.0 ** -6
+    assert ops.round_bf16(np.array([1 + 2.0 ** -8 + 2.0 ** -20]))[0] == 1 + 2.0 ** -7
+    # already representable values are fixed points (the seeded bf16 inputs stay untouched)
+    assert np.array_equal(ops.round_bf16(WL.to_bf16_representable(a)), WL.to_bf16_representable(a))
+
+
+def test_storage_emulation_only_rounds_stores():
+    net = WL.mini_resnet()
+    inp = WL.make_inputs(net, 81)
+    pure = train_step(net, inp["x"], inp["labels"], inp["params"], inp["mom"])
+    emu = train_step(net, inp["x"], inp["labels"], inp["params"], inp["mom"], storage="bf16")
+    for s, a in emu["acts"].items():
+        if s != 0:
+            assert np.array_equal(a, ops.round_bf16(a))
+    for s, g in emu["dacts"].items():
+        assert np.array_equal(g, ops.round_bf16(g))
+    assert abs(emu["loss"] - pure["loss"]) < 2e-2 * pure["loss"]
+    for ge, gp in zip(emu["grads"], pure["grads"]):
+        assert np.max(np.abs(ge - gp)) <= 0.25 * np.max(np.abs(gp))   # tiny net: a sanity bound only
