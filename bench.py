@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the cnnk training step on one MI355X.
+
+A step is one pass of the whole hot path (forward, loss, backward, SGD-momentum update) over one
+batch of seeded synthetic CIFAR-100-shaped data, resident in HBM before the timed region starts.
+Workload: BASELINE configs[2], ResNet-18 adapted to 32x32 inputs, bf16 storage / fp32 accumulate,
+batch 256.  Prints ONE JSON line (see README for the fields).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def layer_key(L, phase):
+    if L["op"] == "conv":
+        return "conv%dx%d s%d %d->%d @%d %s" % (L["R"], L["S"], L["stride"], L["Cin"], L["Cout"], L["H"], phase)
+    if L["op"] == "bn":
+        return "bn%s%s C%d @%d %s" % ("+res" if L["res"] >= 0 else "", "+relu" if L["relu"] else "", L["C"], L["H"], phase)
+    if L["op"] == "pool":
+        return "pool-%s C%d @%d %s" % (L["mode"], L["C"], L["H"], phase)
+    if L["op"] == "add":
+        return "add C%d @%d %s" % (L["C"], L["H"], phase)
+    return "fc_loss %s" % phase
+
+
+def layer_work(L, phase, esz):
+    """(flops, algorithmic HBM bytes) of one call; conv flops at true K."""
+    if L["op"] == "conv":
+        Ho = (L["H"] + 2 * L["pad"] - L["R"]) // L["stride"] + 1
+        Wo = (L["W"] + 2 * L["pad"] - L["S"]) // L["stride"] + 1
+        fl = 2.0 * L["N"] * Ho * Wo * L["Cout"] * L["R"] * L["S"] * L["Cin"]
+        xin = L["N"] * L["H"] * L["W"] * L["Cin"] * esz
+        yout = L["N"] * Ho * Wo * L["Cout"] * esz
+        wb = L["Cout"] * L["R"] * L["S"] * L["Cin"]
+        if phase == "wgrad":
+            return fl, xin + yout + 4 * wb
+        return fl, xin + yout + esz * wb
+    if L["op"] == "bn":
+        T = L["N"] * L["H"] * L["W"] * L["C"] * esz
+        res = 1 if L["res"] >= 0 else 0
+        if phase == "fwd":
+            return 0.0, (3 + res) * T          # statistics pass + normalise pass (+ residual read)
+        return 0.0, (5 + res) * T              # dy, x twice; dx once (+ residual gradient write)
+    if L["op"] == "pool":
+        T = L["N"] * L["H"] * L["W"] * L["C"] * esz
+        out = T // 4 if L["mode"] == "max2" else L["N"] * L["C"] * esz
+        return 0.0, T + out + (out // esz if L["mode"] == "max2" else 0)
+    if L["op"] == "add":
+        T = L["N"] * L["H"] * L["W"] * L["C"] * esz
+        return 0.0, 3 * T
+    return 0.0, 0.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--batch", type=int, default=0, help="override the config's batch (not a bench line)")
+    ap.add_argument("--timed-steps", type=int, default=5, help="extra steps with per-call HIP events")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", action="store_true", help="print the per-call table to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.stderr.write("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)\n")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads as WL
+    from paper_2503_23186_amd import StepRunner
+
+    if not torch.cuda.is_available():
+        sys.stderr.write("bench.py needs a GPU (there is no CPU fallback)\n")
+        sys.exit(2)
+    kw = {"batch": args.batch} if args.batch else {}
+    net = WL.build_config(args.config, **kw)
+    inp = WL.make_inputs(net, args.config)
+    run = StepRunner(net.layers, net.slots, [p["shape"] for p in net.params], net.dtype, keep_probs=False)
+    run.load(inp["x"], inp["labels"], inp["params"], inp["mom"])
+    lr, mu, wd = 0.1, 0.9, 0.0
+    stream = torch.cuda.current_stream().cuda_stream
+
+    for _ in range(args.warmup):
+        run.step(lr, mu, wd, stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run.step(lr, mu, wd, stream)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = 1e3 * dt / args.steps
+    loss = run.loss.item()
+    assert np.isfinite(loss), "loss is not finite"
+
+    # ---- per-call timing with HIP events recorded by the library on the same stream -----------
+    esz = 2 if net.dtype == "bf16" else 4
+    run.enable_timing(True)
+    acc = {}
+    nt = max(args.timed_steps, 1)
+    for _ in range(nt):
+        run.step(lr, mu, wd, stream)
+        torch.cuda.synchronize()
+        times = run.group_times_ms()
+        for g, li, phase in run.group_table():
+            if phase == "none" or li < 0:
+                continue
+            L = net.layers[li]
+            if L["op"] == "conv" and phase == "dgrad" and L["x"] == 0:
+                continue
+            key = layer_key(L, phase)
+            fl, by = layer_work(L, phase, esz)
+            a = acc.setdefault(key, dict(ms=0.0, calls=0, flops=fl, bytes=by, op=L["op"]))
+            a["ms"] += times[g]
+            a["calls"] += 1
+    run.enable_timing(False)
+    rows = []
+    for key, a in acc.items():
+        avg = a["ms"] / a["calls"]
+        rows.append(dict(key=key, op=a["op"], calls_per_step=a["calls"] // nt, avg_ms=avg,
+                         ms_per_step=a["ms"] / nt, flops=a["flops"], bytes=a["bytes"]))
+    rows.sort(key=lambda r: -r["ms_per_step"])
+    conv_ms = sum(r["ms_per_step"] for r in rows if r["op"] == "conv")
+    conv_flops = sum(r["flops"] * r["calls_per_step"] for r in rows if r["op"] == "conv")
+    ew_ms = sum(r["ms_per_step"] for r in rows if r["op"] in ("bn", "pool", "add"))
+    ew_bytes = sum(r["bytes"] * r["calls_per_step"] for r in rows if r["op"] in ("bn", "pool", "add"))
+    if args.layers:
+        for r in rows:
+            tf = r["flops"] / r["avg_ms"] / 1e9 if r["flops"] else 0.0
+            gb = r["bytes"] / r["avg_ms"] / 1e6
+            sys.stderr.write("%-34s x%-2d %8.3f ms/call %8.3f ms/step %8.1f TFLOP/s %8.1f GB/s\n"
+                             % (r["key"], r["calls_per_step"], r["avg_ms"], r["ms_per_step"], tf, gb))
+        sys.stderr.write("timed-step total %.3f ms; conv %.3f ms (%.1f TFLOP/s); bn/pool/add %.3f ms (%.0f GB/s)\n"
+                         % (sum(r["ms_per_step"] for r in rows), conv_ms, conv_flops / conv_ms / 1e9 if conv_ms else 0,
+                            ew_ms, ew_bytes / ew_ms / 1e6 if ew_ms else 0))
+    dom = rows[0]
+    if dom["op"] == "conv":
+        ach = dom["flops"] / dom["avg_ms"] / 1e9
+        roof = dict(bound="mfma", kernel=dom["key"], achieved=round(ach, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                    frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None, avg_ms=round(dom["avg_ms"], 4),
+                    calls_per_step=dom["calls_per_step"])
+    else:
+        ach = dom["bytes"] / dom["avg_ms"] / 1e6
+        roof = dict(bound="hbm", kernel=dom["key"], achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                    frac=round(ach / PEAK_HBM_GBS, 4), traffic=None, avg_ms=round(dom["avg_ms"], 4),
+                    calls_per_step=dom["calls_per_step"])
+    roof["conv_all"] = dict(tflops=round(conv_flops / conv_ms / 1e9, 2) if conv_ms else None,
+                            frac_of_mfma_peak=round(conv_flops / conv_ms / 1e9 / PEAK_BF16_TFLOPS, 4) if conv_ms else None,
+                            ms_per_step=round(conv_ms, 4))
+    roof["elementwise_all"] = dict(gbs=round(ew_bytes / ew_ms / 1e6, 1) if ew_ms else None,
+                                   frac_of_hbm_peak=round(ew_bytes / ew_ms / 1e6 / PEAK_HBM_GBS, 4) if ew_ms else None,
+                                   ms_per_step=round(ew_ms, 4))
+
+    # ---- the oracle on the host cores, on a bounded sample of the same workload ---------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        sample_batch = 8
+        small = WL.build_config(args.config, batch=sample_batch)
+        sinp = WL.make_inputs(small, args.config)
+        t0 = time.perf_counter()
+        oracle.train_step(small, sinp["x"], sinp["labels"], sinp["params"], sinp["mom"], lr, mu, wd)
+        cdt = time.perf_counter() - t0
+        cpu = dict(value=round(sample_batch / cdt, 3), unit="images/s", cores=oracle.ops.num_threads(), kind="oracle",
+                   sample="one fp64 oracle step of the same network at batch %d (%.1f s)" % (sample_batch, cdt))
+
+    out = {
+        "metric": "train images/sec on 1 GPU (ResNet-18 32x32 bf16 b256); conv MFMA % of peak",
+        "value": round(net.batch / (ms_per_step * 1e-3), 1),
+        "unit": "images/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": net.dtype,
+        "data": "synthetic",
+        "config": {"workload": "%s 32x32x3 100-class, batch %d, %s storage / fp32 accumulate, SGD momentum"
+                               % (net.name, net.batch, net.dtype),
+                   "config_id": args.config, "global_batch": net.batch, "loss": round(loss, 5)},
+        "roofline": roof,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -175,9 +175,22 @@ typedef struct cnnk_buffers {
   unsigned char** pool_idx; /* [n_layers] MAX2 layers: one byte per output element */
   float* probs;             /* N*classes softmax output, nullable */
   void* ws; size_t ws_bytes;
+  void** events;            /* nullable: hipEvent_t handles for per-call timing, see below */
+  int n_events;             /* number of handles in events */
 } cnnk_buffers;
 
 size_t cnnk_train_step_workspace_bytes(const cnnk_layer* layers, int n_layers);
+
+/* Per-call timing (the measured analogue of the per-component execution-time profile that the
+ * paper's scheduler consumes, Section III-B step 2).  The step is a sequence of "groups", one per
+ * call of an entry point above, in this order: forward layer i -> group i (i = 0..n-1); backward
+ * layer i (i = n-2..0) -> groups n + 2*(n-2-i) (weight gradient of a CONV, or the whole backward
+ * call of any other layer) and n + 2*(n-2-i) + 1 (data gradient of a CONV; empty otherwise); the
+ * parameter update -> the last group.  cnnk_train_step_event_groups returns their number,
+ * 3*n_layers - 1.  When cnnk_buffers.events holds at least twice that many handles (created by
+ * the caller with timing enabled), handle 2g is recorded on the stream before group g and handle
+ * 2g+1 after it (both are recorded for an empty group).  Otherwise nothing is recorded. */
+int cnnk_train_step_event_groups(int n_layers);
 
 /* Forward over the list, loss, backward over the reversed list, then the update of every
  * parameter, all on one stream without host synchronisation.  labels: N int32 (device);

@@ -21,7 +21,7 @@ EXPORTS = ["cnnk_status_string", "cnnk_version", "cnnk_conv2d_workspace_bytes", 
            "cnnk_conv2d_dgrad", "cnnk_conv2d_wgrad", "cnnk_bn_workspace_bytes", "cnnk_bn_relu_fwd",
            "cnnk_bn_relu_bwd", "cnnk_pool_fwd", "cnnk_pool_bwd", "cnnk_add", "cnnk_grad_route",
            "cnnk_fc_workspace_bytes", "cnnk_fc_softmax_xent", "cnnk_sgd_momentum",
-           "cnnk_train_step_workspace_bytes", "cnnk_train_step"]
+           "cnnk_train_step_workspace_bytes", "cnnk_train_step_event_groups", "cnnk_train_step"]
 
 
 class CnnkError(RuntimeError):
@@ -63,7 +63,8 @@ class Buffers(C.Structure):
                 ("grad", C.POINTER(C.c_void_p)), ("mom", C.POINTER(C.c_void_p)),
                 ("bn_save", C.POINTER(C.c_void_p)), ("bn_running", C.POINTER(C.c_void_p)),
                 ("pool_idx", C.POINTER(C.c_void_p)), ("probs", C.c_void_p),
-                ("ws", C.c_void_p), ("ws_bytes", C.c_size_t)]
+                ("ws", C.c_void_p), ("ws_bytes", C.c_size_t),
+                ("events", C.POINTER(C.c_void_p)), ("n_events", C.c_int)]
 
 
 def _load():
@@ -94,6 +95,7 @@ def _load():
     lib.cnnk_sgd_momentum.argtypes = [sz, vp, vp, vp, vp, cf, cf, cf, vp]
     lib.cnnk_train_step_workspace_bytes.restype = sz
     lib.cnnk_train_step_workspace_bytes.argtypes = [C.POINTER(Layer), ci]
+    lib.cnnk_train_step_event_groups.argtypes = [ci]
     lib.cnnk_train_step.argtypes = [C.POINTER(Layer), ci, C.POINTER(Buffers), vp, cf, cf, cf, vp, vp, vp]
     return lib
 
@@ -211,6 +213,54 @@ def cnnk_train_step_workspace_bytes(layers, n_layers):
     return lib.cnnk_train_step_workspace_bytes(layers, n_layers)
 
 
+def cnnk_train_step_event_groups(n_layers):
+    return lib.cnnk_train_step_event_groups(n_layers)
+
+
 def cnnk_train_step(layers, n_layers, buffers, labels, lr, momentum, weight_decay, loss, pred, stream=0):
     _check(lib.cnnk_train_step(layers, n_layers, C.byref(buffers), ptr(labels), lr, momentum, weight_decay,
                                ptr(loss), ptr(pred), stream), "cnnk_train_step")
+
+
+# ---- HIP runtime plumbing for callers that time launches with events (no arithmetic here) ----
+_hip = None
+
+
+def _hiprt():
+    global _hip
+    if _hip is None:
+        _hip = C.CDLL("libamdhip64.so")
+        _hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        _hip.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+        _hip.hipEventSynchronize.argtypes = [C.c_void_p]
+        _hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        _hip.hipEventDestroy.argtypes = [C.c_void_p]
+    return _hip
+
+
+def hip_event_create():
+    e = C.c_void_p()
+    rc = _hiprt().hipEventCreate(C.byref(e))
+    if rc != 0:
+        raise RuntimeError("hipEventCreate failed: %d" % rc)
+    return e.value
+
+
+def hip_event_record(ev, stream=0):
+    rc = _hiprt().hipEventRecord(ev, stream)
+    if rc != 0:
+        raise RuntimeError("hipEventRecord failed: %d" % rc)
+
+
+def hip_event_synchronize(ev):
+    rc = _hiprt().hipEventSynchronize(ev)
+    if rc != 0:
+        raise RuntimeError("hipEventSynchronize failed: %d" % rc)
+
+
+def hip_event_elapsed_ms(start, stop):
+    ms = C.c_float()
+    rc = _hiprt().hipEventElapsedTime(C.byref(ms), start, stop)
+    if rc != 0:
+        raise RuntimeError("hipEventElapsedTime failed: %d" % rc)
+    return ms.value

@@ -47,6 +47,34 @@ __device__ __forceinline__ void block_reduce_store(float (*acc)[8], int lanes, i
   }
 }
 
+// Finalising reduction: a workgroup owns kFinCh channels; 256/kFinCh thread groups each sum a
+// strided subset of the per-workgroup partials in double, then the groups are combined through
+// LDS in a fixed order.  Returns the two sums for channel c (valid in the threads of group 0).
+constexpr int kFinCh = 16;
+constexpr int kFinGroups = kT / kFinCh;
+
+__device__ __forceinline__ void finalize_sums(const float* __restrict__ part, int nb, int C, int c, int grp,
+                                              double* s1_out, double* s2_out) {
+  __shared__ double fred[2][kFinGroups][kFinCh];
+  double s1 = 0.0, s2 = 0.0;
+  if (c < C) {
+    for (int b = grp; b < nb; b += kFinGroups) {
+      s1 += (double)part[((size_t)b * 2 + 0) * C + c];
+      s2 += (double)part[((size_t)b * 2 + 1) * C + c];
+    }
+  }
+  const int cl = threadIdx.x % kFinCh;
+  fred[0][grp][cl] = s1;
+  fred[1][grp][cl] = s2;
+  __syncthreads();
+  s1 = 0.0; s2 = 0.0;
+  if (grp == 0) {
+    for (int g = 0; g < kFinGroups; ++g) { s1 += fred[0][g][cl]; s2 += fred[1][g][cl]; }
+  }
+  *s1_out = s1;
+  *s2_out = s2;
+}
+
 // Partial sums of (x - shift) and (x - shift)^2 with shift = x[0][c] (keeps fp32 sums benign).
 template <typename T>
 __global__ void __launch_bounds__(kT) stats_partial_kernel(const T* __restrict__ x, size_t m, int C,
@@ -59,6 +87,7 @@ __global__ void __launch_bounds__(kT) stats_partial_kernel(const T* __restrict__
   if (rl < rows) {
     float sh[8];
     load8(x + o * 8, sh);
+#pragma unroll 4
     for (size_t r = (size_t)blockIdx.x * rows + rl; r < m; r += (size_t)gridDim.x * rows) {
       float v[8];
       load8(x + r * C + o * 8, v);
@@ -80,13 +109,10 @@ __global__ void __launch_bounds__(kT) stats_finalize_kernel(const float* __restr
                                                             float eps, float momentum, float* __restrict__ o0,
                                                             float* __restrict__ o1, float* __restrict__ rmean,
                                                             float* __restrict__ rvar) {
-  const int c = blockIdx.x * kT + threadIdx.x;
-  if (c >= C) return;
-  double s1 = 0.0, s2 = 0.0;
-  for (int b = 0; b < nb; ++b) {
-    s1 += (double)part[((size_t)b * 2 + 0) * C + c];
-    s2 += (double)part[((size_t)b * 2 + 1) * C + c];
-  }
+  const int c = blockIdx.x * kFinCh + threadIdx.x % kFinCh, grp = threadIdx.x / kFinCh;
+  double s1, s2;
+  finalize_sums(part, nb, C, c, grp, &s1, &s2);
+  if (c >= C || grp != 0) return;
   const double sh = (double)Elem<T>::ld(x + c);
   const double dm = (double)m;
   if (mode == 1) {
@@ -173,6 +199,7 @@ __global__ void __launch_bounds__(kT) bwd_partial_kernel(const T* __restrict__ d
     float mu[8], is[8];
     load8(mean + o * 8, mu);
     load8(invstd + o * 8, is);
+#pragma unroll 4
     for (size_t r = (size_t)blockIdx.x * rows + rl; r < m; r += (size_t)gridDim.x * rows) {
       float g[8], xv[8];
       load8(dy + r * C + o * 8, g);
@@ -195,13 +222,10 @@ __global__ void __launch_bounds__(kT) bwd_partial_kernel(const T* __restrict__ d
 
 __global__ void __launch_bounds__(kT) bwd_finalize_kernel(const float* __restrict__ part, int nb, int C,
                                                           float* __restrict__ dgamma, float* __restrict__ dbeta) {
-  const int c = blockIdx.x * kT + threadIdx.x;
-  if (c >= C) return;
-  double s1 = 0.0, s2 = 0.0;
-  for (int b = 0; b < nb; ++b) {
-    s1 += (double)part[((size_t)b * 2 + 0) * C + c];
-    s2 += (double)part[((size_t)b * 2 + 1) * C + c];
-  }
+  const int c = blockIdx.x * kFinCh + threadIdx.x % kFinCh, grp = threadIdx.x / kFinCh;
+  double s1, s2;
+  finalize_sums(part, nb, C, c, grp, &s1, &s2);
+  if (c >= C || grp != 0) return;
   dbeta[c] = (float)s1;
   dgamma[c] = (float)s2;
 }
@@ -279,11 +303,11 @@ int channel_stats(int dtype, const void* x, size_t m, int C, float* ch_sum, floa
   float* part = (float*)ws;
   if (dtype == CNNK_BF16) {
     stats_partial_kernel<bf16_t><<<nb, kT, 0, st>>>((const bf16_t*)x, m, C, part);
-    stats_finalize_kernel<bf16_t><<<(C + kT - 1) / kT, kT, 0, st>>>(part, nb, (const bf16_t*)x, m, C, 1, 0.f, 0.f,
+    stats_finalize_kernel<bf16_t><<<(C + kFinCh - 1) / kFinCh, kT, 0, st>>>(part, nb, (const bf16_t*)x, m, C, 1, 0.f, 0.f,
                                                                     ch_sum, ch_sumsq, nullptr, nullptr);
   } else {
     stats_partial_kernel<float><<<nb, kT, 0, st>>>((const float*)x, m, C, part);
-    stats_finalize_kernel<float><<<(C + kT - 1) / kT, kT, 0, st>>>(part, nb, (const float*)x, m, C, 1, 0.f, 0.f,
+    stats_finalize_kernel<float><<<(C + kFinCh - 1) / kFinCh, kT, 0, st>>>(part, nb, (const float*)x, m, C, 1, 0.f, 0.f,
                                                                    ch_sum, ch_sumsq, nullptr, nullptr);
   }
   return launch_status();
@@ -312,12 +336,12 @@ extern "C" int cnnk_bn_relu_fwd(const cnnk_bn_desc* d, const void* x, const void
     float* part = (float*)ws;
     if (d->dtype == CNNK_BF16) {
       stats_partial_kernel<bf16_t><<<nb, kT, 0, st>>>((const bf16_t*)x, m, C, part);
-      stats_finalize_kernel<bf16_t><<<(C + kT - 1) / kT, kT, 0, st>>>(part, nb, (const bf16_t*)x, m, C, 0, d->eps,
+      stats_finalize_kernel<bf16_t><<<(C + kFinCh - 1) / kFinCh, kT, 0, st>>>(part, nb, (const bf16_t*)x, m, C, 0, d->eps,
                                                                       d->momentum, save_mean, save_invstd,
                                                                       running_mean, running_var);
     } else {
       stats_partial_kernel<float><<<nb, kT, 0, st>>>((const float*)x, m, C, part);
-      stats_finalize_kernel<float><<<(C + kT - 1) / kT, kT, 0, st>>>(part, nb, (const float*)x, m, C, 0, d->eps,
+      stats_finalize_kernel<float><<<(C + kFinCh - 1) / kFinCh, kT, 0, st>>>(part, nb, (const float*)x, m, C, 0, d->eps,
                                                                      d->momentum, save_mean, save_invstd,
                                                                      running_mean, running_var);
     }
@@ -355,7 +379,7 @@ extern "C" int cnnk_bn_relu_bwd(const cnnk_bn_desc* d, const void* dy, const voi
   if (d->dtype == CNNK_BF16) {
     bwd_partial_kernel<bf16_t><<<nb, kT, 0, st>>>((const bf16_t*)dy, (const bf16_t*)x, (const bf16_t*)y, save_mean,
                                                   save_invstd, m, C, d->relu, part);
-    bwd_finalize_kernel<<<(C + kT - 1) / kT, kT, 0, st>>>(part, nb, C, dgamma, dbeta);
+    bwd_finalize_kernel<<<(C + kFinCh - 1) / kFinCh, kT, 0, st>>>(part, nb, C, dgamma, dbeta);
     bwd_apply_kernel<bf16_t><<<ew_blocks(n8), kT, 0, st>>>((const bf16_t*)dy, (const bf16_t*)x, (const bf16_t*)y,
                                                            gamma, save_mean, save_invstd, dgamma, dbeta,
                                                            (bf16_t*)dx, (bf16_t*)dresidual, n8, C, inv_m, d->relu,
@@ -363,7 +387,7 @@ extern "C" int cnnk_bn_relu_bwd(const cnnk_bn_desc* d, const void* dy, const voi
   } else {
     bwd_partial_kernel<float><<<nb, kT, 0, st>>>((const float*)dy, (const float*)x, (const float*)y, save_mean,
                                                  save_invstd, m, C, d->relu, part);
-    bwd_finalize_kernel<<<(C + kT - 1) / kT, kT, 0, st>>>(part, nb, C, dgamma, dbeta);
+    bwd_finalize_kernel<<<(C + kFinCh - 1) / kFinCh, kT, 0, st>>>(part, nb, C, dgamma, dbeta);
     bwd_apply_kernel<float><<<ew_blocks(n8), kT, 0, st>>>((const float*)dy, (const float*)x, (const float*)y, gamma,
                                                           save_mean, save_invstd, dgamma, dbeta, (float*)dx,
                                                           (float*)dresidual, n8, C, inv_m, d->relu, flags);

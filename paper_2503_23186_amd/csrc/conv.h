@@ -34,6 +34,12 @@ int conv_mfma_dgrad(const ConvGeom& g, const bf16_t* dy, const bf16_t* w, bf16_t
 int conv_mfma_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws,
                     hipStream_t st);
 
+// thin-input (stem) kernels, bf16 storage
+bool conv_stem_supported(const ConvGeom& g);
+size_t conv_stem_wgrad_ws(const ConvGeom& g);
+int conv_stem_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y, hipStream_t st);
+int conv_stem_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws, hipStream_t st);
+
 // per-channel sum / sum of squares of a tensor with C channels (used when the conv kernel
 // itself does not produce them)
 size_t channel_stats_ws(size_t m, int C);

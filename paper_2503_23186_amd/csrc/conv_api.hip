@@ -22,6 +22,9 @@ int cnnk_validate_conv(const cnnk_conv_desc* d) {
 static bool use_mfma(const cnnk_conv_desc* d, const ConvGeom& g, int pass) {
   return d->dtype == CNNK_BF16 && conv_mfma_supported(g, pass);
 }
+static bool use_stem(const cnnk_conv_desc* d, const ConvGeom& g, int pass) {
+  return d->dtype == CNNK_BF16 && !conv_mfma_supported(g, pass) && conv_stem_supported(g);
+}
 
 extern "C" size_t cnnk_conv2d_workspace_bytes(const cnnk_conv_desc* d, int pass) {
   if (cnnk_validate_conv(d) != CNNK_OK) return 0;
@@ -34,7 +37,8 @@ extern "C" size_t cnnk_conv2d_workspace_bytes(const cnnk_conv_desc* d, int pass)
   } else if (pass == CNNK_PASS_DGRAD) {
     b = use_mfma(d, g, pass) ? conv_mfma_ws(g, pass, false) : 0;
   } else if (pass == CNNK_PASS_WGRAD) {
-    b = use_mfma(d, g, pass) ? conv_mfma_ws(g, pass, false) : conv_direct_wgrad_ws(g);
+    b = use_mfma(d, g, pass) ? conv_mfma_ws(g, pass, false)
+        : use_stem(d, g, pass) ? conv_stem_wgrad_ws(g) : conv_direct_wgrad_ws(g);
   }
   return align_up(b, 256);
 }
@@ -53,6 +57,8 @@ extern "C" int cnnk_conv2d_fwd(const cnnk_conv_desc* d, const void* x, const voi
   hipStream_t st = (hipStream_t)stream;
   if (use_mfma(d, g, CNNK_PASS_FWD))
     rc = conv_mfma_fwd(g, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, nullptr, nullptr, ws, st);
+  else if (use_stem(d, g, CNNK_PASS_FWD))
+    rc = conv_stem_fwd(g, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, st);
   else
     rc = conv_direct_fwd(g, d->dtype, x, w, y, st);
   if (rc != CNNK_OK) return rc;
@@ -85,6 +91,7 @@ extern "C" int cnnk_conv2d_wgrad(const cnnk_conv_desc* d, const void* x, const v
   if (need && (!ws || ws_bytes < need)) return CNNK_ERR_WORKSPACE;
   if (use_mfma(d, g, CNNK_PASS_WGRAD))
     return conv_mfma_wgrad(g, (const bf16_t*)x, (const bf16_t*)dy, dw, ws, st);
+  if (use_stem(d, g, CNNK_PASS_WGRAD)) return conv_stem_wgrad(g, (const bf16_t*)x, (const bf16_t*)dy, dw, ws, st);
   return conv_direct_wgrad(g, d->dtype, x, dy, dw, ws, st);
 }
 

@@ -64,9 +64,8 @@ __global__ void __launch_bounds__(kT) logits_softmax_kernel(const T* __restrict_
   }
 }
 
-// loss = mean(loss_n); db[j] = sum_n dz[n][j]      (single workgroup, fixed order)
-__global__ void __launch_bounds__(kT) loss_db_kernel(const float* __restrict__ loss_n, const float* __restrict__ dz,
-                                                     int N, int K, float* __restrict__ loss, float* __restrict__ db) {
+// loss = mean(loss_n)      (single workgroup, fixed order)
+__global__ void __launch_bounds__(kT) loss_kernel(const float* __restrict__ loss_n, int N, float* __restrict__ loss) {
   __shared__ float red[kT];
   const int tid = threadIdx.x;
   float s = 0.f;
@@ -78,22 +77,30 @@ __global__ void __launch_bounds__(kT) loss_db_kernel(const float* __restrict__ l
     __syncthreads();
   }
   if (tid == 0) loss[0] = red[0] / (float)N;
-  for (int j = tid; j < K; j += kT) {
-    float a = 0.f;
-    for (int n = 0; n < N; ++n) a += dz[(size_t)n * K + j];
-    db[j] = a;
-  }
 }
 
-// dW[j][f] = sum_n dz[n][j] * x[n][f]
+// One workgroup per class j: dW[j][f] = sum_n dz[n][j] * x[n][f] (threads over f), and
+// db[j] = sum_n dz[n][j] (threads over n, fixed-order tree).
 template <typename T>
-__global__ void __launch_bounds__(kT) fc_dw_kernel(const float* __restrict__ dz, const T* __restrict__ x, int N,
-                                                   int F, int K, float* __restrict__ dW) {
-  const int f = blockIdx.x * kT + threadIdx.x, j = blockIdx.y;
-  if (f >= F) return;
-  float a = 0.f;
-  for (int n = 0; n < N; ++n) a = fmaf(dz[(size_t)n * K + j], Elem<T>::ld(x + (size_t)n * F + f), a);
-  dW[(size_t)j * F + f] = a;
+__global__ void __launch_bounds__(kT) fc_dw_db_kernel(const float* __restrict__ dz, const T* __restrict__ x, int N,
+                                                      int F, int K, float* __restrict__ dW, float* __restrict__ db) {
+  __shared__ float red[kT];
+  const int j = blockIdx.x, tid = threadIdx.x;
+  for (int f = tid; f < F; f += kT) {
+    float a = 0.f;
+#pragma unroll 8
+    for (int n = 0; n < N; ++n) a = fmaf(dz[(size_t)n * K + j], Elem<T>::ld(x + (size_t)n * F + f), a);
+    dW[(size_t)j * F + f] = a;
+  }
+  float s = 0.f;
+  for (int n = tid; n < N; n += kT) s += dz[(size_t)n * K + j];
+  red[tid] = s;
+  __syncthreads();
+  for (int o = kT / 2; o > 0; o >>= 1) {
+    if (tid < o) red[tid] += red[tid + o];
+    __syncthreads();
+  }
+  if (tid == 0) db[j] = red[0];
 }
 
 // dx[n][f] = sum_j dz[n][j] * W[j][f]
@@ -132,16 +139,16 @@ extern "C" int cnnk_fc_softmax_xent(const cnnk_fc_desc* d, const void* x, const 
   const int N = d->N, F = d->F, K = d->classes;
   float* dz = (float*)ws;
   float* loss_n = dz + (size_t)N * K;
-  dim3 gw((F + kT - 1) / kT, K), gx((F + kT - 1) / kT, N);
+  dim3 gx((F + kT - 1) / kT, N);
   if (d->dtype == CNNK_BF16) {
     logits_softmax_kernel<bf16_t><<<N, kT, 0, st>>>((const bf16_t*)x, W, b, labels, N, F, K, dz, loss_n, pred, probs);
-    loss_db_kernel<<<1, kT, 0, st>>>(loss_n, dz, N, K, loss, db);
-    fc_dw_kernel<bf16_t><<<gw, kT, 0, st>>>(dz, (const bf16_t*)x, N, F, K, dW);
+    loss_kernel<<<1, kT, 0, st>>>(loss_n, N, loss);
+    fc_dw_db_kernel<bf16_t><<<K, kT, 0, st>>>(dz, (const bf16_t*)x, N, F, K, dW, db);
     fc_dx_kernel<bf16_t><<<gx, kT, 0, st>>>(dz, W, N, F, K, (bf16_t*)dx);
   } else {
     logits_softmax_kernel<float><<<N, kT, 0, st>>>((const float*)x, W, b, labels, N, F, K, dz, loss_n, pred, probs);
-    loss_db_kernel<<<1, kT, 0, st>>>(loss_n, dz, N, K, loss, db);
-    fc_dw_kernel<float><<<gw, kT, 0, st>>>(dz, (const float*)x, N, F, K, dW);
+    loss_kernel<<<1, kT, 0, st>>>(loss_n, N, loss);
+    fc_dw_db_kernel<float><<<K, kT, 0, st>>>(dz, (const float*)x, N, F, K, dW, db);
     fc_dx_kernel<float><<<gx, kT, 0, st>>>(dz, W, N, F, K, (float*)dx);
   }
   return launch_status();

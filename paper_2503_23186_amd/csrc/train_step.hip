@@ -122,6 +122,21 @@ int walk_layers(const cnnk_layer* L, int n, int n_slots, int n_params, Walk* w) 
 
 }  // namespace
 
+extern "C" int cnnk_train_step_event_groups(int n_layers) { return n_layers > 0 ? 3 * n_layers - 1 : 0; }
+
+namespace {
+// Records the caller's events around one group of launches when timing was requested.
+struct GroupTimer {
+  void** ev;
+  hipStream_t st;
+  GroupTimer(const cnnk_buffers* B, int n_layers, void* stream) : ev(nullptr), st((hipStream_t)stream) {
+    if (B->events && B->n_events >= 2 * cnnk_train_step_event_groups(n_layers)) ev = B->events;
+  }
+  void begin(int g) { if (ev) (void)hipEventRecord((hipEvent_t)ev[2 * g], st); }
+  void end(int g) { if (ev) (void)hipEventRecord((hipEvent_t)ev[2 * g + 1], st); }
+};
+}  // namespace
+
 extern "C" size_t cnnk_train_step_workspace_bytes(const cnnk_layer* layers, int n_layers) {
   Walk w;
   if (walk_layers(layers, n_layers, -1, -1, &w) != CNNK_OK) return 0;
@@ -163,9 +178,11 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
 
   void* ws = B->ws;
   const size_t wsb = B->ws_bytes;
+  GroupTimer timer(B, n, stream);
   // ---- forward pass and loss ---------------------------------------------------------------
   for (int i = 0; i < n; ++i) {
     const cnnk_layer& l = L[i];
+    timer.begin(i);
     switch (l.op) {
       case CNNK_OP_CONV: {
         const void* wt = bf16 ? B->param_lp[l.p0] : (const void*)B->param[l.p0];
@@ -191,6 +208,7 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
                                   B->probs, B->dact[l.in0], B->grad[l.p0], B->grad[l.p1], ws, wsb, stream);
         break;
     }
+    timer.end(i);
     if (rc != CNNK_OK) return rc;
   }
   // ---- backward pass ---------------------------------------------------------------------------
@@ -198,9 +216,13 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
   written[L[n - 1].in0] = 1;
   for (int i = n - 2; i >= 0; --i) {
     const cnnk_layer& l = L[i];
+    const int g0 = n + 2 * (n - 2 - i);
+    timer.begin(g0);
     switch (l.op) {
       case CNNK_OP_CONV: {
         rc = cnnk_conv2d_wgrad(&l.d.conv, B->act[l.in0], B->dact[l.out], B->grad[l.p0], ws, wsb, stream);
+        timer.end(g0);
+        timer.begin(g0 + 1);
         if (rc == CNNK_OK && l.in0 != 0) {
           const void* wt = bf16 ? B->param_lp[l.p0] : (const void*)B->param[l.p0];
           rc = cnnk_conv2d_dgrad(&l.d.conv, B->dact[l.out], wt, B->dact[l.in0], written[l.in0], ws, wsb, stream);
@@ -237,9 +259,16 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
       default:
         break;
     }
+    if (l.op != CNNK_OP_CONV) {
+      timer.end(g0);
+      timer.begin(g0 + 1);
+    }
+    timer.end(g0 + 1);
     if (rc != CNNK_OK) return rc;
   }
   // ---- parameter update -----------------------------------------------------------------------
+  const int g_upd = cnnk_train_step_event_groups(n) - 1;
+  timer.begin(g_upd);
   SgdTable t;
   t.count = 0;
   for (size_t p = 0; p < w.param_elems.size(); ++p) {
@@ -257,5 +286,6 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
     }
   }
   if (t.count > 0) rc = sgd_multi(t, lr, momentum, weight_decay, (hipStream_t)stream);
+  timer.end(g_upd);
   return rc;
 }

@@ -109,7 +109,10 @@ class StepRunner:
         b.probs = None if self.probs is None else self.probs.data_ptr()
         b.ws = self.ws.data_ptr()
         b.ws_bytes = self.ws.numel()
+        b.events = None
+        b.n_events = 0
         self.buffers = b
+        self._events = None
 
     # -- host <-> device copies (not part of the timed path) -------------------------------
     def load(self, x, labels, params, mom):
@@ -126,6 +129,31 @@ class StepRunner:
         s = torch.cuda.current_stream().cuda_stream if stream is None else stream
         cnnk.cnnk_train_step(self.c_layers, len(self.layers), self.buffers, self.labels, lr, momentum,
                              weight_decay, self.loss, self.pred, s)
+
+    def enable_timing(self, on=True):
+        """Have cnnk_train_step record a HIP event pair around each of its entry-point calls."""
+        if on and self._events is None:
+            n = 2 * cnnk.cnnk_train_step_event_groups(len(self.layers))
+            self._events = (C.c_void_p * n)(*[cnnk.hip_event_create() for _ in range(n)])
+        self.buffers.events = C.cast(self._events, C.POINTER(C.c_void_p)) if on else None
+        self.buffers.n_events = len(self._events) if on else 0
+
+    def group_times_ms(self):
+        """Elapsed time of every group of the last timed step (call after a synchronise)."""
+        ev = self._events
+        return [cnnk.hip_event_elapsed_ms(ev[2 * g], ev[2 * g + 1]) for g in range(len(ev) // 2)]
+
+    def group_table(self):
+        """(group index, layer index, phase) in the order documented in cnnk.h."""
+        n = len(self.layers)
+        rows = [(i, i, "fwd") for i in range(n)]
+        for i in range(n - 2, -1, -1):
+            g0 = n + 2 * (n - 2 - i)
+            conv = self.layers[i]["op"] == "conv"
+            rows.append((g0, i, "wgrad" if conv else "bwd"))
+            rows.append((g0 + 1, i, "dgrad" if conv else "none"))
+        rows.append((3 * n - 2, -1, "update"))
+        return rows
 
     @staticmethod
     def host(t):

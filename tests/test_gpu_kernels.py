@@ -29,7 +29,8 @@ CONV_SHAPES = [
     (2, 16, 16, 64, 128, 3, 2), (3, 7, 9, 24, 40, 3, 2), (2, 12, 12, 16, 160, 3, 1),
     (2, 16, 16, 64, 128, 1, 2), (5, 8, 8, 256, 64, 1, 1), (2, 9, 9, 40, 24, 1, 2),
     (2, 32, 32, 3, 64, 3, 1), (9, 4, 4, 512, 512, 3, 1), (2, 32, 32, 64, 64, 3, 1),
-    (130, 4, 4, 64, 8, 3, 1),
+    (130, 4, 4, 64, 8, 3, 1), (3, 9, 9, 3, 16, 3, 2), (2, 8, 8, 3, 24, 3, 1), (2, 8, 8, 2, 128, 3, 1),
+    (2, 8, 8, 3, 16, 1, 1), (3, 33, 33, 3, 64, 3, 1),
 ]
 
 
