@@ -53,6 +53,14 @@ const char* cnnk_status_string(int status);
 /* Library version, and the code-object architecture the kernels were built for ("gfx950"). */
 const char* cnnk_version(void);
 
+/* Tuning hook for benchmarking, not needed for normal use: overrides one of the library's
+ * launch heuristics (value 0 restores the built-in choice).  Keys: 0/1/2 = rows / columns /
+ * reduction depth of the implicit-GEMM tile of the forward and data-gradient kernels
+ * (unsupported combinations make the conv calls return CNNK_ERR_UNSUPPORTED); 3 = target
+ * number of workgroups of the weight-gradient kernel; 4/5 = pixel / channel tile of the 3x3
+ * stride-1 LDS-patch kernels (4 = -1 switches them off).  Process-wide, not thread-safe. */
+int cnnk_tune(int key, int value);
+
 /* ---- convolution (Algorithm 1: forward pass / backward pass of a conv layer) -------------- */
 
 /* Scratch bytes needed by the given pass (cnnk_conv_pass) of this convolution. */

@@ -17,7 +17,7 @@ POOL_MAX2, POOL_GAP = 0, 1
 PASS_FWD, PASS_DGRAD, PASS_WGRAD = 0, 1, 2
 OP_CONV, OP_BN, OP_POOL, OP_ADD, OP_FC_LOSS = 0, 1, 2, 3, 4
 
-EXPORTS = ["cnnk_status_string", "cnnk_version", "cnnk_conv2d_workspace_bytes", "cnnk_conv2d_fwd",
+EXPORTS = ["cnnk_status_string", "cnnk_version", "cnnk_tune", "cnnk_conv2d_workspace_bytes", "cnnk_conv2d_fwd",
            "cnnk_conv2d_dgrad", "cnnk_conv2d_wgrad", "cnnk_bn_workspace_bytes", "cnnk_bn_relu_fwd",
            "cnnk_bn_relu_bwd", "cnnk_pool_fwd", "cnnk_pool_bwd", "cnnk_add", "cnnk_grad_route",
            "cnnk_fc_workspace_bytes", "cnnk_fc_softmax_xent", "cnnk_sgd_momentum",
@@ -76,6 +76,7 @@ def _load():
     lib.cnnk_status_string.restype = C.c_char_p
     lib.cnnk_status_string.argtypes = [ci]
     lib.cnnk_version.restype = C.c_char_p
+    lib.cnnk_tune.argtypes = [ci, ci]
     lib.cnnk_conv2d_workspace_bytes.restype = sz
     lib.cnnk_conv2d_workspace_bytes.argtypes = [C.POINTER(ConvDesc), ci]
     lib.cnnk_conv2d_fwd.argtypes = [C.POINTER(ConvDesc), vp, vp, vp, vp, vp, vp, sz, vp]
@@ -122,6 +123,10 @@ def status_string(status):
 
 def version():
     return lib.cnnk_version().decode()
+
+
+def cnnk_tune(key, value):
+    _check(lib.cnnk_tune(int(key), int(value)), "cnnk_tune")
 
 
 def conv_desc(N, H, W, Cin, Cout, R, S, stride, pad, dtype):

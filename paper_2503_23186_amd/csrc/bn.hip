@@ -8,7 +8,7 @@
 namespace {
 
 constexpr int kT = 256;
-constexpr int kMaxBlocks = 1024;
+constexpr int kMaxBlocks = 512;
 
 struct RowMap {
   int lanes;   // threads per row = C/8
@@ -24,7 +24,7 @@ __host__ __device__ inline int reduce_blocks(size_t m, int C) {
 }
 
 // Sum the NV per-thread vectors of 8 channels over the threads that share a channel octet and
-// write them to part[blockIdx.x][v][C].
+// write them to part[v][c][blockIdx.x] (workgroup index fastest, so the finaliser reads rows).
 template <int NV>
 __device__ __forceinline__ void block_reduce_store(float (*acc)[8], int lanes, int rows, int C,
                                                    float* __restrict__ part) {
@@ -42,37 +42,36 @@ __device__ __forceinline__ void block_reduce_store(float (*acc)[8], int lanes, i
     for (int i = tid; i < C; i += kT) {
       float s = 0.f;
       for (int r = 0; r < rows; ++r) s += red[(r * lanes) * 8 + i];
-      part[((size_t)blockIdx.x * NV + v) * C + i] = s;
+      part[((size_t)v * C + i) * gridDim.x + blockIdx.x] = s;
     }
   }
 }
 
-// Finalising reduction: a workgroup owns kFinCh channels; 256/kFinCh thread groups each sum a
-// strided subset of the per-workgroup partials in double, then the groups are combined through
-// LDS in a fixed order.  Returns the two sums for channel c (valid in the threads of group 0).
-constexpr int kFinCh = 16;
-constexpr int kFinGroups = kT / kFinCh;
-
-__device__ __forceinline__ void finalize_sums(const float* __restrict__ part, int nb, int C, int c, int grp,
+// Finalising reduction: one workgroup per channel sums the nb per-workgroup partials
+// part[v][c][0..nb) in double (coalesced rows, fixed-order tree).  Result valid in thread 0.
+__device__ __forceinline__ void finalize_sums(const float* __restrict__ part, int nb, int C, int c,
                                               double* s1_out, double* s2_out) {
-  __shared__ double fred[2][kFinGroups][kFinCh];
+  __shared__ double fred[2][kT];
+  const int t = threadIdx.x;
   double s1 = 0.0, s2 = 0.0;
-  if (c < C) {
-    for (int b = grp; b < nb; b += kFinGroups) {
-      s1 += (double)part[((size_t)b * 2 + 0) * C + c];
-      s2 += (double)part[((size_t)b * 2 + 1) * C + c];
-    }
+  const float* p1 = part + ((size_t)0 * C + c) * nb;
+  const float* p2 = part + ((size_t)1 * C + c) * nb;
+  for (int b = t; b < nb; b += kT) {
+    s1 += (double)p1[b];
+    s2 += (double)p2[b];
   }
-  const int cl = threadIdx.x % kFinCh;
-  fred[0][grp][cl] = s1;
-  fred[1][grp][cl] = s2;
+  fred[0][t] = s1;
+  fred[1][t] = s2;
   __syncthreads();
-  s1 = 0.0; s2 = 0.0;
-  if (grp == 0) {
-    for (int g = 0; g < kFinGroups; ++g) { s1 += fred[0][g][cl]; s2 += fred[1][g][cl]; }
+  for (int o = kT / 2; o > 0; o >>= 1) {
+    if (t < o) {
+      fred[0][t] += fred[0][t + o];
+      fred[1][t] += fred[1][t + o];
+    }
+    __syncthreads();
   }
-  *s1_out = s1;
-  *s2_out = s2;
+  *s1_out = fred[0][0];
+  *s2_out = fred[1][0];
 }
 
 // Partial sums of (x - shift) and (x - shift)^2 with shift = x[0][c] (keeps fp32 sums benign).
@@ -109,10 +108,10 @@ __global__ void __launch_bounds__(kT) stats_finalize_kernel(const float* __restr
                                                             float eps, float momentum, float* __restrict__ o0,
                                                             float* __restrict__ o1, float* __restrict__ rmean,
                                                             float* __restrict__ rvar) {
-  const int c = blockIdx.x * kFinCh + threadIdx.x % kFinCh, grp = threadIdx.x / kFinCh;
+  const int c = blockIdx.x;
   double s1, s2;
-  finalize_sums(part, nb, C, c, grp, &s1, &s2);
-  if (c >= C || grp != 0) return;
+  finalize_sums(part, nb, C, c, &s1, &s2);
+  if (threadIdx.x != 0) return;
   const double sh = (double)Elem<T>::ld(x + c);
   const double dm = (double)m;
   if (mode == 1) {
@@ -130,6 +129,16 @@ __global__ void __launch_bounds__(kT) stats_finalize_kernel(const float* __restr
     rmean[c] = (float)((1.0 - momentum) * rmean[c] + momentum * (sh + mean_s));
     rvar[c] = (float)((1.0 - momentum) * rvar[c] + momentum * unb);
   }
+}
+
+__global__ void __launch_bounds__(kT) sums_finalize_kernel(const float* __restrict__ part, int nb, int C,
+                                                           float* __restrict__ ch_sum, float* __restrict__ ch_sumsq) {
+  const int c = blockIdx.x;
+  double s1, s2;
+  finalize_sums(part, nb, C, c, &s1, &s2);
+  if (threadIdx.x != 0) return;
+  ch_sum[c] = (float)s1;
+  ch_sumsq[c] = (float)s2;
 }
 
 __global__ void __launch_bounds__(kT) stats_from_sums_kernel(const float* __restrict__ ch_sum,
@@ -222,10 +231,10 @@ __global__ void __launch_bounds__(kT) bwd_partial_kernel(const T* __restrict__ d
 
 __global__ void __launch_bounds__(kT) bwd_finalize_kernel(const float* __restrict__ part, int nb, int C,
                                                           float* __restrict__ dgamma, float* __restrict__ dbeta) {
-  const int c = blockIdx.x * kFinCh + threadIdx.x % kFinCh, grp = threadIdx.x / kFinCh;
+  const int c = blockIdx.x;
   double s1, s2;
-  finalize_sums(part, nb, C, c, grp, &s1, &s2);
-  if (c >= C || grp != 0) return;
+  finalize_sums(part, nb, C, c, &s1, &s2);
+  if (threadIdx.x != 0) return;
   dbeta[c] = (float)s1;
   dgamma[c] = (float)s2;
 }
@@ -295,6 +304,11 @@ int validate_bn(const cnnk_bn_desc* d) {
 
 }  // namespace
 
+int channel_sums_finalize(const float* part, int nb, int C, float* ch_sum, float* ch_sumsq, hipStream_t st) {
+  sums_finalize_kernel<<<C, kT, 0, st>>>(part, nb, C, ch_sum, ch_sumsq);
+  return launch_status();
+}
+
 size_t channel_stats_ws(size_t m, int C) { return (size_t)reduce_blocks(m, C) * 2 * C * sizeof(float); }
 
 int channel_stats(int dtype, const void* x, size_t m, int C, float* ch_sum, float* ch_sumsq, void* ws,
@@ -303,11 +317,11 @@ int channel_stats(int dtype, const void* x, size_t m, int C, float* ch_sum, floa
   float* part = (float*)ws;
   if (dtype == CNNK_BF16) {
     stats_partial_kernel<bf16_t><<<nb, kT, 0, st>>>((const bf16_t*)x, m, C, part);
-    stats_finalize_kernel<bf16_t><<<(C + kFinCh - 1) / kFinCh, kT, 0, st>>>(part, nb, (const bf16_t*)x, m, C, 1, 0.f, 0.f,
+    stats_finalize_kernel<bf16_t><<<C, kT, 0, st>>>(part, nb, (const bf16_t*)x, m, C, 1, 0.f, 0.f,
                                                                     ch_sum, ch_sumsq, nullptr, nullptr);
   } else {
     stats_partial_kernel<float><<<nb, kT, 0, st>>>((const float*)x, m, C, part);
-    stats_finalize_kernel<float><<<(C + kFinCh - 1) / kFinCh, kT, 0, st>>>(part, nb, (const float*)x, m, C, 1, 0.f, 0.f,
+    stats_finalize_kernel<float><<<C, kT, 0, st>>>(part, nb, (const float*)x, m, C, 1, 0.f, 0.f,
                                                                    ch_sum, ch_sumsq, nullptr, nullptr);
   }
   return launch_status();
@@ -336,12 +350,12 @@ extern "C" int cnnk_bn_relu_fwd(const cnnk_bn_desc* d, const void* x, const void
     float* part = (float*)ws;
     if (d->dtype == CNNK_BF16) {
       stats_partial_kernel<bf16_t><<<nb, kT, 0, st>>>((const bf16_t*)x, m, C, part);
-      stats_finalize_kernel<bf16_t><<<(C + kFinCh - 1) / kFinCh, kT, 0, st>>>(part, nb, (const bf16_t*)x, m, C, 0, d->eps,
+      stats_finalize_kernel<bf16_t><<<C, kT, 0, st>>>(part, nb, (const bf16_t*)x, m, C, 0, d->eps,
                                                                       d->momentum, save_mean, save_invstd,
                                                                       running_mean, running_var);
     } else {
       stats_partial_kernel<float><<<nb, kT, 0, st>>>((const float*)x, m, C, part);
-      stats_finalize_kernel<float><<<(C + kFinCh - 1) / kFinCh, kT, 0, st>>>(part, nb, (const float*)x, m, C, 0, d->eps,
+      stats_finalize_kernel<float><<<C, kT, 0, st>>>(part, nb, (const float*)x, m, C, 0, d->eps,
                                                                      d->momentum, save_mean, save_invstd,
                                                                      running_mean, running_var);
     }
@@ -379,7 +393,7 @@ extern "C" int cnnk_bn_relu_bwd(const cnnk_bn_desc* d, const void* dy, const voi
   if (d->dtype == CNNK_BF16) {
     bwd_partial_kernel<bf16_t><<<nb, kT, 0, st>>>((const bf16_t*)dy, (const bf16_t*)x, (const bf16_t*)y, save_mean,
                                                   save_invstd, m, C, d->relu, part);
-    bwd_finalize_kernel<<<(C + kFinCh - 1) / kFinCh, kT, 0, st>>>(part, nb, C, dgamma, dbeta);
+    bwd_finalize_kernel<<<C, kT, 0, st>>>(part, nb, C, dgamma, dbeta);
     bwd_apply_kernel<bf16_t><<<ew_blocks(n8), kT, 0, st>>>((const bf16_t*)dy, (const bf16_t*)x, (const bf16_t*)y,
                                                            gamma, save_mean, save_invstd, dgamma, dbeta,
                                                            (bf16_t*)dx, (bf16_t*)dresidual, n8, C, inv_m, d->relu,
@@ -387,7 +401,7 @@ extern "C" int cnnk_bn_relu_bwd(const cnnk_bn_desc* d, const void* dy, const voi
   } else {
     bwd_partial_kernel<float><<<nb, kT, 0, st>>>((const float*)dy, (const float*)x, (const float*)y, save_mean,
                                                  save_invstd, m, C, d->relu, part);
-    bwd_finalize_kernel<<<(C + kFinCh - 1) / kFinCh, kT, 0, st>>>(part, nb, C, dgamma, dbeta);
+    bwd_finalize_kernel<<<C, kT, 0, st>>>(part, nb, C, dgamma, dbeta);
     bwd_apply_kernel<float><<<ew_blocks(n8), kT, 0, st>>>((const float*)dy, (const float*)x, (const float*)y, gamma,
                                                           save_mean, save_invstd, dgamma, dbeta, (float*)dx,
                                                           (float*)dresidual, n8, C, inv_m, d->relu, flags);

@@ -34,11 +34,23 @@ int conv_mfma_dgrad(const ConvGeom& g, const bf16_t* dy, const bf16_t* w, bf16_t
 int conv_mfma_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws,
                     hipStream_t st);
 
+// 3x3 stride-1 kernels with the input patch resident in LDS (forward, data gradient)
+bool conv_patch_supported(const ConvGeom& g, int pass);
+int conv_patch_mtiles(const ConvGeom& g);
+int conv_patch_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y, float* stats, hipStream_t st);
+int conv_patch_dgrad(const ConvGeom& g, const bf16_t* dy, const bf16_t* wt, bf16_t* dx, int accumulate,
+                     hipStream_t st);
+
 // thin-input (stem) kernels, bf16 storage
 bool conv_stem_supported(const ConvGeom& g);
 size_t conv_stem_wgrad_ws(const ConvGeom& g);
 int conv_stem_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y, hipStream_t st);
 int conv_stem_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws, hipStream_t st);
+
+// ch_sum[c] = sum_b part[b][0][c], ch_sumsq[c] = sum_b part[b][1][c]  (double accumulation)
+int channel_sums_finalize(const float* part, int nb, int C, float* ch_sum, float* ch_sumsq, hipStream_t st);
+
+extern int g_cnnk_tune[16];
 
 // per-channel sum / sum of squares of a tensor with C channels (used when the conv kernel
 // itself does not produce them)

@@ -33,7 +33,7 @@ extern "C" size_t cnnk_conv2d_workspace_bytes(const cnnk_conv_desc* d, int pass)
   if (pass == CNNK_PASS_FWD) {
     // room for the per-channel statistics pass over y when the caller asks for ch_sum/ch_sumsq
     b = (g.Cout % 8 == 0 && g.Cout <= 2048) ? channel_stats_ws((size_t)g.N * g.Ho * g.Wo, g.Cout) : 0;
-    if (use_mfma(d, g, pass)) b += conv_mfma_ws(g, pass, true);
+    if (use_mfma(d, g, pass)) { const size_t m = conv_mfma_ws(g, pass, true); if (m > b) b = m; }
   } else if (pass == CNNK_PASS_DGRAD) {
     b = use_mfma(d, g, pass) ? conv_mfma_ws(g, pass, false) : 0;
   } else if (pass == CNNK_PASS_WGRAD) {
@@ -56,8 +56,8 @@ extern "C" int cnnk_conv2d_fwd(const cnnk_conv_desc* d, const void* x, const voi
   }
   hipStream_t st = (hipStream_t)stream;
   if (use_mfma(d, g, CNNK_PASS_FWD))
-    rc = conv_mfma_fwd(g, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, nullptr, nullptr, ws, st);
-  else if (use_stem(d, g, CNNK_PASS_FWD))
+    return conv_mfma_fwd(g, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, ch_sum, ch_sumsq, ws, st);
+  if (use_stem(d, g, CNNK_PASS_FWD))
     rc = conv_stem_fwd(g, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, st);
   else
     rc = conv_direct_fwd(g, d->dtype, x, w, y, st);
@@ -105,6 +105,12 @@ extern "C" const char* cnnk_status_string(int s) {
     case CNNK_ERR_HIP: return "HIP runtime error at launch";
     default: return "unknown status";
   }
+}
+
+extern "C" int cnnk_tune(int key, int value) {
+  if (key < 0 || key >= 16) return CNNK_ERR_SHAPE;
+  g_cnnk_tune[key] = value;
+  return CNNK_OK;
 }
 
 extern "C" const char* cnnk_version(void) { return "cnnk 0.1 (gfx950)"; }

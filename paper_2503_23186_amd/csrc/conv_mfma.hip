@@ -10,8 +10,11 @@
 //  * wgrad_kernel: weight gradient.  GEMM rows are output channels, columns are (tap, input
 //    channel), the reduction runs over output pixels, split across workgroups; both operands
 //    arrive channel-contiguous and are transposed in registers on their way into LDS.
+#include <type_traits>
 #include "common.h"
 #include "conv.h"
+
+int g_cnnk_tune[16] = {0};
 
 namespace {
 
@@ -35,11 +38,14 @@ struct IgemmArgs {
   int ss, os;            // source step per sub-grid index; destination step per sub-grid index
   int accumulate;
   int ntiles;
+  float* stats;          // nullable: [2][Cd][mtiles] per-tile column sums and sums of squares
+  int mtiles;
   TapTable tt;
 };
 
-template <int BM, int BN, int BK, int WM, int WN>
-__global__ void __launch_bounds__(kThreads) igemm_kernel(IgemmArgs a) {
+// OCC: waves per SIMD the register allocation must leave room for (workgroups per CU).
+template <int BM, int BN, int BK, int WM, int WN, int OCC>
+__global__ void __launch_bounds__(kThreads, OCC) igemm_kernel(IgemmArgs a) {
   constexpr int LDK = BK + 8;  // padded row (elements): conflict-free 16-byte fragment reads
   constexpr int KC = BK / 8;
   constexpr int RPP = kThreads / KC;  // tile rows filled per pass of the workgroup
@@ -89,9 +95,15 @@ __global__ void __launch_bounds__(kThreads) igemm_kernel(IgemmArgs a) {
 
   const int cchunks = (a.Cs + BK - 1) / BK;
   const int nstage = ntap * cchunks;
-  uint4 ra[A_IT], rb[B_IT];
+  // Two stages of global loads are kept in flight in registers (sets 0 and 1) while a third one
+  // is consumed from LDS: a load issued at the top of iteration s is written to LDS at the end
+  // of iteration s+1.
+  uint4 ra[2][A_IT], rb[2][B_IT];
+  using S0 = std::integral_constant<int, 0>;
+  using S1 = std::integral_constant<int, 1>;
 
-  auto load_stage = [&](int s) {
+  auto load_stage = [&](int s, auto SET) {
+    constexpr int rs = decltype(SET)::value;
     const int t = tap0 + s / cchunks;
     const int c = (s % cchunks) * BK + kc * 8;
     const int dh = a.tt.dh[t], dw = a.tt.dw[t], wi = a.tt.widx[t];
@@ -100,33 +112,27 @@ __global__ void __launch_bounds__(kThreads) igemm_kernel(IgemmArgs a) {
     for (int it = 0; it < A_IT; ++it) {
       const int hs = a_h[it] + dh, ws = a_w[it] + dw;
       const bool ok = cok && (unsigned)hs < (unsigned)a.Hs && (unsigned)ws < (unsigned)a.Ws;
-      ra[it] = make_uint4(0, 0, 0, 0);
-      if (ok) ra[it] = *reinterpret_cast<const uint4*>(a.src + ((size_t)(a_n[it] + hs * a.Ws + ws)) * a.Cs + c);
+      ra[rs][it] = make_uint4(0, 0, 0, 0);
+      if (ok) ra[rs][it] = *reinterpret_cast<const uint4*>(a.src + ((size_t)(a_n[it] + hs * a.Ws + ws)) * a.Cs + c);
     }
 #pragma unroll
     for (int it = 0; it < B_IT; ++it) {
       const int ch = nt * BN + r0 + it * RPP;
-      rb[it] = make_uint4(0, 0, 0, 0);
-      if (cok && ch < a.Cd && r0 + it * RPP < BN) rb[it] = *reinterpret_cast<const uint4*>(a.wt + ((size_t)ch * a.T + wi) * a.Cs + c);
+      rb[rs][it] = make_uint4(0, 0, 0, 0);
+      if (cok && ch < a.Cd && r0 + it * RPP < BN)
+        rb[rs][it] = *reinterpret_cast<const uint4*>(a.wt + ((size_t)ch * a.T + wi) * a.Cs + c);
     }
   };
-  auto store_stage = [&](int buf) {
+  auto store_stage = [&](int buf, auto SET) {
+    constexpr int rs = decltype(SET)::value;
 #pragma unroll
     for (int it = 0; it < A_IT; ++it)
-      if (r0 + it * RPP < BM) *reinterpret_cast<uint4*>(As + (buf * BM + r0 + it * RPP) * LDK + kc * 8) = ra[it];
+      if (r0 + it * RPP < BM) *reinterpret_cast<uint4*>(As + (buf * BM + r0 + it * RPP) * LDK + kc * 8) = ra[rs][it];
 #pragma unroll
     for (int it = 0; it < B_IT; ++it)
-      if (r0 + it * RPP < BN) *reinterpret_cast<uint4*>(Bs + (buf * BN + r0 + it * RPP) * LDK + kc * 8) = rb[it];
+      if (r0 + it * RPP < BN) *reinterpret_cast<uint4*>(Bs + (buf * BN + r0 + it * RPP) * LDK + kc * 8) = rb[rs][it];
   };
-
-  if (nstage > 0) {
-    load_stage(0);
-    store_stage(0);
-  }
-  __syncthreads();
-  for (int s = 0; s < nstage; ++s) {
-    const int cur = s & 1;
-    if (s + 1 < nstage) load_stage(s + 1);
+  auto compute = [&](int cur) {
     const bf16_t* Ab = As + (cur * BM + wm * TM * 32 + (lane & 31)) * LDK + (lane >> 5) * 8;
     const bf16_t* Bb = Bs + (cur * BN + wn * TN * 32 + (lane & 31)) * LDK + (lane >> 5) * 8;
 #pragma unroll
@@ -142,7 +148,61 @@ __global__ void __launch_bounds__(kThreads) igemm_kernel(IgemmArgs a) {
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
-    if (s + 1 < nstage) store_stage(cur ^ 1);
+  };
+
+  if (nstage > 0) load_stage(0, S0{});
+  if (nstage > 1) load_stage(1, S1{});
+  if (nstage > 0) store_stage(0, S0{});
+  __syncthreads();
+  for (int s = 0; s < nstage; s += 2) {
+    if (s + 2 < nstage) load_stage(s + 2, S0{});
+    compute(0);
+    if (s + 1 < nstage) store_stage(1, S1{});
+    __syncthreads();
+    if (s + 1 >= nstage) break;
+    if (s + 3 < nstage) load_stage(s + 3, S1{});
+    compute(1);
+    if (s + 2 < nstage) store_stage(0, S0{});
+    __syncthreads();
+  }
+
+  // Optional per-channel sum / sum of squares of the fp32 accumulators over this tile's rows
+  // (rows beyond M hold zeros): one partial row per M-tile, reduced by a finalising kernel.
+  if (a.stats) {
+    float* sred = reinterpret_cast<float*>(smem_raw);  // [2][WM][BN]
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float v = acc[i][j][r];
+          s1 += v;
+          s2 = fmaf(v, v, s2);
+        }
+      s1 += __shfl_xor(s1, 32, 64);
+      s2 += __shfl_xor(s2, 32, 64);
+      if (lane < 32) {
+        const int col = wn * TN * 32 + j * 32 + lane;
+        sred[(0 * WM + wm) * BN + col] = s1;
+        sred[(1 * WM + wm) * BN + col] = s2;
+      }
+    }
+    __syncthreads();
+    for (int c = tid; c < BN; c += kThreads) {
+      float t1 = 0.f, t2 = 0.f;
+#pragma unroll
+      for (int w_ = 0; w_ < WM; ++w_) {
+        t1 += sred[(0 * WM + w_) * BN + c];
+        t2 += sred[(1 * WM + w_) * BN + c];
+      }
+      const int col = nt * BN + c;
+      if (col < a.Cd) {
+        a.stats[((size_t)0 * a.Cd + col) * a.mtiles + mt] = t1;
+        a.stats[((size_t)1 * a.Cd + col) * a.mtiles + mt] = t2;
+      }
+    }
     __syncthreads();
   }
 
@@ -343,24 +403,31 @@ struct IgemmPlan {
   int bm, bn, bk;
 };
 
+// Tile choice.  g_cnnk_tune[0..2] (set through cnnk_tune) force BM / BN / BK for experiments.
 IgemmPlan plan_igemm(long maxM, int Cd, int Cs) {
   IgemmPlan p;
-  p.bk = (Cs % 32 == 0) ? 32 : 16;
+  // Measured on MI355X (ResNet-18 b256 shapes): the kernels are bound by L2->CU traffic, so the
+  // largest tile that still gives every CU two workgroups wins; small-M layers prefer 64x64.
   const long b128 = ((maxM + 127) / 128) * ((Cd + 127) / 128);
-  if (Cd > 64 && b128 >= 256) { p.bm = 128; p.bn = 128; }
-  else if (Cd <= 64 && (maxM + 255) / 256 >= 512) { p.bm = 256; p.bn = 64; }
-  else if (((maxM + 127) / 128) * ((Cd + 63) / 64) >= 256) { p.bm = 128; p.bn = 64; }
+  if (Cd <= 64) { p.bm = 128; p.bn = 64; }
+  else if (b128 >= 512) { p.bm = 128; p.bn = 128; }
   else { p.bm = 64; p.bn = 64; }
+  if (g_cnnk_tune[0] > 0) p.bm = g_cnnk_tune[0];
+  if (g_cnnk_tune[1] > 0) p.bn = g_cnnk_tune[1];
+  p.bk = (Cs % 64 == 0) ? 64 : (Cs % 32 == 0) ? 32 : 16;
+  if (p.bk == 64 && (p.bm + p.bn) > 256) p.bk = 32;   // keep two workgroups per CU in LDS
+  if (g_cnnk_tune[2] > 0 && g_cnnk_tune[2] <= p.bk) p.bk = g_cnnk_tune[2];
   return p;
 }
 
-template <int BM, int BN, int BK, int WM, int WN>
+template <int BM, int BN, int BK, int WM, int WN, int OCC>
 int launch_igemm(const IgemmArgs& a, long maxM, hipStream_t st) {
   constexpr size_t stage_bytes = (size_t)2 * (BM + BN) * (BK + 8) * sizeof(bf16_t);
   constexpr size_t epi_bytes = (size_t)BM * (BN + 8) * sizeof(bf16_t);
   constexpr size_t smem = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
+  static_assert(smem <= 160 * 1024, "LDS budget");
   static bool attr_done = false;
-  auto kern = igemm_kernel<BM, BN, BK, WM, WN>;
+  auto kern = igemm_kernel<BM, BN, BK, WM, WN, OCC>;
   if (!attr_done) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)smem) != hipSuccess)
@@ -370,22 +437,24 @@ int launch_igemm(const IgemmArgs& a, long maxM, hipStream_t st) {
   IgemmArgs b = a;
   b.ntiles = (a.Cd + BN - 1) / BN;
   const long mtiles = (maxM + BM - 1) / BM;
+  b.mtiles = (int)mtiles;
   dim3 grid((unsigned)(mtiles * b.ntiles), a.tt.nclass);
   hipLaunchKernelGGL(kern, grid, dim3(kThreads), smem, st, b);
   return launch_status();
 }
 
-int dispatch_igemm(const IgemmArgs& a, long maxM, hipStream_t st) {
-  const IgemmPlan p = plan_igemm(maxM, a.Cd, a.Cs);
-#define CNNK_IGEMM_CASE(BM, BN, WM, WN)                                              \
+int dispatch_igemm(const IgemmArgs& a, long maxM, const IgemmPlan& p, hipStream_t st) {
+#define CNNK_IGEMM_CASE(BM, BN, WM, WN, OCC)                                         \
   if (p.bm == BM && p.bn == BN) {                                                    \
-    if (p.bk == 32) return launch_igemm<BM, BN, 32, WM, WN>(a, maxM, st);            \
-    return launch_igemm<BM, BN, 16, WM, WN>(a, maxM, st);                            \
+    if (p.bk == 64 && BM + BN <= 256) return launch_igemm<BM, BN, (BM + BN <= 256 ? 64 : 32), WM, WN, OCC>(a, maxM, st); \
+    if (p.bk >= 32) return launch_igemm<BM, BN, 32, WM, WN, OCC>(a, maxM, st);       \
+    return launch_igemm<BM, BN, 16, WM, WN, OCC>(a, maxM, st);                       \
   }
-  CNNK_IGEMM_CASE(128, 128, 2, 2)
-  CNNK_IGEMM_CASE(256, 64, 4, 1)
-  CNNK_IGEMM_CASE(128, 64, 4, 1)
-  CNNK_IGEMM_CASE(64, 64, 2, 2)
+  CNNK_IGEMM_CASE(256, 128, 2, 2, 2)
+  CNNK_IGEMM_CASE(128, 128, 2, 2, 2)
+  CNNK_IGEMM_CASE(256, 64, 4, 1, 2)
+  CNNK_IGEMM_CASE(128, 64, 4, 1, 3)
+  CNNK_IGEMM_CASE(64, 64, 2, 2, 4)
 #undef CNNK_IGEMM_CASE
   return CNNK_ERR_UNSUPPORTED;
 }
@@ -395,7 +464,8 @@ void wgrad_plan(const ConvGeom& g, int* bmk, int* chunk, int* splits) {
   const long M = (long)g.N * g.Ho * g.Wo;
   *bmk = g.Cout > 64 ? 128 : 64;
   const long tiles = (long)((g.Cout + *bmk - 1) / *bmk) * ((Q + 127) / 128);
-  long want = (768 + tiles - 1) / tiles;
+  const long target = g_cnnk_tune[3] > 0 ? g_cnnk_tune[3] : (g.Cout <= 64 ? 768 : 384);
+  long want = (target + tiles - 1) / tiles;
   const long maxs = (M + 255) / 256;
   if (want > maxs) want = maxs;
   if (want < 1) want = 1;
@@ -419,7 +489,8 @@ bool conv_mfma_supported(const ConvGeom& g, int pass) {
 }
 
 size_t conv_mfma_ws(const ConvGeom& g, int pass, bool want_stats) {
-  (void)want_stats;
+  if (pass == CNNK_PASS_FWD)   // per-M-tile statistics partials, sized for the smallest tile (64 rows)
+    return want_stats ? align_up(((size_t)g.N * g.Ho * g.Wo + 63) / 64 * 2 * g.Cout * sizeof(float), 256) : 0;
   if (pass == CNNK_PASS_DGRAD) return align_up((size_t)g.Cout * g.R * g.S * g.Cin * sizeof(bf16_t), 256);
   if (pass == CNNK_PASS_WGRAD) {
     int bmk, chunk, splits;
@@ -431,9 +502,15 @@ size_t conv_mfma_ws(const ConvGeom& g, int pass, bool want_stats) {
 
 int conv_mfma_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y, float* ch_sum,
                   float* ch_sumsq, void* ws, hipStream_t st) {
-  (void)ch_sum; (void)ch_sumsq; (void)ws;
+  if (conv_patch_supported(g, CNNK_PASS_FWD)) {
+    float* stats = ch_sum ? reinterpret_cast<float*>(ws) : nullptr;
+    int rc = conv_patch_fwd(g, x, w, y, stats, st);
+    if (rc != CNNK_OK || !ch_sum) return rc;
+    return channel_sums_finalize(stats, conv_patch_mtiles(g), g.Cout, ch_sum, ch_sumsq, st);
+  }
   IgemmArgs a{};
   a.src = x; a.wt = w; a.dst = y;
+  a.stats = ch_sum ? reinterpret_cast<float*>(ws) : nullptr;
   a.Nimg = g.N; a.Hs = g.H; a.Ws = g.W; a.Cs = g.Cin;
   a.Hd = g.Ho; a.Wd = g.Wo; a.Cd = g.Cout;
   a.T = g.R * g.S; a.ss = g.stride; a.os = 1; a.accumulate = 0;
@@ -445,7 +522,11 @@ int conv_mfma_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y
       a.tt.dh[t] = r - g.pad; a.tt.dw[t] = s - g.pad; a.tt.widx[t] = t;
     }
   a.tt.Hm[0] = g.Ho; a.tt.Wm[0] = g.Wo; a.tt.oh[0] = 0; a.tt.ow[0] = 0;
-  return dispatch_igemm(a, (long)g.N * g.Ho * g.Wo, st);
+  const long M = (long)g.N * g.Ho * g.Wo;
+  const IgemmPlan p = plan_igemm(M, a.Cd, a.Cs);
+  int rc = dispatch_igemm(a, M, p, st);
+  if (rc != CNNK_OK || !ch_sum) return rc;
+  return channel_sums_finalize(a.stats, (int)((M + p.bm - 1) / p.bm), g.Cout, ch_sum, ch_sumsq, st);
 }
 
 int conv_mfma_dgrad(const ConvGeom& g, const bf16_t* dy, const bf16_t* w, bf16_t* dx, int accumulate,
@@ -455,6 +536,7 @@ int conv_mfma_dgrad(const ConvGeom& g, const bf16_t* dy, const bf16_t* w, bf16_t
   const int nw = g.Cout * T * g.Cin;
   transpose_weights_kernel<<<(nw + 255) / 256, 256, 0, st>>>(w, wt, g.Cout, T, g.Cin);
   if (launch_status() != CNNK_OK) return CNNK_ERR_HIP;
+  if (conv_patch_supported(g, CNNK_PASS_DGRAD)) return conv_patch_dgrad(g, dy, wt, dx, accumulate, st);
   IgemmArgs a{};
   a.src = dy; a.wt = wt; a.dst = dx;
   a.Nimg = g.N; a.Hs = g.Ho; a.Ws = g.Wo; a.Cs = g.Cout;
@@ -486,7 +568,7 @@ int conv_mfma_dgrad(const ConvGeom& g, const bf16_t* dy, const bf16_t* w, bf16_t
     }
   a.tt.cls_begin[ncls] = ntap;
   a.tt.nclass = ncls;
-  return dispatch_igemm(a, maxM, st);
+  return dispatch_igemm(a, maxM, plan_igemm(maxM, a.Cd, a.Cs), st);
 }
 
 int conv_mfma_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws,

@@ -1,0 +1,384 @@
+// 3x3 stride-1 convolution (forward and data gradient) with the input patch resident in LDS.
+//
+// The plain implicit-GEMM kernel re-fetches the pixel tile for every filter tap, which makes it
+// L2->CU traffic bound on MI355X.  Here a workgroup owns an output tile of TI images x TH rows
+// x W columns, loads the matching input patch (+1 pixel halo, zero padded) for a 32-channel
+// chunk ONCE into LDS in its natural [pixel][channel] layout, and serves all nine taps from it:
+// a tap is just a pixel offset into the patch.  Only the weights stream (one [BN][32] slice per
+// tap, two slices in flight in registers + a two-deep LDS ring).  bf16 MFMA 32x32x16, fp32
+// accumulation, same LDS-transposed epilogue / optional channel statistics / accumulate as the
+// implicit-GEMM kernel.
+#include <type_traits>
+#include "common.h"
+#include "conv.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int CK = 32;          // channels per chunk
+constexpr int PITCH = CK + 8;   // padded LDS row (elements): conflict-free 16-byte fragment reads
+constexpr int kPxPerLoad = kThreads / (CK / 8);  // patch pixels staged per 16-byte load of the workgroup
+
+struct PatchArgs {
+  const bf16_t* src;
+  const bf16_t* wt;   // [Cd][9][Cs]
+  bf16_t* dst;
+  float* stats;       // nullable: [2][Cd][mtiles]
+  int N, H, W, Cs, Cd;
+  int TI, TH;         // tile = TI images x TH rows x W columns (BM pixels)
+  int accumulate, ntiles, mtiles;
+  int toff_h[9], toff_w[9], widx[9];  // patch offset (0..2, 0..2) and weight tap of each step
+};
+
+// PL: 16-byte patch loads per thread, i.e. the patch holds at most PL * 64 pixels.
+template <int BM, int BN, int WM, int WN, int OCC, int PL>
+__global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  constexpr int B_IT = (BN + 63) / 64;  // 64 weight rows per pass (4 chunks of 8 channels per row)
+  constexpr int LDC = BN + 8;
+  static_assert(WM * WN == 4 && TM >= 1 && TN >= 1, "tile shape");
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  const int PW = a.W + 2, PH = a.TH + 2;
+  const int patch_px = a.TI * PH * PW;
+  bf16_t* Pt = reinterpret_cast<bf16_t*>(smem_raw);  // [patch_px][PITCH]
+  bf16_t* Bs = Pt + (size_t)patch_px * PITCH;        // [3][BN][PITCH]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave % WM, wn = wave / WM;
+  int b = blockIdx.x;
+  const int nb = gridDim.x;
+  if ((nb & 7) == 0) b = (b & 7) * (nb >> 3) + (b >> 3);  // consecutive tiles share an XCD
+  const int nt = b % a.ntiles, mt = b / a.ntiles;
+  const int M = a.N * a.H * a.W;
+  const int m0 = mt * BM;
+  const int n0 = m0 / (a.H * a.W), h0 = (m0 / a.W) % a.H;
+
+  const __amdgpu_buffer_rsrc_t src_rs = make_rsrc(a.src, (unsigned)M * a.Cs * 2u);
+  const __amdgpu_buffer_rsrc_t wt_rs = make_rsrc(a.wt, (unsigned)a.Cd * 9u * a.Cs * 2u);
+
+  // byte offset of every patch chunk this thread stages (kOobOffset: zero fill), fixed for the
+  // whole kernel; the channel chunk is added as the scalar offset of the load
+  const int kc = tid & 3;
+  unsigned poff[PL];
+#pragma unroll
+  for (int j = 0; j < PL; ++j) {
+    const int pp = (tid >> 2) + j * (kThreads / 4);
+    poff[j] = kOobOffset;
+    if (pp < patch_px) {
+      const int pw = pp % PW, q = pp / PW;
+      const int ph = q % PH, ti = q / PH;
+      const int n = n0 + ti, hs = h0 + ph - 1, ws = pw - 1;
+      if (n < a.N && (unsigned)hs < (unsigned)a.H && (unsigned)ws < (unsigned)a.W)
+        poff[j] = (unsigned)(((n * a.H + hs) * a.W + ws) * a.Cs + kc * 8) * 2u;
+    }
+  }
+  const int r0 = tid >> 2;  // weight row of this thread inside a 64-row pass
+  unsigned boff[B_IT];
+#pragma unroll
+  for (int it = 0; it < B_IT; ++it) {
+    const int row = r0 + it * 64, ch = nt * BN + row;
+    boff[it] = (row < BN && ch < a.Cd) ? (unsigned)(ch * 9 * a.Cs + kc * 8) * 2u : kOobOffset;
+  }
+  // LDS byte offset (tap (0,0)) of the patch pixel under each of this lane's output rows
+  int abase[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int p = wm * TM * 32 + i * 32 + (lane & 31);
+    const int tw = p % a.W, q = p / a.W;
+    const int th = q % a.TH, ti = q / a.TH;
+    abase[i] = (((ti * PH + th) * PW + tw) * PITCH + (lane >> 5) * 8) * 2;
+  }
+  const int bbase = ((wn * TN * 32 + (lane & 31)) * PITCH + (lane >> 5) * 8) * 2;
+  const unsigned char* Pb = reinterpret_cast<const unsigned char*>(Pt);
+  const unsigned char* Bb = reinterpret_cast<const unsigned char*>(Bs);
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nchunks = a.Cs / CK;
+  uint4 preg[PL];
+  uint4 rb[3][B_IT];  // weights of three steps in flight; all indices below are compile-time
+
+  auto load_patch = [&](int chunk) {
+#pragma unroll
+    for (int j = 0; j < PL; ++j) preg[j] = buffer_load16(src_rs, poff[j], (unsigned)chunk * (CK * 2));
+  };
+  auto store_patch = [&]() {
+#pragma unroll
+    for (int j = 0; j < PL; ++j) {
+      const int pp = (tid >> 2) + j * (kThreads / 4);
+      if (pp < patch_px) *reinterpret_cast<uint4*>(Pt + pp * PITCH + kc * 8) = preg[j];
+    }
+  };
+  // step (chunk, TAP) takes its weights from LDS ring slot TAP % 3 and register set TAP % 3
+  auto load_b = [&](int chunk, auto TAP) {
+    constexpr int tap = decltype(TAP)::value, rs = tap % 3;
+    const unsigned so = (unsigned)(a.widx[tap] * a.Cs + chunk * CK) * 2u;
+#pragma unroll
+    for (int it = 0; it < B_IT; ++it) rb[rs][it] = buffer_load16(wt_rs, boff[it], so);
+  };
+  auto store_b = [&](auto TAP) {
+    constexpr int rs = decltype(TAP)::value % 3;
+#pragma unroll
+    for (int it = 0; it < B_IT; ++it) {
+      const int row = r0 + it * 64;
+      if (row < BN) *reinterpret_cast<uint4*>(Bs + (rs * BN + row) * PITCH + kc * 8) = rb[rs][it];
+    }
+  };
+  auto compute = [&](auto TAP) {
+    constexpr int tap = decltype(TAP)::value, cur = tap % 3;
+    const int off = (a.toff_h[tap] * PW + a.toff_w[tap]) * (PITCH * 2);
+#pragma unroll
+    for (int kk = 0; kk < CK / 16; ++kk) {
+      bf16x8_t af[TM], bfr[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const bf16x8_t*>(Pb + abase[i] + off + kk * 32);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        bfr[j] = *reinterpret_cast<const bf16x8_t*>(Bb + bbase + (cur * BN + j * 32) * (PITCH * 2) + kk * 32);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+  };
+  auto step = [&](int chunk, auto TAP) {
+    constexpr int tap = decltype(TAP)::value;
+    const bool more = chunk + 1 < nchunks;
+    // weights three steps ahead go into the register set this step's weights just left
+    if constexpr (tap + 3 < 9) {
+      load_b(chunk, std::integral_constant<int, tap + 3>{});
+    } else {
+      if (more) load_b(chunk + 1, std::integral_constant<int, tap + 3 - 9>{});
+    }
+    if constexpr (tap == 0) {
+      if (more) load_patch(chunk + 1);
+    }
+    compute(TAP);
+    if constexpr (tap + 1 < 9) {
+      store_b(std::integral_constant<int, tap + 1>{});
+    } else {
+      if (more) {
+        store_b(std::integral_constant<int, 0>{});
+        __syncthreads();  // every wave is done with the current patch
+        store_patch();
+      }
+    }
+    __syncthreads();
+  };
+
+  load_patch(0);
+  load_b(0, std::integral_constant<int, 0>{});
+  load_b(0, std::integral_constant<int, 1>{});
+  load_b(0, std::integral_constant<int, 2>{});
+  store_patch();
+  store_b(std::integral_constant<int, 0>{});
+  __syncthreads();
+  for (int chunk = 0; chunk < nchunks; ++chunk) {
+    step(chunk, std::integral_constant<int, 0>{});
+    step(chunk, std::integral_constant<int, 1>{});
+    step(chunk, std::integral_constant<int, 2>{});
+    step(chunk, std::integral_constant<int, 3>{});
+    step(chunk, std::integral_constant<int, 4>{});
+    step(chunk, std::integral_constant<int, 5>{});
+    step(chunk, std::integral_constant<int, 6>{});
+    step(chunk, std::integral_constant<int, 7>{});
+    step(chunk, std::integral_constant<int, 8>{});
+  }
+
+  if (a.stats) {
+    float* sred = reinterpret_cast<float*>(smem_raw);  // [2][WM][BN]
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float v = acc[i][j][r];
+          s1 += v;
+          s2 = fmaf(v, v, s2);
+        }
+      s1 += __shfl_xor(s1, 32, 64);
+      s2 += __shfl_xor(s2, 32, 64);
+      if (lane < 32) {
+        const int col = wn * TN * 32 + j * 32 + lane;
+        sred[(0 * WM + wm) * BN + col] = s1;
+        sred[(1 * WM + wm) * BN + col] = s2;
+      }
+    }
+    __syncthreads();
+    for (int c = tid; c < BN; c += kThreads) {
+      float t1 = 0.f, t2 = 0.f;
+#pragma unroll
+      for (int w_ = 0; w_ < WM; ++w_) {
+        t1 += sred[(0 * WM + w_) * BN + c];
+        t2 += sred[(1 * WM + w_) * BN + c];
+      }
+      const int col = nt * BN + c;
+      if (col < a.Cd) {
+        a.stats[((size_t)0 * a.Cd + col) * a.mtiles + mt] = t1;
+        a.stats[((size_t)1 * a.Cd + col) * a.mtiles + mt] = t2;
+      }
+    }
+    __syncthreads();
+  }
+
+  bf16_t* Ct = reinterpret_cast<bf16_t*>(smem_raw);
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = wm * TM * 32 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        const int col = wn * TN * 32 + j * 32 + (lane & 31);
+        Ct[row * LDC + col] = f32_to_bf16_hw(acc[i][j][r]);
+      }
+  __syncthreads();
+  for (int idx = tid; idx < BM * (BN / 8); idx += kThreads) {
+    const int row = idx / (BN / 8), ch = idx % (BN / 8);
+    const int m = m0 + row, co = nt * BN + ch * 8;
+    if (m >= M || co >= a.Cd) continue;
+    bf16_t* dp = a.dst + (size_t)m * a.Cd + co;
+    if (a.accumulate) {
+      float o[8], nw[8];
+      load8(dp, o);
+      load8(Ct + row * LDC + ch * 8, nw);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] += nw[e];
+      store8(dp, o);
+    } else {
+      *reinterpret_cast<uint4*>(dp) = *reinterpret_cast<const uint4*>(Ct + row * LDC + ch * 8);
+    }
+  }
+}
+
+struct PatchPlan {
+  int bm, bn, ti, th;
+};
+
+// Tile geometry for BM output pixels: whole images, or a band of whole rows of one image.
+bool tile_geometry(const ConvGeom& g, int bm, int max_px, int* ti, int* th) {
+  const int hw = g.H * g.W;
+  if (hw <= bm) {
+    if (bm % hw != 0) return false;
+    *ti = bm / hw; *th = g.H;
+  } else {
+    if (bm % g.W != 0 || g.H % (bm / g.W) != 0) return false;
+    *ti = 1; *th = bm / g.W;
+  }
+  return (*ti) * (*th + 2) * (g.W + 2) <= max_px;
+}
+
+template <int BM, int BN>
+size_t patch_smem(int patch_px) {
+  const size_t stage = ((size_t)patch_px * PITCH + 3 * BN * PITCH) * sizeof(bf16_t);
+  const size_t epi = (size_t)BM * (BN + 8) * sizeof(bf16_t);
+  return stage > epi ? stage : epi;
+}
+
+template <int BM, int BN, int WM, int WN, int OCC, int PL>
+int launch_patch(PatchArgs& a, hipStream_t st) {
+  auto kern = patch_kernel<BM, BN, WM, WN, OCC, PL>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)patch_smem<BM, BN>(PL * kPxPerLoad)) != hipSuccess)
+      return CNNK_ERR_HIP;
+    attr_done = true;
+  }
+  const long M = (long)a.N * a.H * a.W;
+  a.ntiles = (a.Cd + BN - 1) / BN;
+  a.mtiles = (int)((M + BM - 1) / BM);
+  const size_t smem = patch_smem<BM, BN>(a.TI * (a.TH + 2) * (a.W + 2));
+  hipLaunchKernelGGL(kern, dim3((unsigned)(a.mtiles * a.ntiles)), dim3(kThreads), smem, st, a);
+  return launch_status();
+}
+
+bool plan_patch(const ConvGeom& g, int Cs, int Cd, PatchPlan* p) {
+  if (g.R != 3 || g.S != 3 || g.stride != 1 || g.pad != 1) return false;
+  if (Cs % CK != 0 || Cd % 8 != 0) return false;
+  // byte offsets must stay below the out-of-bounds marker of the buffer loads
+  if ((long)g.N * g.H * g.W * Cs * 2 >= (1L << 31) || (long)Cd * 9 * Cs * 2 >= (1L << 31)) return false;
+  if (g_cnnk_tune[4] < 0) return false;   // patch kernels switched off
+  const long M = (long)g.N * g.H * g.W;
+  // Candidates in order of preference (the larger the pixel tile, the less weight traffic):
+  // the first one that gives every CU a workgroup, else the one with the most workgroups.
+  const int cand[4][3] = {{256, 128, 6}, {256, 64, 10}, {128, 128, 5}, {128, 64, 5}};  // BM, BN, PL
+  int best = -1;
+  long best_blocks = 0;
+  for (int k = 0; k < 4; ++k) {
+    const int bm = cand[k][0], bn = cand[k][1];
+    if (g_cnnk_tune[4] > 0 && (bm != g_cnnk_tune[4] || bn != g_cnnk_tune[5])) continue;
+    if (bn == 128 && Cd <= 64) continue;
+    int ti, th;
+    if (!tile_geometry(g, bm, cand[k][2] * kPxPerLoad, &ti, &th)) continue;
+    const long blocks = ((M + bm - 1) / bm) * ((Cd + bn - 1) / bn);
+    if (blocks >= 256) { best = k; break; }
+    if (blocks > best_blocks) { best = k; best_blocks = blocks; }
+  }
+  if (best < 0) return false;
+  p->bm = cand[best][0]; p->bn = cand[best][1];
+  return tile_geometry(g, p->bm, cand[best][2] * kPxPerLoad, &p->ti, &p->th);
+}
+
+int run_patch(const ConvGeom& g, PatchArgs& a, const PatchPlan& p, hipStream_t st) {
+  a.TI = p.ti; a.TH = p.th;
+  if (p.bm == 256 && p.bn == 128) return launch_patch<256, 128, 2, 2, 2, 6>(a, st);
+  if (p.bm == 256 && p.bn == 64) return launch_patch<256, 64, 4, 1, 2, 10>(a, st);
+  if (p.bm == 128 && p.bn == 128) return launch_patch<128, 128, 2, 2, 2, 5>(a, st);
+  if (p.bm == 128 && p.bn == 64) return launch_patch<128, 64, 4, 1, 3, 5>(a, st);
+  (void)g;
+  return CNNK_ERR_UNSUPPORTED;
+}
+
+}  // namespace
+
+bool conv_patch_supported(const ConvGeom& g, int pass) {
+  PatchPlan p;
+  if (pass == CNNK_PASS_FWD) return plan_patch(g, g.Cin, g.Cout, &p);
+  if (pass == CNNK_PASS_DGRAD) return plan_patch(g, g.Cout, g.Cin, &p);
+  return false;
+}
+
+int conv_patch_mtiles(const ConvGeom& g) {
+  PatchPlan p;
+  if (!plan_patch(g, g.Cin, g.Cout, &p)) return 0;
+  return (int)(((long)g.N * g.H * g.W + p.bm - 1) / p.bm);
+}
+
+int conv_patch_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y, float* stats, hipStream_t st) {
+  PatchPlan p;
+  if (!plan_patch(g, g.Cin, g.Cout, &p)) return CNNK_ERR_UNSUPPORTED;
+  PatchArgs a{};
+  a.src = x; a.wt = w; a.dst = y; a.stats = stats;
+  a.N = g.N; a.H = g.H; a.W = g.W; a.Cs = g.Cin; a.Cd = g.Cout; a.accumulate = 0;
+  for (int r = 0; r < 3; ++r)
+    for (int s = 0; s < 3; ++s) {
+      a.toff_h[r * 3 + s] = r; a.toff_w[r * 3 + s] = s; a.widx[r * 3 + s] = r * 3 + s;
+    }
+  return run_patch(g, a, p, st);
+}
+
+// wt: weights already transposed to [Cin][9][Cout]
+int conv_patch_dgrad(const ConvGeom& g, const bf16_t* dy, const bf16_t* wt, bf16_t* dx, int accumulate,
+                     hipStream_t st) {
+  PatchPlan p;
+  if (!plan_patch(g, g.Cout, g.Cin, &p)) return CNNK_ERR_UNSUPPORTED;
+  PatchArgs a{};
+  a.src = dy; a.wt = wt; a.dst = dx; a.stats = nullptr;
+  a.N = g.N; a.H = g.H; a.W = g.W; a.Cs = g.Cout; a.Cd = g.Cin; a.accumulate = accumulate;
+  // dx[h,w] takes dy[h+1-r, w+1-s] with w[.,r,s,.]: patch offset (2-r, 2-s)
+  for (int r = 0; r < 3; ++r)
+    for (int s = 0; s < 3; ++s) {
+      a.toff_h[r * 3 + s] = 2 - r; a.toff_w[r * 3 + s] = 2 - s; a.widx[r * 3 + s] = r * 3 + s;
+    }
+  return run_patch(g, a, p, st);
+}

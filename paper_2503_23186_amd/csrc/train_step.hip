@@ -8,6 +8,8 @@
 
 namespace {
 
+constexpr size_t kStatBytes = 2 * 2048 * sizeof(float);
+
 struct Walk {
   std::vector<size_t> slot_elems;   // 0 = not seen yet
   std::vector<size_t> param_elems;
@@ -140,7 +142,7 @@ struct GroupTimer {
 extern "C" size_t cnnk_train_step_workspace_bytes(const cnnk_layer* layers, int n_layers) {
   Walk w;
   if (walk_layers(layers, n_layers, -1, -1, &w) != CNNK_OK) return 0;
-  return align_up(w.ws, 256);
+  return align_up(w.ws, 256) + kStatBytes;
 }
 
 extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B, const int* labels, float lr,
@@ -150,7 +152,7 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
   Walk w;
   int rc = walk_layers(L, n, B->n_slots, B->n_params, &w);
   if (rc != CNNK_OK) return rc;
-  if (w.ws > 0 && (!B->ws || B->ws_bytes < w.ws)) return CNNK_ERR_WORKSPACE;
+  if (!B->ws || B->ws_bytes < w.ws + kStatBytes) return CNNK_ERR_WORKSPACE;
   const bool bf16 = w.dtype == CNNK_BF16;
   for (size_t s = 0; s < w.slot_elems.size(); ++s) {
     if (w.slot_elems[s] == 0) continue;
@@ -176,9 +178,14 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
     }
   }
 
-  void* ws = B->ws;
-  const size_t wsb = B->ws_bytes;
+  // The first kStatBytes of the workspace carry the per-channel sums from a convolution to the
+  // batch norm that follows it; the calls themselves get the rest.
+  float* const stat_sum = reinterpret_cast<float*>(B->ws);
+  float* const stat_sq = stat_sum + 2048;
+  void* ws = static_cast<char*>(B->ws) + kStatBytes;
+  const size_t wsb = B->ws_bytes - kStatBytes;
   GroupTimer timer(B, n, stream);
+  int stats_from = -1;   // slot whose per-channel sums are currently held in stat_sum / stat_sq
   // ---- forward pass and loss ---------------------------------------------------------------
   for (int i = 0; i < n; ++i) {
     const cnnk_layer& l = L[i];
@@ -186,15 +193,23 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
     switch (l.op) {
       case CNNK_OP_CONV: {
         const void* wt = bf16 ? B->param_lp[l.p0] : (const void*)B->param[l.p0];
-        rc = cnnk_conv2d_fwd(&l.d.conv, B->act[l.in0], wt, B->act[l.out], nullptr, nullptr, ws, wsb, stream);
+        // hand the statistics to the next layer if that is the batch norm of this output
+        const bool feed = bf16 && i + 1 < n && L[i + 1].op == CNNK_OP_BN && L[i + 1].in0 == l.out &&
+                          l.d.conv.Cout % 8 == 0 && l.d.conv.Cout <= 2048;
+        rc = cnnk_conv2d_fwd(&l.d.conv, B->act[l.in0], wt, B->act[l.out], feed ? stat_sum : nullptr,
+                             feed ? stat_sq : nullptr, ws, wsb, stream);
+        stats_from = feed ? l.out : -1;
         break;
       }
       case CNNK_OP_BN: {
         const int C = l.d.bn.C;
         float* run = B->bn_running ? B->bn_running[i] : nullptr;
+        const bool fed = stats_from == l.in0;
         rc = cnnk_bn_relu_fwd(&l.d.bn, B->act[l.in0], l.in1 >= 0 ? B->act[l.in1] : nullptr, B->param[l.p0],
                               B->param[l.p1], B->act[l.out], B->bn_save[i], B->bn_save[i] + C, run,
-                              run ? run + C : nullptr, nullptr, nullptr, ws, wsb, stream);
+                              run ? run + C : nullptr, fed ? stat_sum : nullptr, fed ? stat_sq : nullptr, ws, wsb,
+                              stream);
+        stats_from = -1;
         break;
       }
       case CNNK_OP_POOL:

@@ -93,6 +93,44 @@ def test_conv_fwd_dgrad_wgrad(K, shape, dtype):
     assert max_rel_err(host(gdw), dw_ref) <= acc_tol
 
 
+PATCH_TILES = [(256, 128), (256, 64), (128, 128), (128, 64)]
+PATCH_SHAPES = [(4, 8, 8, 64, 128), (2, 16, 16, 32, 64), (2, 32, 32, 32, 64), (18, 4, 4, 64, 136),
+                (5, 8, 8, 96, 72), (3, 16, 16, 64, 40), (1, 32, 32, 160, 32)]
+
+
+@pytest.mark.parametrize("tile", PATCH_TILES)
+@pytest.mark.parametrize("shape", PATCH_SHAPES)
+def test_conv_patch_kernels_every_tile(K, shape, tile):
+    """3x3 stride-1 forward / data gradient through each LDS-patch tile configuration."""
+    N, H, W, Cin, Cout = shape
+    x, w, dy, pad = conv_inputs((N, H, W, Cin, Cout, 3, 1), "bf16", 13)
+    d = K.conv_desc(N, H, W, Cin, Cout, 3, 3, 1, 1, K.BF16)
+    K.cnnk_tune(4, tile[0]); K.cnnk_tune(5, tile[1])
+    try:
+        gx, gw, gdy = dev(x, "bf16"), dev(w, "bf16"), dev(dy, "bf16")
+        y_ref = ref.conv2d_fwd(x, w, 1, 1)
+        gy = torch.full(y_ref.shape, 7.0, dtype=gx.dtype, device=gx.device)
+        ws, nb = ws_for(K.cnnk_conv2d_workspace_bytes(d, K.PASS_FWD))
+        s1 = torch.zeros(Cout, device=gx.device); s2 = torch.zeros(Cout, device=gx.device)
+        K.cnnk_conv2d_fwd(d, gx, gw, gy, s1, s2, ws, nb)
+        torch.cuda.synchronize()
+        assert max_rel_err(host(gy), y_ref) <= 4e-3
+        assert max_rel_err(host(s1), y_ref.reshape(-1, Cout).sum(0)) <= 1e-4
+        assert max_rel_err(host(s2), (y_ref ** 2).reshape(-1, Cout).sum(0)) <= 1e-4
+        dx_ref = ref.conv2d_dgrad(dy, w, x.shape, 1, 1)
+        base = rep(np.random.default_rng(5).standard_normal(x.shape), "bf16")
+        ws, nb = ws_for(K.cnnk_conv2d_workspace_bytes(d, K.PASS_DGRAD))
+        gdx = torch.full(x.shape, 3.0, dtype=gx.dtype, device=gx.device)
+        K.cnnk_conv2d_dgrad(d, gdy, gw, gdx, 0, ws, nb)
+        gdx2 = dev(base, "bf16")
+        K.cnnk_conv2d_dgrad(d, gdy, gw, gdx2, 1, ws, nb)
+        torch.cuda.synchronize()
+        assert max_rel_err(host(gdx), dx_ref) <= 4e-3
+        assert max_rel_err(host(gdx2), dx_ref + base) <= 8e-3
+    finally:
+        K.cnnk_tune(4, 0); K.cnnk_tune(5, 0)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("shape,relu,with_res", [((3, 9, 7, 64), True, False), ((2, 16, 16, 160), True, True),
                                                   ((5, 4, 4, 512), False, False), ((8, 32, 32, 16), True, False),
