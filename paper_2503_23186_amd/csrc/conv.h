@@ -41,6 +41,11 @@ int conv_patch_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* 
 int conv_patch_dgrad(const ConvGeom& g, const bf16_t* dy, const bf16_t* wt, bf16_t* dx, int accumulate,
                      hipStream_t st);
 
+// 3x3 stride-1 weight gradient from LDS patches with transposing LDS loads
+bool conv_wgrad_patch_supported(const ConvGeom& g);
+size_t conv_wgrad_patch_ws(const ConvGeom& g);
+int conv_wgrad_patch(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws, hipStream_t st);
+
 // thin-input (stem) kernels, bf16 storage
 bool conv_stem_supported(const ConvGeom& g);
 size_t conv_stem_wgrad_ws(const ConvGeom& g);

@@ -96,13 +96,37 @@ __global__ void __launch_bounds__(256) direct_wgrad_kernel(ConvGeom g, const T* 
   part[(size_t)blockIdx.y * nw + i] = acc;
 }
 
+// out[i] = sum_p part[p][i].  64 float4 columns x 4 partial groups per workgroup; each group sums
+// every fourth partial, the groups are combined through LDS in a fixed order (deterministic).
 __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __restrict__ part,
                                                               float* __restrict__ out, int n, int P) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= n) return;
-  float acc = 0.f;
-  for (int p = 0; p < P; ++p) acc += part[(size_t)p * n + i];
-  out[i] = acc;
+  __shared__ float4 red[4][64];
+  const int col = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const int i4 = blockIdx.x * 64 + col;   // float4 column
+  const int n4 = n >> 2;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (i4 < n4) {
+#pragma unroll 4
+    for (int p = grp; p < P; p += 4) {
+      const float4 v = *reinterpret_cast<const float4*>(part + (size_t)p * n + (size_t)i4 * 4);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+  }
+  red[grp][col] = acc;
+  __syncthreads();
+  if (grp == 0 && i4 < n4) {
+    float4 s = red[0][col];
+#pragma unroll
+    for (int k = 1; k < 4; ++k) { s.x += red[k][col].x; s.y += red[k][col].y; s.z += red[k][col].z; s.w += red[k][col].w; }
+    *reinterpret_cast<float4*>(out + (size_t)i4 * 4) = s;
+  }
+  // scalar tail (n not a multiple of 4)
+  if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+    const int i = (n4 << 2) + threadIdx.x;
+    float a = 0.f;
+    for (int p = 0; p < P; ++p) a += part[(size_t)p * n + i];
+    out[i] = a;
+  }
 }
 
 void wgrad_split(const ConvGeom& g, int* chunk, int* P) {
@@ -160,11 +184,11 @@ int conv_direct_wgrad(const ConvGeom& g, int dtype, const void* x, const void* d
   else
     direct_wgrad_kernel<float><<<grid, 256, 0, st>>>(g, (const float*)x, (const float*)dy, part, chunk);
   if (launch_status() != CNNK_OK) return CNNK_ERR_HIP;
-  reduce_partials_kernel<<<(nw + 255) / 256, 256, 0, st>>>(part, dw, nw, P);
+  reduce_partials_kernel<<<(nw / 4 + 63) / 64 + 1, 256, 0, st>>>(part, dw, nw, P);
   return launch_status();
 }
 
 int reduce_partials(const float* part, float* out, int n, int P, hipStream_t st) {
-  reduce_partials_kernel<<<(n + 255) / 256, 256, 0, st>>>(part, out, n, P);
+  reduce_partials_kernel<<<(n / 4 + 63) / 64 + 1, 256, 0, st>>>(part, out, n, P);
   return launch_status();
 }

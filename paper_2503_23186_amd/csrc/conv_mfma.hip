@@ -493,6 +493,7 @@ size_t conv_mfma_ws(const ConvGeom& g, int pass, bool want_stats) {
     return want_stats ? align_up(((size_t)g.N * g.Ho * g.Wo + 63) / 64 * 2 * g.Cout * sizeof(float), 256) : 0;
   if (pass == CNNK_PASS_DGRAD) return align_up((size_t)g.Cout * g.R * g.S * g.Cin * sizeof(bf16_t), 256);
   if (pass == CNNK_PASS_WGRAD) {
+    if (conv_wgrad_patch_supported(g)) return conv_wgrad_patch_ws(g);
     int bmk, chunk, splits;
     wgrad_plan(g, &bmk, &chunk, &splits);
     return splits > 1 ? (size_t)splits * g.Cout * g.R * g.S * g.Cin * sizeof(float) : 0;
@@ -573,6 +574,7 @@ int conv_mfma_dgrad(const ConvGeom& g, const bf16_t* dy, const bf16_t* w, bf16_t
 
 int conv_mfma_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws,
                     hipStream_t st) {
+  if (conv_wgrad_patch_supported(g)) return conv_wgrad_patch(g, x, dy, dw, ws, st);
   int bmk, chunk, splits;
   wgrad_plan(g, &bmk, &chunk, &splits);
   WgradArgs a{};

@@ -1,0 +1,250 @@
+// Weight gradient of a 3x3 stride-1 convolution with both operands read from LDS in their
+// natural [pixel][channel] layout through the gfx950 transposing LDS load (ds_read_b64_tr_b16).
+//
+// dw[k][r][s][c] = sum_pixels dy[pixel][k] * x[pixel + (r-1, s-1)][c].  The reduction index (the
+// pixel) is the slow index of both tensors, so the MFMA operands (8 consecutive reduction
+// elements per lane) need a transposition; the transposing load does it on the way out of LDS,
+// which leaves the x tile as a patch with a 1-pixel halo from which all nine taps are served
+// (a tap is a pixel offset).  A workgroup owns 64 output channels x (9 taps x 64 input
+// channels) of dw and a range of pixel tiles; each range writes an fp32 partial to the
+// workspace and a fixed-order reduction kernel sums them (deterministic, no atomics).
+#include "common.h"
+#include "conv.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int PS = 128;           // output pixels per stage
+constexpr int CT = 64;            // channels per operand tile (64 k, 64 c)
+constexpr int PITCH_B = CT * 2 + 32;  // LDS row pitch in bytes: 4 consecutive rows cover distinct banks
+constexpr int kDyLoads = PS * (CT / 8) / kThreads;  // 16-byte loads per thread for the dy tile (4)
+
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+
+struct WgPatchArgs {
+  const bf16_t* x;
+  const bf16_t* dy;
+  float* dw;
+  int N, H, W, Cin, Cout;
+  int TI, TH;          // stage = TI images x TH rows x W columns = PS pixels
+  int ctiles;          // Cin / 64
+  int tiles_per_block; // pixel stages per workgroup
+  int mtiles;          // total pixel stages
+  int nw;              // Cout*9*Cin: stride between the partials of consecutive pixel ranges
+};
+
+__device__ __forceinline__ bf16x8_t tr_read8(const unsigned char* lds, int off0, int off1) {
+  // two transposing loads give this lane reduction slots 0..3 and 4..7 of its row / column
+  const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (s16x4_t __attribute__((address_space(3)))*)(lds + off0));
+  const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (s16x4_t __attribute__((address_space(3)))*)(lds + off1));
+  typedef short s16x8_t __attribute__((ext_vector_type(8)));
+  const s16x8_t v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8_t, v);
+}
+
+// PL: 16-byte loads per thread for the x patch (patch holds at most PL * 32 pixels)
+template <int PL>
+__global__ void __launch_bounds__(kThreads, 2) wgrad_patch_kernel(WgPatchArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int PW = a.W + 2, PH = a.TH + 2;
+  const int patch_px = a.TI * PH * PW;
+  unsigned char* Dl = smem;                      // dy tile  [PS][PITCH_B]
+  unsigned char* Xl = smem + PS * PITCH_B;       // x patch  [patch_px][PITCH_B]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 4, i16 = lane & 15;
+  const int kt = blockIdx.x / a.ctiles, ct = blockIdx.x % a.ctiles;  // 64-channel tiles of k and c
+  const int t_begin = blockIdx.y * a.tiles_per_block;
+  const int t_end = min(t_begin + a.tiles_per_block, a.mtiles);
+  const int M = a.N * a.H * a.W;
+
+  const __amdgpu_buffer_rsrc_t x_rs = make_rsrc(a.x, (unsigned)M * a.Cin * 2u);
+  const __amdgpu_buffer_rsrc_t dy_rs = make_rsrc(a.dy, (unsigned)M * a.Cout * 2u);
+
+  // wave -> 32 output channels (row tile wave%2) x 9 taps x 32 input channels (half wave/2)
+  const int row_half = wave & 1, col_half = wave >> 1;
+  // per-lane LDS byte offsets of the transposing loads
+  //   A (dy): pixel = ks*16 + (g/2)*8 + i16/4 (+4), channel = row_half*32 + (g%2)*16 + (i16%4)*4
+  const int a_off = (((g >> 1) * 8 + (i16 >> 2)) * PITCH_B) + (row_half * 32 + (g & 1) * 16 + (i16 & 3) * 4) * 2;
+  //   B (x): patch position of that pixel at tap (0,0), channel = col_half*32 + ...
+  int b_off[PS / 16][2];
+#pragma unroll
+  for (int ks = 0; ks < PS / 16; ++ks)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int p = ks * 16 + (g >> 1) * 8 + (i16 >> 2) + 4 * h;
+      const int tw = p % a.W, q = p / a.W;
+      const int th = q % a.TH, ti = q / a.TH;
+      b_off[ks][h] = ((ti * PH + th) * PW + tw) * PITCH_B + (col_half * 32 + (g & 1) * 16 + (i16 & 3) * 4) * 2;
+    }
+
+  f32x16_t acc[9];
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+
+  const int kc = tid & 7;  // 16-byte chunk (8 channels) inside a 64-channel row
+  uint4 dreg[kDyLoads], xreg[PL];
+  // Per-thread load descriptors, fixed for the whole kernel: a stage only moves the origin
+  // (image n0, row h0), which enters as one scalar byte offset per tensor.
+  int xrel[PL], xdh[PL], xti[PL];   // byte offset relative to pixel (n0, h0, 0); row shift; image shift
+#pragma unroll
+  for (int j = 0; j < PL; ++j) {
+    const int pp = (tid >> 3) + j * (kThreads / 8);
+    const int pw = pp % PW, q = pp / PW;
+    const int ph = q % PH, ti = q / PH;
+    const bool ok = pp < patch_px && pw >= 1 && pw <= a.W;
+    xdh[j] = ok ? ph - 1 : -(1 << 20);   // a row shift that never passes the range test
+    xti[j] = ti;
+    xrel[j] = (((ti * a.H + ph - 1) * a.W + pw - 1) * a.Cin + ct * CT + kc * 8) * 2;
+  }
+  const int drel = ((tid >> 3) * a.Cout + kt * CT + kc * 8) * 2;
+
+  auto load_stage = [&](int t) {
+    const int m0 = t * PS;
+    const unsigned dbase = (unsigned)m0 * a.Cout * 2u;
+#pragma unroll
+    for (int j = 0; j < kDyLoads; ++j) {
+      const int p = (tid >> 3) + j * (kThreads / 8);
+      const unsigned off = (m0 + p < M) ? dbase + (unsigned)(drel + j * (kThreads / 8) * a.Cout * 2) : kOobOffset;
+      dreg[j] = buffer_load16(dy_rs, off, 0);
+    }
+    const int n0 = m0 / (a.H * a.W), h0 = (m0 / a.W) % a.H;
+    const int xbase = ((n0 * a.H + h0) * a.W) * a.Cin * 2;
+#pragma unroll
+    for (int j = 0; j < PL; ++j) {
+      const bool ok = (unsigned)(h0 + xdh[j]) < (unsigned)a.H && n0 + xti[j] < a.N;
+      xreg[j] = buffer_load16(x_rs, ok ? (unsigned)(xbase + xrel[j]) : kOobOffset, 0);
+    }
+  };
+  auto store_stage = [&]() {
+#pragma unroll
+    for (int j = 0; j < kDyLoads; ++j) {
+      const int p = (tid >> 3) + j * (kThreads / 8);
+      *reinterpret_cast<uint4*>(Dl + p * PITCH_B + kc * 16) = dreg[j];
+    }
+#pragma unroll
+    for (int j = 0; j < PL; ++j) {
+      const int pp = (tid >> 3) + j * (kThreads / 8);
+      if (pp < patch_px) *reinterpret_cast<uint4*>(Xl + pp * PITCH_B + kc * 16) = xreg[j];
+    }
+  };
+
+  if (t_begin < t_end) {
+    load_stage(t_begin);
+    store_stage();
+  }
+  __syncthreads();
+  for (int t = t_begin; t < t_end; ++t) {
+    if (t + 1 < t_end) load_stage(t + 1);
+#pragma unroll
+    for (int ks = 0; ks < PS / 16; ++ks) {
+      const bf16x8_t af = tr_read8(Dl, a_off + ks * 16 * PITCH_B, a_off + (ks * 16 + 4) * PITCH_B);
+#pragma unroll
+      for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int s = 0; s < 3; ++s) {
+          const int toff = (r * PW + s) * PITCH_B;
+          const bf16x8_t bf = tr_read8(Xl, b_off[ks][0] + toff, b_off[ks][1] + toff);
+          acc[r * 3 + s] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bf, acc[r * 3 + s], 0, 0, 0);
+        }
+    }
+    __syncthreads();  // every wave is done reading this stage
+    if (t + 1 < t_end) store_stage();
+    __syncthreads();
+  }
+
+  // dw[k][tap][c]: this lane holds column c = ct*64 + col_half*32 + lane%32 and rows
+  // k = kt*64 + row_half*32 + (r/4)*8 + (lane/32)*4 + r%4
+  const int c = ct * CT + col_half * 32 + (lane & 31);
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int k = kt * CT + row_half * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+      a.dw[(size_t)blockIdx.y * a.nw + ((size_t)k * 9 + t) * a.Cin + c] = acc[t][r];
+    }
+}
+
+bool wg_geometry(const ConvGeom& g, int* ti, int* th) {
+  const int hw = g.H * g.W;
+  if (hw <= PS) {
+    if (PS % hw != 0) return false;
+    *ti = PS / hw; *th = g.H;
+  } else {
+    if (PS % g.W != 0 || g.H % (PS / g.W) != 0) return false;
+    *ti = 1; *th = PS / g.W;
+  }
+  return (*ti) * (*th + 2) * (g.W + 2) <= 9 * 32;
+}
+
+template <int PL>
+int launch_wg(const WgPatchArgs& a, dim3 grid, size_t smem, hipStream_t st) {
+  auto kern = wgrad_patch_kernel<PL>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)((PS + PL * 32) * PITCH_B)) != hipSuccess)
+      return CNNK_ERR_HIP;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(kern, grid, dim3(kThreads), smem, st, a);
+  return launch_status();
+}
+
+}  // namespace
+
+bool conv_wgrad_patch_supported(const ConvGeom& g) {
+  if (g_cnnk_tune[6] < 0) return false;
+  if (g.R != 3 || g.S != 3 || g.stride != 1 || g.pad != 1) return false;
+  if (g.Cin % CT != 0 || g.Cout % CT != 0) return false;
+  const long M = (long)g.N * g.H * g.W;
+  if (M * g.Cin * 2 >= (1L << 31) || M * g.Cout * 2 >= (1L << 31)) return false;
+  int ti, th;
+  return wg_geometry(g, &ti, &th);
+}
+
+static void wg_plan(const ConvGeom& g, WgPatchArgs* a, int* splits) {
+  a->ctiles = g.Cin / CT;
+  const int otiles = (g.Cout / CT) * a->ctiles;
+  const long M = (long)g.N * g.H * g.W;
+  a->mtiles = (int)((M + PS - 1) / PS);
+  const int target = g_cnnk_tune[6] > 0 ? g_cnnk_tune[6] : 256;
+  int sp = (target + otiles - 1) / otiles;
+  if (sp > a->mtiles) sp = a->mtiles;
+  if (sp < 1) sp = 1;
+  a->tiles_per_block = (a->mtiles + sp - 1) / sp;
+  *splits = (a->mtiles + a->tiles_per_block - 1) / a->tiles_per_block;
+  a->nw = g.Cout * 9 * g.Cin;
+}
+
+size_t conv_wgrad_patch_ws(const ConvGeom& g) {
+  WgPatchArgs a{};
+  int splits;
+  wg_plan(g, &a, &splits);
+  return splits > 1 ? (size_t)splits * a.nw * sizeof(float) : 0;
+}
+
+int conv_wgrad_patch(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws, hipStream_t st) {
+  WgPatchArgs a{};
+  if (!wg_geometry(g, &a.TI, &a.TH)) return CNNK_ERR_UNSUPPORTED;
+  int splits;
+  wg_plan(g, &a, &splits);
+  a.x = x; a.dy = dy;
+  a.dw = splits > 1 ? reinterpret_cast<float*>(ws) : dw;
+  a.N = g.N; a.H = g.H; a.W = g.W; a.Cin = g.Cin; a.Cout = g.Cout;
+  const int otiles = (g.Cout / CT) * a.ctiles;
+  const int patch_px = a.TI * (a.TH + 2) * (a.W + 2);
+  const size_t smem = (size_t)(PS + patch_px) * PITCH_B;
+  dim3 grid(otiles, splits);
+  const int pl = (patch_px + 31) / 32;
+  int rc;
+  if (pl <= 6) rc = launch_wg<6>(a, grid, smem, st);
+  else if (pl <= 7) rc = launch_wg<7>(a, grid, smem, st);
+  else rc = launch_wg<9>(a, grid, smem, st);
+  if (rc != CNNK_OK || splits == 1) return rc;
+  return reduce_partials(a.dw, dw, a.nw, splits, st);
+}

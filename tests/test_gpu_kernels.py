@@ -93,6 +93,30 @@ def test_conv_fwd_dgrad_wgrad(K, shape, dtype):
     assert max_rel_err(host(gdw), dw_ref) <= acc_tol
 
 
+WG_SHAPES = [(4, 8, 8, 64, 128), (3, 16, 16, 64, 64), (2, 32, 32, 128, 64), (18, 4, 4, 64, 64), (5, 8, 8, 192, 64),
+             (1, 32, 32, 64, 64)]
+
+
+@pytest.mark.parametrize("target", [1, 4, 0])
+@pytest.mark.parametrize("shape", WG_SHAPES)
+def test_conv_wgrad_patch_kernel(K, shape, target):
+    """3x3 stride-1 weight gradient through the LDS-patch kernel: one workgroup per output tile
+    (plain stores), a few (atomic accumulation), and the default split."""
+    N, H, W, Cin, Cout = shape
+    x, w, dy, pad = conv_inputs((N, H, W, Cin, Cout, 3, 1), "bf16", 17)
+    d = K.conv_desc(N, H, W, Cin, Cout, 3, 3, 1, 1, K.BF16)
+    K.cnnk_tune(6, target)
+    try:
+        dw_ref = ref.conv2d_wgrad(x, dy, w.shape, 1, 1)
+        gdw = torch.full(w.shape, 9.0, dtype=torch.float32, device="cuda:0")
+        ws, nb = ws_for(K.cnnk_conv2d_workspace_bytes(d, K.PASS_WGRAD))
+        K.cnnk_conv2d_wgrad(d, dev(x, "bf16"), dev(dy, "bf16"), gdw, ws, nb)
+        torch.cuda.synchronize()
+        assert max_rel_err(host(gdw), dw_ref) <= 1e-4
+    finally:
+        K.cnnk_tune(6, 0)
+
+
 PATCH_TILES = [(256, 128), (256, 64), (128, 128), (128, 64)]
 PATCH_SHAPES = [(4, 8, 8, 64, 128), (2, 16, 16, 32, 64), (2, 32, 32, 32, 64), (18, 4, 4, 64, 136),
                 (5, 8, 8, 96, 72), (3, 16, 16, 64, 40), (1, 32, 32, 160, 32)]
