@@ -93,6 +93,16 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// Division of small non-negative integers by a runtime constant without the ~30-instruction
+// hardware-less integer division: q = (x * magic) >> 32 with magic = floor(2^32 / d) + 1 is exact
+// for 0 <= x < 2^16 and 1 <= d < 2^16 (x * (magic * d - 2^32) < 2^32 because magic*d - 2^32 <= d).
+struct FastDiv {
+  unsigned d, magic;
+  __host__ __device__ void init(unsigned dd) { d = dd; magic = dd > 1 ? (unsigned)(0x100000000ull / dd) + 1u : 0u; }
+  __device__ __forceinline__ int div(int x) const { return d > 1 ? (int)__umulhi((unsigned)x, magic) : x; }
+  __device__ __forceinline__ void divmod(int x, int* q, int* r) const { *q = div(x); *r = x - *q * (int)d; }
+};
+
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline int conv_out(int H, int pad, int R, int stride) { return (H + 2 * pad - R) / stride + 1; }
 static inline size_t elem_size(int dtype) { return dtype == CNNK_BF16 ? 2 : 4; }

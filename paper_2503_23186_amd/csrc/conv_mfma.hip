@@ -70,19 +70,30 @@ __global__ void __launch_bounds__(kThreads, OCC) igemm_kernel(IgemmArgs a) {
   const int tap0 = a.tt.cls_begin[cls], ntap = a.tt.cls_begin[cls + 1] - tap0;
 
   const int kc = tid % KC, r0 = tid / KC;
-  int a_n[A_IT], a_h[A_IT], a_w[A_IT];
+  const __amdgpu_buffer_rsrc_t src_rs = make_rsrc(a.src, (unsigned)a.Nimg * a.Hs * a.Ws * a.Cs * 2u);
+  const __amdgpu_buffer_rsrc_t wt_rs = make_rsrc(a.wt, (unsigned)a.Cd * a.T * a.Cs * 2u);
+  // Per tile row: source coordinates at tap (0,0) and the byte offset of that pixel; a tap adds
+  // a uniform offset and two range tests, padding is an out-of-range buffer offset (reads 0).
+  int a_h[A_IT], a_w[A_IT];
+  unsigned a_off[A_IT];
 #pragma unroll
   for (int it = 0; it < A_IT; ++it) {
     const int m = mt * BM + r0 + it * RPP;
     if (m < M && r0 + it * RPP < BM) {
       const int j = m % Wm, q = m / Wm;
       const int i = q % Hm, n = q / Hm;
-      a_n[it] = n * a.Hs * a.Ws;
       a_h[it] = i * a.ss;
       a_w[it] = j * a.ss;
+      a_off[it] = (unsigned)(((n * a.Hs + a_h[it]) * a.Ws + a_w[it]) * a.Cs + kc * 8) * 2u;
     } else {
-      a_n[it] = 0; a_h[it] = -(1 << 20); a_w[it] = 0;
+      a_h[it] = -(1 << 20); a_w[it] = 0; a_off[it] = 0;
     }
+  }
+  unsigned b_off[B_IT];
+#pragma unroll
+  for (int it = 0; it < B_IT; ++it) {
+    const int row = r0 + it * RPP, ch = nt * BN + row;
+    b_off[it] = (row < BN && ch < a.Cd) ? (unsigned)(ch * a.T * a.Cs + kc * 8) * 2u : kOobOffset;
   }
 
   f32x16_t acc[TM][TN];
@@ -105,23 +116,18 @@ __global__ void __launch_bounds__(kThreads, OCC) igemm_kernel(IgemmArgs a) {
   auto load_stage = [&](int s, auto SET) {
     constexpr int rs = decltype(SET)::value;
     const int t = tap0 + s / cchunks;
-    const int c = (s % cchunks) * BK + kc * 8;
+    const int c0 = (s % cchunks) * BK;
     const int dh = a.tt.dh[t], dw = a.tt.dw[t], wi = a.tt.widx[t];
-    const bool cok = c < a.Cs;
+    const bool cok = c0 + kc * 8 < a.Cs;                       // ragged last channel chunk
+    const int tap_off = ((dh * a.Ws + dw) * a.Cs + c0) * 2;   // uniform
 #pragma unroll
     for (int it = 0; it < A_IT; ++it) {
-      const int hs = a_h[it] + dh, ws = a_w[it] + dw;
-      const bool ok = cok && (unsigned)hs < (unsigned)a.Hs && (unsigned)ws < (unsigned)a.Ws;
-      ra[rs][it] = make_uint4(0, 0, 0, 0);
-      if (ok) ra[rs][it] = *reinterpret_cast<const uint4*>(a.src + ((size_t)(a_n[it] + hs * a.Ws + ws)) * a.Cs + c);
+      const bool ok = cok && (unsigned)(a_h[it] + dh) < (unsigned)a.Hs && (unsigned)(a_w[it] + dw) < (unsigned)a.Ws;
+      ra[rs][it] = buffer_load16(src_rs, ok ? a_off[it] + (unsigned)tap_off : kOobOffset, 0);
     }
+    const unsigned so = (unsigned)(wi * a.Cs + c0) * 2u;
 #pragma unroll
-    for (int it = 0; it < B_IT; ++it) {
-      const int ch = nt * BN + r0 + it * RPP;
-      rb[rs][it] = make_uint4(0, 0, 0, 0);
-      if (cok && ch < a.Cd && r0 + it * RPP < BN)
-        rb[rs][it] = *reinterpret_cast<const uint4*>(a.wt + ((size_t)ch * a.T + wi) * a.Cs + c);
-    }
+    for (int it = 0; it < B_IT; ++it) rb[rs][it] = buffer_load16(wt_rs, cok ? b_off[it] : kOobOffset, so);
   };
   auto store_stage = [&](int buf, auto SET) {
     constexpr int rs = decltype(SET)::value;
@@ -216,7 +222,7 @@ __global__ void __launch_bounds__(kThreads, OCC) igemm_kernel(IgemmArgs a) {
       for (int r = 0; r < 16; ++r) {
         const int row = wm * TM * 32 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
         const int col = wn * TN * 32 + j * 32 + (lane & 31);
-        Ct[row * LDC + col] = f32_to_bf16(acc[i][j][r]);
+        Ct[row * LDC + col] = f32_to_bf16_hw(acc[i][j][r]);
       }
   __syncthreads();
   const int oh = a.tt.oh[cls], ow = a.tt.ow[cls];
@@ -483,8 +489,9 @@ bool conv_mfma_supported(const ConvGeom& g, int pass) {
   if (g.R != g.S || (g.R != 1 && g.R != 3)) return false;
   if (g.stride < 1 || g.stride > 2) return false;
   // 32-bit element offsets inside the kernels
+  // byte offsets of the buffer loads must stay below their out-of-bounds marker (2 GiB)
   const long e_in = (long)g.N * g.H * g.W * g.Cin, e_out = (long)g.N * g.Ho * g.Wo * g.Cout;
-  if (e_in >= (1L << 31) || e_out >= (1L << 31)) return false;
+  if (e_in >= (1L << 30) || e_out >= (1L << 30) || (long)g.Cout * g.R * g.S * g.Cin >= (1L << 30)) return false;
   return true;
 }
 

@@ -16,7 +16,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int CK = 32;          // channels per chunk
-constexpr int PITCH = CK + 8;   // padded LDS row (elements): conflict-free 16-byte fragment reads
+
 constexpr int kPxPerLoad = kThreads / (CK / 8);  // patch pixels staged per 16-byte load of the workgroup
 
 struct PatchArgs {
@@ -26,22 +26,37 @@ struct PatchArgs {
   float* stats;       // nullable: [2][Cd][mtiles]
   int N, H, W, Cs, Cd;
   int TI, TH;         // tile = TI images x TH rows x W columns (BM pixels)
-  int accumulate, ntiles, mtiles;
+  int accumulate, ntiles, mtiles, dbg;
   int toff_h[9], toff_w[9], widx[9];  // patch offset (0..2, 0..2) and weight tap of each step
+  FastDiv dPW, dPH, dW, dTH;          // divisors used to decode tile-local pixel indices (< 2^16)
 };
 
+// LDS rows are dense 64-byte rows (32 channels) whose four 16-byte chunks are XOR-swizzled with
+// bits 2..3 of the row index: 16 lanes reading one chunk of 16 consecutive rows, and 16 lanes
+// writing 4 whole rows, both touch every bank once.
+__device__ __forceinline__ int swz_off(int row, int chunk) { return row * 64 + ((chunk ^ ((row >> 2) & 3)) << 4); }
+
 // PL: 16-byte patch loads per thread, i.e. the patch holds at most PL * 64 pixels.
+//
+// Software pipeline (u = chunk*9 + tap is the step index; a step is one tap of one chunk):
+//   weights: global load of step u+4 -> register set (u+1)%3 ... stored to LDS ring slot (u+2)%3 at
+//            the end of step u, so that at step u the ring holds steps u and u+1;
+//   patch:   chunk c+1 is loaded at tap 0 of chunk c and stored to the other patch buffer at tap 6;
+//   MFMA operands of step u+1 are read from LDS into the second fragment set while the MFMAs of
+//   step u run from the first, so the matrix pipe never waits for LDS after a barrier.
 template <int BM, int BN, int WM, int WN, int OCC, int PL>
 __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   constexpr int B_IT = (BN + 63) / 64;  // 64 weight rows per pass (4 chunks of 8 channels per row)
   constexpr int LDC = BN + 8;
-  static_assert(WM * WN == 4 && TM >= 1 && TN >= 1, "tile shape");
+  constexpr int KK = CK / 16;
+  static_assert(WM * WN == 4 && TM >= 1 && TN >= 1 && KK == 2, "tile shape");
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const int PW = a.W + 2, PH = a.TH + 2;
   const int patch_px = a.TI * PH * PW;
-  bf16_t* Pt = reinterpret_cast<bf16_t*>(smem_raw);  // [patch_px][PITCH]
-  bf16_t* Bs = Pt + (size_t)patch_px * PITCH;        // [3][BN][PITCH]
+  const int patch_bytes = patch_px * 64;
+  unsigned char* Pb = smem_raw;                      // [2][patch_px][64 B]
+  unsigned char* Bb = smem_raw + 2 * patch_bytes;    // [3][BN][64 B]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wn = wave / WM;
@@ -56,41 +71,49 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   const __amdgpu_buffer_rsrc_t src_rs = make_rsrc(a.src, (unsigned)M * a.Cs * 2u);
   const __amdgpu_buffer_rsrc_t wt_rs = make_rsrc(a.wt, (unsigned)a.Cd * 9u * a.Cs * 2u);
 
-  // byte offset of every patch chunk this thread stages (kOobOffset: zero fill), fixed for the
-  // whole kernel; the channel chunk is added as the scalar offset of the load
   const int kc = tid & 3;
-  unsigned poff[PL];
+  unsigned poff[PL];   // global byte offset of each staged patch chunk (kOobOffset: zero fill)
+  int pst[PL];         // its LDS byte offset inside a patch buffer (-1: not staged)
 #pragma unroll
   for (int j = 0; j < PL; ++j) {
     const int pp = (tid >> 2) + j * (kThreads / 4);
     poff[j] = kOobOffset;
+    pst[j] = -1;
     if (pp < patch_px) {
-      const int pw = pp % PW, q = pp / PW;
-      const int ph = q % PH, ti = q / PH;
+      pst[j] = swz_off(pp, kc);
+      int q, pw, ti, ph;
+      a.dPW.divmod(pp, &q, &pw);
+      a.dPH.divmod(q, &ti, &ph);
       const int n = n0 + ti, hs = h0 + ph - 1, ws = pw - 1;
       if (n < a.N && (unsigned)hs < (unsigned)a.H && (unsigned)ws < (unsigned)a.W)
         poff[j] = (unsigned)(((n * a.H + hs) * a.W + ws) * a.Cs + kc * 8) * 2u;
     }
+    if (a.dbg & 1) poff[j] = kOobOffset;
   }
   const int r0 = tid >> 2;  // weight row of this thread inside a 64-row pass
   unsigned boff[B_IT];
+  int bst[B_IT];
 #pragma unroll
   for (int it = 0; it < B_IT; ++it) {
     const int row = r0 + it * 64, ch = nt * BN + row;
     boff[it] = (row < BN && ch < a.Cd) ? (unsigned)(ch * 9 * a.Cs + kc * 8) * 2u : kOobOffset;
+    if (a.dbg & 2) boff[it] = kOobOffset;
+    bst[it] = swz_off(row, kc);
   }
-  // LDS byte offset (tap (0,0)) of the patch pixel under each of this lane's output rows
-  int abase[TM];
+  // patch pixel (tap (0,0)) under each of this lane's output rows, and the weight-row offsets
+  int app[TM];
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int p = wm * TM * 32 + i * 32 + (lane & 31);
-    const int tw = p % a.W, q = p / a.W;
-    const int th = q % a.TH, ti = q / a.TH;
-    abase[i] = (((ti * PH + th) * PW + tw) * PITCH + (lane >> 5) * 8) * 2;
+    int q, tw, ti, th;
+    a.dW.divmod(p, &q, &tw);
+    a.dTH.divmod(q, &ti, &th);
+    app[i] = (ti * PH + th) * PW + tw;
   }
-  const int bbase = ((wn * TN * 32 + (lane & 31)) * PITCH + (lane >> 5) * 8) * 2;
-  const unsigned char* Pb = reinterpret_cast<const unsigned char*>(Pt);
-  const unsigned char* Bb = reinterpret_cast<const unsigned char*>(Bs);
+  const int khalf = lane >> 5;
+  int bfo[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) bfo[j] = swz_off(wn * TN * 32 + j * 32 + (lane & 31), khalf);
 
   f32x16_t acc[TM][TN];
 #pragma unroll
@@ -102,94 +125,115 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
 
   const int nchunks = a.Cs / CK;
   uint4 preg[PL];
-  uint4 rb[3][B_IT];  // weights of three steps in flight; all indices below are compile-time
+  uint4 rb[3][B_IT];
+  bf16x8_t af[2][TM][KK], bfr[2][TN][KK];
 
   auto load_patch = [&](int chunk) {
 #pragma unroll
     for (int j = 0; j < PL; ++j) preg[j] = buffer_load16(src_rs, poff[j], (unsigned)chunk * (CK * 2));
   };
-  auto store_patch = [&]() {
+  auto store_patch = [&](int buf) {
 #pragma unroll
-    for (int j = 0; j < PL; ++j) {
-      const int pp = (tid >> 2) + j * (kThreads / 4);
-      if (pp < patch_px) *reinterpret_cast<uint4*>(Pt + pp * PITCH + kc * 8) = preg[j];
-    }
+    for (int j = 0; j < PL; ++j)
+      if (pst[j] >= 0) *reinterpret_cast<uint4*>(Pb + buf * patch_bytes + pst[j]) = preg[j];
   };
-  // step (chunk, TAP) takes its weights from LDS ring slot TAP % 3 and register set TAP % 3
-  auto load_b = [&](int chunk, auto TAP) {
+  auto load_b = [&](int chunk, auto TAP) {   // weights of step (chunk, TAP) -> register set TAP % 3
     constexpr int tap = decltype(TAP)::value, rs = tap % 3;
     const unsigned so = (unsigned)(a.widx[tap] * a.Cs + chunk * CK) * 2u;
 #pragma unroll
     for (int it = 0; it < B_IT; ++it) rb[rs][it] = buffer_load16(wt_rs, boff[it], so);
   };
-  auto store_b = [&](auto TAP) {
+  auto store_b = [&](auto TAP) {             // register set TAP % 3 -> ring slot TAP % 3
     constexpr int rs = decltype(TAP)::value % 3;
 #pragma unroll
-    for (int it = 0; it < B_IT; ++it) {
-      const int row = r0 + it * 64;
-      if (row < BN) *reinterpret_cast<uint4*>(Bs + (rs * BN + row) * PITCH + kc * 8) = rb[rs][it];
+    for (int it = 0; it < B_IT; ++it)
+      if (r0 + it * 64 < BN) *reinterpret_cast<uint4*>(Bb + rs * (BN * 64) + bst[it]) = rb[rs][it];
+  };
+  // MFMA operands of tap TAP from patch buffer `pbuf` and ring slot TAP % 3 into fragment set SET
+  auto read_frags = [&](int pbuf, auto TAP, auto SET) {
+    constexpr int tap = decltype(TAP)::value, fs = decltype(SET)::value;
+    const int tpx = a.toff_h[tap] * PW + a.toff_w[tap];
+    const unsigned char* P = Pb + pbuf * patch_bytes;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int pp = app[i] + tpx;
+      const int o = pp * 64 + ((khalf ^ ((pp >> 2) & 3)) << 4);
+      af[fs][i][0] = *reinterpret_cast<const bf16x8_t*>(P + o);
+      af[fs][i][1] = *reinterpret_cast<const bf16x8_t*>(P + (o ^ 32));   // chunk + 2
+    }
+    const unsigned char* B = Bb + (tap % 3) * (BN * 64);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      bfr[fs][j][0] = *reinterpret_cast<const bf16x8_t*>(B + bfo[j]);
+      bfr[fs][j][1] = *reinterpret_cast<const bf16x8_t*>(B + (bfo[j] ^ 32));
     }
   };
-  auto compute = [&](auto TAP) {
-    constexpr int tap = decltype(TAP)::value, cur = tap % 3;
-    const int off = (a.toff_h[tap] * PW + a.toff_w[tap]) * (PITCH * 2);
+  auto mfmas = [&](auto SET) {
+    constexpr int fs = decltype(SET)::value;
 #pragma unroll
-    for (int kk = 0; kk < CK / 16; ++kk) {
-      bf16x8_t af[TM], bfr[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const bf16x8_t*>(Pb + abase[i] + off + kk * 32);
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        bfr[j] = *reinterpret_cast<const bf16x8_t*>(Bb + bbase + (cur * BN + j * 32) * (PITCH * 2) + kk * 32);
+    for (int kk = 0; kk < KK; ++kk)
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-    }
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[fs][i][kk], bfr[fs][j][kk], acc[i][j], 0, 0, 0);
   };
-  auto step = [&](int chunk, auto TAP) {
-    constexpr int tap = decltype(TAP)::value;
+  // PAR = chunk % 2: patch buffer of this chunk, and the parity that fixes the fragment set
+  auto step = [&](int chunk, auto PARC, auto TAP) {
+    constexpr int par = decltype(PARC)::value, tap = decltype(TAP)::value;
+    constexpr int cur = (par + tap) % 2;
     const bool more = chunk + 1 < nchunks;
-    // weights three steps ahead go into the register set this step's weights just left
-    if constexpr (tap + 3 < 9) {
-      load_b(chunk, std::integral_constant<int, tap + 3>{});
+    if constexpr (tap + 4 < 9) {
+      load_b(chunk, std::integral_constant<int, tap + 4>{});
     } else {
-      if (more) load_b(chunk + 1, std::integral_constant<int, tap + 3 - 9>{});
+      if (more) load_b(chunk + 1, std::integral_constant<int, tap + 4 - 9>{});
     }
     if constexpr (tap == 0) {
       if (more) load_patch(chunk + 1);
     }
-    compute(TAP);
+    if (!(a.dbg & 8)) {
     if constexpr (tap + 1 < 9) {
-      store_b(std::integral_constant<int, tap + 1>{});
+      read_frags(par, std::integral_constant<int, tap + 1>{}, std::integral_constant<int, cur ^ 1>{});
     } else {
-      if (more) {
-        store_b(std::integral_constant<int, 0>{});
-        __syncthreads();  // every wave is done with the current patch
-        store_patch();
-      }
+      if (more) read_frags(par ^ 1, std::integral_constant<int, 0>{}, std::integral_constant<int, cur ^ 1>{});
     }
-    __syncthreads();
+    }
+    if (!(a.dbg & 16)) mfmas(std::integral_constant<int, cur>{});
+    if constexpr (tap + 2 < 9) {
+      store_b(std::integral_constant<int, tap + 2>{});
+    } else {
+      if (more) store_b(std::integral_constant<int, tap + 2 - 9>{});
+    }
+    if constexpr (tap == 6) {
+      if (more) store_patch(par ^ 1);
+    }
+    if (!(a.dbg & 4)) __syncthreads();
+  };
+  auto chunk_body = [&](int chunk, auto PARC) {
+    step(chunk, PARC, std::integral_constant<int, 0>{});
+    step(chunk, PARC, std::integral_constant<int, 1>{});
+    step(chunk, PARC, std::integral_constant<int, 2>{});
+    step(chunk, PARC, std::integral_constant<int, 3>{});
+    step(chunk, PARC, std::integral_constant<int, 4>{});
+    step(chunk, PARC, std::integral_constant<int, 5>{});
+    step(chunk, PARC, std::integral_constant<int, 6>{});
+    step(chunk, PARC, std::integral_constant<int, 7>{});
+    step(chunk, PARC, std::integral_constant<int, 8>{});
   };
 
   load_patch(0);
   load_b(0, std::integral_constant<int, 0>{});
   load_b(0, std::integral_constant<int, 1>{});
   load_b(0, std::integral_constant<int, 2>{});
-  store_patch();
+  store_patch(0);
   store_b(std::integral_constant<int, 0>{});
+  store_b(std::integral_constant<int, 1>{});
+  load_b(0, std::integral_constant<int, 3>{});   // register set 0 is free again
   __syncthreads();
-  for (int chunk = 0; chunk < nchunks; ++chunk) {
-    step(chunk, std::integral_constant<int, 0>{});
-    step(chunk, std::integral_constant<int, 1>{});
-    step(chunk, std::integral_constant<int, 2>{});
-    step(chunk, std::integral_constant<int, 3>{});
-    step(chunk, std::integral_constant<int, 4>{});
-    step(chunk, std::integral_constant<int, 5>{});
-    step(chunk, std::integral_constant<int, 6>{});
-    step(chunk, std::integral_constant<int, 7>{});
-    step(chunk, std::integral_constant<int, 8>{});
+  read_frags(0, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+  for (int chunk = 0; chunk < nchunks; chunk += 2) {
+    chunk_body(chunk, std::integral_constant<int, 0>{});
+    if (chunk + 1 < nchunks) chunk_body(chunk + 1, std::integral_constant<int, 1>{});
   }
 
   if (a.stats) {
@@ -230,6 +274,7 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
     __syncthreads();
   }
 
+  if (a.dbg & 64) return;
   bf16_t* Ct = reinterpret_cast<bf16_t*>(smem_raw);
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -245,7 +290,7 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   for (int idx = tid; idx < BM * (BN / 8); idx += kThreads) {
     const int row = idx / (BN / 8), ch = idx % (BN / 8);
     const int m = m0 + row, co = nt * BN + ch * 8;
-    if (m >= M || co >= a.Cd) continue;
+    if (m >= M || co >= a.Cd || (a.dbg & 32)) continue;
     bf16_t* dp = a.dst + (size_t)m * a.Cd + co;
     if (a.accumulate) {
       float o[8], nw[8];
@@ -279,7 +324,7 @@ bool tile_geometry(const ConvGeom& g, int bm, int max_px, int* ti, int* th) {
 
 template <int BM, int BN>
 size_t patch_smem(int patch_px) {
-  const size_t stage = ((size_t)patch_px * PITCH + 3 * BN * PITCH) * sizeof(bf16_t);
+  const size_t stage = (size_t)2 * patch_px * 64 + (size_t)3 * BN * 64;
   const size_t epi = (size_t)BM * (BN + 8) * sizeof(bf16_t);
   return stage > epi ? stage : epi;
 }
@@ -311,13 +356,14 @@ bool plan_patch(const ConvGeom& g, int Cs, int Cd, PatchPlan* p) {
   const long M = (long)g.N * g.H * g.W;
   // Candidates in order of preference (the larger the pixel tile, the less weight traffic):
   // the first one that gives every CU a workgroup, else the one with the most workgroups.
-  const int cand[4][3] = {{256, 128, 6}, {256, 64, 10}, {128, 128, 5}, {128, 64, 5}};  // BM, BN, PL
+  const int cand[4][3] = {{256, 64, 10}, {128, 128, 5}, {128, 64, 5}, {256, 128, 6}};  // BM, BN, PL (last: forced only)
   int best = -1;
   long best_blocks = 0;
   for (int k = 0; k < 4; ++k) {
     const int bm = cand[k][0], bn = cand[k][1];
     if (g_cnnk_tune[4] > 0 && (bm != g_cnnk_tune[4] || bn != g_cnnk_tune[5])) continue;
     if (bn == 128 && Cd <= 64) continue;
+    if (k == 3 && g_cnnk_tune[4] <= 0) continue;   // 256x128 needs more registers than two waves per SIMD leave
     int ti, th;
     if (!tile_geometry(g, bm, cand[k][2] * kPxPerLoad, &ti, &th)) continue;
     const long blocks = ((M + bm - 1) / bm) * ((Cd + bn - 1) / bn);
@@ -331,6 +377,8 @@ bool plan_patch(const ConvGeom& g, int Cs, int Cd, PatchPlan* p) {
 
 int run_patch(const ConvGeom& g, PatchArgs& a, const PatchPlan& p, hipStream_t st) {
   a.TI = p.ti; a.TH = p.th;
+  a.dbg = g_cnnk_tune[7];
+  a.dPW.init(a.W + 2); a.dPH.init(a.TH + 2); a.dW.init(a.W); a.dTH.init(a.TH);
   if (p.bm == 256 && p.bn == 128) return launch_patch<256, 128, 2, 2, 2, 6>(a, st);
   if (p.bm == 256 && p.bn == 64) return launch_patch<256, 64, 4, 1, 2, 10>(a, st);
   if (p.bm == 128 && p.bn == 128) return launch_patch<128, 128, 2, 2, 2, 5>(a, st);

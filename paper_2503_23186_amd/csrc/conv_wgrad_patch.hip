@@ -31,6 +31,7 @@ struct WgPatchArgs {
   int tiles_per_block; // pixel stages per workgroup
   int mtiles;          // total pixel stages
   int nw;              // Cout*9*Cin: stride between the partials of consecutive pixel ranges
+  FastDiv dPW, dPH, dW, dTH;
 };
 
 __device__ __forceinline__ bf16x8_t tr_read8(const unsigned char* lds, int off0, int off1) {
@@ -75,8 +76,9 @@ __global__ void __launch_bounds__(kThreads, 2) wgrad_patch_kernel(WgPatchArgs a)
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int p = ks * 16 + (g >> 1) * 8 + (i16 >> 2) + 4 * h;
-      const int tw = p % a.W, q = p / a.W;
-      const int th = q % a.TH, ti = q / a.TH;
+      int q, tw, ti, th;
+      a.dW.divmod(p, &q, &tw);
+      a.dTH.divmod(q, &ti, &th);
       b_off[ks][h] = ((ti * PH + th) * PW + tw) * PITCH_B + (col_half * 32 + (g & 1) * 16 + (i16 & 3) * 4) * 2;
     }
 
@@ -94,8 +96,9 @@ __global__ void __launch_bounds__(kThreads, 2) wgrad_patch_kernel(WgPatchArgs a)
 #pragma unroll
   for (int j = 0; j < PL; ++j) {
     const int pp = (tid >> 3) + j * (kThreads / 8);
-    const int pw = pp % PW, q = pp / PW;
-    const int ph = q % PH, ti = q / PH;
+    int q, pw, ti, ph;
+    a.dPW.divmod(pp, &q, &pw);
+    a.dPH.divmod(q, &ti, &ph);
     const bool ok = pp < patch_px && pw >= 1 && pw <= a.W;
     xdh[j] = ok ? ph - 1 : -(1 << 20);   // a row shift that never passes the range test
     xti[j] = ti;
@@ -236,6 +239,7 @@ int conv_wgrad_patch(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float
   a.x = x; a.dy = dy;
   a.dw = splits > 1 ? reinterpret_cast<float*>(ws) : dw;
   a.N = g.N; a.H = g.H; a.W = g.W; a.Cin = g.Cin; a.Cout = g.Cout;
+  a.dPW.init(a.W + 2); a.dPH.init(a.TH + 2); a.dW.init(a.W); a.dTH.init(a.TH);
   const int otiles = (g.Cout / CT) * a.ctiles;
   const int patch_px = a.TI * (a.TH + 2) * (a.W + 2);
   const size_t smem = (size_t)(PS + patch_px) * PITCH_B;
