@@ -141,26 +141,6 @@ __global__ void __launch_bounds__(kT) sums_finalize_kernel(const float* __restri
   ch_sumsq[c] = (float)s2;
 }
 
-__global__ void __launch_bounds__(kT) stats_from_sums_kernel(const float* __restrict__ ch_sum,
-                                                             const float* __restrict__ ch_sumsq, size_t m, int C,
-                                                             float eps, float momentum, float* __restrict__ mean,
-                                                             float* __restrict__ invstd, float* __restrict__ rmean,
-                                                             float* __restrict__ rvar) {
-  const int c = blockIdx.x * kT + threadIdx.x;
-  if (c >= C) return;
-  const double dm = (double)m;
-  const double mu = (double)ch_sum[c] / dm;
-  double var = (double)ch_sumsq[c] / dm - mu * mu;
-  if (var < 0.0) var = 0.0;
-  mean[c] = (float)mu;
-  invstd[c] = (float)(1.0 / sqrt(var + (double)eps));
-  if (rmean) {
-    const double unb = m > 1 ? var * dm / (dm - 1.0) : var;
-    rmean[c] = (float)((1.0 - momentum) * rmean[c] + momentum * mu);
-    rvar[c] = (float)((1.0 - momentum) * rvar[c] + momentum * unb);
-  }
-}
-
 template <typename T>
 __global__ void __launch_bounds__(kT) bn_apply_kernel(const T* __restrict__ x, const T* __restrict__ res,
                                                       const float* __restrict__ gamma,
@@ -178,6 +158,71 @@ __global__ void __launch_bounds__(kT) bn_apply_kernel(const T* __restrict__ x, c
     load8(invstd + c0, is);
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = fmaf(g[e], (v[e] - mu[e]) * is[e], b[e]);
+    if (res) {
+      float r[8];
+      load8(res + i * 8, r);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] += r[e];
+    }
+    if (relu) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
+    }
+    store8(y + i * 8, v);
+  }
+}
+
+// Normalise (+ residual) (+ ReLU) with the statistics taken directly from per-channel sums
+// (sum x, sum x^2 over m positions, e.g. from the convolution that produced x): every thread
+// derives mean / invstd of its 8 channels itself, so no separate statistics kernel runs.
+// Workgroup 0 also writes save_mean / save_invstd and updates the running statistics.
+template <typename T>
+__global__ void __launch_bounds__(kT) bn_apply_sums_kernel(const T* __restrict__ x, const T* __restrict__ res,
+                                                           const float* __restrict__ gamma,
+                                                           const float* __restrict__ beta,
+                                                           const float* __restrict__ ch_sum,
+                                                           const float* __restrict__ ch_sumsq, float inv_m,
+                                                           float unbias, float eps, float momentum,
+                                                           float* __restrict__ save_mean,
+                                                           float* __restrict__ save_invstd,
+                                                           float* __restrict__ rmean, float* __restrict__ rvar,
+                                                           T* __restrict__ y, size_t n8, int C, int relu) {
+  int cur_c0 = -1;
+  float sc[8], bi[8];
+  if (blockIdx.x == 0) {
+    for (int c = threadIdx.x; c < C; c += kT) {
+      const float mu = ch_sum[c] * inv_m;
+      const float var = fmaxf(fmaf(ch_sumsq[c], inv_m, -mu * mu), 0.f);
+      save_mean[c] = mu;
+      save_invstd[c] = rsqrtf(var + eps);
+      if (rmean) {
+        rmean[c] = (1.f - momentum) * rmean[c] + momentum * mu;
+        rvar[c] = (1.f - momentum) * rvar[c] + momentum * var * unbias;
+      }
+    }
+  }
+  for (size_t i = (size_t)blockIdx.x * kT + threadIdx.x; i < n8; i += (size_t)gridDim.x * kT) {
+    const int c0 = (int)((i * 8) % C);
+    if (c0 != cur_c0) {
+      cur_c0 = c0;
+      float s1[8], s2[8], g[8], b[8];
+      load8(ch_sum + c0, s1);
+      load8(ch_sumsq + c0, s2);
+      load8(gamma + c0, g);
+      load8(beta + c0, b);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float mu = s1[e] * inv_m;
+        const float var = fmaxf(fmaf(s2[e], inv_m, -mu * mu), 0.f);
+        const float is = rsqrtf(var + eps);
+        sc[e] = g[e] * is;
+        bi[e] = fmaf(-mu, sc[e], b[e]);
+      }
+    }
+    float v[8];
+    load8(x + i * 8, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = fmaf(v[e], sc[e], bi[e]);
     if (res) {
       float r[8];
       load8(res + i * 8, r);
@@ -360,8 +405,21 @@ extern "C" int cnnk_bn_relu_fwd(const cnnk_bn_desc* d, const void* x, const void
                                                                      running_mean, running_var);
     }
   } else {
-    stats_from_sums_kernel<<<(C + kT - 1) / kT, kT, 0, st>>>(ch_sum, ch_sumsq, m, C, d->eps, d->momentum,
-                                                             save_mean, save_invstd, running_mean, running_var);
+    // statistics handed in as sums: one fused kernel (statistics + normalise)
+    const size_t n8s = m * C / 8;
+    const float inv_m = (float)(1.0 / (double)m);
+    const float unbias = m > 1 ? (float)((double)m / ((double)m - 1.0)) : 1.f;
+    if (d->dtype == CNNK_BF16)
+      bn_apply_sums_kernel<bf16_t><<<ew_blocks(n8s), kT, 0, st>>>((const bf16_t*)x, (const bf16_t*)residual, gamma, beta,
+                                                                 ch_sum, ch_sumsq, inv_m, unbias, d->eps, d->momentum,
+                                                                 save_mean, save_invstd, running_mean, running_var,
+                                                                 (bf16_t*)y, n8s, C, d->relu);
+    else
+      bn_apply_sums_kernel<float><<<ew_blocks(n8s), kT, 0, st>>>((const float*)x, (const float*)residual, gamma, beta,
+                                                                ch_sum, ch_sumsq, inv_m, unbias, d->eps, d->momentum,
+                                                                save_mean, save_invstd, running_mean, running_var,
+                                                                (float*)y, n8s, C, d->relu);
+    return launch_status();
   }
   if (launch_status() != CNNK_OK) return CNNK_ERR_HIP;
   const size_t n8 = m * C / 8;

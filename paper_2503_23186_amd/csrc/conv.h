@@ -34,6 +34,19 @@ int conv_mfma_dgrad(const ConvGeom& g, const bf16_t* dy, const bf16_t* w, bf16_t
 int conv_mfma_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws,
                     hipStream_t st);
 
+// data gradient with weights already transposed to [Cin][R*S][Cout], and the batched transposition
+constexpr int kMaxTranspose = 32;
+struct TransposeTable {
+  int count;
+  int block_begin[kMaxTranspose + 1];
+  const bf16_t* src[kMaxTranspose];
+  bf16_t* dst[kMaxTranspose];
+  int Cout[kMaxTranspose], T[kMaxTranspose], Cin[kMaxTranspose];
+};
+int conv_transpose_weights_multi(TransposeTable& t, hipStream_t st);
+int conv_mfma_dgrad_pt(const ConvGeom& g, const bf16_t* dy, const bf16_t* wt, bf16_t* dx, int accumulate,
+                       hipStream_t st);
+
 // 3x3 stride-1 kernels with the input patch resident in LDS (forward, data gradient)
 bool conv_patch_supported(const ConvGeom& g, int pass);
 int conv_patch_mtiles(const ConvGeom& g);

@@ -259,6 +259,18 @@ __global__ void __launch_bounds__(256) transpose_weights_kernel(const bf16_t* __
   wt[idx] = w[((size_t)k * T + t) * Cin + c];
 }
 
+__global__ void __launch_bounds__(256) transpose_weights_multi_kernel(TransposeTable t) {
+  int k = 0;
+  while (k + 1 < t.count && (int)blockIdx.x >= t.block_begin[k + 1]) ++k;
+  const int idx = (blockIdx.x - t.block_begin[k]) * 256 + threadIdx.x;
+  const int Cout = t.Cout[k], T = t.T[k], Cin = t.Cin[k];
+  if (idx >= Cout * T * Cin) return;
+  const int ko = idx % Cout;
+  const int tt = (idx / Cout) % T;
+  const int c = idx / (Cout * T);
+  t.dst[k][idx] = t.src[k][((size_t)ko * T + tt) * Cin + c];
+}
+
 // ------------------------------------------------------------------------------------------
 struct WgradArgs {
   const bf16_t* x;
@@ -537,6 +549,18 @@ int conv_mfma_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y
   return channel_sums_finalize(a.stats, (int)((M + p.bm - 1) / p.bm), g.Cout, ch_sum, ch_sumsq, st);
 }
 
+int conv_transpose_weights_multi(TransposeTable& t, hipStream_t st) {
+  int blocks = 0;
+  for (int k = 0; k < t.count; ++k) {
+    t.block_begin[k] = blocks;
+    blocks += (t.Cout[k] * t.T[k] * t.Cin[k] + 255) / 256;
+  }
+  t.block_begin[t.count] = blocks;
+  if (blocks == 0) return CNNK_OK;
+  transpose_weights_multi_kernel<<<blocks, 256, 0, st>>>(t);
+  return launch_status();
+}
+
 int conv_mfma_dgrad(const ConvGeom& g, const bf16_t* dy, const bf16_t* w, bf16_t* dx, int accumulate,
                     void* ws, hipStream_t st) {
   const int T = g.R * g.S;
@@ -544,6 +568,13 @@ int conv_mfma_dgrad(const ConvGeom& g, const bf16_t* dy, const bf16_t* w, bf16_t
   const int nw = g.Cout * T * g.Cin;
   transpose_weights_kernel<<<(nw + 255) / 256, 256, 0, st>>>(w, wt, g.Cout, T, g.Cin);
   if (launch_status() != CNNK_OK) return CNNK_ERR_HIP;
+  return conv_mfma_dgrad_pt(g, dy, wt, dx, accumulate, st);
+}
+
+// wt: weights already transposed to [Cin][R*S][Cout]
+int conv_mfma_dgrad_pt(const ConvGeom& g, const bf16_t* dy, const bf16_t* wt, bf16_t* dx, int accumulate,
+                       hipStream_t st) {
+  const int T = g.R * g.S;
   if (conv_patch_supported(g, CNNK_PASS_DGRAD)) return conv_patch_dgrad(g, dy, wt, dx, accumulate, st);
   IgemmArgs a{};
   a.src = dy; a.wt = wt; a.dst = dx;

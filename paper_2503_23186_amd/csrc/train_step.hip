@@ -5,17 +5,26 @@
 #include <vector>
 #include "common.h"
 #include "sgd.h"
+#include "conv.h"
 
 namespace {
 
-constexpr size_t kStatBytes = 2 * 2048 * sizeof(float);
+constexpr int kStatSlots = 4;   // convolutions whose per-channel sums may be pending at once
+constexpr size_t kStatBytes = kStatSlots * 2 * 2048 * sizeof(float);
 
 struct Walk {
   std::vector<size_t> slot_elems;   // 0 = not seen yet
   std::vector<size_t> param_elems;
   size_t ws = 0;
+  size_t wt_bytes = 0;               // transposed bf16 weights of every conv whose data gradient runs on MFMA
+  std::vector<size_t> wt_off;        // per layer: offset into that region, or (size_t)-1
   int dtype = -1;
 };
+
+bool dgrad_pretransposed(const cnnk_layer& l) {
+  if (l.op != CNNK_OP_CONV || l.in0 == 0 || l.d.conv.dtype != CNNK_BF16) return false;
+  return conv_mfma_supported(make_geom(&l.d.conv), CNNK_PASS_DGRAD);
+}
 
 bool set_elems(std::vector<size_t>& v, int id, size_t n) {
   if (id < 0 || id >= (int)v.size()) return false;
@@ -41,6 +50,7 @@ int walk_layers(const cnnk_layer* L, int n, int n_slots, int n_params, Walk* w) 
   if (n_params >= 0 && max_param >= n_params) return CNNK_ERR_SHAPE;
   w->slot_elems.assign(max_slot + 1, 0);
   w->param_elems.assign(max_param + 1, 0);
+  w->wt_off.assign(n, (size_t)-1);
   for (int i = 0; i < n; ++i) {
     const cnnk_layer& l = L[i];
     int dt = -1;
@@ -57,6 +67,10 @@ int walk_layers(const cnnk_layer* L, int n, int n_slots, int n_params, Walk* w) 
              set_elems(w->slot_elems, l.out, (size_t)d.N * Ho * Wo * d.Cout) &&
              set_elems(w->param_elems, l.p0, (size_t)d.Cout * d.R * d.S * d.Cin);
         for (int p = 0; p < 3; ++p) w->ws = max_sz(w->ws, cnnk_conv2d_workspace_bytes(&d, p));
+        if (dgrad_pretransposed(l)) {
+          w->wt_off[i] = w->wt_bytes;
+          w->wt_bytes += align_up((size_t)d.Cout * d.R * d.S * d.Cin * sizeof(bf16_t), 256);
+        }
         break;
       }
       case CNNK_OP_BN: {
@@ -142,7 +156,7 @@ struct GroupTimer {
 extern "C" size_t cnnk_train_step_workspace_bytes(const cnnk_layer* layers, int n_layers) {
   Walk w;
   if (walk_layers(layers, n_layers, -1, -1, &w) != CNNK_OK) return 0;
-  return align_up(w.ws, 256) + kStatBytes;
+  return align_up(w.ws, 256) + kStatBytes + w.wt_bytes;
 }
 
 extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B, const int* labels, float lr,
@@ -152,7 +166,7 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
   Walk w;
   int rc = walk_layers(L, n, B->n_slots, B->n_params, &w);
   if (rc != CNNK_OK) return rc;
-  if (!B->ws || B->ws_bytes < w.ws + kStatBytes) return CNNK_ERR_WORKSPACE;
+  if (!B->ws || B->ws_bytes < w.ws + kStatBytes + w.wt_bytes) return CNNK_ERR_WORKSPACE;
   const bool bf16 = w.dtype == CNNK_BF16;
   for (size_t s = 0; s < w.slot_elems.size(); ++s) {
     if (w.slot_elems[s] == 0) continue;
@@ -180,12 +194,13 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
 
   // The first kStatBytes of the workspace carry the per-channel sums from a convolution to the
   // batch norm that follows it; the calls themselves get the rest.
-  float* const stat_sum = reinterpret_cast<float*>(B->ws);
-  float* const stat_sq = stat_sum + 2048;
-  void* ws = static_cast<char*>(B->ws) + kStatBytes;
-  const size_t wsb = B->ws_bytes - kStatBytes;
+  float* const stat_base = reinterpret_cast<float*>(B->ws);
+  int stat_slot[kStatSlots];   // tensor slot whose sums each buffer holds, -1 = free
+  for (int k = 0; k < kStatSlots; ++k) stat_slot[k] = -1;
+  char* const wt_region = static_cast<char*>(B->ws) + kStatBytes;
+  void* ws = wt_region + w.wt_bytes;
+  const size_t wsb = B->ws_bytes - kStatBytes - w.wt_bytes;
   GroupTimer timer(B, n, stream);
-  int stats_from = -1;   // slot whose per-channel sums are currently held in stat_sum / stat_sq
   // ---- forward pass and loss ---------------------------------------------------------------
   for (int i = 0; i < n; ++i) {
     const cnnk_layer& l = L[i];
@@ -193,23 +208,32 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
     switch (l.op) {
       case CNNK_OP_CONV: {
         const void* wt = bf16 ? B->param_lp[l.p0] : (const void*)B->param[l.p0];
-        // hand the statistics to the next layer if that is the batch norm of this output
-        const bool feed = bf16 && i + 1 < n && L[i + 1].op == CNNK_OP_BN && L[i + 1].in0 == l.out &&
-                          l.d.conv.Cout % 8 == 0 && l.d.conv.Cout <= 2048;
-        rc = cnnk_conv2d_fwd(&l.d.conv, B->act[l.in0], wt, B->act[l.out], feed ? stat_sum : nullptr,
-                             feed ? stat_sq : nullptr, ws, wsb, stream);
-        stats_from = feed ? l.out : -1;
+        // hand the per-channel sums to the batch norm that consumes this output, if one does and
+        // a buffer is free
+        int sb = -1;
+        if (bf16 && l.d.conv.Cout % 8 == 0 && l.d.conv.Cout <= 2048) {
+          bool wanted = false;
+          for (int j = i + 1; j < n && !wanted; ++j) wanted = L[j].op == CNNK_OP_BN && L[j].in0 == l.out;
+          for (int k = 0; wanted && k < kStatSlots && sb < 0; ++k)
+            if (stat_slot[k] < 0) sb = k;
+        }
+        float* ssum = sb >= 0 ? stat_base + (size_t)sb * 4096 : nullptr;
+        rc = cnnk_conv2d_fwd(&l.d.conv, B->act[l.in0], wt, B->act[l.out], ssum, ssum ? ssum + 2048 : nullptr, ws, wsb,
+                             stream);
+        if (sb >= 0) stat_slot[sb] = l.out;
         break;
       }
       case CNNK_OP_BN: {
         const int C = l.d.bn.C;
         float* run = B->bn_running ? B->bn_running[i] : nullptr;
-        const bool fed = stats_from == l.in0;
+        int sb = -1;
+        for (int k = 0; k < kStatSlots; ++k)
+          if (stat_slot[k] == l.in0) sb = k;
+        const float* ssum = sb >= 0 ? stat_base + (size_t)sb * 4096 : nullptr;
         rc = cnnk_bn_relu_fwd(&l.d.bn, B->act[l.in0], l.in1 >= 0 ? B->act[l.in1] : nullptr, B->param[l.p0],
                               B->param[l.p1], B->act[l.out], B->bn_save[i], B->bn_save[i] + C, run,
-                              run ? run + C : nullptr, fed ? stat_sum : nullptr, fed ? stat_sq : nullptr, ws, wsb,
-                              stream);
-        stats_from = -1;
+                              run ? run + C : nullptr, ssum, ssum ? ssum + 2048 : nullptr, ws, wsb, stream);
+        if (sb >= 0) stat_slot[sb] = -1;
         break;
       }
       case CNNK_OP_POOL:
@@ -227,6 +251,26 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
     if (rc != CNNK_OK) return rc;
   }
   // ---- backward pass ---------------------------------------------------------------------------
+  // all weight transpositions of the data-gradient kernels in one launch (per 32 layers)
+  {
+    TransposeTable t;
+    t.count = 0;
+    for (int i = 0; i < n; ++i) {
+      if (w.wt_off[i] == (size_t)-1) continue;
+      const cnnk_conv_desc& d = L[i].d.conv;
+      const int k = t.count++;
+      t.src[k] = static_cast<const bf16_t*>(B->param_lp[L[i].p0]);
+      t.dst[k] = reinterpret_cast<bf16_t*>(wt_region + w.wt_off[i]);
+      t.Cout[k] = d.Cout; t.T[k] = d.R * d.S; t.Cin[k] = d.Cin;
+      if (t.count == kMaxTranspose) {
+        rc = conv_transpose_weights_multi(t, (hipStream_t)stream);
+        if (rc != CNNK_OK) return rc;
+        t.count = 0;
+      }
+    }
+    if (t.count > 0) rc = conv_transpose_weights_multi(t, (hipStream_t)stream);
+    if (rc != CNNK_OK) return rc;
+  }
   std::vector<char> written(w.slot_elems.size(), 0);
   written[L[n - 1].in0] = 1;
   for (int i = n - 2; i >= 0; --i) {
@@ -239,8 +283,14 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
         timer.end(g0);
         timer.begin(g0 + 1);
         if (rc == CNNK_OK && l.in0 != 0) {
-          const void* wt = bf16 ? B->param_lp[l.p0] : (const void*)B->param[l.p0];
-          rc = cnnk_conv2d_dgrad(&l.d.conv, B->dact[l.out], wt, B->dact[l.in0], written[l.in0], ws, wsb, stream);
+          if (w.wt_off[i] != (size_t)-1) {
+            rc = conv_mfma_dgrad_pt(make_geom(&l.d.conv), static_cast<const bf16_t*>(B->dact[l.out]),
+                                    reinterpret_cast<const bf16_t*>(wt_region + w.wt_off[i]),
+                                    static_cast<bf16_t*>(B->dact[l.in0]), written[l.in0], (hipStream_t)stream);
+          } else {
+            const void* wt = bf16 ? B->param_lp[l.p0] : (const void*)B->param[l.p0];
+            rc = cnnk_conv2d_dgrad(&l.d.conv, B->dact[l.out], wt, B->dact[l.in0], written[l.in0], ws, wsb, stream);
+          }
           written[l.in0] = 1;
         }
         break;
