@@ -95,7 +95,8 @@ __device__ __forceinline__ float wave_max(float v) {
 
 // Division of small non-negative integers by a runtime constant without the ~30-instruction
 // hardware-less integer division: q = (x * magic) >> 32 with magic = floor(2^32 / d) + 1 is exact
-// for 0 <= x < 2^16 and 1 <= d < 2^16 (x * (magic * d - 2^32) < 2^32 because magic*d - 2^32 <= d).
+// whenever x * d < 2^32 (the excess x * (magic*d - 2^32) / (d * 2^32) stays below 1/d because
+// magic*d - 2^32 <= d).  Callers keep x * d far below that bound.
 struct FastDiv {
   unsigned d, magic;
   __host__ __device__ void init(unsigned dd) { d = dd; magic = dd > 1 ? (unsigned)(0x100000000ull / dd) + 1u : 0u; }

@@ -59,6 +59,13 @@ bool conv_wgrad_patch_supported(const ConvGeom& g);
 size_t conv_wgrad_patch_ws(const ConvGeom& g);
 int conv_wgrad_patch(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws, hipStream_t st);
 
+// fewer than 8 input channels: zero-pad to 8 in the workspace, then the MFMA kernels
+bool conv_pad_supported(const ConvGeom& g);
+size_t conv_pad_ws(const ConvGeom& g, int pass, bool want_stats);
+int conv_pad_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y, float* ch_sum, float* ch_sumsq,
+                 void* ws, hipStream_t st);
+int conv_pad_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws, hipStream_t st);
+
 // thin-input (stem) kernels, bf16 storage
 bool conv_stem_supported(const ConvGeom& g);
 size_t conv_stem_wgrad_ws(const ConvGeom& g);

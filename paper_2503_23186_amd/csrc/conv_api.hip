@@ -22,8 +22,11 @@ int cnnk_validate_conv(const cnnk_conv_desc* d) {
 static bool use_mfma(const cnnk_conv_desc* d, const ConvGeom& g, int pass) {
   return d->dtype == CNNK_BF16 && conv_mfma_supported(g, pass);
 }
+static bool use_pad(const cnnk_conv_desc* d, const ConvGeom& g, int pass) {
+  return d->dtype == CNNK_BF16 && pass != CNNK_PASS_DGRAD && g_cnnk_tune[8] >= 0 && conv_pad_supported(g);
+}
 static bool use_stem(const cnnk_conv_desc* d, const ConvGeom& g, int pass) {
-  return d->dtype == CNNK_BF16 && !conv_mfma_supported(g, pass) && conv_stem_supported(g);
+  return d->dtype == CNNK_BF16 && !conv_mfma_supported(g, pass) && !use_pad(d, g, pass) && conv_stem_supported(g);
 }
 
 extern "C" size_t cnnk_conv2d_workspace_bytes(const cnnk_conv_desc* d, int pass) {
@@ -34,10 +37,12 @@ extern "C" size_t cnnk_conv2d_workspace_bytes(const cnnk_conv_desc* d, int pass)
     // room for the per-channel statistics pass over y when the caller asks for ch_sum/ch_sumsq
     b = (g.Cout % 8 == 0 && g.Cout <= 2048) ? channel_stats_ws((size_t)g.N * g.Ho * g.Wo, g.Cout) : 0;
     if (use_mfma(d, g, pass)) { const size_t m = conv_mfma_ws(g, pass, true); if (m > b) b = m; }
+    if (use_pad(d, g, pass)) { const size_t m = conv_pad_ws(g, pass, true); if (m > b) b = m; }
   } else if (pass == CNNK_PASS_DGRAD) {
     b = use_mfma(d, g, pass) ? conv_mfma_ws(g, pass, false) : 0;
   } else if (pass == CNNK_PASS_WGRAD) {
     b = use_mfma(d, g, pass) ? conv_mfma_ws(g, pass, false)
+        : use_pad(d, g, pass) ? conv_pad_ws(g, pass, false)
         : use_stem(d, g, pass) ? conv_stem_wgrad_ws(g) : conv_direct_wgrad_ws(g);
   }
   return align_up(b, 256);
@@ -57,6 +62,10 @@ extern "C" int cnnk_conv2d_fwd(const cnnk_conv_desc* d, const void* x, const voi
   hipStream_t st = (hipStream_t)stream;
   if (use_mfma(d, g, CNNK_PASS_FWD))
     return conv_mfma_fwd(g, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, ch_sum, ch_sumsq, ws, st);
+  if (use_pad(d, g, CNNK_PASS_FWD)) {
+    if (!ws || ws_bytes < cnnk_conv2d_workspace_bytes(d, CNNK_PASS_FWD)) return CNNK_ERR_WORKSPACE;
+    return conv_pad_fwd(g, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, ch_sum, ch_sumsq, ws, st);
+  }
   if (use_stem(d, g, CNNK_PASS_FWD))
     rc = conv_stem_fwd(g, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, st);
   else
@@ -91,6 +100,7 @@ extern "C" int cnnk_conv2d_wgrad(const cnnk_conv_desc* d, const void* x, const v
   if (need && (!ws || ws_bytes < need)) return CNNK_ERR_WORKSPACE;
   if (use_mfma(d, g, CNNK_PASS_WGRAD))
     return conv_mfma_wgrad(g, (const bf16_t*)x, (const bf16_t*)dy, dw, ws, st);
+  if (use_pad(d, g, CNNK_PASS_WGRAD)) return conv_pad_wgrad(g, (const bf16_t*)x, (const bf16_t*)dy, dw, ws, st);
   if (use_stem(d, g, CNNK_PASS_WGRAD)) return conv_stem_wgrad(g, (const bf16_t*)x, (const bf16_t*)dy, dw, ws, st);
   return conv_direct_wgrad(g, d->dtype, x, dy, dw, ws, st);
 }

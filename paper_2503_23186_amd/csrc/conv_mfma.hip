@@ -259,16 +259,28 @@ __global__ void __launch_bounds__(256) transpose_weights_kernel(const bf16_t* __
   wt[idx] = w[((size_t)k * T + t) * Cin + c];
 }
 
+// dst[c][t][k] = src[k][t][c] for every tensor of the table: one workgroup per (tap, 32x32 tile),
+// staged through LDS so that both the reads (along c) and the writes (along k) are contiguous.
 __global__ void __launch_bounds__(256) transpose_weights_multi_kernel(TransposeTable t) {
+  __shared__ bf16_t tile[32][33];
   int k = 0;
   while (k + 1 < t.count && (int)blockIdx.x >= t.block_begin[k + 1]) ++k;
-  const int idx = (blockIdx.x - t.block_begin[k]) * 256 + threadIdx.x;
   const int Cout = t.Cout[k], T = t.T[k], Cin = t.Cin[k];
-  if (idx >= Cout * T * Cin) return;
-  const int ko = idx % Cout;
-  const int tt = (idx / Cout) % T;
-  const int c = idx / (Cout * T);
-  t.dst[k][idx] = t.src[k][((size_t)ko * T + tt) * Cin + c];
+  const int ct = (Cin + 31) / 32, kt = (Cout + 31) / 32;
+  int b = blockIdx.x - t.block_begin[k];
+  const int c0 = (b % ct) * 32; b /= ct;
+  const int k0 = (b % kt) * 32;
+  const int tap = b / kt;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+  const bf16_t* src = t.src[k];
+  bf16_t* dst = t.dst[k];
+#pragma unroll
+  for (int r = ty; r < 32; r += 8)
+    if (k0 + r < Cout && c0 + tx < Cin) tile[r][tx] = src[((size_t)(k0 + r) * T + tap) * Cin + c0 + tx];
+  __syncthreads();
+#pragma unroll
+  for (int r = ty; r < 32; r += 8)
+    if (c0 + r < Cin && k0 + tx < Cout) dst[((size_t)(c0 + r) * T + tap) * Cout + k0 + tx] = tile[tx][r];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -553,7 +565,7 @@ int conv_transpose_weights_multi(TransposeTable& t, hipStream_t st) {
   int blocks = 0;
   for (int k = 0; k < t.count; ++k) {
     t.block_begin[k] = blocks;
-    blocks += (t.Cout[k] * t.T[k] * t.Cin[k] + 255) / 256;
+    blocks += t.T[k] * ((t.Cout[k] + 31) / 32) * ((t.Cin[k] + 31) / 32);
   }
   t.block_begin[t.count] = blocks;
   if (blocks == 0) return CNNK_OK;

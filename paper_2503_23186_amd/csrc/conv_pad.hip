@@ -1,0 +1,85 @@
+// Convolutions with fewer than 8 input channels (the 3-channel stem) in bf16 mode: the input and
+// the weights are zero-padded to 8 channels in the workspace so that a pixel's channels form one
+// 16-byte vector, then the bf16 MFMA kernels run on the padded problem.  The layer is bound by
+// the 64-channel side (output write / dy read), so the padded reduction costs nothing.
+#include "common.h"
+#include "conv.h"
+
+namespace {
+
+// dst[m][0..8) = src[m][0..C) followed by zeros
+__global__ void __launch_bounds__(256) pad_channels_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst,
+                                                           size_t rows, int C) {
+  for (size_t m = (size_t)blockIdx.x * 256 + threadIdx.x; m < rows; m += (size_t)gridDim.x * 256) {
+    unsigned short v[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) v[c] = c < C ? src[m * C + c] : (unsigned short)0;
+    uint4 o;
+    o.x = v[0] | (v[1] << 16); o.y = v[2] | (v[3] << 16); o.z = v[4] | (v[5] << 16); o.w = v[6] | (v[7] << 16);
+    *reinterpret_cast<uint4*>(dst + m * 8) = o;
+  }
+}
+
+// dw[row][0..C) = dw8[row][0..C)
+__global__ void __launch_bounds__(256) unpad_dw_kernel(const float* __restrict__ dw8, float* __restrict__ dw, int rows,
+                                                       int C) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= rows * C) return;
+  dw[i] = dw8[(size_t)(i / C) * 8 + i % C];
+}
+
+ConvGeom padded(const ConvGeom& g) {
+  ConvGeom p = g;
+  p.Cin = 8;
+  return p;
+}
+
+inline unsigned pad_blocks(size_t rows) {
+  size_t b = (rows + 255) / 256;
+  return (unsigned)(b > 4096 ? 4096 : (b < 1 ? 1 : b));
+}
+
+size_t x8_bytes(const ConvGeom& g) { return align_up((size_t)g.N * g.H * g.W * 8 * sizeof(bf16_t), 256); }
+size_t w8_bytes(const ConvGeom& g) { return align_up((size_t)g.Cout * g.R * g.S * 8 * sizeof(bf16_t), 256); }
+size_t dw8_bytes(const ConvGeom& g) { return align_up((size_t)g.Cout * g.R * g.S * 8 * sizeof(float), 256); }
+
+}  // namespace
+
+bool conv_pad_supported(const ConvGeom& g) {
+  return g.Cin < 8 && conv_mfma_supported(padded(g), CNNK_PASS_FWD);
+}
+
+size_t conv_pad_ws(const ConvGeom& g, int pass, bool want_stats) {
+  const ConvGeom p = padded(g);
+  if (pass == CNNK_PASS_FWD) return x8_bytes(g) + w8_bytes(g) + conv_mfma_ws(p, pass, want_stats);
+  if (pass == CNNK_PASS_WGRAD) return x8_bytes(g) + dw8_bytes(g) + conv_mfma_ws(p, pass, false);
+  return 0;
+}
+
+int conv_pad_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y, float* ch_sum, float* ch_sumsq,
+                 void* ws, hipStream_t st) {
+  char* base = static_cast<char*>(ws);
+  bf16_t* x8 = reinterpret_cast<bf16_t*>(base);
+  bf16_t* w8 = reinterpret_cast<bf16_t*>(base + x8_bytes(g));
+  void* rest = base + x8_bytes(g) + w8_bytes(g);
+  const size_t px = (size_t)g.N * g.H * g.W, wr = (size_t)g.Cout * g.R * g.S;
+  pad_channels_kernel<<<pad_blocks(px), 256, 0, st>>>(x, x8, px, g.Cin);
+  pad_channels_kernel<<<pad_blocks(wr), 256, 0, st>>>(w, w8, wr, g.Cin);
+  if (launch_status() != CNNK_OK) return CNNK_ERR_HIP;
+  return conv_mfma_fwd(padded(g), x8, w8, y, ch_sum, ch_sumsq, rest, st);
+}
+
+int conv_pad_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws, hipStream_t st) {
+  char* base = static_cast<char*>(ws);
+  bf16_t* x8 = reinterpret_cast<bf16_t*>(base);
+  float* dw8 = reinterpret_cast<float*>(base + x8_bytes(g));
+  void* rest = base + x8_bytes(g) + dw8_bytes(g);
+  const size_t px = (size_t)g.N * g.H * g.W;
+  pad_channels_kernel<<<pad_blocks(px), 256, 0, st>>>(x, x8, px, g.Cin);
+  if (launch_status() != CNNK_OK) return CNNK_ERR_HIP;
+  int rc = conv_mfma_wgrad(padded(g), x8, dy, dw8, rest, st);
+  if (rc != CNNK_OK) return rc;
+  const int rows = g.Cout * g.R * g.S;
+  unpad_dw_kernel<<<(rows * g.Cin + 255) / 256, 256, 0, st>>>(dw8, dw, rows, g.Cin);
+  return launch_status();
+}

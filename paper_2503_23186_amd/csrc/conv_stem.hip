@@ -10,9 +10,16 @@ namespace {
 constexpr int kT = 256;
 constexpr int kMaxK = 28;
 
+// Host-built decode of the reduction index j = (r*S + s)*Cin + c, and magic-number divisors for
+// the pixel index (integer division has no hardware instruction).
+struct StemTab {
+  int r[kMaxK], s[kMaxK], c[kMaxK];
+  FastDiv dWo, dHo;
+};
+
 // Forward: one thread per output position; couts in register chunks of 32; weights in LDS as
 // fp32 [K][Cout], read as broadcast float4.
-__global__ void __launch_bounds__(kT) stem_fwd_kernel(ConvGeom g, const bf16_t* __restrict__ x,
+__global__ void __launch_bounds__(kT) stem_fwd_kernel(ConvGeom g, StemTab tab, const bf16_t* __restrict__ x,
                                                       const bf16_t* __restrict__ w, bf16_t* __restrict__ y) {
   extern __shared__ __align__(16) float wl[];  // [K][Cout]
   const int K = g.R * g.S * g.Cin;
@@ -24,17 +31,16 @@ __global__ void __launch_bounds__(kT) stem_fwd_kernel(ConvGeom g, const bf16_t* 
   const long M = (long)g.N * g.Ho * g.Wo;
   const long m = (long)blockIdx.x * kT + threadIdx.x;
   if (m >= M) return;
-  const int wo = (int)(m % g.Wo);
-  const long q = m / g.Wo;
-  const int ho = (int)(q % g.Ho), n = (int)(q / g.Ho);
+  int q, wo, n, ho;
+  tab.dWo.divmod((int)m, &q, &wo);
+  tab.dHo.divmod(q, &n, &ho);
   float xv[kMaxK];
 #pragma unroll
   for (int j = 0; j < kMaxK; ++j) {
     float v = 0.f;
     if (j < K) {
-      const int c = j % g.Cin, t = j / g.Cin;
-      const int s_ = t % g.S, r = t / g.S;
-      const int hi = ho * g.stride + r - g.pad, wi = wo * g.stride + s_ - g.pad;
+      const int c = tab.c[j];
+      const int hi = ho * g.stride + tab.r[j] - g.pad, wi = wo * g.stride + tab.s[j] - g.pad;
       if ((unsigned)hi < (unsigned)g.H && (unsigned)wi < (unsigned)g.W)
         v = bf16_to_f32(x[(((size_t)n * g.H + hi) * g.W + wi) * g.Cin + c]);
     }
@@ -76,7 +82,7 @@ __global__ void __launch_bounds__(kT) stem_fwd_kernel(ConvGeom g, const bf16_t* 
 constexpr int kSub = 128;
 constexpr int kPixPerBlock = 512;
 
-__global__ void __launch_bounds__(kT) stem_wgrad_kernel(ConvGeom g, const bf16_t* __restrict__ x,
+__global__ void __launch_bounds__(kT) stem_wgrad_kernel(ConvGeom g, StemTab tab, const bf16_t* __restrict__ x,
                                                         const bf16_t* __restrict__ dy, float* __restrict__ part) {
   __shared__ __align__(16) float smem[kT * 32];             // 32 KB
   bf16_t* dyl = reinterpret_cast<bf16_t*>(smem);              // [kSub][64] bf16 = 16 KB
@@ -115,13 +121,11 @@ __global__ void __launch_bounds__(kT) stem_wgrad_kernel(ConvGeom g, const bf16_t
       const int jj = e % 8, j = (e / 8) * 7 + jj;
       float v = 0.f;
       if (jj < 7 && j < K && m0 + p < m_end) {
-        const long m = m0 + p;
-        const int wo = (int)(m % g.Wo);
-        const long q = m / g.Wo;
-        const int ho = (int)(q % g.Ho), n = (int)(q / g.Ho);
-        const int c = j % g.Cin, t = j / g.Cin;
-        const int s = t % g.S, r = t / g.S;
-        const int hi = ho * g.stride + r - g.pad, wi = wo * g.stride + s - g.pad;
+        int q, wo, n, ho;
+        tab.dWo.divmod((int)(m0 + p), &q, &wo);
+        tab.dHo.divmod(q, &n, &ho);
+        const int c = tab.c[j];
+        const int hi = ho * g.stride + tab.r[j] - g.pad, wi = wo * g.stride + tab.s[j] - g.pad;
         if ((unsigned)hi < (unsigned)g.H && (unsigned)wi < (unsigned)g.W)
           v = bf16_to_f32(x[(((size_t)n * g.H + hi) * g.W + wi) * g.Cin + c]);
       }
@@ -165,10 +169,25 @@ __global__ void __launch_bounds__(kT) stem_wgrad_kernel(ConvGeom g, const bf16_t
   }
 }
 
+StemTab make_tab(const ConvGeom& g) {
+  StemTab t{};
+  for (int j = 0; j < g.R * g.S * g.Cin && j < kMaxK; ++j) {
+    t.c[j] = j % g.Cin;
+    t.s[j] = (j / g.Cin) % g.S;
+    t.r[j] = j / g.Cin / g.S;
+  }
+  t.dWo.init(g.Wo);
+  t.dHo.init(g.Ho);
+  return t;
+}
+
 }  // namespace
 
 bool conv_stem_supported(const ConvGeom& g) {
-  return g.R * g.S * g.Cin <= kMaxK && g.Cout % 8 == 0 && g.Cout <= 512;
+  // pixel indices are decoded with magic-number division: index * divisor must stay below 2^32
+  const long M = (long)g.N * g.Ho * g.Wo;
+  return g.R * g.S * g.Cin <= kMaxK && g.Cout % 8 == 0 && g.Cout <= 512 && M * g.Wo < (1L << 32) &&
+         M / g.Wo * g.Ho < (1L << 32) && M < (1L << 31);
 }
 
 size_t conv_stem_wgrad_ws(const ConvGeom& g) {
@@ -180,7 +199,7 @@ size_t conv_stem_wgrad_ws(const ConvGeom& g) {
 int conv_stem_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y, hipStream_t st) {
   const long M = (long)g.N * g.Ho * g.Wo;
   const size_t smem = (size_t)g.R * g.S * g.Cin * g.Cout * sizeof(float);
-  stem_fwd_kernel<<<(unsigned)((M + kT - 1) / kT), kT, smem, st>>>(g, x, w, y);
+  stem_fwd_kernel<<<(unsigned)((M + kT - 1) / kT), kT, smem, st>>>(g, make_tab(g), x, w, y);
   return launch_status();
 }
 
@@ -189,7 +208,7 @@ int conv_stem_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float*
   const int nb = (int)((M + kPixPerBlock - 1) / kPixPerBlock);
   dim3 grid(nb, (g.Cout + 63) / 64);
   float* part = nb > 1 ? reinterpret_cast<float*>(ws) : dw;
-  stem_wgrad_kernel<<<grid, kT, 0, st>>>(g, x, dy, part);
+  stem_wgrad_kernel<<<grid, kT, 0, st>>>(g, make_tab(g), x, dy, part);
   if (launch_status() != CNNK_OK) return CNNK_ERR_HIP;
   if (nb > 1) return reduce_partials(part, dw, g.Cout * g.R * g.S * g.Cin, nb, st);
   return CNNK_OK;

@@ -19,11 +19,20 @@ __global__ void __launch_bounds__(kT) logits_softmax_kernel(const T* __restrict_
   __shared__ int redi[kT / 64];
   const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const T* xr = x + (size_t)n * F;
-  for (int j = wave; j < K; j += kT / 64) {
-    float acc = 0.f;
-    for (int f = lane; f < F; f += 64) acc = fmaf(Elem<T>::ld(xr + f), W[(size_t)j * F + f], acc);
-    acc = wave_sum(acc);
-    if (lane == 0) z[j] = acc + b[j];
+  // four classes per pass of a wave: independent dot products keep several loads in flight
+  for (int j0 = wave * 4; j0 < K; j0 += (kT / 64) * 4) {
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int f = lane; f < F; f += 64) {
+      const float xv = Elem<T>::ld(xr + f);
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (j0 + q < K) acc[q] = fmaf(xv, W[(size_t)(j0 + q) * F + f], acc[q]);
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float s = wave_sum(acc[q]);
+      if (lane == 0 && j0 + q < K) z[j0 + q] = s + b[j0 + q];
+    }
   }
   __syncthreads();
   // max and its lowest index

@@ -45,6 +45,16 @@ def conv_inputs(shape, dtype, seed):
     return x, w, dy, pad
 
 
+@pytest.mark.parametrize("shape", [s for s in CONV_SHAPES if s[3] < 8])
+def test_thin_input_fma_kernels(K, shape):
+    """The plain-FMA kernels for very thin inputs (normally superseded by the padded MFMA path)."""
+    K.cnnk_tune(8, -1)
+    try:
+        test_conv_fwd_dgrad_wgrad(K, shape, "bf16")
+    finally:
+        K.cnnk_tune(8, 0)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("shape", CONV_SHAPES)
 def test_conv_fwd_dgrad_wgrad(K, shape, dtype):

@@ -55,7 +55,8 @@ def test_every_layer_on_oracle_inputs(name, make, cid):
             x, w, dy = acts[L["x"]], P[L["w"]], dacts[L["y"]]
             gx, gw, gdy = dev(x, dtype), dev(w, dtype), dev(dy, dtype)
             gy = torch.empty(acts[L["y"]].shape, dtype=gx.dtype, device="cuda:0")
-            K.cnnk_conv2d_fwd(d, gx, gw, gy)
+            ws, nb = ws_for(K.cnnk_conv2d_workspace_bytes(d, K.PASS_FWD))
+            K.cnnk_conv2d_fwd(d, gx, gw, gy, None, None, ws, nb)
             chk("conv_y", gy, acts[L["y"]], out_tol)
             gdw = torch.empty(w.shape, dtype=torch.float32, device="cuda:0")
             ws, nb = ws_for(K.cnnk_conv2d_workspace_bytes(d, K.PASS_WGRAD))
