@@ -71,6 +71,8 @@ def main():
     ap.add_argument("--timed-steps", type=int, default=5, help="extra steps with per-call HIP events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", action="store_true", help="print the per-call table to stderr")
+    ap.add_argument("--one-stream", action="store_true",
+                    help="keep the weight gradients on the main stream (default: a second stream)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.stderr.write("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)\n")
@@ -87,7 +89,8 @@ def main():
     kw = {"batch": args.batch} if args.batch else {}
     net = WL.build_config(args.config, **kw)
     inp = WL.make_inputs(net, args.config)
-    run = StepRunner(net.layers, net.slots, [p["shape"] for p in net.params], net.dtype, keep_probs=False)
+    run = StepRunner(net.layers, net.slots, [p["shape"] for p in net.params], net.dtype, keep_probs=False,
+                     two_streams=not args.one_stream)
     run.load(inp["x"], inp["labels"], inp["params"], inp["mom"])
     lr, mu, wd = 0.1, 0.9, 0.0
     stream = torch.cuda.current_stream().cuda_stream

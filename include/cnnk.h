@@ -187,6 +187,17 @@ typedef struct cnnk_buffers {
   void* ws; size_t ws_bytes;
   void** events;            /* nullable: hipEvent_t handles for per-call timing, see below */
   int n_events;             /* number of handles in events */
+  /* Optional second stream for the weight gradients (all three or none; ignored while per-call
+   * timing is on).  The weight gradient of a convolution depends only on tensors that are final
+   * when the backward pass reaches the layer, and nothing but the parameter update consumes it,
+   * so it can run beside the rest of the backward pass: the step records ev_fork on `stream`
+   * before each weight gradient and makes aux_stream wait for it, and joins through ev_join
+   * before the update.  aux_stream must not carry other work during the call; both events are
+   * hipEvent_t handles created by the caller (timing may be disabled).  With an aux stream the
+   * workspace must be twice cnnk_train_step_workspace_bytes. */
+  void* aux_stream;
+  void* ev_fork;
+  void* ev_join;
 } cnnk_buffers;
 
 size_t cnnk_train_step_workspace_bytes(const cnnk_layer* layers, int n_layers);

@@ -64,7 +64,8 @@ class Buffers(C.Structure):
                 ("bn_save", C.POINTER(C.c_void_p)), ("bn_running", C.POINTER(C.c_void_p)),
                 ("pool_idx", C.POINTER(C.c_void_p)), ("probs", C.c_void_p),
                 ("ws", C.c_void_p), ("ws_bytes", C.c_size_t),
-                ("events", C.POINTER(C.c_void_p)), ("n_events", C.c_int)]
+                ("events", C.POINTER(C.c_void_p)), ("n_events", C.c_int),
+                ("aux_stream", C.c_void_p), ("ev_fork", C.c_void_p), ("ev_join", C.c_void_p)]
 
 
 def _load():

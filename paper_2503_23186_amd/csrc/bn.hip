@@ -8,7 +8,7 @@
 namespace {
 
 constexpr int kT = 256;
-constexpr int kMaxBlocks = 512;
+constexpr int kMaxBlocks = 2048;
 
 struct RowMap {
   int lanes;   // threads per row = C/8
@@ -17,7 +17,7 @@ struct RowMap {
 
 __host__ __device__ inline int reduce_blocks(size_t m, int C) {
   const int rows = kT / (C / 8);
-  size_t nb = (m + (size_t)rows * 8 - 1) / ((size_t)rows * 8);  // at least 8 rows per thread
+  size_t nb = (m + (size_t)rows * 4 - 1) / ((size_t)rows * 4);  // at least 4 rows per thread
   if (nb > kMaxBlocks) nb = kMaxBlocks;
   if (nb < 1) nb = 1;
   return (int)nb;

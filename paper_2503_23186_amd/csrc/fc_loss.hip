@@ -22,6 +22,7 @@ __global__ void __launch_bounds__(kT) logits_softmax_kernel(const T* __restrict_
   // four classes per pass of a wave: independent dot products keep several loads in flight
   for (int j0 = wave * 4; j0 < K; j0 += (kT / 64) * 4) {
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
     for (int f = lane; f < F; f += 64) {
       const float xv = Elem<T>::ld(xr + f);
 #pragma unroll

@@ -156,7 +156,7 @@ struct GroupTimer {
 extern "C" size_t cnnk_train_step_workspace_bytes(const cnnk_layer* layers, int n_layers) {
   Walk w;
   if (walk_layers(layers, n_layers, -1, -1, &w) != CNNK_OK) return 0;
-  return align_up(w.ws, 256) + kStatBytes + w.wt_bytes;
+  return align_up(align_up(w.ws, 256) + kStatBytes + w.wt_bytes, 256);
 }
 
 extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B, const int* labels, float lr,
@@ -166,7 +166,7 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
   Walk w;
   int rc = walk_layers(L, n, B->n_slots, B->n_params, &w);
   if (rc != CNNK_OK) return rc;
-  if (!B->ws || B->ws_bytes < w.ws + kStatBytes + w.wt_bytes) return CNNK_ERR_WORKSPACE;
+  if (!B->ws || B->ws_bytes < align_up(w.ws, 256) + kStatBytes + w.wt_bytes) return CNNK_ERR_WORKSPACE;
   const bool bf16 = w.dtype == CNNK_BF16;
   for (size_t s = 0; s < w.slot_elems.size(); ++s) {
     if (w.slot_elems[s] == 0) continue;
@@ -197,9 +197,19 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
   float* const stat_base = reinterpret_cast<float*>(B->ws);
   int stat_slot[kStatSlots];   // tensor slot whose sums each buffer holds, -1 = free
   for (int k = 0; k < kStatSlots; ++k) stat_slot[k] = -1;
+  // second stream for the weight gradients (off while per-call timing is requested)
+  const bool timing = B->events && B->n_events >= 2 * cnnk_train_step_event_groups(n);
+  const size_t ws_one = align_up(align_up(w.ws, 256) + kStatBytes + w.wt_bytes, 256);
+  hipStream_t aux = nullptr;
+  if (B->aux_stream && B->ev_fork && B->ev_join && !timing) {
+    if (B->ws_bytes < 2 * ws_one) return CNNK_ERR_WORKSPACE;
+    aux = (hipStream_t)B->aux_stream;
+  }
+  void* const aux_ws = static_cast<char*>(B->ws) + ws_one;
+  const size_t aux_wsb = aux ? B->ws_bytes - ws_one : 0;
   char* const wt_region = static_cast<char*>(B->ws) + kStatBytes;
   void* ws = wt_region + w.wt_bytes;
-  const size_t wsb = B->ws_bytes - kStatBytes - w.wt_bytes;
+  const size_t wsb = (aux ? ws_one : B->ws_bytes) - kStatBytes - w.wt_bytes;
   GroupTimer timer(B, n, stream);
   // ---- forward pass and loss ---------------------------------------------------------------
   for (int i = 0; i < n; ++i) {
@@ -279,7 +289,15 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
     timer.begin(g0);
     switch (l.op) {
       case CNNK_OP_CONV: {
-        rc = cnnk_conv2d_wgrad(&l.d.conv, B->act[l.in0], B->dact[l.out], B->grad[l.p0], ws, wsb, stream);
+        if (aux) {
+          // dy and x are final here: fork the weight gradient onto the second stream
+          if (hipEventRecord((hipEvent_t)B->ev_fork, (hipStream_t)stream) != hipSuccess ||
+              hipStreamWaitEvent(aux, (hipEvent_t)B->ev_fork, 0) != hipSuccess)
+            return CNNK_ERR_HIP;
+          rc = cnnk_conv2d_wgrad(&l.d.conv, B->act[l.in0], B->dact[l.out], B->grad[l.p0], aux_ws, aux_wsb, aux);
+        } else {
+          rc = cnnk_conv2d_wgrad(&l.d.conv, B->act[l.in0], B->dact[l.out], B->grad[l.p0], ws, wsb, stream);
+        }
         timer.end(g0);
         timer.begin(g0 + 1);
         if (rc == CNNK_OK && l.in0 != 0) {
@@ -332,6 +350,11 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
     if (rc != CNNK_OK) return rc;
   }
   // ---- parameter update -----------------------------------------------------------------------
+  if (aux) {
+    if (hipEventRecord((hipEvent_t)B->ev_join, aux) != hipSuccess ||
+        hipStreamWaitEvent((hipStream_t)stream, (hipEvent_t)B->ev_join, 0) != hipSuccess)
+      return CNNK_ERR_HIP;
+  }
   const int g_upd = cnnk_train_step_event_groups(n) - 1;
   timer.begin(g_upd);
   SgdTable t;

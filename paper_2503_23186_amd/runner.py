@@ -23,7 +23,8 @@ def _numel(shape):
 
 
 class StepRunner:
-    def __init__(self, layers, slot_shapes, param_shapes, dtype, device="cuda:0", keep_probs=True):
+    def __init__(self, layers, slot_shapes, param_shapes, dtype, device="cuda:0", keep_probs=True,
+                 two_streams=True):
         """dtype: 'f32' or 'bf16' (storage mode of activations and conv weights)."""
         if not torch.cuda.is_available():
             raise RuntimeError("StepRunner needs a GPU: the HIP path has no CPU fallback")
@@ -90,7 +91,8 @@ class StepRunner:
         self.pred = z((self.N,), torch.int32)
         self.probs = z((self.N, self.classes), torch.float32) if keep_probs else None
         self.ws_bytes = int(cnnk.cnnk_train_step_workspace_bytes(self.c_layers, nl))
-        self.ws = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device=self.dev)
+        self.ws = torch.empty(max(self.ws_bytes, 256) * (2 if two_streams else 1), dtype=torch.uint8,
+                              device=self.dev)
 
         def parr(ts):
             a = (C.c_void_p * len(ts))()
@@ -111,6 +113,11 @@ class StepRunner:
         b.ws_bytes = self.ws.numel()
         b.events = None
         b.n_events = 0
+        # second stream (default priority) + two events for the weight gradients
+        self.aux_stream = torch.cuda.Stream(device=self.dev) if two_streams else None
+        b.aux_stream = self.aux_stream.cuda_stream if two_streams else None
+        b.ev_fork = cnnk.hip_event_create() if two_streams else None
+        b.ev_join = cnnk.hip_event_create() if two_streams else None
         self.buffers = b
         self._events = None
 

@@ -162,3 +162,25 @@ def test_fp32_resnet18_narrow():
     net = WL.resnet18(batch=4, dtype="f32", size=16, widths=(16, 32, 64, 128))
     inp, runner, out = run_both(net, 30)
     check_step(net, inp, runner, out, TOL["f32"])
+
+
+def test_two_streams_match_one_stream():
+    """The weight gradients forked onto a second stream give bit-identical results to the
+    single-stream order, over several consecutive steps (workspace halves and events reused)."""
+    from paper_2503_23186_amd import StepRunner
+    net = WL.mini_resnet(batch=16, dtype="bf16", widths=(64, 128))
+    inp = WL.make_inputs(net, 0)
+    runs = []
+    for two in (False, True):
+        r = StepRunner(net.layers, net.slots, [p["shape"] for p in net.params], net.dtype, two_streams=two)
+        r.load(inp["x"], inp["labels"], inp["params"], inp["mom"])
+        for _ in range(3):
+            r.step(0.1, 0.9, 1e-4)
+        torch.cuda.synchronize()
+        runs.append(r)
+    a, b = runs
+    assert a.loss.item() == b.loss.item()
+    for k in range(len(net.params)):
+        assert torch.equal(a.grad[k], b.grad[k]), "grad %d" % k
+        assert torch.equal(a.param[k], b.param[k]), "param %d" % k
+        assert torch.equal(a.mom[k], b.mom[k]), "mom %d" % k
