@@ -23,6 +23,10 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 def layer_key(L, phase):
     if L["op"] == "conv":
+        # the forward and input-gradient calls of a 3x3 stride-1 convolution with Cin == Cout are
+        # launches of one kernel on one grid (operands swapped): one class
+        if phase in ("fwd", "dgrad") and L["R"] == 3 and L["stride"] == 1 and L["Cin"] == L["Cout"] and L["Cin"] % 64 == 0:
+            phase = "fwd+dgrad (patch_kernel)"
         return "conv%dx%d s%d %d->%d @%d %s" % (L["R"], L["S"], L["stride"], L["Cin"], L["Cout"], L["H"], phase)
     if L["op"] == "bn":
         return "bn%s%s C%d @%d %s" % ("+res" if L["res"] >= 0 else "", "+relu" if L["relu"] else "", L["C"], L["H"], phase)

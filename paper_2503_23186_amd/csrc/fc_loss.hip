@@ -12,27 +12,66 @@ template <typename T>
 __global__ void __launch_bounds__(kT) logits_softmax_kernel(const T* __restrict__ x, const float* __restrict__ W,
                                                             const float* __restrict__ b,
                                                             const int* __restrict__ labels, int N, int F, int K,
-                                                            float* __restrict__ dz, float* __restrict__ loss_n,
+                                                            int vec, float* __restrict__ dz, float* __restrict__ loss_n,
                                                             int* __restrict__ pred, float* __restrict__ probs) {
   __shared__ float z[kMaxClasses];
   __shared__ float red[kT / 64];
   __shared__ int redi[kT / 64];
   const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const T* xr = x + (size_t)n * F;
-  // four classes per pass of a wave: independent dot products keep several loads in flight
-  for (int j0 = wave * 4; j0 < K; j0 += (kT / 64) * 4) {
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 8
-    for (int f = lane; f < F; f += 64) {
-      const float xv = Elem<T>::ld(xr + f);
+  if (vec) {
+    // F % 8 == 0 and F <= 1024: the sample's features stay in registers (8 consecutive per lane
+    // and 512-feature chunk), weight rows stream in as 32-byte pieces, four classes in flight
+    float xv[2][8];
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-        if (j0 + q < K) acc[q] = fmaf(xv, W[(size_t)(j0 + q) * F + f], acc[q]);
+    for (int c = 0; c < 2; ++c) {
+      const int f0 = (lane + 64 * c) * 8;
+      if (f0 < F) load8(xr + f0, xv[c]);
+      else
+#pragma unroll
+        for (int e = 0; e < 8; ++e) xv[c][e] = 0.f;
     }
+    for (int j0 = wave; j0 < K; j0 += 4 * (kT / 64)) {
+      float acc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const float s = wave_sum(acc[q]);
-      if (lane == 0 && j0 + q < K) z[j0 + q] = s + b[j0 + q];
+      for (int q = 0; q < 4; ++q) {
+        const int j = j0 + q * (kT / 64);
+        if (j < K) {
+#pragma unroll
+          for (int c = 0; c < 2; ++c) {
+            const int f0 = (lane + 64 * c) * 8;
+            if (f0 < F) {
+              float wv[8];
+              load8(W + (size_t)j * F + f0, wv);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) acc[q] = fmaf(xv[c][e], wv[e], acc[q]);
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int j = j0 + q * (kT / 64);
+        const float sq = wave_sum(acc[q]);
+        if (lane == 0 && j < K) z[j] = sq + b[j];
+      }
+    }
+  } else {
+    // four classes per pass of a wave: independent dot products keep several loads in flight
+    for (int j0 = wave * 4; j0 < K; j0 += (kT / 64) * 4) {
+      float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+      for (int f = lane; f < F; f += 64) {
+        const float xv = Elem<T>::ld(xr + f);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (j0 + q < K) acc[q] = fmaf(xv, W[(size_t)(j0 + q) * F + f], acc[q]);
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float sq = wave_sum(acc[q]);
+        if (lane == 0 && j0 + q < K) z[j0 + q] = sq + b[j0 + q];
+      }
     }
   }
   __syncthreads();
@@ -113,6 +152,50 @@ __global__ void __launch_bounds__(kT) fc_dw_db_kernel(const float* __restrict__ 
   if (tid == 0) db[j] = red[0];
 }
 
+// The same for F % 8 == 0: wave w takes the samples n = w, w+4, ..., a lane 8 consecutive features
+// (16- or 32-byte loads); the four per-wave sums are combined through LDS in wave order.
+template <typename T>
+__global__ void __launch_bounds__(kT) fc_dw_db_vec_kernel(const float* __restrict__ dz, const T* __restrict__ x,
+                                                          int N, int F, int K, float* __restrict__ dW,
+                                                          float* __restrict__ db) {
+  __shared__ float part[kT / 64][512];
+  __shared__ float red[kT];
+  const int j = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int fb = 0; fb < F; fb += 512) {
+    const int f0 = fb + lane * 8;
+    float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (f0 < F) {
+#pragma unroll 4
+      for (int n = wave; n < N; n += kT / 64) {
+        float xv[8];
+        load8(x + (size_t)n * F + f0, xv);
+        const float g = dz[(size_t)n * K + j];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a[e] = fmaf(g, xv[e], a[e]);
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) part[wave][lane * 8 + e] = a[e];
+    __syncthreads();
+    for (int f = tid; f < 512 && fb + f < F; f += kT) {
+      float sum = part[0][f];
+#pragma unroll
+      for (int w = 1; w < kT / 64; ++w) sum += part[w][f];
+      dW[(size_t)j * F + fb + f] = sum;
+    }
+    __syncthreads();
+  }
+  float sacc = 0.f;
+  for (int n = tid; n < N; n += kT) sacc += dz[(size_t)n * K + j];
+  red[tid] = sacc;
+  __syncthreads();
+  for (int o = kT / 2; o > 0; o >>= 1) {
+    if (tid < o) red[tid] += red[tid + o];
+    __syncthreads();
+  }
+  if (tid == 0) db[j] = red[0];
+}
+
 // dx[n][f] = sum_j dz[n][j] * W[j][f]
 template <typename T>
 __global__ void __launch_bounds__(kT) fc_dx_kernel(const float* __restrict__ dz, const float* __restrict__ W, int N,
@@ -150,15 +233,22 @@ extern "C" int cnnk_fc_softmax_xent(const cnnk_fc_desc* d, const void* x, const 
   float* dz = (float*)ws;
   float* loss_n = dz + (size_t)N * K;
   dim3 gx((F + kT - 1) / kT, N);
+  const int vec = (F % 8 == 0 && F <= 1024) ? 1 : 0;
   if (d->dtype == CNNK_BF16) {
-    logits_softmax_kernel<bf16_t><<<N, kT, 0, st>>>((const bf16_t*)x, W, b, labels, N, F, K, dz, loss_n, pred, probs);
+    logits_softmax_kernel<bf16_t><<<N, kT, 0, st>>>((const bf16_t*)x, W, b, labels, N, F, K, vec, dz, loss_n, pred, probs);
     loss_kernel<<<1, kT, 0, st>>>(loss_n, N, loss);
-    fc_dw_db_kernel<bf16_t><<<K, kT, 0, st>>>(dz, (const bf16_t*)x, N, F, K, dW, db);
+    if (F % 8 == 0)
+      fc_dw_db_vec_kernel<bf16_t><<<K, kT, 0, st>>>(dz, (const bf16_t*)x, N, F, K, dW, db);
+    else
+      fc_dw_db_kernel<bf16_t><<<K, kT, 0, st>>>(dz, (const bf16_t*)x, N, F, K, dW, db);
     fc_dx_kernel<bf16_t><<<gx, kT, 0, st>>>(dz, W, N, F, K, (bf16_t*)dx);
   } else {
-    logits_softmax_kernel<float><<<N, kT, 0, st>>>((const float*)x, W, b, labels, N, F, K, dz, loss_n, pred, probs);
+    logits_softmax_kernel<float><<<N, kT, 0, st>>>((const float*)x, W, b, labels, N, F, K, vec, dz, loss_n, pred, probs);
     loss_kernel<<<1, kT, 0, st>>>(loss_n, N, loss);
-    fc_dw_db_kernel<float><<<K, kT, 0, st>>>(dz, (const float*)x, N, F, K, dW, db);
+    if (F % 8 == 0)
+      fc_dw_db_vec_kernel<float><<<K, kT, 0, st>>>(dz, (const float*)x, N, F, K, dW, db);
+    else
+      fc_dw_db_kernel<float><<<K, kT, 0, st>>>(dz, (const float*)x, N, F, K, dW, db);
     fc_dx_kernel<float><<<gx, kT, 0, st>>>(dz, W, N, F, K, (float*)dx);
   }
   return launch_status();
