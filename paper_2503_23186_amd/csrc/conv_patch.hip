@@ -26,7 +26,7 @@ struct PatchArgs {
   float* stats;       // nullable: [2][Cd][mtiles]
   int N, H, W, Cs, Cd;
   int TI, TH;         // tile = TI images x TH rows x W columns (BM pixels)
-  int accumulate, ntiles, mtiles, dbg;
+  int accumulate, ntiles, mtiles;
   int toff_h[9], toff_w[9], widx[9];  // patch offset (0..2, 0..2) and weight tap of each step
   FastDiv dPW, dPH, dW, dTH;          // divisors used to decode tile-local pixel indices (< 2^16)
 };
@@ -39,7 +39,7 @@ __device__ __forceinline__ int swz_off(int row, int chunk) { return row * 64 + (
 // PL: 16-byte patch loads per thread, i.e. the patch holds at most PL * 64 pixels.
 //
 // Software pipeline (u = chunk*9 + tap is the step index; a step is one tap of one chunk):
-//   weights: global load of step u+4 -> register set (u+1)%3 ... stored to LDS ring slot (u+2)%3 at
+//   weights: global load of step u+DL -> a register set ... stored to LDS ring slot (u+2)%3 at
 //            the end of step u, so that at step u the ring holds steps u and u+1;
 //   patch:   chunk c+1 is loaded at tap 0 of chunk c and stored to the other patch buffer at tap 6;
 //   MFMA operands of step u+1 are read from LDS into the second fragment set while the MFMAs of
@@ -73,14 +73,13 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
 
   const int kc = tid & 3;
   unsigned poff[PL];   // global byte offset of each staged patch chunk (kOobOffset: zero fill)
-  int pst[PL];         // its LDS byte offset inside a patch buffer (-1: not staged)
+  // its LDS byte offset inside a patch buffer is pst0 + j * 64 rows (the swizzle repeats every 16 rows)
+  const int pst0 = swz_off(tid >> 2, kc);
 #pragma unroll
   for (int j = 0; j < PL; ++j) {
     const int pp = (tid >> 2) + j * (kThreads / 4);
     poff[j] = kOobOffset;
-    pst[j] = -1;
     if (pp < patch_px) {
-      pst[j] = swz_off(pp, kc);
       int q, pw, ti, ph;
       a.dPW.divmod(pp, &q, &pw);
       a.dPH.divmod(q, &ti, &ph);
@@ -88,7 +87,6 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
       if (n < a.N && (unsigned)hs < (unsigned)a.H && (unsigned)ws < (unsigned)a.W)
         poff[j] = (unsigned)(((n * a.H + hs) * a.W + ws) * a.Cs + kc * 8) * 2u;
     }
-    if (a.dbg & 1) poff[j] = kOobOffset;
   }
   const int r0 = tid >> 2;  // weight row of this thread inside a 64-row pass
   unsigned boff[B_IT];
@@ -97,7 +95,6 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   for (int it = 0; it < B_IT; ++it) {
     const int row = r0 + it * 64, ch = nt * BN + row;
     boff[it] = (row < BN && ch < a.Cd) ? (unsigned)(ch * 9 * a.Cs + kc * 8) * 2u : kOobOffset;
-    if (a.dbg & 2) boff[it] = kOobOffset;
     bst[it] = swz_off(row, kc);
   }
   // patch pixel (tap (0,0)) under each of this lane's output rows, and the weight-row offsets
@@ -125,7 +122,11 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
 
   const int nchunks = a.Cs / CK;
   uint4 preg[PL];
-  uint4 rb[3][B_IT];
+  // weight prefetch: with one 16-byte load per thread and step (BN <= 64) there is a register set
+  // per tap and the load runs a whole chunk (9 steps) ahead, which covers the L2/HBM latency;
+  // wider tiles keep 3 sets and a distance of 4 steps
+  constexpr int NS = B_IT == 1 ? 9 : 3, DL = B_IT == 1 ? 9 : 4;
+  uint4 rb[NS][B_IT];
   bf16x8_t af[2][TM][KK], bfr[2][TN][KK];
 
   auto load_patch = [&](int chunk) {
@@ -135,19 +136,21 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   auto store_patch = [&](int buf) {
 #pragma unroll
     for (int j = 0; j < PL; ++j)
-      if (pst[j] >= 0) *reinterpret_cast<uint4*>(Pb + buf * patch_bytes + pst[j]) = preg[j];
+      if ((tid >> 2) + j * (kThreads / 4) < patch_px)
+        *reinterpret_cast<uint4*>(Pb + buf * patch_bytes + pst0 + j * (kThreads / 4) * 64) = preg[j];
   };
-  auto load_b = [&](int chunk, auto TAP) {   // weights of step (chunk, TAP) -> register set TAP % 3
-    constexpr int tap = decltype(TAP)::value, rs = tap % 3;
+  auto load_b = [&](int chunk, auto TAP) {   // weights of step (chunk, TAP) -> register set TAP % NS
+    constexpr int tap = decltype(TAP)::value, rs = tap % NS;
     const unsigned so = (unsigned)(a.widx[tap] * a.Cs + chunk * CK) * 2u;
 #pragma unroll
     for (int it = 0; it < B_IT; ++it) rb[rs][it] = buffer_load16(wt_rs, boff[it], so);
   };
-  auto store_b = [&](auto TAP) {             // register set TAP % 3 -> ring slot TAP % 3
-    constexpr int rs = decltype(TAP)::value % 3;
+  auto store_b = [&](auto TAP) {             // register set TAP % NS -> ring slot TAP % 3
+    constexpr int rs = decltype(TAP)::value % NS, slot = decltype(TAP)::value % 3;
 #pragma unroll
     for (int it = 0; it < B_IT; ++it)
-      if (r0 + it * 64 < BN) *reinterpret_cast<uint4*>(Bb + rs * (BN * 64) + bst[it]) = rb[rs][it];
+      if (BN % 64 == 0 || r0 + it * 64 < BN)
+        *reinterpret_cast<uint4*>(Bb + slot * (BN * 64) + bst[it]) = rb[rs][it];
   };
   // MFMA operands of tap TAP from patch buffer `pbuf` and ring slot TAP % 3 into fragment set SET
   auto read_frags = [&](int pbuf, auto TAP, auto SET) {
@@ -178,36 +181,33 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[fs][i][kk], bfr[fs][j][kk], acc[i][j], 0, 0, 0);
   };
-  // PAR = chunk % 2: patch buffer of this chunk, and the parity that fixes the fragment set
+  // PAR = chunk % 2: patch buffer of this chunk, and the parity that fixes the fragment set.
+  // Nothing in a step is conditional on "is there another chunk": past the last chunk the loads
+  // fetch in-range or zero-filled bytes that land in LDS slots nobody reads any more.  Straight
+  // line code lets the compiler count the loads in flight exactly, so every wait is for the
+  // oldest load only.
   auto step = [&](int chunk, auto PARC, auto TAP) {
     constexpr int par = decltype(PARC)::value, tap = decltype(TAP)::value;
     constexpr int cur = (par + tap) % 2;
-    const bool more = chunk + 1 < nchunks;
-    if constexpr (tap + 4 < 9) {
-      load_b(chunk, std::integral_constant<int, tap + 4>{});
+    if constexpr (tap + DL < 9) {
+      load_b(chunk, std::integral_constant<int, tap + DL>{});
     } else {
-      if (more) load_b(chunk + 1, std::integral_constant<int, tap + 4 - 9>{});
+      load_b(chunk + 1, std::integral_constant<int, tap + DL - 9>{});
     }
-    if constexpr (tap == 0) {
-      if (more) load_patch(chunk + 1);
-    }
-    if (!(a.dbg & 8)) {
+    if constexpr (tap == 0) load_patch(chunk + 1);
     if constexpr (tap + 1 < 9) {
       read_frags(par, std::integral_constant<int, tap + 1>{}, std::integral_constant<int, cur ^ 1>{});
     } else {
-      if (more) read_frags(par ^ 1, std::integral_constant<int, 0>{}, std::integral_constant<int, cur ^ 1>{});
+      read_frags(par ^ 1, std::integral_constant<int, 0>{}, std::integral_constant<int, cur ^ 1>{});
     }
-    }
-    if (!(a.dbg & 16)) mfmas(std::integral_constant<int, cur>{});
+    mfmas(std::integral_constant<int, cur>{});
     if constexpr (tap + 2 < 9) {
       store_b(std::integral_constant<int, tap + 2>{});
     } else {
-      if (more) store_b(std::integral_constant<int, tap + 2 - 9>{});
+      store_b(std::integral_constant<int, tap + 2 - 9>{});
     }
-    if constexpr (tap == 6) {
-      if (more) store_patch(par ^ 1);
-    }
-    if (!(a.dbg & 4)) __syncthreads();
+    if constexpr (tap == 6) store_patch(par ^ 1);
+    __syncthreads();
   };
   auto chunk_body = [&](int chunk, auto PARC) {
     step(chunk, PARC, std::integral_constant<int, 0>{});
@@ -225,10 +225,18 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   load_b(0, std::integral_constant<int, 0>{});
   load_b(0, std::integral_constant<int, 1>{});
   load_b(0, std::integral_constant<int, 2>{});
+  if constexpr (NS == 9) {
+    load_b(0, std::integral_constant<int, 3>{});
+    load_b(0, std::integral_constant<int, 4>{});
+    load_b(0, std::integral_constant<int, 5>{});
+    load_b(0, std::integral_constant<int, 6>{});
+    load_b(0, std::integral_constant<int, 7>{});
+    load_b(0, std::integral_constant<int, 8>{});
+  }
   store_patch(0);
   store_b(std::integral_constant<int, 0>{});
   store_b(std::integral_constant<int, 1>{});
-  load_b(0, std::integral_constant<int, 3>{});   // register set 0 is free again
+  if constexpr (NS == 3) load_b(0, std::integral_constant<int, 3>{});   // register set 0 is free again
   __syncthreads();
   read_frags(0, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
   for (int chunk = 0; chunk < nchunks; chunk += 2) {
@@ -274,7 +282,6 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
     __syncthreads();
   }
 
-  if (a.dbg & 64) return;
   bf16_t* Ct = reinterpret_cast<bf16_t*>(smem_raw);
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -290,7 +297,7 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   for (int idx = tid; idx < BM * (BN / 8); idx += kThreads) {
     const int row = idx / (BN / 8), ch = idx % (BN / 8);
     const int m = m0 + row, co = nt * BN + ch * 8;
-    if (m >= M || co >= a.Cd || (a.dbg & 32)) continue;
+    if (m >= M || co >= a.Cd) continue;
     bf16_t* dp = a.dst + (size_t)m * a.Cd + co;
     if (a.accumulate) {
       float o[8], nw[8];
@@ -356,7 +363,7 @@ bool plan_patch(const ConvGeom& g, int Cs, int Cd, PatchPlan* p) {
   const long M = (long)g.N * g.H * g.W;
   // Candidates in order of preference (the larger the pixel tile, the less weight traffic):
   // the first one that gives every CU a workgroup, else the one with the most workgroups.
-  const int cand[4][3] = {{256, 64, 10}, {128, 128, 5}, {128, 64, 5}, {256, 128, 6}};  // BM, BN, PL (last: forced only)
+  const int cand[4][3] = {{256, 64, 7}, {128, 128, 5}, {128, 64, 5}, {256, 128, 6}};  // BM, BN, PL (last: forced only)
   int best = -1;
   long best_blocks = 0;
   for (int k = 0; k < 4; ++k) {
@@ -377,10 +384,11 @@ bool plan_patch(const ConvGeom& g, int Cs, int Cd, PatchPlan* p) {
 
 int run_patch(const ConvGeom& g, PatchArgs& a, const PatchPlan& p, hipStream_t st) {
   a.TI = p.ti; a.TH = p.th;
-  a.dbg = g_cnnk_tune[7];
   a.dPW.init(a.W + 2); a.dPH.init(a.TH + 2); a.dW.init(a.W); a.dTH.init(a.TH);
   if (p.bm == 256 && p.bn == 128) return launch_patch<256, 128, 2, 2, 2, 6>(a, st);
-  if (p.bm == 256 && p.bn == 64) return launch_patch<256, 64, 4, 1, 2, 10>(a, st);
+  if (p.bm == 256 && p.bn == 64)
+    return a.TI * (a.TH + 2) * (a.W + 2) <= 6 * kPxPerLoad ? launch_patch<256, 64, 4, 1, 2, 6>(a, st)
+                                                            : launch_patch<256, 64, 4, 1, 2, 7>(a, st);
   if (p.bm == 128 && p.bn == 128) return launch_patch<128, 128, 2, 2, 2, 5>(a, st);
   if (p.bm == 128 && p.bn == 64) return launch_patch<128, 64, 4, 1, 3, 5>(a, st);
   (void)g;
