@@ -113,12 +113,18 @@ __global__ void __launch_bounds__(kThreads, OCC) igemm_kernel(IgemmArgs a) {
   using S0 = std::integral_constant<int, 0>;
   using S1 = std::integral_constant<int, 1>;
 
-  auto load_stage = [&](int s, auto SET) {
+  // Loads are issued in stage order, so the (tap, channel chunk) of the next stage is a running
+  // pair; a stage past the last one still issues its loads, all at the out-of-range offset (they
+  // return zeros without touching memory).  Unconditional loads and stores keep the main loop free
+  // of divergent joins, which lets the compiler wait for exactly the oldest loads in flight.
+  int ld_tap = 0, ld_chunk = 0;
+  auto load_stage = [&](auto SET) {
     constexpr int rs = decltype(SET)::value;
-    const int t = tap0 + s / cchunks;
-    const int c0 = (s % cchunks) * BK;
+    const bool live = ld_tap < ntap;
+    const int t = live ? tap0 + ld_tap : 0;
+    const int c0 = ld_chunk * BK;
     const int dh = a.tt.dh[t], dw = a.tt.dw[t], wi = a.tt.widx[t];
-    const bool cok = c0 + kc * 8 < a.Cs;                       // ragged last channel chunk
+    const bool cok = live && c0 + kc * 8 < a.Cs;               // ragged last channel chunk
     const int tap_off = ((dh * a.Ws + dw) * a.Cs + c0) * 2;   // uniform
 #pragma unroll
     for (int it = 0; it < A_IT; ++it) {
@@ -128,15 +134,18 @@ __global__ void __launch_bounds__(kThreads, OCC) igemm_kernel(IgemmArgs a) {
     const unsigned so = (unsigned)(wi * a.Cs + c0) * 2u;
 #pragma unroll
     for (int it = 0; it < B_IT; ++it) rb[rs][it] = buffer_load16(wt_rs, cok ? b_off[it] : kOobOffset, so);
+    if (++ld_chunk == cchunks) { ld_chunk = 0; ++ld_tap; }
   };
   auto store_stage = [&](int buf, auto SET) {
     constexpr int rs = decltype(SET)::value;
 #pragma unroll
     for (int it = 0; it < A_IT; ++it)
-      if (r0 + it * RPP < BM) *reinterpret_cast<uint4*>(As + (buf * BM + r0 + it * RPP) * LDK + kc * 8) = ra[rs][it];
+      if (BM % RPP == 0 || r0 + it * RPP < BM)
+        *reinterpret_cast<uint4*>(As + (buf * BM + r0 + it * RPP) * LDK + kc * 8) = ra[rs][it];
 #pragma unroll
     for (int it = 0; it < B_IT; ++it)
-      if (r0 + it * RPP < BN) *reinterpret_cast<uint4*>(Bs + (buf * BN + r0 + it * RPP) * LDK + kc * 8) = rb[rs][it];
+      if (BN % RPP == 0 || r0 + it * RPP < BN)
+        *reinterpret_cast<uint4*>(Bs + (buf * BN + r0 + it * RPP) * LDK + kc * 8) = rb[rs][it];
   };
   auto compute = [&](int cur) {
     const bf16_t* Ab = As + (cur * BM + wm * TM * 32 + (lane & 31)) * LDK + (lane >> 5) * 8;
@@ -156,19 +165,19 @@ __global__ void __launch_bounds__(kThreads, OCC) igemm_kernel(IgemmArgs a) {
     }
   };
 
-  if (nstage > 0) load_stage(0, S0{});
-  if (nstage > 1) load_stage(1, S1{});
-  if (nstage > 0) store_stage(0, S0{});
+  load_stage(S0{});
+  load_stage(S1{});
+  store_stage(0, S0{});
   __syncthreads();
   for (int s = 0; s < nstage; s += 2) {
-    if (s + 2 < nstage) load_stage(s + 2, S0{});
+    load_stage(S0{});       // stage s + 2
     compute(0);
-    if (s + 1 < nstage) store_stage(1, S1{});
+    store_stage(1, S1{});   // stage s + 1 (zeros past the end, into the buffer nobody reads)
     __syncthreads();
     if (s + 1 >= nstage) break;
-    if (s + 3 < nstage) load_stage(s + 3, S1{});
+    load_stage(S1{});       // stage s + 3
     compute(1);
-    if (s + 2 < nstage) store_stage(0, S0{});
+    store_stage(0, S0{});   // stage s + 2
     __syncthreads();
   }
 
