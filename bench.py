@@ -75,6 +75,8 @@ def main():
     ap.add_argument("--timed-steps", type=int, default=5, help="extra steps with per-call HIP events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", action="store_true", help="print the per-call table to stderr")
+    ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
+                    help="kernel-selection override passed to cnnk_tune (experiments; not a bench line)")
     ap.add_argument("--one-stream", action="store_true",
                     help="keep the weight gradients on the main stream (default: a second stream)")
     args = ap.parse_args()
@@ -90,6 +92,10 @@ def main():
     if not torch.cuda.is_available():
         sys.stderr.write("bench.py needs a GPU (there is no CPU fallback)\n")
         sys.exit(2)
+    for kv in args.tune:
+        from paper_2503_23186_amd import cnnk
+        k, v = kv.split("=")
+        cnnk.cnnk_tune(int(k), int(v))
     kw = {"batch": args.batch} if args.batch else {}
     net = WL.build_config(args.config, **kw)
     inp = WL.make_inputs(net, args.config)

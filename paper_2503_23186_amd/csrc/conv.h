@@ -76,6 +76,11 @@ int conv_stem_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float*
 int channel_sums_finalize(const float* part, int nb, int C, float* ch_sum, float* ch_sumsq, hipStream_t st);
 
 extern int g_cnnk_tune[16];
+// Compute units the weight-gradient kernels size their grids for (256 = the whole device).  The
+// training step lowers it for the weight gradients it runs on its second stream, beside the rest
+// of the backward pass: fewer, longer-lived workgroups leave the other stream room to run.
+// Workspace sizes are always computed for the whole device (the upper bound).
+extern thread_local int t_cnnk_wgrad_cus;
 
 // per-channel sum / sum of squares of a tensor with C channels (used when the conv kernel
 // itself does not produce them)

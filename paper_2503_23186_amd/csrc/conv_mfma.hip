@@ -15,6 +15,7 @@
 #include "conv.h"
 
 int g_cnnk_tune[16] = {0};
+thread_local int t_cnnk_wgrad_cus = 256;
 
 namespace {
 
@@ -498,12 +499,12 @@ int dispatch_igemm(const IgemmArgs& a, long maxM, const IgemmPlan& p, hipStream_
   return CNNK_ERR_UNSUPPORTED;
 }
 
-void wgrad_plan(const ConvGeom& g, int* bmk, int* chunk, int* splits) {
+void wgrad_plan(const ConvGeom& g, int* bmk, int* chunk, int* splits, int cus = 256) {
   const int Q = g.R * g.S * g.Cin;
   const long M = (long)g.N * g.Ho * g.Wo;
   *bmk = g.Cout > 64 ? 128 : 64;
   const long tiles = (long)((g.Cout + *bmk - 1) / *bmk) * ((Q + 127) / 128);
-  const long target = g_cnnk_tune[3] > 0 ? g_cnnk_tune[3] : (g.Cout <= 64 ? 768 : 384);
+  const long target = g_cnnk_tune[3] > 0 ? g_cnnk_tune[3] : 3L * cus / (g.Cout <= 64 ? 1 : 2);   // 768 / 384 workgroups on the whole device
   long want = (target + tiles - 1) / tiles;
   const long maxs = (M + 255) / 256;
   if (want > maxs) want = maxs;
@@ -635,7 +636,7 @@ int conv_mfma_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float*
                     hipStream_t st) {
   if (conv_wgrad_patch_supported(g)) return conv_wgrad_patch(g, x, dy, dw, ws, st);
   int bmk, chunk, splits;
-  wgrad_plan(g, &bmk, &chunk, &splits);
+  wgrad_plan(g, &bmk, &chunk, &splits, t_cnnk_wgrad_cus);
   WgradArgs a{};
   a.x = x; a.dy = dy;
   a.part = splits > 1 ? reinterpret_cast<float*>(ws) : dw;

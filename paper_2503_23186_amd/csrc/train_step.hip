@@ -9,6 +9,9 @@
 
 namespace {
 
+// grid budget (in compute units) of a weight gradient that runs beside the backward pass: measured
+// optimum on ResNet-18 b256 (96..128 are within 1 %, 64 and 192 are 3 % slower)
+constexpr int kAuxWgradCus = 112;
 constexpr int kStatSlots = 4;   // convolutions whose per-channel sums may be pending at once
 constexpr size_t kStatBytes = kStatSlots * 2 * 2048 * sizeof(float);
 
@@ -294,7 +297,9 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
           if (hipEventRecord((hipEvent_t)B->ev_fork, (hipStream_t)stream) != hipSuccess ||
               hipStreamWaitEvent(aux, (hipEvent_t)B->ev_fork, 0) != hipSuccess)
             return CNNK_ERR_HIP;
+          t_cnnk_wgrad_cus = kAuxWgradCus;
           rc = cnnk_conv2d_wgrad(&l.d.conv, B->act[l.in0], B->dact[l.out], B->grad[l.p0], aux_ws, aux_wsb, aux);
+          t_cnnk_wgrad_cus = 256;
         } else {
           rc = cnnk_conv2d_wgrad(&l.d.conv, B->act[l.in0], B->dact[l.out], B->grad[l.p0], ws, wsb, stream);
         }

@@ -165,22 +165,26 @@ def test_fp32_resnet18_narrow():
 
 
 def test_two_streams_match_one_stream():
-    """The weight gradients forked onto a second stream give bit-identical results to the
-    single-stream order, over several consecutive steps (workspace halves and events reused)."""
+    """The weight gradients forked onto a second stream give the results of the single-stream
+    order over several consecutive steps (workspace halves and events reused).  The forked
+    weight gradients split their pixel range over fewer workgroups, so the fp32 partial sums are
+    grouped differently: equal up to fp32 rounding, and each mode is bit-reproducible."""
     from paper_2503_23186_amd import StepRunner
     net = WL.mini_resnet(batch=16, dtype="bf16", widths=(64, 128))
     inp = WL.make_inputs(net, 0)
     runs = []
-    for two in (False, True):
+    for two in (False, True, True):
         r = StepRunner(net.layers, net.slots, [p["shape"] for p in net.params], net.dtype, two_streams=two)
         r.load(inp["x"], inp["labels"], inp["params"], inp["mom"])
         for _ in range(3):
             r.step(0.1, 0.9, 1e-4)
         torch.cuda.synchronize()
         runs.append(r)
-    a, b = runs
-    assert a.loss.item() == b.loss.item()
+    a, b, c = runs
+    assert abs(a.loss.item() - b.loss.item()) <= 1e-5 * abs(a.loss.item())
     for k in range(len(net.params)):
-        assert torch.equal(a.grad[k], b.grad[k]), "grad %d" % k
-        assert torch.equal(a.param[k], b.param[k]), "param %d" % k
-        assert torch.equal(a.mom[k], b.mom[k]), "mom %d" % k
+        for name in ("grad", "param", "mom"):
+            ta, tb, tc = (getattr(r, name)[k] for r in (a, b, c))
+            assert torch.equal(tb, tc), "%s %d differs between two identical runs" % (name, k)
+            scale = ta.abs().max().item() + 1e-30
+            assert (ta - tb).abs().max().item() <= 1e-4 * scale, "%s %d" % (name, k)
