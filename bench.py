@@ -17,6 +17,12 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
+# counters read for a plain copy of known size (summary and commands under profiles/); None for a
+# class that was not measured.
+MEASURED_TRAFFIC_BYTES = {
+    "conv3x3 s1 64->64 @32 fwd+dgrad (patch_kernel)": 66294 * 1024,
+}
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
@@ -161,7 +167,9 @@ def main():
     if dom["op"] == "conv":
         ach = dom["flops"] / dom["avg_ms"] / 1e9
         roof = dict(bound="mfma", kernel=dom["key"], achieved=round(ach, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                    frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None, avg_ms=round(dom["avg_ms"], 4),
+                    frac=round(ach / PEAK_BF16_TFLOPS, 4),
+                    traffic=MEASURED_TRAFFIC_BYTES.get(dom["key"]) if args.config == 3 and not args.batch else None,
+                    avg_ms=round(dom["avg_ms"], 4),
                     calls_per_step=dom["calls_per_step"])
     else:
         ach = dom["bytes"] / dom["avg_ms"] / 1e6
