@@ -60,7 +60,8 @@ const char* cnnk_version(void);
  * number of workgroups of the weight-gradient kernel; 4/5 = pixel / channel tile of the 3x3
  * stride-1 LDS-patch kernels (4 = -1 switches them off); 6 = target number of workgroups of
  * the 3x3 stride-1 weight-gradient kernel (-1 switches it off); 8 = -1 keeps convolutions with
- * fewer than 8 input channels on the plain-FMA kernels.  Process-wide, not thread-safe. */
+ * fewer than 8 input channels on the plain-FMA kernels; 9 = -1 makes cnnk_train_step hand y to
+ * every batch-norm backward call (no mask recomputation).  Process-wide, not thread-safe. */
 int cnnk_tune(int key, int value);
 
 /* ---- convolution (Algorithm 1: forward pass / backward pass of a conv layer) -------------- */
@@ -109,9 +110,14 @@ int cnnk_bn_relu_fwd(const cnnk_bn_desc* d, const void* x, const void* residual,
 /* dz = dy*[y>0] (strict; dz = dy without ReLU); dbeta = sum dz; dgamma = sum dz*xhat;
  * dx = (gamma*invstd/m)*(m*dz - dbeta - xhat*dgamma), xhat = (x-mean)*invstd; dresidual = dz.
  * y may be NULL when d->relu == 0; dresidual is nullable.
+ * With ReLU and no residual branch (dresidual == NULL) y may also be NULL if beta is given: the
+ * mask is then recomputed as [x*sc + bi > 0] with sc = gamma*invstd, bi = beta - mean*sc, the
+ * arithmetic (and rounding) of cnnk_bn_relu_fwd on the same x, gamma, beta and saved statistics,
+ * which saves reading y.  beta is nullable otherwise.
  * flags bit 0: add into dx instead of overwriting; bit 1: add into dresidual. */
 int cnnk_bn_relu_bwd(const cnnk_bn_desc* d, const void* dy, const void* x, const void* y,
-                     const float* gamma, const float* save_mean, const float* save_invstd,
+                     const float* gamma, const float* beta, const float* save_mean,
+                     const float* save_invstd,
                      void* dx, void* dresidual, int flags, float* dgamma, float* dbeta,
                      void* ws, size_t ws_bytes, void* stream);
 

@@ -86,7 +86,7 @@ def _load():
     lib.cnnk_bn_workspace_bytes.restype = sz
     lib.cnnk_bn_workspace_bytes.argtypes = [C.POINTER(BnDesc)]
     lib.cnnk_bn_relu_fwd.argtypes = [C.POINTER(BnDesc)] + [vp] * 11 + [vp, sz, vp]
-    lib.cnnk_bn_relu_bwd.argtypes = [C.POINTER(BnDesc)] + [vp] * 8 + [ci, vp, vp, vp, sz, vp]
+    lib.cnnk_bn_relu_bwd.argtypes = [C.POINTER(BnDesc)] + [vp] * 9 + [ci, vp, vp, vp, sz, vp]
     lib.cnnk_pool_fwd.argtypes = [C.POINTER(PoolDesc), vp, vp, vp, vp]
     lib.cnnk_pool_bwd.argtypes = [C.POINTER(PoolDesc), vp, vp, vp, ci, vp]
     lib.cnnk_add.argtypes = [sz, ci, vp, vp, vp, vp]
@@ -176,9 +176,9 @@ def cnnk_bn_relu_fwd(d, x, residual, gamma, beta, y, save_mean, save_invstd, run
                                 ptr(ch_sum), ptr(ch_sumsq), ptr(ws), ws_bytes, stream), "cnnk_bn_relu_fwd")
 
 
-def cnnk_bn_relu_bwd(d, dy, x, y, gamma, save_mean, save_invstd, dx, dresidual, flags, dgamma, dbeta,
+def cnnk_bn_relu_bwd(d, dy, x, y, gamma, beta, save_mean, save_invstd, dx, dresidual, flags, dgamma, dbeta,
                      ws=None, ws_bytes=0, stream=0):
-    _check(lib.cnnk_bn_relu_bwd(C.byref(d), ptr(dy), ptr(x), ptr(y), ptr(gamma), ptr(save_mean),
+    _check(lib.cnnk_bn_relu_bwd(C.byref(d), ptr(dy), ptr(x), ptr(y), ptr(gamma), ptr(beta), ptr(save_mean),
                                 ptr(save_invstd), ptr(dx), ptr(dresidual), int(flags), ptr(dgamma),
                                 ptr(dbeta), ptr(ws), ws_bytes, stream), "cnnk_bn_relu_bwd")
 

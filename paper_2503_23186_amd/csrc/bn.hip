@@ -3,6 +3,7 @@
 // per-channel reductions are per-thread partial sums -> LDS -> per-workgroup partials -> a small
 // finalising kernel that sums the partials in double precision (fixed order, no atomics).
 #include "common.h"
+#include <type_traits>
 #include "conv.h"
 
 namespace {
@@ -49,29 +50,30 @@ __device__ __forceinline__ void block_reduce_store(float (*acc)[8], int lanes, i
 
 // Finalising reduction: one workgroup per channel sums the nb per-workgroup partials
 // part[v][c][0..nb) in double (coalesced rows, fixed-order tree).  Result valid in thread 0.
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// One wavefront per channel (four channels per workgroup): the lanes stride over the nb partials,
+// the xor-butterfly gives every lane the total.  Fixed order, no LDS, no barrier.
+constexpr int kFinCh = kT / 64;   // channels per finalising workgroup
+inline unsigned fin_blocks(int C) { return (unsigned)((C + kFinCh - 1) / kFinCh); }
+
 __device__ __forceinline__ void finalize_sums(const float* __restrict__ part, int nb, int C, int c,
                                               double* s1_out, double* s2_out) {
-  __shared__ double fred[2][kT];
-  const int t = threadIdx.x;
+  const int lane = threadIdx.x & 63;
   double s1 = 0.0, s2 = 0.0;
   const float* p1 = part + ((size_t)0 * C + c) * nb;
   const float* p2 = part + ((size_t)1 * C + c) * nb;
-  for (int b = t; b < nb; b += kT) {
+#pragma unroll 4
+  for (int b = lane; b < nb; b += 64) {
     s1 += (double)p1[b];
     s2 += (double)p2[b];
   }
-  fred[0][t] = s1;
-  fred[1][t] = s2;
-  __syncthreads();
-  for (int o = kT / 2; o > 0; o >>= 1) {
-    if (t < o) {
-      fred[0][t] += fred[0][t + o];
-      fred[1][t] += fred[1][t + o];
-    }
-    __syncthreads();
-  }
-  *s1_out = fred[0][0];
-  *s2_out = fred[1][0];
+  *s1_out = wave_sum_f64(s1);
+  *s2_out = wave_sum_f64(s2);
 }
 
 // Partial sums of (x - shift) and (x - shift)^2 with shift = x[0][c] (keeps fp32 sums benign).
@@ -108,10 +110,11 @@ __global__ void __launch_bounds__(kT) stats_finalize_kernel(const float* __restr
                                                             float eps, float momentum, float* __restrict__ o0,
                                                             float* __restrict__ o1, float* __restrict__ rmean,
                                                             float* __restrict__ rvar) {
-  const int c = blockIdx.x;
+  const int c = blockIdx.x * kFinCh + (threadIdx.x >> 6);
+  if (c >= C) return;
   double s1, s2;
   finalize_sums(part, nb, C, c, &s1, &s2);
-  if (threadIdx.x != 0) return;
+  if ((threadIdx.x & 63) != 0) return;
   const double sh = (double)Elem<T>::ld(x + c);
   const double dm = (double)m;
   if (mode == 1) {
@@ -133,43 +136,94 @@ __global__ void __launch_bounds__(kT) stats_finalize_kernel(const float* __restr
 
 __global__ void __launch_bounds__(kT) sums_finalize_kernel(const float* __restrict__ part, int nb, int C,
                                                            float* __restrict__ ch_sum, float* __restrict__ ch_sumsq) {
-  const int c = blockIdx.x;
+  const int c = blockIdx.x * kFinCh + (threadIdx.x >> 6);
+  if (c >= C) return;
   double s1, s2;
   finalize_sums(part, nb, C, c, &s1, &s2);
-  if (threadIdx.x != 0) return;
+  if ((threadIdx.x & 63) != 0) return;
   ch_sum[c] = (float)s1;
   ch_sumsq[c] = (float)s2;
 }
 
+// sc = gamma * invstd, bi = beta - mean * sc: the one place this is written, so that the forward
+// kernels and the mask recomputation of the backward kernels round identically.
+__device__ __forceinline__ void bn_scale_bias(float g, float b, float mu, float is, float* sc, float* bi) {
+  *sc = g * is;
+  *bi = fmaf(-mu, *sc, b);
+}
+
+// The element-wise kernels use the row mapping of the reductions: a thread owns one octet of
+// channels (o = tid % (C/8)) for the whole launch, keeps that octet's coefficients in registers, and
+// walks rows blockIdx.x*rows + tid/(C/8), +gridDim.x*rows, ... four rows in flight.  No per-vector
+// index arithmetic beyond one multiply-add, no per-vector coefficient loads.
+template <typename T, typename F>
+__device__ __forceinline__ void for_rows4(size_t m, int C, int lanes, int rows, F body) {
+  const int tid = threadIdx.x, o = tid % lanes, rl = tid / lanes;
+  if (rl >= rows) return;
+  const size_t step = (size_t)gridDim.x * rows;
+  size_t r = (size_t)blockIdx.x * rows + rl;
+  for (; r + 3 * step < m; r += 4 * step) {
+    const size_t i0 = r * C + o * 8, d = step * C;
+    body(i0, i0 + d, i0 + 2 * d, i0 + 3 * d, std::integral_constant<int, 4>{});
+  }
+  for (; r < m; r += step) {
+    const size_t i0 = r * C + o * 8;
+    body(i0, i0, i0, i0, std::integral_constant<int, 1>{});
+  }
+}
+
+template <typename T>
+__device__ __forceinline__ void bn_apply_rows(const T* __restrict__ x, const T* __restrict__ res, T* __restrict__ y,
+                                              size_t m, int C, int relu, const float* sc, const float* bi) {
+  const int lanes = C / 8, rows = kT / lanes;
+  for_rows4<T>(m, C, lanes, rows, [&](size_t i0, size_t i1, size_t i2, size_t i3, auto NN) {
+    constexpr int n = decltype(NN)::value;
+    const size_t idx[4] = {i0, i1, i2, i3};
+    float v[4][8], r[4][8];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if (k < n) load8(x + idx[k], v[k]);
+    if (res) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        if (k < n) load8(res + idx[k], r[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (k >= n) break;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[k][e] = fmaf(v[k][e], sc[e], bi[e]);
+      if (res) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[k][e] += r[k][e];
+      }
+      if (relu) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[k][e] = v[k][e] > 0.f ? v[k][e] : 0.f;
+      }
+      store8(y + idx[k], v[k]);
+    }
+  });
+}
+
+// y = gamma * (x - mean) * invstd + beta (+ residual) (ReLU), as x * sc + bi with sc = gamma * invstd,
+// bi = beta - mean * sc (the same two roundings whichever kernel produced the statistics).
 template <typename T>
 __global__ void __launch_bounds__(kT) bn_apply_kernel(const T* __restrict__ x, const T* __restrict__ res,
                                                       const float* __restrict__ gamma,
                                                       const float* __restrict__ beta,
                                                       const float* __restrict__ mean,
                                                       const float* __restrict__ invstd, T* __restrict__ y,
-                                                      size_t n8, int C, int relu) {
-  for (size_t i = (size_t)blockIdx.x * kT + threadIdx.x; i < n8; i += (size_t)gridDim.x * kT) {
-    const int c0 = (int)((i * 8) % C);
-    float v[8], g[8], b[8], mu[8], is[8];
-    load8(x + i * 8, v);
-    load8(gamma + c0, g);
-    load8(beta + c0, b);
-    load8(mean + c0, mu);
-    load8(invstd + c0, is);
+                                                      size_t m, int C, int relu) {
+  const int o = threadIdx.x % (C / 8);
+  float g[8], b[8], mu[8], is[8], sc[8], bi[8];
+  load8(gamma + o * 8, g);
+  load8(beta + o * 8, b);
+  load8(mean + o * 8, mu);
+  load8(invstd + o * 8, is);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = fmaf(g[e], (v[e] - mu[e]) * is[e], b[e]);
-    if (res) {
-      float r[8];
-      load8(res + i * 8, r);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] += r[e];
-    }
-    if (relu) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
-    }
-    store8(y + i * 8, v);
-  }
+  for (int e = 0; e < 8; ++e) bn_scale_bias(g[e], b[e], mu[e], is[e], &sc[e], &bi[e]);
+  bn_apply_rows<T>(x, res, y, m, C, relu, sc, bi);
 }
 
 // Normalise (+ residual) (+ ReLU) with the statistics taken directly from per-channel sums
@@ -186,9 +240,7 @@ __global__ void __launch_bounds__(kT) bn_apply_sums_kernel(const T* __restrict__
                                                            float* __restrict__ save_mean,
                                                            float* __restrict__ save_invstd,
                                                            float* __restrict__ rmean, float* __restrict__ rvar,
-                                                           T* __restrict__ y, size_t n8, int C, int relu) {
-  int cur_c0 = -1;
-  float sc[8], bi[8];
+                                                           T* __restrict__ y, size_t m, int C, int relu) {
   if (blockIdx.x == 0) {
     for (int c = threadIdx.x; c < C; c += kT) {
       const float mu = ch_sum[c] * inv_m;
@@ -201,68 +253,62 @@ __global__ void __launch_bounds__(kT) bn_apply_sums_kernel(const T* __restrict__
       }
     }
   }
-  for (size_t i = (size_t)blockIdx.x * kT + threadIdx.x; i < n8; i += (size_t)gridDim.x * kT) {
-    const int c0 = (int)((i * 8) % C);
-    if (c0 != cur_c0) {
-      cur_c0 = c0;
-      float s1[8], s2[8], g[8], b[8];
-      load8(ch_sum + c0, s1);
-      load8(ch_sumsq + c0, s2);
-      load8(gamma + c0, g);
-      load8(beta + c0, b);
+  const int o = threadIdx.x % (C / 8);
+  float s1[8], s2[8], g[8], b[8], sc[8], bi[8];
+  load8(ch_sum + o * 8, s1);
+  load8(ch_sumsq + o * 8, s2);
+  load8(gamma + o * 8, g);
+  load8(beta + o * 8, b);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float mu = s1[e] * inv_m;
-        const float var = fmaxf(fmaf(s2[e], inv_m, -mu * mu), 0.f);
-        const float is = rsqrtf(var + eps);
-        sc[e] = g[e] * is;
-        bi[e] = fmaf(-mu, sc[e], b[e]);
-      }
-    }
-    float v[8];
-    load8(x + i * 8, v);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = fmaf(v[e], sc[e], bi[e]);
-    if (res) {
-      float r[8];
-      load8(res + i * 8, r);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] += r[e];
-    }
-    if (relu) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
-    }
-    store8(y + i * 8, v);
+  for (int e = 0; e < 8; ++e) {
+    const float mu = s1[e] * inv_m;
+    const float var = fmaxf(fmaf(s2[e], inv_m, -mu * mu), 0.f);
+    const float is = rsqrtf(var + eps);
+    bn_scale_bias(g[e], b[e], mu, is, &sc[e], &bi[e]);
   }
+  bn_apply_rows<T>(x, res, y, m, C, relu, sc, bi);
 }
 
-// Partial sums of dz and dz*xhat.
-template <typename T>
+// Partial sums of dz and dz*xhat.  MODE 0: no ReLU; 1: mask [y > 0]; 2: mask [x*sc + bi > 0]
+// recomputed with the forward's arithmetic (y is not read).
+template <typename T, int MODE>
 __global__ void __launch_bounds__(kT) bwd_partial_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                                                          const T* __restrict__ y,
+                                                         const float* __restrict__ gamma,
+                                                         const float* __restrict__ beta,
                                                          const float* __restrict__ mean,
                                                          const float* __restrict__ invstd, size_t m, int C,
-                                                         int relu, float* __restrict__ part) {
+                                                         float* __restrict__ part) {
   const int lanes = C / 8, rows = kT / lanes;
   const int tid = threadIdx.x, o = tid % lanes, rl = tid / lanes;
   float acc[2][8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[0][e] = acc[1][e] = 0.f;
   if (rl < rows) {
-    float mu[8], is[8];
+    float mu[8], is[8], sc[8], bi[8];
     load8(mean + o * 8, mu);
     load8(invstd + o * 8, is);
+    if (MODE == 2) {
+      float ga[8], be[8];
+      load8(gamma + o * 8, ga);
+      load8(beta + o * 8, be);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) bn_scale_bias(ga[e], be[e], mu[e], is[e], &sc[e], &bi[e]);
+    }
 #pragma unroll 4
     for (size_t r = (size_t)blockIdx.x * rows + rl; r < m; r += (size_t)gridDim.x * rows) {
       float g[8], xv[8];
       load8(dy + r * C + o * 8, g);
       load8(x + r * C + o * 8, xv);
-      if (relu) {
+      if (MODE == 1) {
         float yv[8];
         load8(y + r * C + o * 8, yv);
 #pragma unroll
         for (int e = 0; e < 8; ++e) g[e] = yv[e] > 0.f ? g[e] : 0.f;
+      }
+      if (MODE == 2) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) g[e] = fmaf(xv[e], sc[e], bi[e]) > 0.f ? g[e] : 0.f;
       }
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
@@ -276,66 +322,102 @@ __global__ void __launch_bounds__(kT) bwd_partial_kernel(const T* __restrict__ d
 
 __global__ void __launch_bounds__(kT) bwd_finalize_kernel(const float* __restrict__ part, int nb, int C,
                                                           float* __restrict__ dgamma, float* __restrict__ dbeta) {
-  const int c = blockIdx.x;
+  const int c = blockIdx.x * kFinCh + (threadIdx.x >> 6);
+  if (c >= C) return;
   double s1, s2;
   finalize_sums(part, nb, C, c, &s1, &s2);
-  if (threadIdx.x != 0) return;
+  if ((threadIdx.x & 63) != 0) return;
   dbeta[c] = (float)s1;
   dgamma[c] = (float)s2;
 }
 
-template <typename T>
+template <typename T, int MODE>
 __global__ void __launch_bounds__(kT) bwd_apply_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                                                        const T* __restrict__ y, const float* __restrict__ gamma,
+                                                       const float* __restrict__ beta,
                                                        const float* __restrict__ mean,
                                                        const float* __restrict__ invstd,
                                                        const float* __restrict__ dgamma,
                                                        const float* __restrict__ dbeta, T* __restrict__ dx,
-                                                       T* __restrict__ dres, size_t n8, int C, float inv_m,
-                                                       int relu, int flags) {
-  for (size_t i = (size_t)blockIdx.x * kT + threadIdx.x; i < n8; i += (size_t)gridDim.x * kT) {
-    const int c0 = (int)((i * 8) % C);
-    float g[8], xv[8], ga[8], mu[8], is[8], dg[8], db[8], out[8];
-    load8(dy + i * 8, g);
-    load8(x + i * 8, xv);
-    load8(gamma + c0, ga);
-    load8(mean + c0, mu);
-    load8(invstd + c0, is);
-    load8(dgamma + c0, dg);
-    load8(dbeta + c0, db);
-    if (relu) {
-      float yv[8];
-      load8(y + i * 8, yv);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) g[e] = yv[e] > 0.f ? g[e] : 0.f;
-    }
+                                                       T* __restrict__ dres, size_t m, int C, float inv_m,
+                                                       int flags) {
+  const int lanes = C / 8, rows = kT / lanes;
+  const int o = threadIdx.x % lanes;
+  // dx = a * (dz - (dbeta + xhat * dgamma) / m), xhat = (x - mu) * is, a = gamma * is
+  float a[8], mu[8], is[8], dgm[8], dbm[8], sc[8], bi[8];
+  {
+    float ga[8], dg[8], db[8];
+    load8(gamma + o * 8, ga);
+    load8(mean + o * 8, mu);
+    load8(invstd + o * 8, is);
+    load8(dgamma + o * 8, dg);
+    load8(dbeta + o * 8, db);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const float xh = (xv[e] - mu[e]) * is[e];
-      out[e] = ga[e] * is[e] * (g[e] - (db[e] + xh * dg[e]) * inv_m);
+      a[e] = ga[e] * is[e];
+      dgm[e] = dg[e] * inv_m;
+      dbm[e] = db[e] * inv_m;
     }
-    if (flags & 1) {
-      float old[8];
-      load8(dx + i * 8, old);
+    if (MODE == 2) {
+      float be[8];
+      load8(beta + o * 8, be);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) out[e] += old[e];
-    }
-    store8(dx + i * 8, out);
-    if (dres) {
-      if (flags & 2) {
-        float old[8];
-        load8(dres + i * 8, old);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) g[e] += old[e];
-      }
-      store8(dres + i * 8, g);
+      for (int e = 0; e < 8; ++e) bn_scale_bias(ga[e], be[e], mu[e], is[e], &sc[e], &bi[e]);
     }
   }
+  for_rows4<T>(m, C, lanes, rows, [&](size_t i0, size_t i1, size_t i2, size_t i3, auto NN) {
+    constexpr int n = decltype(NN)::value;
+    const size_t idx[4] = {i0, i1, i2, i3};
+    float g[4][8], xv[4][8], yv[4][8];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if (k < n) {
+        load8(dy + idx[k], g[k]);
+        load8(x + idx[k], xv[k]);
+        if (MODE == 1) load8(y + idx[k], yv[k]);
+      }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (k >= n) break;
+      float out[8];
+      if (MODE == 1) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) g[k][e] = yv[k][e] > 0.f ? g[k][e] : 0.f;
+      }
+      if (MODE == 2) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) g[k][e] = fmaf(xv[k][e], sc[e], bi[e]) > 0.f ? g[k][e] : 0.f;
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float xh = (xv[k][e] - mu[e]) * is[e];
+        out[e] = a[e] * (g[k][e] - fmaf(xh, dgm[e], dbm[e]));
+      }
+      if (flags & 1) {
+        float old[8];
+        load8(dx + idx[k], old);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) out[e] += old[e];
+      }
+      store8(dx + idx[k], out);
+      if (dres) {
+        if (flags & 2) {
+          float old[8];
+          load8(dres + idx[k], old);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) g[k][e] += old[e];
+        }
+        store8(dres + idx[k], g[k]);
+      }
+    }
+  });
 }
 
-inline unsigned ew_blocks(size_t n8) {
-  size_t b = (n8 + kT - 1) / kT;
-  if (b > 8192) b = 8192;
+// Grid of the element-wise kernels: every thread gets about eight rows, capped.
+inline unsigned row_blocks(size_t m, int C) {
+  const int rows = kT / (C / 8);
+  size_t b = (m + (size_t)rows * 8 - 1) / ((size_t)rows * 8);
+  if (b > 4096) b = 4096;
   return (unsigned)(b < 1 ? 1 : b);
 }
 
@@ -350,7 +432,7 @@ int validate_bn(const cnnk_bn_desc* d) {
 }  // namespace
 
 int channel_sums_finalize(const float* part, int nb, int C, float* ch_sum, float* ch_sumsq, hipStream_t st) {
-  sums_finalize_kernel<<<C, kT, 0, st>>>(part, nb, C, ch_sum, ch_sumsq);
+  sums_finalize_kernel<<<fin_blocks(C), kT, 0, st>>>(part, nb, C, ch_sum, ch_sumsq);
   return launch_status();
 }
 
@@ -362,11 +444,11 @@ int channel_stats(int dtype, const void* x, size_t m, int C, float* ch_sum, floa
   float* part = (float*)ws;
   if (dtype == CNNK_BF16) {
     stats_partial_kernel<bf16_t><<<nb, kT, 0, st>>>((const bf16_t*)x, m, C, part);
-    stats_finalize_kernel<bf16_t><<<C, kT, 0, st>>>(part, nb, (const bf16_t*)x, m, C, 1, 0.f, 0.f,
+    stats_finalize_kernel<bf16_t><<<fin_blocks(C), kT, 0, st>>>(part, nb, (const bf16_t*)x, m, C, 1, 0.f, 0.f,
                                                                     ch_sum, ch_sumsq, nullptr, nullptr);
   } else {
     stats_partial_kernel<float><<<nb, kT, 0, st>>>((const float*)x, m, C, part);
-    stats_finalize_kernel<float><<<C, kT, 0, st>>>(part, nb, (const float*)x, m, C, 1, 0.f, 0.f,
+    stats_finalize_kernel<float><<<fin_blocks(C), kT, 0, st>>>(part, nb, (const float*)x, m, C, 1, 0.f, 0.f,
                                                                    ch_sum, ch_sumsq, nullptr, nullptr);
   }
   return launch_status();
@@ -395,74 +477,82 @@ extern "C" int cnnk_bn_relu_fwd(const cnnk_bn_desc* d, const void* x, const void
     float* part = (float*)ws;
     if (d->dtype == CNNK_BF16) {
       stats_partial_kernel<bf16_t><<<nb, kT, 0, st>>>((const bf16_t*)x, m, C, part);
-      stats_finalize_kernel<bf16_t><<<C, kT, 0, st>>>(part, nb, (const bf16_t*)x, m, C, 0, d->eps,
+      stats_finalize_kernel<bf16_t><<<fin_blocks(C), kT, 0, st>>>(part, nb, (const bf16_t*)x, m, C, 0, d->eps,
                                                                       d->momentum, save_mean, save_invstd,
                                                                       running_mean, running_var);
     } else {
       stats_partial_kernel<float><<<nb, kT, 0, st>>>((const float*)x, m, C, part);
-      stats_finalize_kernel<float><<<C, kT, 0, st>>>(part, nb, (const float*)x, m, C, 0, d->eps,
+      stats_finalize_kernel<float><<<fin_blocks(C), kT, 0, st>>>(part, nb, (const float*)x, m, C, 0, d->eps,
                                                                      d->momentum, save_mean, save_invstd,
                                                                      running_mean, running_var);
     }
   } else {
     // statistics handed in as sums: one fused kernel (statistics + normalise)
-    const size_t n8s = m * C / 8;
     const float inv_m = (float)(1.0 / (double)m);
     const float unbias = m > 1 ? (float)((double)m / ((double)m - 1.0)) : 1.f;
     if (d->dtype == CNNK_BF16)
-      bn_apply_sums_kernel<bf16_t><<<ew_blocks(n8s), kT, 0, st>>>((const bf16_t*)x, (const bf16_t*)residual, gamma, beta,
+      bn_apply_sums_kernel<bf16_t><<<row_blocks(m, C), kT, 0, st>>>((const bf16_t*)x, (const bf16_t*)residual, gamma, beta,
                                                                  ch_sum, ch_sumsq, inv_m, unbias, d->eps, d->momentum,
                                                                  save_mean, save_invstd, running_mean, running_var,
-                                                                 (bf16_t*)y, n8s, C, d->relu);
+                                                                 (bf16_t*)y, m, C, d->relu);
     else
-      bn_apply_sums_kernel<float><<<ew_blocks(n8s), kT, 0, st>>>((const float*)x, (const float*)residual, gamma, beta,
+      bn_apply_sums_kernel<float><<<row_blocks(m, C), kT, 0, st>>>((const float*)x, (const float*)residual, gamma, beta,
                                                                 ch_sum, ch_sumsq, inv_m, unbias, d->eps, d->momentum,
                                                                 save_mean, save_invstd, running_mean, running_var,
-                                                                (float*)y, n8s, C, d->relu);
+                                                                (float*)y, m, C, d->relu);
     return launch_status();
   }
   if (launch_status() != CNNK_OK) return CNNK_ERR_HIP;
-  const size_t n8 = m * C / 8;
   if (d->dtype == CNNK_BF16)
-    bn_apply_kernel<bf16_t><<<ew_blocks(n8), kT, 0, st>>>((const bf16_t*)x, (const bf16_t*)residual, gamma, beta,
-                                                          save_mean, save_invstd, (bf16_t*)y, n8, C, d->relu);
+    bn_apply_kernel<bf16_t><<<row_blocks(m, C), kT, 0, st>>>((const bf16_t*)x, (const bf16_t*)residual, gamma, beta,
+                                                          save_mean, save_invstd, (bf16_t*)y, m, C, d->relu);
   else
-    bn_apply_kernel<float><<<ew_blocks(n8), kT, 0, st>>>((const float*)x, (const float*)residual, gamma, beta,
-                                                         save_mean, save_invstd, (float*)y, n8, C, d->relu);
+    bn_apply_kernel<float><<<row_blocks(m, C), kT, 0, st>>>((const float*)x, (const float*)residual, gamma, beta,
+                                                         save_mean, save_invstd, (float*)y, m, C, d->relu);
+  return launch_status();
+}
+
+template <typename T, int MODE>
+static int bn_bwd_launch(const cnnk_bn_desc* d, const void* dy, const void* x, const void* y, const float* gamma,
+                         const float* beta, const float* save_mean, const float* save_invstd, void* dx,
+                         void* dresidual, int flags, float* dgamma, float* dbeta, float* part, hipStream_t st) {
+  const size_t m = (size_t)d->N * d->H * d->W;
+  const int C = d->C;
+  const int nb = reduce_blocks(m, C);
+  const float inv_m = (float)(1.0 / (double)m);
+  bwd_partial_kernel<T, MODE><<<nb, kT, 0, st>>>((const T*)dy, (const T*)x, (const T*)y, gamma, beta, save_mean,
+                                                 save_invstd, m, C, part);
+  bwd_finalize_kernel<<<fin_blocks(C), kT, 0, st>>>(part, nb, C, dgamma, dbeta);
+  bwd_apply_kernel<T, MODE><<<row_blocks(m, C), kT, 0, st>>>((const T*)dy, (const T*)x, (const T*)y, gamma, beta,
+                                                             save_mean, save_invstd, dgamma, dbeta, (T*)dx,
+                                                             (T*)dresidual, m, C, inv_m, flags);
   return launch_status();
 }
 
 extern "C" int cnnk_bn_relu_bwd(const cnnk_bn_desc* d, const void* dy, const void* x, const void* y,
-                                const float* gamma, const float* save_mean, const float* save_invstd, void* dx,
-                                void* dresidual, int flags, float* dgamma, float* dbeta, void* ws,
-                                size_t ws_bytes, void* stream) {
+                                const float* gamma, const float* beta, const float* save_mean,
+                                const float* save_invstd, void* dx, void* dresidual, int flags, float* dgamma,
+                                float* dbeta, void* ws, size_t ws_bytes, void* stream) {
   int rc = validate_bn(d);
   if (rc != CNNK_OK) return rc;
   if (!dy || !x || !gamma || !save_mean || !save_invstd || !dx || !dgamma || !dbeta) return CNNK_ERR_NULL;
-  if (d->relu && !y) return CNNK_ERR_NULL;
+  // ReLU mask: from y, or recomputed from x when y is withheld (no residual branch, beta given)
+  if (d->relu && !y && (!beta || dresidual)) return CNNK_ERR_NULL;
+  const int mode = !d->relu ? 0 : (y ? 1 : 2);
   const size_t m = (size_t)d->N * d->H * d->W;
-  const int C = d->C;
-  if (!ws || ws_bytes < channel_stats_ws(m, C)) return CNNK_ERR_WORKSPACE;
+  if (!ws || ws_bytes < channel_stats_ws(m, d->C)) return CNNK_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
-  const int nb = reduce_blocks(m, C);
   float* part = (float*)ws;
-  const size_t n8 = m * C / 8;
-  const float inv_m = (float)(1.0 / (double)m);
+#define CNNK_BN_BWD(T, MODE) \
+  return bn_bwd_launch<T, MODE>(d, dy, x, y, gamma, beta, save_mean, save_invstd, dx, dresidual, flags, dgamma, \
+                                dbeta, part, st)
   if (d->dtype == CNNK_BF16) {
-    bwd_partial_kernel<bf16_t><<<nb, kT, 0, st>>>((const bf16_t*)dy, (const bf16_t*)x, (const bf16_t*)y, save_mean,
-                                                  save_invstd, m, C, d->relu, part);
-    bwd_finalize_kernel<<<C, kT, 0, st>>>(part, nb, C, dgamma, dbeta);
-    bwd_apply_kernel<bf16_t><<<ew_blocks(n8), kT, 0, st>>>((const bf16_t*)dy, (const bf16_t*)x, (const bf16_t*)y,
-                                                           gamma, save_mean, save_invstd, dgamma, dbeta,
-                                                           (bf16_t*)dx, (bf16_t*)dresidual, n8, C, inv_m, d->relu,
-                                                           flags);
-  } else {
-    bwd_partial_kernel<float><<<nb, kT, 0, st>>>((const float*)dy, (const float*)x, (const float*)y, save_mean,
-                                                 save_invstd, m, C, d->relu, part);
-    bwd_finalize_kernel<<<C, kT, 0, st>>>(part, nb, C, dgamma, dbeta);
-    bwd_apply_kernel<float><<<ew_blocks(n8), kT, 0, st>>>((const float*)dy, (const float*)x, (const float*)y, gamma,
-                                                          save_mean, save_invstd, dgamma, dbeta, (float*)dx,
-                                                          (float*)dresidual, n8, C, inv_m, d->relu, flags);
+    if (mode == 0) CNNK_BN_BWD(bf16_t, 0);
+    if (mode == 1) CNNK_BN_BWD(bf16_t, 1);
+    CNNK_BN_BWD(bf16_t, 2);
   }
-  return launch_status();
+  if (mode == 0) CNNK_BN_BWD(float, 0);
+  if (mode == 1) CNNK_BN_BWD(float, 1);
+  CNNK_BN_BWD(float, 2);
+#undef CNNK_BN_BWD
 }

@@ -322,8 +322,10 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
         const int C = l.d.bn.C;
         const bool res = l.in1 > 0;
         const int flags = (written[l.in0] ? 1 : 0) | ((res && written[l.in1]) ? 2 : 0);
-        rc = cnnk_bn_relu_bwd(&l.d.bn, B->dact[l.out], B->act[l.in0], B->act[l.out], B->param[l.p0], B->bn_save[i],
-                              B->bn_save[i] + C, B->dact[l.in0], res ? B->dact[l.in1] : nullptr, flags,
+        // without a residual branch the ReLU mask is recomputed from x (y is not read)
+        const void* ymask = (l.d.bn.relu && !res && g_cnnk_tune[9] >= 0) ? nullptr : B->act[l.out];
+        rc = cnnk_bn_relu_bwd(&l.d.bn, B->dact[l.out], B->act[l.in0], ymask, B->param[l.p0], B->param[l.p1],
+                              B->bn_save[i], B->bn_save[i] + C, B->dact[l.in0], res ? B->dact[l.in1] : nullptr, flags,
                               B->grad[l.p0], B->grad[l.p1], ws, wsb, stream);
         written[l.in0] = 1;
         if (res) written[l.in1] = 1;

@@ -209,17 +209,32 @@ def test_bn_relu_fwd_bwd(K, shape, relu, with_res, dtype):
                                                        want_dres=with_res)
     gdx = torch.zeros_like(gx); gdres = torch.zeros_like(gx) if with_res else None
     gdg = torch.zeros(Cc, device=gx.device); gdb = torch.zeros(Cc, device=gx.device)
-    K.cnnk_bn_relu_bwd(d, dev(dy, dtype), gx, dev(y_in, dtype), gg, dev_f32(mean_ref), dev_f32(invstd_ref),
+    K.cnnk_bn_relu_bwd(d, dev(dy, dtype), gx, dev(y_in, dtype), gg, gb, dev_f32(mean_ref), dev_f32(invstd_ref),
                        gdx, gdres, 0, gdg, gdb, ws, nb)
     torch.cuda.synchronize()
     assert max_rel_err(host(gdg), dg_ref) <= 1e-4 and max_rel_err(host(gdb), db_ref) <= 1e-4
     assert max_rel_err(host(gdx), dx_ref) <= stor
     if with_res:
         assert np.array_equal(host(gdres), dres_ref)
+    if relu and not with_res:
+        # y withheld: the mask is recomputed from x with the forward's arithmetic, so it must equal
+        # the mask of the kernel's own forward output for the statistics that forward saved
+        K.cnnk_bn_relu_fwd(d, gx, None, gg, gb, gy, gmean, ginv, None, None, None, None, ws, nb)
+        torch.cuda.synchronize()
+        dx_r, _, dg_r, db_r = ref.bn_relu_bwd(dy, x, host(gy), gamma, host(gmean), host(ginv), relu=True,
+                                              want_dres=False)
+        gdx3 = torch.zeros_like(gx)
+        K.cnnk_bn_relu_bwd(d, dev(dy, dtype), gx, None, gg, gb, gmean, ginv, gdx3, None, 0, gdg, gdb, ws, nb)
+        torch.cuda.synchronize()
+        assert max_rel_err(host(gdg), dg_r) <= 1e-4 and max_rel_err(host(gdb), db_r) <= 1e-4
+        assert max_rel_err(host(gdx3), dx_r) <= stor
+        # withheld y needs beta and no residual branch
+        with pytest.raises(RuntimeError):
+            K.cnnk_bn_relu_bwd(d, dev(dy, dtype), gx, None, gg, None, gmean, ginv, gdx3, None, 0, gdg, gdb, ws, nb)
     # accumulate flags
     base = rep(rng.standard_normal(shape), dtype)
     gdx2 = dev(base, dtype); gdres2 = dev(base, dtype) if with_res else None
-    K.cnnk_bn_relu_bwd(d, dev(dy, dtype), gx, dev(y_in, dtype), gg, dev_f32(mean_ref), dev_f32(invstd_ref),
+    K.cnnk_bn_relu_bwd(d, dev(dy, dtype), gx, dev(y_in, dtype), gg, gb, dev_f32(mean_ref), dev_f32(invstd_ref),
                        gdx2, gdres2, 3, gdg, gdb, ws, nb)
     torch.cuda.synchronize()
     assert max_rel_err(host(gdx2), dx_ref + base) <= 2 * stor

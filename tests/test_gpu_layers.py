@@ -86,7 +86,7 @@ def test_every_layer_on_oracle_inputs(name, make, cid):
             gdx = torch.empty(x.shape, dtype=gx.dtype, device="cuda:0")
             gdr = torch.empty(x.shape, dtype=gx.dtype, device="cuda:0") if res is not None else None
             gdg = torch.empty(L["C"], device="cuda:0"); gdb = torch.empty(L["C"], device="cuda:0")
-            K.cnnk_bn_relu_bwd(d, dev(dy, dtype), gx, dev(y, dtype), gg, dev_f32(mean), dev_f32(invstd), gdx, gdr, 0,
+            K.cnnk_bn_relu_bwd(d, dev(dy, dtype), gx, dev(y, dtype), gg, gb, dev_f32(mean), dev_f32(invstd), gdx, gdr, 0,
                                gdg, gdb, ws, nb)
             chk("bn_dgamma", gdg, dg_ref, acc_tol); chk("bn_dbeta", gdb, db_ref, acc_tol)
             chk("bn_dx", gdx, q(dx_ref), out_tol)
