@@ -27,6 +27,7 @@ struct PatchArgs {
   int N, H, W, Cs, Cd;
   int TI, TH;         // tile = TI images x TH rows x W columns (BM pixels)
   int accumulate, ntiles, mtiles;
+  int perm;           // row permutation of the pixel tile, see tile_pixel()
   int toff_h[9], toff_w[9], widx[9];  // patch offset (0..2, 0..2) and weight tap of each step
   FastDiv dPW, dPH, dW, dTH;          // divisors used to decode tile-local pixel indices (< 2^16)
 };
@@ -36,14 +37,45 @@ struct PatchArgs {
 // writing 4 whole rows, both touch every bank once.
 __device__ __forceinline__ int swz_off(int row, int chunk) { return row * 64 + ((chunk ^ ((row >> 2) & 3)) << 4); }
 
+// Which pixel of the tile (index (ti*TH + th)*W + tw) the GEMM row `rho` stands for.  The MFMA does
+// not care which 32 pixels share a tile, but the LDS does: a quarter-wave reads 16 patch rows at
+// once and they must differ modulo 16 (the bank pattern repeats every 16 rows).  With W >= 16 the
+// 16 pixels are consecutive; narrower images put several image rows into one quarter-wave, whose
+// patch rows collide unless they are picked apart:
+//   perm 1 (W = 8, TH = 8): image rows th and th+4 share a quarter-wave (4 patch rows = 40 = 8 mod 16);
+//   perm 2 (W = 4, TH = 4): row th of four consecutive images (one padded image = 36 = 4 mod 16).
+__device__ __forceinline__ int tile_pixel(int rho, int perm) {
+  if (perm == 1) {
+    const int u = (rho >> 3) & 7;
+    return (rho & ~0x38) | ((((u >> 1) | ((u & 1) << 2))) << 3);
+  }
+  if (perm == 2) {
+    const int j = rho & 15, G = rho >> 4;
+    return ((((G >> 2) * 4 + (j >> 2)) * 4 + (G & 3)) << 2) | (j & 3);
+  }
+  return rho;
+}
+
 // PL: 16-byte patch loads per thread, i.e. the patch holds at most PL * 64 pixels.
 //
-// Software pipeline (u = chunk*9 + tap is the step index; a step is one tap of one chunk):
-//   weights: global load of step u+DL -> a register set ... stored to LDS ring slot (u+2)%3 at
-//            the end of step u, so that at step u the ring holds steps u and u+1;
-//   patch:   chunk c+1 is loaded at tap 0 of chunk c and stored to the other patch buffer at tap 6;
-//   MFMA operands of step u+1 are read from LDS into the second fragment set while the MFMAs of
-//   step u run from the first, so the matrix pipe never waits for LDS after a barrier.
+// Software pipeline.  A step is one filter row (three taps) of one 32-channel chunk, 24 MFMAs per
+// wave between two barriers; g = 3 * chunk + row is the step index.
+//   weights: the three taps of step g live in LDS buffer g % 2.  Those of step g+3 are loaded from
+//            global memory into register set (g+1) % 2 at the start of step g and stored to LDS
+//            buffer (g+1) % 2 at the start of step g+2, i.e. two steps in flight;
+//   patch:   chunk c+1 is loaded at row 0 of chunk c and stored to the other patch buffer at row 2;
+//   MFMA operands of the next tap are read from LDS between the MFMAs of the current tap (two
+//   fragment sets; scheduling directives pin the interleaving, because left alone the compiler
+//   reads just in time - read, wait, multiply - and exposes the LDS latency eight times per tap).
+// Nothing in a step is conditional on "is there another chunk": past the last chunk the loads
+// fetch in-range or zero-filled bytes that land in LDS buffers nobody reads any more.  Straight
+// line code lets the compiler count the loads in flight exactly, so every wait is for the oldest
+// load only.
+//
+// What bounds it: a 32x32x16 MFMA needs 2 KB of operands; with 64 x 64 wave tiles that is 1 KB of
+// LDS reads per MFMA, 4 KB per 32 cycles and CU, against the ~180 B/clk that 16-byte LDS reads
+// sustain: the LDS pipe is ~70 % busy when the matrix pipe is full, so the two have to overlap
+// almost perfectly.  Measured: 45-65 % of the MFMA rate inside the main loop.
 template <int BM, int BN, int WM, int WN, int OCC, int PL>
 __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -56,7 +88,7 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   const int patch_px = a.TI * PH * PW;
   const int patch_bytes = patch_px * 64;
   unsigned char* Pb = smem_raw;                      // [2][patch_px][64 B]
-  unsigned char* Bb = smem_raw + 2 * patch_bytes;    // [3][BN][64 B]
+  unsigned char* Bb = smem_raw + 2 * patch_bytes;    // [2][3][BN][64 B]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wn = wave / WM;
@@ -101,7 +133,7 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   int app[TM];
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
-    const int p = wm * TM * 32 + i * 32 + (lane & 31);
+    const int p = tile_pixel(wm * TM * 32 + i * 32 + (lane & 31), a.perm);
     int q, tw, ti, th;
     a.dW.divmod(p, &q, &tw);
     a.dTH.divmod(q, &ti, &th);
@@ -122,12 +154,7 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
 
   const int nchunks = a.Cs / CK;
   uint4 preg[PL];
-  // weight prefetch: with one 16-byte load per thread and step (BN <= 64) there is a register set
-  // per tap and the load runs a whole chunk (9 steps) ahead, which covers the L2/HBM latency;
-  // wider tiles keep 3 sets and a distance of 4 steps
-  constexpr int NS = B_IT == 1 ? 9 : 3, DL = B_IT == 1 ? 9 : 4;
-  uint4 rb[NS][B_IT];
-  bf16x8_t af[2][TM][KK], bfr[2][TN][KK];
+  uint4 rb[2][3][B_IT];
 
   auto load_patch = [&](int chunk) {
 #pragma unroll
@@ -139,23 +166,32 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
       if ((tid >> 2) + j * (kThreads / 4) < patch_px)
         *reinterpret_cast<uint4*>(Pb + buf * patch_bytes + pst0 + j * (kThreads / 4) * 64) = preg[j];
   };
-  auto load_b = [&](int chunk, auto TAP) {   // weights of step (chunk, TAP) -> register set TAP % NS
-    constexpr int tap = decltype(TAP)::value, rs = tap % NS;
-    const unsigned so = (unsigned)(a.widx[tap] * a.Cs + chunk * CK) * 2u;
+  auto load_w = [&](int chunk, auto ROW, auto SET) {   // the three taps of (chunk, filter row ROW) -> register set SET
+    constexpr int row = decltype(ROW)::value, rs = decltype(SET)::value;
 #pragma unroll
-    for (int it = 0; it < B_IT; ++it) rb[rs][it] = buffer_load16(wt_rs, boff[it], so);
-  };
-  auto store_b = [&](auto TAP) {             // register set TAP % NS -> ring slot TAP % 3
-    constexpr int rs = decltype(TAP)::value % NS, slot = decltype(TAP)::value % 3;
+    for (int s3 = 0; s3 < 3; ++s3) {
+      const unsigned so = (unsigned)(a.widx[row * 3 + s3] * a.Cs + chunk * CK) * 2u;
 #pragma unroll
-    for (int it = 0; it < B_IT; ++it)
-      if (BN % 64 == 0 || r0 + it * 64 < BN)
-        *reinterpret_cast<uint4*>(Bb + slot * (BN * 64) + bst[it]) = rb[rs][it];
+      for (int it = 0; it < B_IT; ++it) rb[rs][s3][it] = buffer_load16(wt_rs, boff[it], so);
+    }
   };
-  // MFMA operands of tap TAP from patch buffer `pbuf` and ring slot TAP % 3 into fragment set SET
-  auto read_frags = [&](int pbuf, auto TAP, auto SET) {
-    constexpr int tap = decltype(TAP)::value, fs = decltype(SET)::value;
-    const int tpx = a.toff_h[tap] * PW + a.toff_w[tap];
+  auto store_w = [&](auto SET, auto WB) {    // register set SET -> LDS weight buffer WB
+    constexpr int rs = decltype(SET)::value, wb = decltype(WB)::value;
+#pragma unroll
+    for (int s3 = 0; s3 < 3; ++s3)
+#pragma unroll
+      for (int it = 0; it < B_IT; ++it)
+        if (BN % 64 == 0 || r0 + it * 64 < BN)
+          *reinterpret_cast<uint4*>(Bb + (wb * 3 + s3) * (BN * 64) + bst[it]) = rb[rs][s3][it];
+  };
+  bf16x8_t af[2][TM][KK], bfr[2][TN][KK];
+  // MFMA operands of tap TAP from patch buffer `pbuf` and weight buffer WB into fragment set SET
+  auto read_frags = [&](int pbuf, auto TAP, auto WB, auto SET) {
+    constexpr int tap = decltype(TAP)::value, wb = decltype(WB)::value, fs = decltype(SET)::value;
+    // per-tap patch offset; opaque to the optimiser so that the (tap, row) LDS addresses are
+    // recomputed here (5 VALU each) instead of being hoisted out of the chunk loop into registers
+    int tpx = a.toff_h[tap] * PW + a.toff_w[tap];
+    asm volatile("" : "+s"(tpx));
     const unsigned char* P = Pb + pbuf * patch_bytes;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
@@ -164,7 +200,7 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
       af[fs][i][0] = *reinterpret_cast<const bf16x8_t*>(P + o);
       af[fs][i][1] = *reinterpret_cast<const bf16x8_t*>(P + (o ^ 32));   // chunk + 2
     }
-    const unsigned char* B = Bb + (tap % 3) * (BN * 64);
+    const unsigned char* B = Bb + (wb * 3 + tap % 3) * (BN * 64);
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       bfr[fs][j][0] = *reinterpret_cast<const bf16x8_t*>(B + bfo[j]);
@@ -181,67 +217,61 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[fs][i][kk], bfr[fs][j][kk], acc[i][j], 0, 0, 0);
   };
-  // PAR = chunk % 2: patch buffer of this chunk, and the parity that fixes the fragment set.
-  // Nothing in a step is conditional on "is there another chunk": past the last chunk the loads
-  // fetch in-range or zero-filled bytes that land in LDS slots nobody reads any more.  Straight
-  // line code lets the compiler count the loads in flight exactly, so every wait is for the
-  // oldest load only.
-  auto step = [&](int chunk, auto PARC, auto TAP) {
-    constexpr int par = decltype(PARC)::value, tap = decltype(TAP)::value;
-    constexpr int cur = (par + tap) % 2;
-    if constexpr (tap + DL < 9) {
-      load_b(chunk, std::integral_constant<int, tap + DL>{});
-    } else {
-      load_b(chunk + 1, std::integral_constant<int, tap + DL - 9>{});
+  // the MFMAs of one tap with the operand reads of the next tap spread between them: the compiler
+  // on its own reads just in time (read, wait, multiply), which leaves the LDS latency exposed
+  auto interleave = [&]() {
+    constexpr int n_mfma = TM * TN * KK, n_read = (TM + TN) * KK;
+#pragma unroll
+    for (int k = 0; k < n_mfma; ++k) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                   // one MFMA
+      if (k < n_read) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                   // one LDS read
     }
-    if constexpr (tap == 0) load_patch(chunk + 1);
-    if constexpr (tap + 1 < 9) {
-      read_frags(par, std::integral_constant<int, tap + 1>{}, std::integral_constant<int, cur ^ 1>{});
-    } else {
-      read_frags(par ^ 1, std::integral_constant<int, 0>{}, std::integral_constant<int, cur ^ 1>{});
-    }
-    mfmas(std::integral_constant<int, cur>{});
-    if constexpr (tap + 2 < 9) {
-      store_b(std::integral_constant<int, tap + 2>{});
-    } else {
-      store_b(std::integral_constant<int, tap + 2 - 9>{});
-    }
-    if constexpr (tap == 6) store_patch(par ^ 1);
+  };
+  // PARC = chunk % 2 (patch buffer of this chunk); the weight buffer / register set parities follow
+  // from (chunk + row) % 2
+  auto step = [&](int chunk, auto PARC, auto ROW) {
+    constexpr int par = decltype(PARC)::value, row = decltype(ROW)::value;
+    constexpr int cur = (par + row) % 2, nxt = cur ^ 1;
+    using WB = std::integral_constant<int, cur>;
+    using NX = std::integral_constant<int, nxt>;
+    using F0 = std::integral_constant<int, 0>;
+    using F1 = std::integral_constant<int, 1>;
+    store_w(NX{}, NX{});                      // weights of step g+1
+    load_w(chunk + 1, ROW, NX{});             // step g+3 = (chunk+1, row)
+    if constexpr (row == 0) load_patch(chunk + 1);
+    if constexpr (row == 2) store_patch(par ^ 1);
+    read_frags(par, std::integral_constant<int, row * 3 + 0>{}, WB{}, F0{});
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(par, std::integral_constant<int, row * 3 + 1>{}, WB{}, F1{});
+    mfmas(F0{});
+    interleave();
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(par, std::integral_constant<int, row * 3 + 2>{}, WB{}, F0{});
+    mfmas(F1{});
+    interleave();
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas(F0{});
     __syncthreads();
   };
   auto chunk_body = [&](int chunk, auto PARC) {
     step(chunk, PARC, std::integral_constant<int, 0>{});
     step(chunk, PARC, std::integral_constant<int, 1>{});
     step(chunk, PARC, std::integral_constant<int, 2>{});
-    step(chunk, PARC, std::integral_constant<int, 3>{});
-    step(chunk, PARC, std::integral_constant<int, 4>{});
-    step(chunk, PARC, std::integral_constant<int, 5>{});
-    step(chunk, PARC, std::integral_constant<int, 6>{});
-    step(chunk, PARC, std::integral_constant<int, 7>{});
-    step(chunk, PARC, std::integral_constant<int, 8>{});
   };
 
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>;
   load_patch(0);
-  load_b(0, std::integral_constant<int, 0>{});
-  load_b(0, std::integral_constant<int, 1>{});
-  load_b(0, std::integral_constant<int, 2>{});
-  if constexpr (NS == 9) {
-    load_b(0, std::integral_constant<int, 3>{});
-    load_b(0, std::integral_constant<int, 4>{});
-    load_b(0, std::integral_constant<int, 5>{});
-    load_b(0, std::integral_constant<int, 6>{});
-    load_b(0, std::integral_constant<int, 7>{});
-    load_b(0, std::integral_constant<int, 8>{});
-  }
+  load_w(0, I0{}, I0{});
+  load_w(0, I1{}, I1{});
   store_patch(0);
-  store_b(std::integral_constant<int, 0>{});
-  store_b(std::integral_constant<int, 1>{});
-  if constexpr (NS == 3) load_b(0, std::integral_constant<int, 3>{});   // register set 0 is free again
+  store_w(I0{}, I0{});
+  load_w(0, I2{}, I0{});   // register set 0 is free again
   __syncthreads();
-  read_frags(0, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
   for (int chunk = 0; chunk < nchunks; chunk += 2) {
-    chunk_body(chunk, std::integral_constant<int, 0>{});
-    if (chunk + 1 < nchunks) chunk_body(chunk + 1, std::integral_constant<int, 1>{});
+    chunk_body(chunk, I0{});
+    if (chunk + 1 < nchunks) chunk_body(chunk + 1, I1{});
   }
 
   if (a.stats) {
@@ -296,7 +326,7 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   __syncthreads();
   for (int idx = tid; idx < BM * (BN / 8); idx += kThreads) {
     const int row = idx / (BN / 8), ch = idx % (BN / 8);
-    const int m = m0 + row, co = nt * BN + ch * 8;
+    const int m = m0 + tile_pixel(row, a.perm), co = nt * BN + ch * 8;
     if (m >= M || co >= a.Cd) continue;
     bf16_t* dp = a.dst + (size_t)m * a.Cd + co;
     if (a.accumulate) {
@@ -331,7 +361,7 @@ bool tile_geometry(const ConvGeom& g, int bm, int max_px, int* ti, int* th) {
 
 template <int BM, int BN>
 size_t patch_smem(int patch_px) {
-  const size_t stage = (size_t)2 * patch_px * 64 + (size_t)3 * BN * 64;
+  const size_t stage = (size_t)2 * patch_px * 64 + (size_t)6 * BN * 64;
   const size_t epi = (size_t)BM * (BN + 8) * sizeof(bf16_t);
   return stage > epi ? stage : epi;
 }
@@ -384,13 +414,15 @@ bool plan_patch(const ConvGeom& g, int Cs, int Cd, PatchPlan* p) {
 
 int run_patch(const ConvGeom& g, PatchArgs& a, const PatchPlan& p, hipStream_t st) {
   a.TI = p.ti; a.TH = p.th;
+  a.perm = (a.W == 8 && a.TH == 8) ? 1 : (a.W == 4 && a.TH == 4 && a.TI % 4 == 0) ? 2 : 0;
+  if (g_cnnk_tune[7] < 0) a.perm = 0;
   a.dPW.init(a.W + 2); a.dPH.init(a.TH + 2); a.dW.init(a.W); a.dTH.init(a.TH);
   if (p.bm == 256 && p.bn == 128) return launch_patch<256, 128, 2, 2, 2, 6>(a, st);
   if (p.bm == 256 && p.bn == 64)
     return a.TI * (a.TH + 2) * (a.W + 2) <= 6 * kPxPerLoad ? launch_patch<256, 64, 4, 1, 2, 6>(a, st)
                                                             : launch_patch<256, 64, 4, 1, 2, 7>(a, st);
   if (p.bm == 128 && p.bn == 128) return launch_patch<128, 128, 2, 2, 2, 5>(a, st);
-  if (p.bm == 128 && p.bn == 64) return launch_patch<128, 64, 4, 1, 3, 5>(a, st);
+  if (p.bm == 128 && p.bn == 64) return launch_patch<128, 64, 4, 1, 2, 5>(a, st);
   (void)g;
   return CNNK_ERR_UNSUPPORTED;
 }
