@@ -199,7 +199,9 @@ typedef struct cnnk_buffers {
    * when the backward pass reaches the layer, and nothing but the parameter update consumes it,
    * so it can run beside the rest of the backward pass: the step records ev_fork on `stream`
    * before each weight gradient and makes aux_stream wait for it, and joins through ev_join
-   * before the update.  aux_stream must not carry other work during the call; both events are
+   * before the update; each convolution's weights are updated on the second stream too, right
+   * after their gradient (and after the data gradient that still reads them).  aux_stream must
+   * not carry other work during the call; both events are
    * hipEvent_t handles created by the caller (timing may be disabled).  With an aux stream the
    * workspace must be twice cnnk_train_step_workspace_bytes. */
   void* aux_stream;

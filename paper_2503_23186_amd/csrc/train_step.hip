@@ -214,9 +214,61 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
   void* ws = wt_region + w.wt_bytes;
   const size_t wsb = (aux ? ws_one : B->ws_bytes) - kStatBytes - w.wt_bytes;
   GroupTimer timer(B, n, stream);
+  // Side branches of the forward pass: a convolution i whose output goes through a plain batch norm
+  // (i+1: no ReLU, no residual) into nothing but the residual input of a later batch norm j - the
+  // projection shortcut of a residual block.  With a second stream the pair runs there, launched
+  // when the main stream reaches the first other reader a < i of the same input, and joined in
+  // front of j.
+  std::vector<int> side_of(n, -1);     // side_of[a] = i: launch the branch that starts at i before layer a
+  std::vector<char> on_side(n, 0), join_before(n, 0);
+  if (aux && bf16) {
+    for (int i = 0; i + 1 < n; ++i) {
+      const cnnk_layer& c = L[i];
+      const cnnk_layer& b = L[i + 1];
+      if (c.op != CNNK_OP_CONV || b.op != CNNK_OP_BN || b.in0 != c.out || b.in1 >= 0 || b.d.bn.relu) continue;
+      int readers_c = 0, readers_b = 0, j = -1, a = -1;
+      for (int k = 0; k < n; ++k) {
+        if (L[k].op == CNNK_OP_FC_LOSS) { if (L[k].in0 == c.out || L[k].in0 == b.out) readers_b = 99; continue; }
+        const bool two = L[k].op == CNNK_OP_BN || L[k].op == CNNK_OP_ADD;
+        if (L[k].in0 == c.out || (two && L[k].in1 == c.out)) ++readers_c;
+        if (L[k].in0 == b.out) readers_b = 99;
+        if (two && L[k].in1 == b.out) { ++readers_b; j = (L[k].op == CNNK_OP_BN) ? k : -1; }
+        if (a < 0 && k < i && (L[k].in0 == c.in0 || (two && L[k].in1 == c.in0))) a = k;
+      }
+      if (readers_c != 1 || readers_b != 1 || j <= i + 1 || a < 0 || side_of[a] >= 0) continue;
+      side_of[a] = i;
+      on_side[i] = on_side[i + 1] = 1;
+      join_before[j] = 1;
+    }
+  }
+  float* const aux_stat = reinterpret_cast<float*>(aux_ws);              // sums hand-off of a side branch
+  void* const aux_scratch = static_cast<char*>(aux_ws) + 2 * 2048 * sizeof(float);
+  const size_t aux_scratch_b = aux ? aux_wsb - 2 * 2048 * sizeof(float) : 0;
   // ---- forward pass and loss ---------------------------------------------------------------
   for (int i = 0; i < n; ++i) {
     const cnnk_layer& l = L[i];
+    if (side_of[i] >= 0) {
+      const int s0 = side_of[i];
+      const cnnk_layer& c = L[s0];
+      const cnnk_layer& b = L[s0 + 1];
+      if (hipEventRecord((hipEvent_t)B->ev_fork, (hipStream_t)stream) != hipSuccess ||
+          hipStreamWaitEvent(aux, (hipEvent_t)B->ev_fork, 0) != hipSuccess)
+        return CNNK_ERR_HIP;
+      const bool sums = c.d.conv.Cout % 8 == 0 && c.d.conv.Cout <= 2048;
+      rc = cnnk_conv2d_fwd(&c.d.conv, B->act[c.in0], B->param_lp[c.p0], B->act[c.out], sums ? aux_stat : nullptr,
+                           sums ? aux_stat + 2048 : nullptr, aux_scratch, aux_scratch_b, aux);
+      if (rc != CNNK_OK) return rc;
+      float* run = B->bn_running ? B->bn_running[s0 + 1] : nullptr;
+      rc = cnnk_bn_relu_fwd(&b.d.bn, B->act[b.in0], nullptr, B->param[b.p0], B->param[b.p1], B->act[b.out],
+                            B->bn_save[s0 + 1], B->bn_save[s0 + 1] + b.d.bn.C, run, run ? run + b.d.bn.C : nullptr,
+                            sums ? aux_stat : nullptr, sums ? aux_stat + 2048 : nullptr, aux_scratch, aux_scratch_b,
+                            aux);
+      if (rc != CNNK_OK) return rc;
+      if (hipEventRecord((hipEvent_t)B->ev_join, aux) != hipSuccess) return CNNK_ERR_HIP;
+    }
+    if (on_side[i]) continue;
+    if (join_before[i] && hipStreamWaitEvent((hipStream_t)stream, (hipEvent_t)B->ev_join, 0) != hipSuccess)
+      return CNNK_ERR_HIP;
     timer.begin(i);
     switch (l.op) {
       case CNNK_OP_CONV: {
@@ -285,6 +337,7 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
     if (rc != CNNK_OK) return rc;
   }
   std::vector<char> written(w.slot_elems.size(), 0);
+  std::vector<char> updated(w.param_elems.size(), 0);   // parameters already updated on the second stream
   written[L[n - 1].in0] = 1;
   for (int i = n - 2; i >= 0; --i) {
     const cnnk_layer& l = L[i];
@@ -315,6 +368,22 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
             rc = cnnk_conv2d_dgrad(&l.d.conv, B->dact[l.out], wt, B->dact[l.in0], written[l.in0], ws, wsb, stream);
           }
           written[l.in0] = 1;
+        }
+        if (aux && rc == CNNK_OK) {
+          // The update of this layer's weights follows its weight gradient on the second stream,
+          // once the data gradient above (the last reader of the weights in this step) is done.
+          if (l.in0 != 0 && (hipEventRecord((hipEvent_t)B->ev_fork, (hipStream_t)stream) != hipSuccess ||
+                             hipStreamWaitEvent(aux, (hipEvent_t)B->ev_fork, 0) != hipSuccess))
+            return CNNK_ERR_HIP;
+          SgdTable t1;
+          t1.count = 1;
+          t1.w[0] = B->param[l.p0];
+          t1.v[0] = B->mom[l.p0];
+          t1.g[0] = B->grad[l.p0];
+          t1.wlp[0] = (bf16 && B->param_lp) ? B->param_lp[l.p0] : nullptr;
+          t1.n[0] = w.param_elems[l.p0];
+          rc = sgd_multi(t1, lr, momentum, weight_decay, aux);
+          updated[l.p0] = 1;
         }
         break;
       }
@@ -367,7 +436,7 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
   SgdTable t;
   t.count = 0;
   for (size_t p = 0; p < w.param_elems.size(); ++p) {
-    if (w.param_elems[p] == 0) continue;
+    if (w.param_elems[p] == 0 || updated[p]) continue;
     const int k = t.count++;
     t.w[k] = B->param[p];
     t.v[k] = B->mom[p];
