@@ -177,3 +177,44 @@ def test_step_full_size_against_fixture():
         assert nerr <= 1.5 * floor + 2e-2, (name, nerr, floor)
         assert serr <= 1.5 * sfloor + 4.0 * floor * (t["l2"] / np.sqrt(t["size"])) / scale + 2e-2, (name, serr, sfloor)
     print("worst norm deviation per class:", {k: "%.1e" % v for k, v in worst.items()})
+
+
+def test_conv_beyond_2gib_falls_back(K):
+    """A tensor of 2^30 elements or more is outside what the buffer-load kernels address (byte
+    offset 2^31 marks padding); the library must route it to the pointer-based kernels.  Forward
+    and data gradient of a thin 3x3 convolution on a 1 x 11600 x 11600 x 8 image (2.15 GB per
+    tensor), generated on the device and checked on windows sampled at both ends of the tensor."""
+    N, H, W, C = 1, 11600, 11600, 8
+    assert N * H * W * C >= 1 << 30
+    gen = torch.Generator(device="cuda:0").manual_seed(3)
+    gx = torch.randn((N, H, W, C), generator=gen, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
+    gw = (torch.randn((C, 3, 3, C), generator=gen, device="cuda:0", dtype=torch.float32) * 0.1).to(torch.bfloat16)
+    d = K.conv_desc(N, H, W, C, C, 3, 3, 1, 1, K.BF16)
+    ws, nb = ws_for(max(K.cnnk_conv2d_workspace_bytes(d, p) for p in (0, 1)))
+    gy = torch.empty((N, H, W, C), dtype=torch.bfloat16, device="cuda:0")
+    K.cnnk_conv2d_fwd(d, gx, gw, gy, None, None, ws, nb)
+    torch.cuda.synchronize()
+    w = host(gw)
+    rng = np.random.default_rng(4)
+    spots = [(0, 0), (0, W - 1), (H - 1, 0), (H - 1, W - 1), (H - 2, W - 3)]
+    spots += [(int(rng.integers(1, H - 1)), int(rng.integers(1, W - 1))) for _ in range(11)]
+    got, want = [], []
+    for h, wi in spots:
+        h0, h1, w0, w1 = max(h - 1, 0), min(h + 2, H), max(wi - 1, 0), min(wi + 2, W)
+        win = np.zeros((1, 3, 3, C))
+        win[0, h0 - (h - 1):h1 - (h - 1), w0 - (wi - 1):w1 - (wi - 1), :] = host(gx[0, h0:h1, w0:w1, :])
+        want.append(ref.conv2d_fwd(win, w, 1, 0)[0, 0, 0, :])
+        got.append(host(gy[0, h, wi, :]))
+    assert max_rel_err(np.array(got), np.array(want)) <= 1e-2
+    # data gradient, written into the buffer that held x (dy := y)
+    K.cnnk_conv2d_dgrad(d, gy, gw, gx, 0, ws, nb)
+    torch.cuda.synchronize()
+    got, want = [], []
+    for h, wi in spots:
+        h0, h1, w0, w1 = max(h - 1, 0), min(h + 2, H), max(wi - 1, 0), min(wi + 2, W)
+        dyc = np.zeros((1, 3, 3, C))
+        dyc[0, h0 - (h - 1):h1 - (h - 1), w0 - (wi - 1):w1 - (wi - 1), :] = host(gy[0, h0:h1, w0:w1, :])
+        # the 3x3 block of outputs around (h, wi) read a 5x5 block of inputs whose centre is (h, wi)
+        want.append(ref.conv2d_dgrad(dyc, w, (1, 5, 5, C), 1, 0)[0, 2, 2, :])
+        got.append(host(gx[0, h, wi, :]))
+    assert max_rel_err(np.array(got), np.array(want)) <= 1e-2
