@@ -148,21 +148,38 @@ __global__ void __launch_bounds__(kThreads, OCC) igemm_kernel(IgemmArgs a) {
       if (BN % RPP == 0 || r0 + it * RPP < BN)
         *reinterpret_cast<uint4*>(Bs + (buf * BN + r0 + it * RPP) * LDK + kc * 8) = rb[rs][it];
   };
+  // One stage of MFMAs: the operands of 16-element slice kk+1 are read from LDS between the MFMAs
+  // of slice kk (two fragment sets; the scheduling directives pin the alternation, because left
+  // alone the compiler reads just in time and exposes the LDS latency once per slice).
   auto compute = [&](int cur) {
     const bf16_t* Ab = As + (cur * BM + wm * TM * 32 + (lane & 31)) * LDK + (lane >> 5) * 8;
     const bf16_t* Bb = Bs + (cur * BN + wn * TN * 32 + (lane & 31)) * LDK + (lane >> 5) * 8;
+    constexpr int KK = BK / 16;
+    bf16x8_t af[2][TM], bfr[2][TN];
+    auto read_slice = [&](int kk, int set) {   // both constants after unrolling
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8_t af[TM], bfr[TN];
+      for (int i = 0; i < TM; ++i) af[set][i] = *reinterpret_cast<const bf16x8_t*>(Ab + i * 32 * LDK + kk * 16);
 #pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const bf16x8_t*>(Ab + i * 32 * LDK + kk * 16);
+      for (int j = 0; j < TN; ++j) bfr[set][j] = *reinterpret_cast<const bf16x8_t*>(Bb + j * 32 * LDK + kk * 16);
+    };
+    read_slice(0, 0);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) bfr[j] = *reinterpret_cast<const bf16x8_t*>(Bb + j * 32 * LDK + kk * 16);
+    for (int kk = 0; kk < KK; ++kk) {
+      if (kk + 1 < KK) read_slice(kk + 1, (kk + 1) & 1);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+      if (kk + 1 < KK) {
+#pragma unroll
+        for (int q = 0; q < TM * TN; ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                    // one MFMA
+          if (q < TM + TN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
