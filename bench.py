@@ -59,8 +59,11 @@ def layer_work(L, phase, esz):
         T = L["N"] * L["H"] * L["W"] * L["C"] * esz
         res = 1 if L["res"] >= 0 else 0
         if phase == "fwd":
-            return 0.0, (3 + res) * T          # statistics pass + normalise pass (+ residual read)
-        return 0.0, (5 + res) * T              # dy, x twice; dx once (+ residual gradient write)
+            # inside the step the statistics arrive from the convolution's epilogue: the call reads x
+            # (and the residual) and writes y
+            return 0.0, (2 + res) * T
+        # dy and x twice, dx once; with a residual branch also y twice (the mask) and the residual gradient
+        return 0.0, (5 + 3 * res) * T
     if L["op"] == "pool":
         T = L["N"] * L["H"] * L["W"] * L["C"] * esz
         out = T // 4 if L["mode"] == "max2" else L["N"] * L["C"] * esz

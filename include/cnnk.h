@@ -194,16 +194,22 @@ typedef struct cnnk_buffers {
   void* ws; size_t ws_bytes;
   void** events;            /* nullable: hipEvent_t handles for per-call timing, see below */
   int n_events;             /* number of handles in events */
-  /* Optional second stream for the weight gradients (all three or none; ignored while per-call
-   * timing is on).  The weight gradient of a convolution depends only on tensors that are final
-   * when the backward pass reaches the layer, and nothing but the parameter update consumes it,
-   * so it can run beside the rest of the backward pass: the step records ev_fork on `stream`
-   * before each weight gradient and makes aux_stream wait for it, and joins through ev_join
-   * before the update; each convolution's weights are updated on the second stream too, right
-   * after their gradient (and after the data gradient that still reads them).  aux_stream must
-   * not carry other work during the call; both events are
-   * hipEvent_t handles created by the caller (timing may be disabled).  With an aux stream the
-   * workspace must be twice cnnk_train_step_workspace_bytes. */
+  /* Optional second stream (all three handles or none; ignored while per-call timing is on).
+   * Work that the rest of the step does not wait for runs there, beside the main stream:
+   *  - every weight gradient: it depends only on tensors that are final when the backward pass
+   *    reaches the layer, and only the parameter update consumes it;
+   *  - the update of each convolution's weights, right after their gradient and after the data
+   *    gradient that still reads them;
+   *  - in the forward pass, a projection shortcut (a convolution and the plain batch norm behind
+   *    it whose output is only the residual input of a later batch norm), launched when the main
+   *    stream reaches the first other reader of the same input.
+   * The step forks with ev_fork (recorded on `stream`, waited for on aux_stream) and joins with
+   * ev_join (the other way round), the last time in front of the update of the remaining
+   * parameters.  aux_stream must not carry other work during the call and must have the default
+   * priority; both events are hipEvent_t handles created by the caller (timing may be disabled).
+   * With an aux stream the workspace must be twice cnnk_train_step_workspace_bytes.  Results are
+   * bit-reproducible for a given mode; between the modes they differ by fp32 rounding (the forked
+   * weight gradients split their reduction over fewer workgroups). */
   void* aux_stream;
   void* ev_fork;
   void* ev_join;
