@@ -7,27 +7,67 @@
 
 namespace {
 constexpr int kT = 256;
-constexpr int kPerBlock = kT * 4;
+constexpr int kVec = 4;                    // float4 accesses
+constexpr int kIters = 4;                  // float4 per thread, all loads issued before the arithmetic
+constexpr int kPerBlock = kT * kVec * kIters;
 
+__device__ __forceinline__ float sgd_one(float wi, float vi, float gi, float lr, float mu, float wd, float* vn) {
+  const float gp = fmaf(wd, wi, gi);
+  *vn = fmaf(mu, vi, gp);
+  return fmaf(-lr, *vn, wi);
+}
+
+// Elements [begin, end) of one tensor; begin is a multiple of kPerBlock, the tensors are 16-byte
+// aligned (checked on the host, else kVec-wide accesses are not used).
 __device__ __forceinline__ void sgd_range(float* __restrict__ w, float* __restrict__ v, const float* __restrict__ g,
                                           bf16_t* __restrict__ wlp, size_t begin, size_t end, float lr, float mu,
-                                          float wd) {
+                                          float wd, bool vec) {
+  if (vec && begin + kPerBlock <= end) {
+    float4 wv[kIters], vv[kIters], gv[kIters];
+#pragma unroll
+    for (int k = 0; k < kIters; ++k) {
+      const size_t i = begin + ((size_t)k * kT + threadIdx.x) * kVec;
+      wv[k] = *reinterpret_cast<const float4*>(w + i);
+      vv[k] = *reinterpret_cast<const float4*>(v + i);
+      gv[k] = *reinterpret_cast<const float4*>(g + i);
+    }
+#pragma unroll
+    for (int k = 0; k < kIters; ++k) {
+      const size_t i = begin + ((size_t)k * kT + threadIdx.x) * kVec;
+      float4 vn, wn;
+      wn.x = sgd_one(wv[k].x, vv[k].x, gv[k].x, lr, mu, wd, &vn.x);
+      wn.y = sgd_one(wv[k].y, vv[k].y, gv[k].y, lr, mu, wd, &vn.y);
+      wn.z = sgd_one(wv[k].z, vv[k].z, gv[k].z, lr, mu, wd, &vn.z);
+      wn.w = sgd_one(wv[k].w, vv[k].w, gv[k].w, lr, mu, wd, &vn.w);
+      *reinterpret_cast<float4*>(v + i) = vn;
+      *reinterpret_cast<float4*>(w + i) = wn;
+      if (wlp) {
+        uint2 p;
+        p.x = (unsigned)f32_to_bf16(wn.x) | ((unsigned)f32_to_bf16(wn.y) << 16);
+        p.y = (unsigned)f32_to_bf16(wn.z) | ((unsigned)f32_to_bf16(wn.w) << 16);
+        *reinterpret_cast<uint2*>(wlp + i) = p;
+      }
+    }
+    return;
+  }
   for (size_t i = begin + threadIdx.x; i < end; i += kT) {
-    const float wi = w[i];
-    const float gp = fmaf(wd, wi, g[i]);
-    const float vn = fmaf(mu, v[i], gp);
-    const float wn = fmaf(-lr, vn, wi);
+    float vn;
+    const float wn = sgd_one(w[i], v[i], g[i], lr, mu, wd, &vn);
     v[i] = vn;
     w[i] = wn;
     if (wlp) wlp[i] = f32_to_bf16(wn);
   }
 }
 
+__device__ __forceinline__ bool sgd_aligned(const float* w, const float* v, const float* g, const bf16_t* wlp) {
+  return ((((size_t)w | (size_t)v | (size_t)g) & 15) == 0) && (((size_t)wlp & 7) == 0);
+}
+
 __global__ void __launch_bounds__(kT) sgd_kernel(float* w, float* v, const float* g, bf16_t* wlp, size_t n, float lr,
                                                  float mu, float wd) {
   const size_t begin = (size_t)blockIdx.x * kPerBlock;
   const size_t end = begin + kPerBlock < n ? begin + kPerBlock : n;
-  sgd_range(w, v, g, wlp, begin, end, lr, mu, wd);
+  sgd_range(w, v, g, wlp, begin, end, lr, mu, wd, sgd_aligned(w, v, g, wlp));
 }
 
 __global__ void __launch_bounds__(kT) sgd_multi_kernel(SgdTable t, float lr, float mu, float wd) {
@@ -36,7 +76,8 @@ __global__ void __launch_bounds__(kT) sgd_multi_kernel(SgdTable t, float lr, flo
   const size_t begin = (size_t)(blockIdx.x - t.block_begin[k]) * kPerBlock;
   const size_t n = t.n[k];
   const size_t end = begin + kPerBlock < n ? begin + kPerBlock : n;
-  sgd_range(t.w[k], t.v[k], t.g[k], reinterpret_cast<bf16_t*>(t.wlp[k]), begin, end, lr, mu, wd);
+  bf16_t* wlp = reinterpret_cast<bf16_t*>(t.wlp[k]);
+  sgd_range(t.w[k], t.v[k], t.g[k], wlp, begin, end, lr, mu, wd, sgd_aligned(t.w[k], t.v[k], t.g[k], wlp));
 }
 }  // namespace
 

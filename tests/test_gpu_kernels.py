@@ -342,3 +342,19 @@ def test_sgd_add_route(K):
             tol = 4e-3 if dtype == "bf16" else 1e-6
             assert max_rel_err(host(gy), a + b) <= tol and max_rel_err(host(gr), a + b) <= tol
             assert np.array_equal(host(gc), a)
+
+
+def test_sgd_unaligned_tensors(K):
+    """Tensors that are not 16-byte aligned take the scalar path of the update kernel."""
+    rng = np.random.default_rng(52)
+    n = 9000
+    w = rng.standard_normal(n + 1).astype(np.float32).astype(np.float64)
+    v = rng.standard_normal(n + 1).astype(np.float32).astype(np.float64)
+    g = rng.standard_normal(n + 1).astype(np.float32).astype(np.float64)
+    w_ref, v_ref = w[1:].copy(), v[1:].copy()
+    ref.sgd_momentum(w_ref, v_ref, g[1:], 0.1, 0.9, 5e-4)
+    gw, gv, gg = dev_f32(w), dev_f32(v), dev_f32(g)
+    K.cnnk_sgd_momentum(n, gw[1:], gv[1:], gg[1:], None, 0.1, 0.9, 5e-4)
+    torch.cuda.synchronize()
+    assert max_rel_err(host(gw[1:]), w_ref) <= 1e-6 and max_rel_err(host(gv[1:]), v_ref) <= 1e-6
+    assert host(gw[:1])[0] == w[0] and host(gv[:1])[0] == v[0]
