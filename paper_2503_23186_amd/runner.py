@@ -22,6 +22,42 @@ def _numel(shape):
     return n
 
 
+def build_c_layers(layers, dt):
+    """The layer list (dicts of workloads.nets.Net.layers) as the array of cnnk_layer structs that
+    cnnk_train_step takes.  Marshalling only; needs no GPU."""
+    nl = len(layers)
+    arr = (cnnk.Layer * nl)()
+    for i, L in enumerate(layers):
+        cl = arr[i]
+        cl.in0 = cl.in1 = cl.out = cl.p0 = cl.p1 = -1
+        op = L["op"]
+        if op == "conv":
+            cl.op = cnnk.OP_CONV
+            cl.in0, cl.out, cl.p0 = L["x"], L["y"], L["w"]
+            cl.d.conv = cnnk.conv_desc(L["N"], L["H"], L["W"], L["Cin"], L["Cout"], L["R"], L["S"],
+                                       L["stride"], L["pad"], dt)
+        elif op == "bn":
+            cl.op = cnnk.OP_BN
+            cl.in0, cl.in1, cl.out, cl.p0, cl.p1 = L["x"], L["res"], L["y"], L["gamma"], L["beta"]
+            cl.d.bn = cnnk.bn_desc(L["N"], L["H"], L["W"], L["C"], dt, L["relu"], BN_EPS, BN_MOMENTUM)
+        elif op == "pool":
+            cl.op = cnnk.OP_POOL
+            cl.in0, cl.out = L["x"], L["y"]
+            mode = cnnk.POOL_MAX2 if L["mode"] == "max2" else cnnk.POOL_GAP
+            cl.d.pool = cnnk.pool_desc(L["N"], L["H"], L["W"], L["C"], dt, mode)
+        elif op == "add":
+            cl.op = cnnk.OP_ADD
+            cl.in0, cl.in1, cl.out = L["a"], L["b"], L["y"]
+            cl.d.pool = cnnk.pool_desc(L["N"], L["H"], L["W"], L["C"], dt, 0)
+        elif op == "fc_loss":
+            cl.op = cnnk.OP_FC_LOSS
+            cl.in0, cl.p0, cl.p1 = L["x"], L["W"], L["b"]
+            cl.d.fc = cnnk.fc_desc(L["N"], L["F"], L["classes"], dt)
+        else:
+            raise ValueError(op)
+    return arr
+
+
 class StepRunner:
     def __init__(self, layers, slot_shapes, param_shapes, dtype, device="cuda:0", keep_probs=True,
                  two_streams=True):
@@ -48,44 +84,19 @@ class StepRunner:
         self.bn_save = [None] * nl
         self.bn_running = [None] * nl
         self.pool_idx = [None] * nl
-        self.c_layers = (cnnk.Layer * nl)()
+        self.c_layers = build_c_layers(layers, self.dt)
         self.N = self.slot_shapes[0][0]
         self.classes = None
         for i, L in enumerate(layers):
-            cl = self.c_layers[i]
-            cl.in0 = cl.in1 = cl.out = cl.p0 = cl.p1 = -1
-            op = L["op"]
-            if op == "conv":
-                cl.op = cnnk.OP_CONV
-                cl.in0, cl.out, cl.p0 = L["x"], L["y"], L["w"]
-                cl.d.conv = cnnk.conv_desc(L["N"], L["H"], L["W"], L["Cin"], L["Cout"], L["R"], L["S"],
-                                           L["stride"], L["pad"], self.dt)
-            elif op == "bn":
-                cl.op = cnnk.OP_BN
-                cl.in0, cl.in1, cl.out, cl.p0, cl.p1 = L["x"], L["res"], L["y"], L["gamma"], L["beta"]
-                cl.d.bn = cnnk.bn_desc(L["N"], L["H"], L["W"], L["C"], self.dt, L["relu"], BN_EPS, BN_MOMENTUM)
+            if L["op"] == "bn":
                 self.bn_save[i] = z((2, L["C"]), torch.float32)
                 run = z((2, L["C"]), torch.float32)
                 run[1].fill_(1.0)
                 self.bn_running[i] = run
-            elif op == "pool":
-                cl.op = cnnk.OP_POOL
-                cl.in0, cl.out = L["x"], L["y"]
-                mode = cnnk.POOL_MAX2 if L["mode"] == "max2" else cnnk.POOL_GAP
-                cl.d.pool = cnnk.pool_desc(L["N"], L["H"], L["W"], L["C"], self.dt, mode)
-                if mode == cnnk.POOL_MAX2:
-                    self.pool_idx[i] = z((L["N"], L["H"] // 2, L["W"] // 2, L["C"]), torch.uint8)
-            elif op == "add":
-                cl.op = cnnk.OP_ADD
-                cl.in0, cl.in1, cl.out = L["a"], L["b"], L["y"]
-                cl.d.pool = cnnk.pool_desc(L["N"], L["H"], L["W"], L["C"], self.dt, 0)
-            elif op == "fc_loss":
-                cl.op = cnnk.OP_FC_LOSS
-                cl.in0, cl.p0, cl.p1 = L["x"], L["W"], L["b"]
-                cl.d.fc = cnnk.fc_desc(L["N"], L["F"], L["classes"], self.dt)
+            elif L["op"] == "pool" and L["mode"] == "max2":
+                self.pool_idx[i] = z((L["N"], L["H"] // 2, L["W"] // 2, L["C"]), torch.uint8)
+            elif L["op"] == "fc_loss":
                 self.classes = L["classes"]
-            else:
-                raise ValueError(op)
         self.labels = z((self.N,), torch.int32)
         self.loss = z((1,), torch.float32)
         self.pred = z((self.N,), torch.int32)

@@ -84,3 +84,39 @@ def test_train_step_validates_the_layer_list(cnnk):
     with pytest.raises(cnnk.CnnkError) as e:
         cnnk.cnnk_train_step(layers, nl, b, 256, 0.1, 0.9, 0.0, 256, 256)
     assert e.value.status == 1
+
+
+def test_train_step_checks_the_workspace_before_any_launch(cnnk):
+    """Workspace too small, and the second stream without the doubled workspace: both are argument
+    errors found on the host (no GPU needed; the fake pointers are never dereferenced)."""
+    import ctypes as C
+    import workloads as WL
+    from paper_2503_23186_amd.runner import build_c_layers
+    net = WL.mini_resnet(batch=4, dtype="bf16", widths=(64, 128))
+    nl, ns, npar = len(net.layers), len(net.slots), len(net.params)
+    layers = build_c_layers(net.layers, cnnk.BF16)
+    need = cnnk.cnnk_train_step_workspace_bytes(layers, nl)
+    assert need > 0
+    fake = 4096
+
+    def arr(n):
+        a = (C.c_void_p * n)()
+        for k in range(n):
+            a[k] = fake
+        return a
+
+    keep = dict(act=arr(ns), dact=arr(ns), param=arr(npar), param_lp=arr(npar), grad=arr(npar), mom=arr(npar),
+                bn_save=arr(nl), bn_running=arr(nl), pool_idx=arr(nl))
+    b = cnnk.Buffers()
+    b.n_slots, b.n_params = ns, npar
+    for k, a in keep.items():
+        setattr(b, k, C.cast(a, C.POINTER(C.c_void_p)))
+    b.ws, b.ws_bytes = fake, need - 1
+    with pytest.raises(cnnk.CnnkError) as e:
+        cnnk.cnnk_train_step(layers, nl, b, fake, 0.1, 0.9, 0.0, fake, fake)
+    assert e.value.status == 4
+    b.ws_bytes = need            # enough for one stream, not for two
+    b.aux_stream, b.ev_fork, b.ev_join = fake, fake, fake
+    with pytest.raises(cnnk.CnnkError) as e:
+        cnnk.cnnk_train_step(layers, nl, b, fake, 0.1, 0.9, 0.0, fake, fake)
+    assert e.value.status == 4
