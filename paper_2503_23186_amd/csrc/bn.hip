@@ -270,7 +270,8 @@ __global__ void __launch_bounds__(kT) bn_apply_sums_kernel(const T* __restrict__
 }
 
 // Partial sums of dz and dz*xhat.  MODE 0: no ReLU; 1: mask [y > 0]; 2: mask [x*sc + bi > 0]
-// recomputed with the forward's arithmetic (y is not read).
+// recomputed with the forward's arithmetic (y is not read).  The element-wise kernel also knows
+// MODE 3: dz was written by this kernel into dres (the residual gradient is dz itself), read it there.
 template <typename T, int MODE>
 __global__ void __launch_bounds__(kT) bwd_partial_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                                                          const T* __restrict__ y,
@@ -278,7 +279,7 @@ __global__ void __launch_bounds__(kT) bwd_partial_kernel(const T* __restrict__ d
                                                          const float* __restrict__ beta,
                                                          const float* __restrict__ mean,
                                                          const float* __restrict__ invstd, size_t m, int C,
-                                                         float* __restrict__ part) {
+                                                         float* __restrict__ part, T* __restrict__ dz_out) {
   const int lanes = C / 8, rows = kT / lanes;
   const int tid = threadIdx.x, o = tid % lanes, rl = tid / lanes;
   float acc[2][8];
@@ -310,6 +311,9 @@ __global__ void __launch_bounds__(kT) bwd_partial_kernel(const T* __restrict__ d
 #pragma unroll
         for (int e = 0; e < 8; ++e) g[e] = fmaf(xv[e], sc[e], bi[e]) > 0.f ? g[e] : 0.f;
       }
+      // the masked gradient is exact in the storage type (dy or 0): written here, it spares the
+      // element-wise pass the reads of dy and y
+      if (dz_out) store8(dz_out + r * C + o * 8, g);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         acc[0][e] += g[e];
@@ -372,7 +376,7 @@ __global__ void __launch_bounds__(kT) bwd_apply_kernel(const T* __restrict__ dy,
 #pragma unroll
     for (int k = 0; k < 4; ++k)
       if (k < n) {
-        load8(dy + idx[k], g[k]);
+        load8((MODE == 3 ? dres : dy) + idx[k], g[k]);
         load8(x + idx[k], xv[k]);
         if (MODE == 1) load8(y + idx[k], yv[k]);
       }
@@ -400,7 +404,7 @@ __global__ void __launch_bounds__(kT) bwd_apply_kernel(const T* __restrict__ dy,
         for (int e = 0; e < 8; ++e) out[e] += old[e];
       }
       store8(dx + idx[k], out);
-      if (dres) {
+      if (dres && MODE != 3) {
         if (flags & 2) {
           float old[8];
           load8(dres + idx[k], old);
@@ -520,12 +524,19 @@ static int bn_bwd_launch(const cnnk_bn_desc* d, const void* dy, const void* x, c
   const int C = d->C;
   const int nb = reduce_blocks(m, C);
   const float inv_m = (float)(1.0 / (double)m);
+  // a residual gradient that is written, not accumulated, is written by the first pass already
+  const bool dz_first = MODE == 1 && dresidual && !(flags & 2);
   bwd_partial_kernel<T, MODE><<<nb, kT, 0, st>>>((const T*)dy, (const T*)x, (const T*)y, gamma, beta, save_mean,
-                                                 save_invstd, m, C, part);
+                                                 save_invstd, m, C, part, dz_first ? (T*)dresidual : nullptr);
   bwd_finalize_kernel<<<fin_blocks(C), kT, 0, st>>>(part, nb, C, dgamma, dbeta);
-  bwd_apply_kernel<T, MODE><<<row_blocks(m, C), kT, 0, st>>>((const T*)dy, (const T*)x, (const T*)y, gamma, beta,
-                                                             save_mean, save_invstd, dgamma, dbeta, (T*)dx,
-                                                             (T*)dresidual, m, C, inv_m, flags);
+  if (dz_first)
+    bwd_apply_kernel<T, 3><<<row_blocks(m, C), kT, 0, st>>>((const T*)dy, (const T*)x, (const T*)y, gamma, beta,
+                                                            save_mean, save_invstd, dgamma, dbeta, (T*)dx,
+                                                            (T*)dresidual, m, C, inv_m, flags);
+  else
+    bwd_apply_kernel<T, MODE><<<row_blocks(m, C), kT, 0, st>>>((const T*)dy, (const T*)x, (const T*)y, gamma, beta,
+                                                               save_mean, save_invstd, dgamma, dbeta, (T*)dx,
+                                                               (T*)dresidual, m, C, inv_m, flags);
   return launch_status();
 }
 
