@@ -49,7 +49,7 @@ int conv_mfma_dgrad_pt(const ConvGeom& g, const bf16_t* dy, const bf16_t* wt, bf
 
 // 3x3 stride-1 kernels with the input patch resident in LDS (forward, data gradient)
 bool conv_patch_supported(const ConvGeom& g, int pass);
-int conv_patch_mtiles(const ConvGeom& g);
+int conv_patch_stat_rows(const ConvGeom& g);
 int conv_patch_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y, float* stats, hipStream_t st);
 int conv_patch_dgrad(const ConvGeom& g, const bf16_t* dy, const bf16_t* wt, bf16_t* dx, int accumulate,
                      hipStream_t st);

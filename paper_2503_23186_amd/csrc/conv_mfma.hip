@@ -547,8 +547,8 @@ bool conv_mfma_supported(const ConvGeom& g, int pass) {
 }
 
 size_t conv_mfma_ws(const ConvGeom& g, int pass, bool want_stats) {
-  if (pass == CNNK_PASS_FWD)   // per-M-tile statistics partials, sized for the smallest tile (64 rows)
-    return want_stats ? align_up(((size_t)g.N * g.Ho * g.Wo + 63) / 64 * 2 * g.Cout * sizeof(float), 256) : 0;
+  if (pass == CNNK_PASS_FWD)   // statistics partials, sized for the finest granularity (32 rows per partial)
+    return want_stats ? align_up(((size_t)g.N * g.Ho * g.Wo + 31) / 32 * 2 * g.Cout * sizeof(float), 256) : 0;
   if (pass == CNNK_PASS_DGRAD) return align_up((size_t)g.Cout * g.R * g.S * g.Cin * sizeof(bf16_t), 256);
   if (pass == CNNK_PASS_WGRAD) {
     if (conv_wgrad_patch_supported(g)) return conv_wgrad_patch_ws(g);
@@ -565,7 +565,7 @@ int conv_mfma_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y
     float* stats = ch_sum ? reinterpret_cast<float*>(ws) : nullptr;
     int rc = conv_patch_fwd(g, x, w, y, stats, st);
     if (rc != CNNK_OK || !ch_sum) return rc;
-    return channel_sums_finalize(stats, conv_patch_mtiles(g), g.Cout, ch_sum, ch_sumsq, st);
+    return channel_sums_finalize(stats, conv_patch_stat_rows(g), g.Cout, ch_sum, ch_sumsq, st);
   }
   IgemmArgs a{};
   a.src = x; a.wt = w; a.dst = y;

@@ -23,13 +23,14 @@ struct PatchArgs {
   const bf16_t* src;
   const bf16_t* wt;   // [Cd][9][Cs]
   bf16_t* dst;
-  float* stats;       // nullable: [2][Cd][mtiles]
+  float* stats;       // nullable: [2][Cd][mtiles * WM]
   int N, H, W, Cs, Cd;
   int TI, TH;         // tile = TI images x TH rows x W columns (BM pixels)
   int accumulate, ntiles, mtiles;
+  int tpb;            // pixel tiles a workgroup walks (consecutive, same channel tile); mtiles % tpb == 0
   int perm;           // row permutation of the pixel tile, see tile_pixel()
   int toff_h[9], toff_w[9], widx[9];  // patch offset (0..2, 0..2) and weight tap of each step
-  FastDiv dPW, dPH, dW, dTH;          // divisors used to decode tile-local pixel indices (< 2^16)
+  FastDiv dPW, dPH, dW, dTH, dH;      // divisors used to decode pixel indices
 };
 
 // LDS rows are dense 64-byte rows (32 channels) whose four 16-byte chunks are XOR-swizzled with
@@ -80,9 +81,8 @@ template <int BM, int BN, int WM, int WN, int OCC, int PL>
 __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   constexpr int B_IT = (BN + 63) / 64;  // 64 weight rows per pass (4 chunks of 8 channels per row)
-  constexpr int LDC = BN + 8;
   constexpr int KK = CK / 16;
-  static_assert(WM * WN == 4 && TM >= 1 && TN >= 1 && KK == 2, "tile shape");
+  static_assert(WM * WN == 4 && TM >= 1 && TN == 2 && KK == 2, "tile shape");
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const int PW = a.W + 2, PH = a.TH + 2;
   const int patch_px = a.TI * PH * PW;
@@ -95,31 +95,40 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   int b = blockIdx.x;
   const int nb = gridDim.x;
   if ((nb & 7) == 0) b = (b & 7) * (nb >> 3) + (b >> 3);  // consecutive tiles share an XCD
-  const int nt = b % a.ntiles, mt = b / a.ntiles;
+  const int nt = b % a.ntiles;
+  int mt = (b / a.ntiles) * a.tpb;            // current pixel tile; the workgroup walks tpb of them
+  const int mt_end = mt + a.tpb;
   const int M = a.N * a.H * a.W;
-  const int m0 = mt * BM;
-  const int n0 = m0 / (a.H * a.W), h0 = (m0 / a.W) % a.H;
 
   const __amdgpu_buffer_rsrc_t src_rs = make_rsrc(a.src, (unsigned)M * a.Cs * 2u);
   const __amdgpu_buffer_rsrc_t wt_rs = make_rsrc(a.wt, (unsigned)a.Cd * 9u * a.Cs * 2u);
 
   const int kc = tid & 3;
-  unsigned poff[PL];   // global byte offset of each staged patch chunk (kOobOffset: zero fill)
+  // global byte offset of each staged patch chunk of a pixel tile (kOobOffset: zero fill; a tile
+  // past the workgroup's range is all zero fill)
+  auto patch_offsets = [&](int mtile, unsigned* off) __attribute__((always_inline)) {
+    const int m0 = mtile * BM;
+    int q0, hh, n0, h0;
+    a.dW.divmod(m0, &q0, &hh);
+    a.dH.divmod(q0, &n0, &h0);
+#pragma unroll
+    for (int j = 0; j < PL; ++j) {
+      const int pp = (tid >> 2) + j * (kThreads / 4);
+      off[j] = kOobOffset;
+      if (pp < patch_px && mtile < mt_end) {
+        int q, pw, ti, ph;
+        a.dPW.divmod(pp, &q, &pw);
+        a.dPH.divmod(q, &ti, &ph);
+        const int n = n0 + ti, hs = h0 + ph - 1, ws = pw - 1;
+        if (n < a.N && (unsigned)hs < (unsigned)a.H && (unsigned)ws < (unsigned)a.W)
+          off[j] = (unsigned)(((n * a.H + hs) * a.W + ws) * a.Cs + kc * 8) * 2u;
+      }
+    }
+  };
+  unsigned poff[PL];
+  patch_offsets(mt, poff);
   // its LDS byte offset inside a patch buffer is pst0 + j * 64 rows (the swizzle repeats every 16 rows)
   const int pst0 = swz_off(tid >> 2, kc);
-#pragma unroll
-  for (int j = 0; j < PL; ++j) {
-    const int pp = (tid >> 2) + j * (kThreads / 4);
-    poff[j] = kOobOffset;
-    if (pp < patch_px) {
-      int q, pw, ti, ph;
-      a.dPW.divmod(pp, &q, &pw);
-      a.dPH.divmod(q, &ti, &ph);
-      const int n = n0 + ti, hs = h0 + ph - 1, ws = pw - 1;
-      if (n < a.N && (unsigned)hs < (unsigned)a.H && (unsigned)ws < (unsigned)a.W)
-        poff[j] = (unsigned)(((n * a.H + hs) * a.W + ws) * a.Cs + kc * 8) * 2u;
-    }
-  }
   const int r0 = tid >> 2;  // weight row of this thread inside a 64-row pass
   unsigned boff[B_IT];
   int bst[B_IT];
@@ -156,9 +165,23 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   uint4 preg[PL];
   uint4 rb[2][3][B_IT];
 
-  auto load_patch = [&](int chunk) {
+  auto load_patch = [&](const unsigned* off, int chunk) {
 #pragma unroll
-    for (int j = 0; j < PL; ++j) preg[j] = buffer_load16(src_rs, poff[j], (unsigned)chunk * (CK * 2));
+    for (int j = 0; j < PL; ++j) preg[j] = buffer_load16(src_rs, off[j], (unsigned)chunk * (CK * 2));
+  };
+  // the chunk after chunk c of the current tile: c + 1, or chunk 0 of the next tile
+  int c_in_tile = 0;
+  auto load_next_patch = [&]() __attribute__((always_inline)) {
+    if (c_in_tile + 1 == nchunks) {
+      unsigned nxt[PL];     // computed here rather than kept: registers are scarce in the main loop
+      patch_offsets(mt + 1, nxt);
+#pragma unroll
+      for (int j = 0; j < PL; ++j) preg[j] = buffer_load16(src_rs, nxt[j], 0u);
+    } else {
+      const unsigned so = (unsigned)__builtin_amdgcn_readfirstlane((c_in_tile + 1) * (CK * 2));
+#pragma unroll
+      for (int j = 0; j < PL; ++j) preg[j] = buffer_load16(src_rs, poff[j], so);
+    }
   };
   auto store_patch = [&](int buf) {
 #pragma unroll
@@ -190,7 +213,7 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
     constexpr int tap = decltype(TAP)::value, wb = decltype(WB)::value, fs = decltype(SET)::value;
     // per-tap patch offset; opaque to the optimiser so that the (tap, row) LDS addresses are
     // recomputed here (5 VALU each) instead of being hoisted out of the chunk loop into registers
-    int tpx = a.toff_h[tap] * PW + a.toff_w[tap];
+    int tpx = __builtin_amdgcn_readfirstlane(a.toff_h[tap] * PW + a.toff_w[tap]);
     asm volatile("" : "+s"(tpx));
     const unsigned char* P = Pb + pbuf * patch_bytes;
 #pragma unroll
@@ -229,7 +252,7 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   };
   // PARC = chunk % 2 (patch buffer of this chunk); the weight buffer / register set parities follow
   // from (chunk + row) % 2
-  auto step = [&](int chunk, auto PARC, auto ROW) {
+  auto step = [&](auto PARC, auto ROW) __attribute__((always_inline)) {
     constexpr int par = decltype(PARC)::value, row = decltype(ROW)::value;
     constexpr int cur = (par + row) % 2, nxt = cur ^ 1;
     using WB = std::integral_constant<int, cur>;
@@ -237,8 +260,8 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
     using F0 = std::integral_constant<int, 0>;
     using F1 = std::integral_constant<int, 1>;
     store_w(NX{}, NX{});                      // weights of step g+1
-    load_w(chunk + 1, ROW, NX{});             // step g+3 = (chunk+1, row)
-    if constexpr (row == 0) load_patch(chunk + 1);
+    load_w(__builtin_amdgcn_readfirstlane(c_in_tile + 1 == nchunks ? 0 : c_in_tile + 1), ROW, NX{});   // step g+3: same row of the next chunk
+    if constexpr (row == 0) load_next_patch();
     if constexpr (row == 2) store_patch(par ^ 1);
     read_frags(par, std::integral_constant<int, row * 3 + 0>{}, WB{}, F0{});
     __builtin_amdgcn_sched_barrier(0);
@@ -253,92 +276,102 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
     mfmas(F0{});
     __syncthreads();
   };
-  auto chunk_body = [&](int chunk, auto PARC) {
-    step(chunk, PARC, std::integral_constant<int, 0>{});
-    step(chunk, PARC, std::integral_constant<int, 1>{});
-    step(chunk, PARC, std::integral_constant<int, 2>{});
+  // Epilogue of one pixel tile, wave-local (no workgroup barrier, 1.1 KB of LDS per wave): optional
+  // per-channel sums of the fp32 accumulators over this wave's 64 rows (one partial row per wave:
+  // mtiles * WM rows in all, reduced by a finalising kernel), then eight passes of 8 rows x 64
+  // columns through LDS so that every lane stores 16 contiguous bytes.
+  auto epilogue = [&](int mtile) __attribute__((always_inline)) {
+    if (a.stats) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float v = acc[i][j][r];
+            s1 += v;
+            s2 = fmaf(v, v, s2);
+          }
+        s1 += __shfl_xor(s1, 32, 64);
+        s2 += __shfl_xor(s2, 32, 64);
+        const int col = nt * BN + wn * TN * 32 + j * 32 + (lane & 31);
+        if (lane < 32 && col < a.Cd) {
+          const size_t prow = (size_t)mtile * WM + wm, nrow = (size_t)a.mtiles * WM;
+          a.stats[((size_t)0 * a.Cd + col) * nrow + prow] = s1;
+          a.stats[((size_t)1 * a.Cd + col) * nrow + prow] = s2;
+        }
+      }
+    }
+    constexpr int LDW = TN * 32 + 8;
+    bf16_t* Cw = reinterpret_cast<bf16_t*>(smem_raw + 2 * patch_bytes + 6 * BN * 64) + wave * 8 * LDW;
+    const int mbase = mtile * BM;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+#pragma unroll
+        for (int rho = 0; rho < 4; ++rho)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            Cw[((lane >> 5) * 4 + rho) * LDW + j * 32 + (lane & 31)] = f32_to_bf16_hw(acc[i][j][q * 4 + rho]);
+        const int lrow = lane >> 3, ch = lane & 7;
+        const int row = wm * TM * 32 + i * 32 + q * 8 + lrow;
+        const int m = mbase + tile_pixel(row, a.perm), co = nt * BN + wn * TN * 32 + ch * 8;
+        const uint4 v = *reinterpret_cast<const uint4*>(Cw + lrow * LDW + ch * 8);
+        if (m < M && co < a.Cd) {
+          bf16_t* dp = a.dst + (size_t)m * a.Cd + co;
+          if (a.accumulate) {
+            float o[8], nw[8];
+            load8(dp, o);
+            load8(Cw + lrow * LDW + ch * 8, nw);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] += nw[e];
+            store8(dp, o);
+          } else {
+            *reinterpret_cast<uint4*>(dp) = v;
+          }
+        }
+      }
   };
 
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
   using I2 = std::integral_constant<int, 2>;
-  load_patch(0);
+  // One chunk = three steps; after the last chunk of a pixel tile the accumulators are written out
+  // and the workgroup moves on to its next tile, whose first patch chunk and weights are already
+  // on their way (the prefetches do not know about tile borders).
+  auto chunk_body = [&](auto PARC) __attribute__((always_inline)) {
+    step(PARC, std::integral_constant<int, 0>{});
+    step(PARC, std::integral_constant<int, 1>{});
+    step(PARC, std::integral_constant<int, 2>{});
+    if (c_in_tile + 1 == nchunks) {
+      epilogue(mt);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      ++mt;
+      c_in_tile = 0;
+      patch_offsets(mt, poff);
+    } else {
+      ++c_in_tile;
+    }
+  };
+
+  load_patch(poff, 0);
   load_w(0, I0{}, I0{});
   load_w(0, I1{}, I1{});
   store_patch(0);
   store_w(I0{}, I0{});
   load_w(0, I2{}, I0{});   // register set 0 is free again
   __syncthreads();
-  for (int chunk = 0; chunk < nchunks; chunk += 2) {
-    chunk_body(chunk, I0{});
-    if (chunk + 1 < nchunks) chunk_body(chunk + 1, I1{});
-  }
-
-  if (a.stats) {
-    float* sred = reinterpret_cast<float*>(smem_raw);  // [2][WM][BN]
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      float s1 = 0.f, s2 = 0.f;
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float v = acc[i][j][r];
-          s1 += v;
-          s2 = fmaf(v, v, s2);
-        }
-      s1 += __shfl_xor(s1, 32, 64);
-      s2 += __shfl_xor(s2, 32, 64);
-      if (lane < 32) {
-        const int col = wn * TN * 32 + j * 32 + lane;
-        sred[(0 * WM + wm) * BN + col] = s1;
-        sred[(1 * WM + wm) * BN + col] = s2;
-      }
-    }
-    __syncthreads();
-    for (int c = tid; c < BN; c += kThreads) {
-      float t1 = 0.f, t2 = 0.f;
-#pragma unroll
-      for (int w_ = 0; w_ < WM; ++w_) {
-        t1 += sred[(0 * WM + w_) * BN + c];
-        t2 += sred[(1 * WM + w_) * BN + c];
-      }
-      const int col = nt * BN + c;
-      if (col < a.Cd) {
-        a.stats[((size_t)0 * a.Cd + col) * a.mtiles + mt] = t1;
-        a.stats[((size_t)1 * a.Cd + col) * a.mtiles + mt] = t2;
-      }
-    }
-    __syncthreads();
-  }
-
-  bf16_t* Ct = reinterpret_cast<bf16_t*>(smem_raw);
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = wm * TM * 32 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        const int col = wn * TN * 32 + j * 32 + (lane & 31);
-        Ct[row * LDC + col] = f32_to_bf16_hw(acc[i][j][r]);
-      }
-  __syncthreads();
-  for (int idx = tid; idx < BM * (BN / 8); idx += kThreads) {
-    const int row = idx / (BN / 8), ch = idx % (BN / 8);
-    const int m = m0 + tile_pixel(row, a.perm), co = nt * BN + ch * 8;
-    if (m >= M || co >= a.Cd) continue;
-    bf16_t* dp = a.dst + (size_t)m * a.Cd + co;
-    if (a.accumulate) {
-      float o[8], nw[8];
-      load8(dp, o);
-      load8(Ct + row * LDC + ch * 8, nw);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) o[e] += nw[e];
-      store8(dp, o);
-    } else {
-      *reinterpret_cast<uint4*>(dp) = *reinterpret_cast<const uint4*>(Ct + row * LDC + ch * 8);
-    }
+  const int total_chunks = a.tpb * nchunks;
+  for (int g2 = 0; g2 < total_chunks; g2 += 2) {
+    chunk_body(I0{});
+    if (g2 + 1 < total_chunks) chunk_body(I1{});
   }
 }
 
@@ -361,9 +394,8 @@ bool tile_geometry(const ConvGeom& g, int bm, int max_px, int* ti, int* th) {
 
 template <int BM, int BN>
 size_t patch_smem(int patch_px) {
-  const size_t stage = (size_t)2 * patch_px * 64 + (size_t)6 * BN * 64;
-  const size_t epi = (size_t)BM * (BN + 8) * sizeof(bf16_t);
-  return stage > epi ? stage : epi;
+  // two patch buffers, two weight buffers of three taps, 8 rows x 72 columns of epilogue staging per wave
+  return (size_t)2 * patch_px * 64 + (size_t)6 * BN * 64 + (size_t)4 * 8 * 72 * sizeof(bf16_t);
 }
 
 template <int BM, int BN, int WM, int WN, int OCC, int PL>
@@ -379,8 +411,14 @@ int launch_patch(PatchArgs& a, hipStream_t st) {
   const long M = (long)a.N * a.H * a.W;
   a.ntiles = (a.Cd + BN - 1) / BN;
   a.mtiles = (int)((M + BM - 1) / BM);
+  // Pixel tiles per workgroup: as many as still leave two workgroups for every CU.  A workgroup
+  // that walks several tiles hides the prologue of all but the first behind the MFMAs before it.
+  a.tpb = 1;
+  for (int t = 2; t <= 8; t *= 2)
+    if (a.mtiles % t == 0 && (long)a.ntiles * (a.mtiles / t) >= 512) a.tpb = t;
+  if (g_cnnk_tune[13] > 0 && a.mtiles % g_cnnk_tune[13] == 0) a.tpb = g_cnnk_tune[13];
   const size_t smem = patch_smem<BM, BN>(a.TI * (a.TH + 2) * (a.W + 2));
-  hipLaunchKernelGGL(kern, dim3((unsigned)(a.mtiles * a.ntiles)), dim3(kThreads), smem, st, a);
+  hipLaunchKernelGGL(kern, dim3((unsigned)(a.mtiles / a.tpb * a.ntiles)), dim3(kThreads), smem, st, a);
   return launch_status();
 }
 
@@ -416,7 +454,7 @@ int run_patch(const ConvGeom& g, PatchArgs& a, const PatchPlan& p, hipStream_t s
   a.TI = p.ti; a.TH = p.th;
   a.perm = (a.W == 8 && a.TH == 8) ? 1 : (a.W == 4 && a.TH == 4 && a.TI % 4 == 0) ? 2 : 0;
   if (g_cnnk_tune[7] < 0) a.perm = 0;
-  a.dPW.init(a.W + 2); a.dPH.init(a.TH + 2); a.dW.init(a.W); a.dTH.init(a.TH);
+  a.dPW.init(a.W + 2); a.dPH.init(a.TH + 2); a.dW.init(a.W); a.dTH.init(a.TH); a.dH.init(a.H);
   if (p.bm == 256 && p.bn == 128) return launch_patch<256, 128, 2, 2, 2, 6>(a, st);
   if (p.bm == 256 && p.bn == 64)
     return a.TI * (a.TH + 2) * (a.W + 2) <= 6 * kPxPerLoad ? launch_patch<256, 64, 4, 1, 2, 6>(a, st)
@@ -436,10 +474,12 @@ bool conv_patch_supported(const ConvGeom& g, int pass) {
   return false;
 }
 
-int conv_patch_mtiles(const ConvGeom& g) {
+// rows of the statistics partials that conv_patch_fwd writes: one per wave row of every pixel tile
+int conv_patch_stat_rows(const ConvGeom& g) {
   PatchPlan p;
   if (!plan_patch(g, g.Cin, g.Cout, &p)) return 0;
-  return (int)(((long)g.N * g.H * g.W + p.bm - 1) / p.bm);
+  const int wm = p.bn == 64 ? 4 : 2;
+  return (int)(((long)g.N * g.H * g.W + p.bm - 1) / p.bm) * wm;
 }
 
 int conv_patch_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y, float* stats, hipStream_t st) {
