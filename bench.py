@@ -62,8 +62,9 @@ def layer_work(L, phase, esz):
             # inside the step the statistics arrive from the convolution's epilogue: the call reads x
             # (and the residual) and writes y
             return 0.0, (2 + res) * T
-        # dy and x twice, dx once; with a residual branch also y twice (the mask) and the residual gradient
-        return 0.0, (5 + 3 * res) * T
+        # dy and x twice, dx once; with a residual branch: dy, y, x in, masked gradient out (it is the
+        # residual gradient), then that and x in, dx out
+        return 0.0, (5 + 2 * res) * T
     if L["op"] == "pool":
         T = L["N"] * L["H"] * L["W"] * L["C"] * esz
         out = T // 4 if L["mode"] == "max2" else L["N"] * L["C"] * esz
