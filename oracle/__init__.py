@@ -3,9 +3,11 @@
 Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import this package.
 It shares no code with the HIP path and never imports it.  ops.py wraps the C library
 (cnnk_ref.c, direct loops in double precision); step.py chains the operators over a layer
-list by the chain rule (forward, loss, backward, SGD-momentum update).
+list by the chain rule (forward, loss, backward, SGD-momentum update); loop.py is the epoch loop
+around it (mini-batches, validation in inference mode, best-so-far checkpoint).
 """
 from . import ops
-from .step import train_step, forward_loss
+from .step import train_step, forward_loss, eval_forward, initial_running
+from . import loop
 
-__all__ = ["ops", "train_step", "forward_loss"]
+__all__ = ["ops", "train_step", "forward_loss", "eval_forward", "initial_running", "loop"]

@@ -160,6 +160,27 @@ int cnnk_ref_bn_relu_fwd(int N, int H, int W, int C, double eps, double momentum
   return 0;
 }
 
+/* Inference-mode batch norm (validation pass of Algorithm 1's epoch loop): the batch statistics
+ * are replaced by the running ones, y = act(gamma*(x - running_mean)/sqrt(running_var + eps) +
+ * beta [+ residual]); nothing is updated. */
+int cnnk_ref_bn_relu_infer(int N, int H, int W, int C, double eps, int relu, const double* x,
+                           const double* residual, const double* gamma, const double* beta,
+                           const double* running_mean, const double* running_var, double* y) {
+  if (!x || !gamma || !beta || !running_mean || !running_var || !y) return 1;
+  if (N <= 0 || H <= 0 || W <= 0 || C <= 0) return 2;
+  const size_t m = (size_t)N * H * W;
+#pragma omp parallel for schedule(static)
+  for (int c = 0; c < C; ++c) {
+    const double invstd = 1.0 / sqrt(running_var[c] + eps);
+    for (size_t i = 0; i < m; ++i) {
+      double u = gamma[c] * ((x[i * C + c] - running_mean[c]) * invstd) + beta[c];
+      if (residual) u += residual[i * C + c];
+      y[i * C + c] = (relu && !(u > 0.0)) ? 0.0 : u;
+    }
+  }
+  return 0;
+}
+
 /* Backward pass of the block above.  dz = dy * [y > 0] (strict; all ones without ReLU);
  * dresidual = dz; dbeta = sum dz; dgamma = sum dz*xhat;
  * dx = (gamma*invstd/m) * (m*dz - dbeta - xhat*dgamma). */

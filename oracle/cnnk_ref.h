@@ -25,6 +25,10 @@ int cnnk_ref_bn_relu_fwd(int N, int H, int W, int C, double eps, double momentum
                          const double* x, const double* residual, const double* gamma,
                          const double* beta, double* y, double* save_mean, double* save_invstd,
                          double* running_mean, double* running_var);
+/* Inference mode: running statistics in place of the batch's; updates nothing. */
+int cnnk_ref_bn_relu_infer(int N, int H, int W, int C, double eps, int relu, const double* x,
+                           const double* residual, const double* gamma, const double* beta,
+                           const double* running_mean, const double* running_var, double* y);
 int cnnk_ref_bn_relu_bwd(int N, int H, int W, int C, int relu, const double* dy, const double* x,
                          const double* y, const double* gamma, const double* save_mean,
                          const double* save_invstd, double* dx, double* dresidual, double* dgamma,

@@ -83,6 +83,18 @@ def bn_relu_fwd(x, gamma, beta, relu=True, residual=None, eps=1e-5, momentum=0.1
     return y, mean, invstd
 
 
+def bn_relu_infer(x, gamma, beta, running_mean, running_var, relu=True, residual=None, eps=1e-5):
+    """Inference-mode batch norm: running statistics instead of the batch's."""
+    x, gamma, beta = _f64(x), _f64(gamma), _f64(beta)
+    N, H, W_, Cc = x.shape
+    residual = None if residual is None else _f64(residual)
+    y = np.empty_like(x)
+    _chk(lib().cnnk_ref_bn_relu_infer(N, H, W_, Cc, C.c_double(eps), int(relu), _p(x), _p(residual),
+                                      _p(gamma), _p(beta), _p(_f64(running_mean)), _p(_f64(running_var)),
+                                      _p(y)), "bn_relu_infer")
+    return y
+
+
 def bn_relu_bwd(dy, x, y, gamma, mean, invstd, relu=True, want_dres=False):
     dy, x, y, gamma = _f64(dy), _f64(x), _f64(y), _f64(gamma)
     N, H, W_, Cc = x.shape

@@ -29,9 +29,15 @@ def _q(storage):
     raise ValueError(storage)
 
 
-def forward_loss(net, x, labels, params, storage=None):
-    """Forward pass and loss only.  Returns (loss, fc_result, acts, saved)."""
+def forward_loss(net, x, labels, params, storage=None, running=None, infer=False):
+    """Forward pass and loss only.  Returns (loss, fc_result, acts, saved).
+
+    running: {layer index: [running_mean, running_var]} (float64 arrays).  Training mode
+    (infer=False) updates them in place; inference mode (infer=True) normalises with them
+    instead of the batch statistics and changes nothing."""
     q = _q(storage)
+    if infer and running is None:
+        raise ValueError("inference mode needs running statistics")
     acts = {0: np.asarray(x, dtype=np.float64)}
     saved = {}
     out = None
@@ -41,9 +47,15 @@ def forward_loss(net, x, labels, params, storage=None):
             acts[L["y"]] = q(ops.conv2d_fwd(acts[L["x"]], params[L["w"]], L["stride"], L["pad"]))
         elif op == "bn":
             res = acts[L["res"]] if L["res"] >= 0 else None
+            if infer:
+                rm, rv = running[i]
+                acts[L["y"]] = q(ops.bn_relu_infer(acts[L["x"]], params[L["gamma"]], params[L["beta"]], rm, rv,
+                                                   relu=bool(L["relu"]), residual=res, eps=BN_EPS))
+                continue
+            rm, rv = running[i] if running is not None else (None, None)
             y, mean, invstd = ops.bn_relu_fwd(acts[L["x"]], params[L["gamma"]], params[L["beta"]],
                                               relu=bool(L["relu"]), residual=res, eps=BN_EPS,
-                                              momentum=BN_MOMENTUM)
+                                              momentum=BN_MOMENTUM, running_mean=rm, running_var=rv)
             acts[L["y"]] = q(y)
             saved[i] = (mean, invstd)
         elif op == "pool":
@@ -60,10 +72,27 @@ def forward_loss(net, x, labels, params, storage=None):
     return out["loss"], out, acts, saved
 
 
-def train_step(net, x, labels, params, mom, lr=0.1, momentum=0.9, weight_decay=0.0, storage=None):
-    """One step.  Returns dict(loss, pred, acts, dacts, grads, params, mom); inputs are not modified."""
+def initial_running(net):
+    """Running statistics before the first step: mean 0, variance 1."""
+    return {i: [np.zeros(L["C"]), np.ones(L["C"])] for i, L in enumerate(net.layers) if L["op"] == "bn"}
+
+
+def eval_forward(net, x, labels, params, running, storage=None):
+    """Validation pass: forward in inference mode.  Returns dict(loss, pred, probs, n_correct)."""
+    loss, fc, _, _ = forward_loss(net, x, labels, params, storage, running=running, infer=True)
+    labels = np.asarray(labels)
+    return dict(loss=loss, pred=fc["pred"], probs=fc["probs"], n_correct=int(np.sum(fc["pred"] == labels)))
+
+
+def train_step(net, x, labels, params, mom, lr=0.1, momentum=0.9, weight_decay=0.0, storage=None,
+               running=None):
+    """One step.  Returns dict(loss, pred, acts, dacts, grads, params, mom[, running]); inputs are
+    not modified (the running statistics, if given, are copied and the copy is advanced)."""
     q = _q(storage)
-    loss, fc, acts, saved = forward_loss(net, x, labels, params, storage)
+    if running is not None:
+        running = {i: [np.array(rm, dtype=np.float64), np.array(rv, dtype=np.float64)]
+                   for i, (rm, rv) in running.items()}
+    loss, fc, acts, saved = forward_loss(net, x, labels, params, storage, running=running)
     grads = [None] * len(params)
     dacts = {}
 
@@ -109,4 +138,4 @@ def train_step(net, x, labels, params, mom, lr=0.1, momentum=0.9, weight_decay=0
         new_params.append(w2)
         new_mom.append(v2)
     return dict(loss=loss, pred=fc["pred"], probs=fc["probs"], acts=acts, dacts=dacts, grads=grads,
-                params=new_params, mom=new_mom, saved=saved)
+                params=new_params, mom=new_mom, saved=saved, running=running)

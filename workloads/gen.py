@@ -53,3 +53,28 @@ def make_inputs(net, config_id=0, perturb_bn=False, zero_momentum=False):
         v = np.zeros(shp) if zero_momentum else 1e-2 * vr.standard_normal(shp)
         mom.append(np.ascontiguousarray(v.astype(np.float32).astype(np.float64)))
     return dict(x=np.ascontiguousarray(x), labels=labels, params=params, mom=mom)
+
+
+def make_dataset(net, config_id, n_train, n_val, signal=0.5):
+    """A seeded synthetic train/validation set of the net's input shape, standing in for a labelled
+    image set: every class has a fixed N(0,1) template image, a sample is N(0,1) noise plus
+    `signal` times its class's template, labels are uniform in [0, classes).  With signal > 0
+    the labels can be learnt, so a validation metric has something to improve on.
+    Returns dict(train_x, train_y, val_x, val_y) (float64 NHWC / int32)."""
+    _, H, W, C = net.slots[0]
+    templates = rng_for(config_id, 10).standard_normal((net.classes, H, W, C))
+    out = {}
+    for name, n, sid in (("train", n_train, 11), ("val", n_val, 13)):
+        y = rng_for(config_id, sid).integers(0, net.classes, size=n).astype(np.int32)
+        x = rng_for(config_id, sid + 1).standard_normal((n, H, W, C)) + signal * templates[y]
+        x = to_bf16_representable(x) if net.dtype == "bf16" else x.astype(np.float32).astype(np.float64)
+        out[name + "_x"] = np.ascontiguousarray(x)
+        out[name + "_y"] = y
+    return out
+
+
+def epoch_orders(config_id, n_train, batch, epochs):
+    """The sample order of every epoch: a seeded permutation of range(n_train) cut to a whole
+    number of mini-batches (consecutive slices of `batch` indices are the mini-batches)."""
+    keep = (n_train // batch) * batch
+    return [rng_for(config_id, 1000 + e).permutation(n_train)[:keep].astype(np.int64) for e in range(epochs)]

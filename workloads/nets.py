@@ -103,8 +103,8 @@ class Net:
         return fwd, tot
 
 
-def tiny_cnn(batch=8, dtype="f32", size=32, cout=16):
-    n = Net("tiny_cnn", batch, dtype)
+def tiny_cnn(batch=8, dtype="f32", size=32, cout=16, classes=100):
+    n = Net("tiny_cnn", batch, dtype, classes=classes)
     x = n.slot(batch, size, size, 3)
     t = n.bn(n.conv(x, cout, 3, 1))
     n.fc_loss(n.pool(t, "gap"))
