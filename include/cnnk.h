@@ -110,6 +110,14 @@ int cnnk_bn_relu_fwd(const cnnk_bn_desc* d, const void* x, const void* residual,
                      const float* ch_sum, const float* ch_sumsq, void* ws, size_t ws_bytes,
                      void* stream);
 
+/* Inference-mode batch norm, for the validation pass of Algorithm 1's epoch loop ("if validation
+ * metric improved"): y = act(gamma*(x - running_mean)/sqrt(running_var + eps) + beta [+ residual]).
+ * Reads C floats each of running_mean / running_var (as maintained by cnnk_bn_relu_fwd); writes
+ * only y.  residual is nullable.  d->momentum is ignored. */
+int cnnk_bn_relu_infer(const cnnk_bn_desc* d, const void* x, const void* residual,
+                       const float* gamma, const float* beta, const float* running_mean,
+                       const float* running_var, void* y, void* stream);
+
 /* dz = dy*[y>0] (strict; dz = dy without ReLU); dbeta = sum dz; dgamma = sum dz*xhat;
  * dx = (gamma*invstd/m)*(m*dz - dbeta - xhat*dgamma), xhat = (x-mean)*invstd; dresidual = dz.
  * y may be NULL when d->relu == 0; dresidual is nullable.
@@ -152,10 +160,15 @@ size_t cnnk_fc_workspace_bytes(const cnnk_fc_desc* d);
  * dW = dz^T x; db = sum_n dz; dx = dz W.
  * x, dx: N*F of dtype; W, dW: classes*F float; b, db: classes float; labels, pred: N int32
  * (labels must lie in [0, classes): not checked on the device, out-of-range labels contribute
- * a zero target); loss: 1 float; probs (nullable): N*classes float softmax output. */
+ * a zero target); loss: 1 float; probs (nullable): N*classes float softmax output.
+ * dx, dW, db: all three, or all NULL for the forward half only (loss, pred, probs). */
 int cnnk_fc_softmax_xent(const cnnk_fc_desc* d, const void* x, const float* W, const float* b,
                          const int* labels, float* loss, int* pred, float* probs, void* dx,
                          float* dW, float* db, void* ws, size_t ws_bytes, void* stream);
+
+/* *n_correct += #{i < n : pred[i] == labels[i]} (device int; the caller zeroes it, so that the
+ * count can run over several validation batches).  Integer addition: order-independent. */
+int cnnk_count_correct(int n, const int* pred, const int* labels, int* n_correct, void* stream);
 
 /* ---- parameter update (Algorithm 1: theta = theta - eta * grad, with momentum) ------------ */
 
@@ -237,6 +250,16 @@ int cnnk_train_step_event_groups(int n_layers);
 int cnnk_train_step(const cnnk_layer* layers, int n_layers, const cnnk_buffers* buf,
                     const int* labels, float lr, float momentum, float weight_decay,
                     float* loss, int* pred, void* stream);
+
+/* Validation pass of Algorithm 1's epoch loop on one batch: the forward half of cnnk_train_step
+ * over the same layer list in inference mode (every batch norm normalises with
+ * buf->bn_running, which must be given), then loss, pred and, if n_correct is not NULL,
+ * *n_correct += #{pred == label}.  Reads param / param_lp and bn_running; overwrites act[1..],
+ * pool_idx, probs (if given) and the workspace; leaves parameters, gradients, momentum, saved and
+ * running statistics untouched.  Runs on `stream` alone (aux_stream and events are ignored); the
+ * workspace of cnnk_train_step_workspace_bytes suffices. */
+int cnnk_eval_step(const cnnk_layer* layers, int n_layers, const cnnk_buffers* buf,
+                   const int* labels, float* loss, int* pred, int* n_correct, void* stream);
 
 #ifdef __cplusplus
 }

@@ -19,9 +19,10 @@ OP_CONV, OP_BN, OP_POOL, OP_ADD, OP_FC_LOSS = 0, 1, 2, 3, 4
 
 EXPORTS = ["cnnk_status_string", "cnnk_version", "cnnk_tune", "cnnk_conv2d_workspace_bytes", "cnnk_conv2d_fwd",
            "cnnk_conv2d_dgrad", "cnnk_conv2d_wgrad", "cnnk_bn_workspace_bytes", "cnnk_bn_relu_fwd",
-           "cnnk_bn_relu_bwd", "cnnk_pool_fwd", "cnnk_pool_bwd", "cnnk_add", "cnnk_grad_route",
-           "cnnk_fc_workspace_bytes", "cnnk_fc_softmax_xent", "cnnk_sgd_momentum",
-           "cnnk_train_step_workspace_bytes", "cnnk_train_step_event_groups", "cnnk_train_step"]
+           "cnnk_bn_relu_infer", "cnnk_bn_relu_bwd", "cnnk_pool_fwd", "cnnk_pool_bwd", "cnnk_add", "cnnk_grad_route",
+           "cnnk_fc_workspace_bytes", "cnnk_fc_softmax_xent", "cnnk_count_correct", "cnnk_sgd_momentum",
+           "cnnk_train_step_workspace_bytes", "cnnk_train_step_event_groups", "cnnk_train_step",
+           "cnnk_eval_step"]
 
 
 class CnnkError(RuntimeError):
@@ -86,6 +87,7 @@ def _load():
     lib.cnnk_bn_workspace_bytes.restype = sz
     lib.cnnk_bn_workspace_bytes.argtypes = [C.POINTER(BnDesc)]
     lib.cnnk_bn_relu_fwd.argtypes = [C.POINTER(BnDesc)] + [vp] * 11 + [vp, sz, vp]
+    lib.cnnk_bn_relu_infer.argtypes = [C.POINTER(BnDesc)] + [vp] * 7 + [vp]
     lib.cnnk_bn_relu_bwd.argtypes = [C.POINTER(BnDesc)] + [vp] * 9 + [ci, vp, vp, vp, sz, vp]
     lib.cnnk_pool_fwd.argtypes = [C.POINTER(PoolDesc), vp, vp, vp, vp]
     lib.cnnk_pool_bwd.argtypes = [C.POINTER(PoolDesc), vp, vp, vp, ci, vp]
@@ -94,11 +96,13 @@ def _load():
     lib.cnnk_fc_workspace_bytes.restype = sz
     lib.cnnk_fc_workspace_bytes.argtypes = [C.POINTER(FcDesc)]
     lib.cnnk_fc_softmax_xent.argtypes = [C.POINTER(FcDesc)] + [vp] * 10 + [vp, sz, vp]
+    lib.cnnk_count_correct.argtypes = [ci, vp, vp, vp, vp]
     lib.cnnk_sgd_momentum.argtypes = [sz, vp, vp, vp, vp, cf, cf, cf, vp]
     lib.cnnk_train_step_workspace_bytes.restype = sz
     lib.cnnk_train_step_workspace_bytes.argtypes = [C.POINTER(Layer), ci]
     lib.cnnk_train_step_event_groups.argtypes = [ci]
     lib.cnnk_train_step.argtypes = [C.POINTER(Layer), ci, C.POINTER(Buffers), vp, cf, cf, cf, vp, vp, vp]
+    lib.cnnk_eval_step.argtypes = [C.POINTER(Layer), ci, C.POINTER(Buffers), vp, vp, vp, vp, vp]
     return lib
 
 
@@ -176,6 +180,11 @@ def cnnk_bn_relu_fwd(d, x, residual, gamma, beta, y, save_mean, save_invstd, run
                                 ptr(ch_sum), ptr(ch_sumsq), ptr(ws), ws_bytes, stream), "cnnk_bn_relu_fwd")
 
 
+def cnnk_bn_relu_infer(d, x, residual, gamma, beta, running_mean, running_var, y, stream=0):
+    _check(lib.cnnk_bn_relu_infer(C.byref(d), ptr(x), ptr(residual), ptr(gamma), ptr(beta), ptr(running_mean),
+                                  ptr(running_var), ptr(y), stream), "cnnk_bn_relu_infer")
+
+
 def cnnk_bn_relu_bwd(d, dy, x, y, gamma, beta, save_mean, save_invstd, dx, dresidual, flags, dgamma, dbeta,
                      ws=None, ws_bytes=0, stream=0):
     _check(lib.cnnk_bn_relu_bwd(C.byref(d), ptr(dy), ptr(x), ptr(y), ptr(gamma), ptr(beta), ptr(save_mean),
@@ -210,6 +219,10 @@ def cnnk_fc_softmax_xent(d, x, W, b, labels, loss, pred, probs, dx, dW, db, ws=N
            "cnnk_fc_softmax_xent")
 
 
+def cnnk_count_correct(n, pred, labels, n_correct, stream=0):
+    _check(lib.cnnk_count_correct(int(n), ptr(pred), ptr(labels), ptr(n_correct), stream), "cnnk_count_correct")
+
+
 def cnnk_sgd_momentum(n, w, v, g, w_bf16, lr, momentum, weight_decay=0.0, stream=0):
     _check(lib.cnnk_sgd_momentum(n, ptr(w), ptr(v), ptr(g), ptr(w_bf16), lr, momentum, weight_decay, stream),
            "cnnk_sgd_momentum")
@@ -226,6 +239,11 @@ def cnnk_train_step_event_groups(n_layers):
 def cnnk_train_step(layers, n_layers, buffers, labels, lr, momentum, weight_decay, loss, pred, stream=0):
     _check(lib.cnnk_train_step(layers, n_layers, C.byref(buffers), ptr(labels), lr, momentum, weight_decay,
                                ptr(loss), ptr(pred), stream), "cnnk_train_step")
+
+
+def cnnk_eval_step(layers, n_layers, buffers, labels, loss, pred, n_correct=None, stream=0):
+    _check(lib.cnnk_eval_step(layers, n_layers, C.byref(buffers), ptr(labels), ptr(loss), ptr(pred),
+                              ptr(n_correct), stream), "cnnk_eval_step")
 
 
 # ---- HIP runtime plumbing for callers that time launches with events (no arithmetic here) ----

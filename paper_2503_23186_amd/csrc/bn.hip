@@ -226,6 +226,25 @@ __global__ void __launch_bounds__(kT) bn_apply_kernel(const T* __restrict__ x, c
   bn_apply_rows<T>(x, res, y, m, C, relu, sc, bi);
 }
 
+// Inference mode: the running statistics stand in for the batch's; nothing is reduced or updated.
+template <typename T>
+__global__ void __launch_bounds__(kT) bn_infer_kernel(const T* __restrict__ x, const T* __restrict__ res,
+                                                      const float* __restrict__ gamma,
+                                                      const float* __restrict__ beta,
+                                                      const float* __restrict__ rmean,
+                                                      const float* __restrict__ rvar, float eps,
+                                                      T* __restrict__ y, size_t m, int C, int relu) {
+  const int o = threadIdx.x % (C / 8);
+  float g[8], b[8], mu[8], var[8], sc[8], bi[8];
+  load8(gamma + o * 8, g);
+  load8(beta + o * 8, b);
+  load8(rmean + o * 8, mu);
+  load8(rvar + o * 8, var);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) bn_scale_bias(g[e], b[e], mu[e], 1.f / sqrtf(var[e] + eps), &sc[e], &bi[e]);
+  bn_apply_rows<T>(x, res, y, m, C, relu, sc, bi);
+}
+
 // Normalise (+ residual) (+ ReLU) with the statistics taken directly from per-channel sums
 // (sum x, sum x^2 over m positions, e.g. from the convolution that produced x): every thread
 // derives mean / invstd of its 8 channels itself, so no separate statistics kernel runs.
@@ -513,6 +532,26 @@ extern "C" int cnnk_bn_relu_fwd(const cnnk_bn_desc* d, const void* x, const void
   else
     bn_apply_kernel<float><<<row_blocks(m, C), kT, 0, st>>>((const float*)x, (const float*)residual, gamma, beta,
                                                          save_mean, save_invstd, (float*)y, m, C, d->relu);
+  return launch_status();
+}
+
+extern "C" int cnnk_bn_relu_infer(const cnnk_bn_desc* d, const void* x, const void* residual, const float* gamma,
+                                  const float* beta, const float* running_mean, const float* running_var,
+                                  void* y, void* stream) {
+  int rc = validate_bn(d);
+  if (rc != CNNK_OK) return rc;
+  if (!x || !gamma || !beta || !running_mean || !running_var || !y) return CNNK_ERR_NULL;
+  const size_t m = (size_t)d->N * d->H * d->W;
+  const int C = d->C;
+  hipStream_t st = (hipStream_t)stream;
+  if (d->dtype == CNNK_BF16)
+    bn_infer_kernel<bf16_t><<<row_blocks(m, C), kT, 0, st>>>((const bf16_t*)x, (const bf16_t*)residual, gamma, beta,
+                                                          running_mean, running_var, d->eps, (bf16_t*)y, m, C,
+                                                          d->relu);
+  else
+    bn_infer_kernel<float><<<row_blocks(m, C), kT, 0, st>>>((const float*)x, (const float*)residual, gamma, beta,
+                                                         running_mean, running_var, d->eps, (float*)y, m, C,
+                                                         d->relu);
   return launch_status();
 }
 

@@ -207,6 +207,23 @@ __global__ void __launch_bounds__(kT) fc_dx_kernel(const float* __restrict__ dz,
   Elem<T>::st(dx + (size_t)n * F + f, a);
 }
 
+// *n_correct += number of samples with pred == label (integer atomic: order-independent).
+__global__ void __launch_bounds__(kT) count_correct_kernel(const int* __restrict__ pred,
+                                                           const int* __restrict__ labels, int N,
+                                                           int* __restrict__ n_correct) {
+  __shared__ int red[kT];
+  const int tid = threadIdx.x;
+  int c = 0;
+  for (int n = tid; n < N; n += kT) c += pred[n] == labels[n] ? 1 : 0;
+  red[tid] = c;
+  __syncthreads();
+  for (int o = kT / 2; o > 0; o >>= 1) {
+    if (tid < o) red[tid] += red[tid + o];
+    __syncthreads();
+  }
+  if (tid == 0) atomicAdd(n_correct, red[0]);
+}
+
 int validate_fc(const cnnk_fc_desc* d) {
   if (!d) return CNNK_ERR_NULL;
   if (d->N <= 0 || d->F <= 0 || d->classes <= 0) return CNNK_ERR_SHAPE;
@@ -226,7 +243,9 @@ extern "C" int cnnk_fc_softmax_xent(const cnnk_fc_desc* d, const void* x, const 
                                     float* db, void* ws, size_t ws_bytes, void* stream) {
   int rc = validate_fc(d);
   if (rc != CNNK_OK) return rc;
-  if (!x || !W || !b || !labels || !loss || !pred || !dx || !dW || !db) return CNNK_ERR_NULL;
+  if (!x || !W || !b || !labels || !loss || !pred) return CNNK_ERR_NULL;
+  const bool backward = dx || dW || db;   // all three or none
+  if (backward && (!dx || !dW || !db)) return CNNK_ERR_NULL;
   if (!ws || ws_bytes < cnnk_fc_workspace_bytes(d)) return CNNK_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   const int N = d->N, F = d->F, K = d->classes;
@@ -237,6 +256,7 @@ extern "C" int cnnk_fc_softmax_xent(const cnnk_fc_desc* d, const void* x, const 
   if (d->dtype == CNNK_BF16) {
     logits_softmax_kernel<bf16_t><<<N, kT, 0, st>>>((const bf16_t*)x, W, b, labels, N, F, K, vec, dz, loss_n, pred, probs);
     loss_kernel<<<1, kT, 0, st>>>(loss_n, N, loss);
+    if (!backward) return launch_status();
     if (F % 8 == 0)
       fc_dw_db_vec_kernel<bf16_t><<<K, kT, 0, st>>>(dz, (const bf16_t*)x, N, F, K, dW, db);
     else
@@ -245,11 +265,19 @@ extern "C" int cnnk_fc_softmax_xent(const cnnk_fc_desc* d, const void* x, const 
   } else {
     logits_softmax_kernel<float><<<N, kT, 0, st>>>((const float*)x, W, b, labels, N, F, K, vec, dz, loss_n, pred, probs);
     loss_kernel<<<1, kT, 0, st>>>(loss_n, N, loss);
+    if (!backward) return launch_status();
     if (F % 8 == 0)
       fc_dw_db_vec_kernel<float><<<K, kT, 0, st>>>(dz, (const float*)x, N, F, K, dW, db);
     else
       fc_dw_db_kernel<float><<<K, kT, 0, st>>>(dz, (const float*)x, N, F, K, dW, db);
     fc_dx_kernel<float><<<gx, kT, 0, st>>>(dz, W, N, F, K, (float*)dx);
   }
+  return launch_status();
+}
+
+extern "C" int cnnk_count_correct(int n, const int* pred, const int* labels, int* n_correct, void* stream) {
+  if (!pred || !labels || !n_correct) return CNNK_ERR_NULL;
+  if (n <= 0) return CNNK_ERR_SHAPE;
+  count_correct_kernel<<<1, kT, 0, (hipStream_t)stream>>>(pred, labels, n, n_correct);
   return launch_status();
 }

@@ -458,3 +458,54 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
   timer.end(g_upd);
   return rc;
 }
+
+// Validation pass: the forward half of the step in inference mode.
+extern "C" int cnnk_eval_step(const cnnk_layer* L, int n, const cnnk_buffers* B, const int* labels, float* loss,
+                              int* pred, int* n_correct, void* stream) {
+  if (!B || !labels || !loss || !pred) return CNNK_ERR_NULL;
+  if (!B->act || !B->param || !B->bn_running || !B->pool_idx) return CNNK_ERR_NULL;
+  Walk w;
+  int rc = walk_layers(L, n, B->n_slots, B->n_params, &w);
+  if (rc != CNNK_OK) return rc;
+  if (!B->ws || B->ws_bytes < align_up(w.ws, 256) + kStatBytes + w.wt_bytes) return CNNK_ERR_WORKSPACE;
+  const bool bf16 = w.dtype == CNNK_BF16;
+  for (size_t s = 0; s < w.slot_elems.size(); ++s)
+    if (w.slot_elems[s] != 0 && !B->act[s]) return CNNK_ERR_NULL;
+  for (size_t p = 0; p < w.param_elems.size(); ++p)
+    if (w.param_elems[p] != 0 && !B->param[p]) return CNNK_ERR_NULL;
+  for (int i = 0; i < n; ++i) {
+    if (L[i].op == CNNK_OP_CONV && bf16 && (!B->param_lp || !B->param_lp[L[i].p0])) return CNNK_ERR_NULL;
+    if (L[i].op == CNNK_OP_BN && !B->bn_running[i]) return CNNK_ERR_NULL;
+    if (L[i].op == CNNK_OP_POOL && L[i].d.pool.mode == CNNK_POOL_MAX2 && !B->pool_idx[i]) return CNNK_ERR_NULL;
+  }
+  void* ws = static_cast<char*>(B->ws) + kStatBytes + w.wt_bytes;
+  const size_t wsb = B->ws_bytes - kStatBytes - w.wt_bytes;
+  for (int i = 0; i < n && rc == CNNK_OK; ++i) {
+    const cnnk_layer& l = L[i];
+    switch (l.op) {
+      case CNNK_OP_CONV: {
+        const void* wt = bf16 ? B->param_lp[l.p0] : (const void*)B->param[l.p0];
+        rc = cnnk_conv2d_fwd(&l.d.conv, B->act[l.in0], wt, B->act[l.out], nullptr, nullptr, ws, wsb, stream);
+        break;
+      }
+      case CNNK_OP_BN: {
+        const float* run = B->bn_running[i];
+        rc = cnnk_bn_relu_infer(&l.d.bn, B->act[l.in0], l.in1 >= 0 ? B->act[l.in1] : nullptr, B->param[l.p0],
+                                B->param[l.p1], run, run + l.d.bn.C, B->act[l.out], stream);
+        break;
+      }
+      case CNNK_OP_POOL:
+        rc = cnnk_pool_fwd(&l.d.pool, B->act[l.in0], B->act[l.out], B->pool_idx[i], stream);
+        break;
+      case CNNK_OP_ADD:
+        rc = cnnk_add(w.slot_elems[l.out], w.dtype, B->act[l.in0], B->act[l.in1], B->act[l.out], stream);
+        break;
+      case CNNK_OP_FC_LOSS:
+        rc = cnnk_fc_softmax_xent(&l.d.fc, B->act[l.in0], B->param[l.p0], B->param[l.p1], labels, loss, pred,
+                                  B->probs, nullptr, nullptr, nullptr, ws, wsb, stream);
+        if (rc == CNNK_OK && n_correct) rc = cnnk_count_correct(l.d.fc.N, pred, labels, n_correct, stream);
+        break;
+    }
+  }
+  return rc;
+}
