@@ -199,6 +199,18 @@ def main():
                                    frac_of_hbm_peak=round(ew_bytes / ew_ms / 1e6 / PEAK_HBM_GBS, 4) if ew_ms else None,
                                    ms_per_step=round(ew_ms, 4))
 
+    # ---- the validation pass of the epoch loop (inference-mode forward), reported beside the step ----
+    from paper_2503_23186_amd import cnnk as _cnnk
+    for _ in range(3):
+        _cnnk.cnnk_eval_step(run.c_layers, len(net.layers), run.buffers, run.labels, run.loss, run.pred, None, stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    n_eval = 20
+    for _ in range(n_eval):
+        _cnnk.cnnk_eval_step(run.c_layers, len(net.layers), run.buffers, run.labels, run.loss, run.pred, None, stream)
+    torch.cuda.synchronize()
+    eval_ms = 1e3 * (time.perf_counter() - t0) / n_eval
+
     # ---- the oracle on the host cores, on a bounded sample of the same workload ---------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -230,6 +242,7 @@ def main():
                    "config_id": args.config, "global_batch": net.batch, "loss": round(loss, 5)},
         "roofline": roof,
         "cpu_baseline": cpu,
+        "validation_pass": {"ms_per_batch": round(eval_ms, 4), "images_per_s": round(net.batch / (eval_ms * 1e-3), 1)},
     }
     print(json.dumps(out))
 
