@@ -145,6 +145,43 @@ __global__ void __launch_bounds__(kT) sums_finalize_kernel(const float* __restri
   ch_sumsq[c] = (float)s2;
 }
 
+// The same with a whole workgroup per channel, for many partials (a wavefront alone would walk
+// them in nb/64 dependent rounds): threads stride the partials, butterfly per wavefront, the four
+// wavefront sums added in order.
+constexpr int kWideFinalize = 1024;   // partials per channel from which the wide kernels are used
+__device__ __forceinline__ void finalize_sums_wide(const float* __restrict__ part, int nb, int C, int c,
+                                                   double* s1_out, double* s2_out) {
+  __shared__ double comb[2][kT / 64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float* p1 = part + ((size_t)0 * C + c) * nb;
+  const float* p2 = part + ((size_t)1 * C + c) * nb;
+  double s1 = 0.0, s2 = 0.0;
+#pragma unroll 4
+  for (int b = tid; b < nb; b += kT) {
+    s1 += (double)p1[b];
+    s2 += (double)p2[b];
+  }
+  s1 = wave_sum_f64(s1);
+  s2 = wave_sum_f64(s2);
+  if (lane == 0) { comb[0][wave] = s1; comb[1][wave] = s2; }
+  __syncthreads();
+  double t1 = comb[0][0], t2 = comb[1][0];
+#pragma unroll
+  for (int w_ = 1; w_ < kT / 64; ++w_) { t1 += comb[0][w_]; t2 += comb[1][w_]; }
+  *s1_out = t1;
+  *s2_out = t2;
+}
+
+__global__ void __launch_bounds__(kT) sums_finalize_wide_kernel(const float* __restrict__ part, int nb, int C,
+                                                                float* __restrict__ ch_sum,
+                                                                float* __restrict__ ch_sumsq) {
+  double s1, s2;
+  finalize_sums_wide(part, nb, C, blockIdx.x, &s1, &s2);
+  if (threadIdx.x != 0) return;
+  ch_sum[blockIdx.x] = (float)s1;
+  ch_sumsq[blockIdx.x] = (float)s2;
+}
+
 // sc = gamma * invstd, bi = beta - mean * sc: the one place this is written, so that the forward
 // kernels and the mask recomputation of the backward kernels round identically.
 __device__ __forceinline__ void bn_scale_bias(float g, float b, float mu, float is, float* sc, float* bi) {
@@ -354,6 +391,15 @@ __global__ void __launch_bounds__(kT) bwd_finalize_kernel(const float* __restric
   dgamma[c] = (float)s2;
 }
 
+__global__ void __launch_bounds__(kT) bwd_finalize_wide_kernel(const float* __restrict__ part, int nb, int C,
+                                                               float* __restrict__ dgamma, float* __restrict__ dbeta) {
+  double s1, s2;
+  finalize_sums_wide(part, nb, C, blockIdx.x, &s1, &s2);
+  if (threadIdx.x != 0) return;
+  dbeta[blockIdx.x] = (float)s1;
+  dgamma[blockIdx.x] = (float)s2;
+}
+
 template <typename T, int MODE>
 __global__ void __launch_bounds__(kT) bwd_apply_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                                                        const T* __restrict__ y, const float* __restrict__ gamma,
@@ -455,7 +501,8 @@ int validate_bn(const cnnk_bn_desc* d) {
 }  // namespace
 
 int channel_sums_finalize(const float* part, int nb, int C, float* ch_sum, float* ch_sumsq, hipStream_t st) {
-  sums_finalize_kernel<<<fin_blocks(C), kT, 0, st>>>(part, nb, C, ch_sum, ch_sumsq);
+  if (nb >= kWideFinalize) sums_finalize_wide_kernel<<<C, kT, 0, st>>>(part, nb, C, ch_sum, ch_sumsq);
+  else sums_finalize_kernel<<<fin_blocks(C), kT, 0, st>>>(part, nb, C, ch_sum, ch_sumsq);
   return launch_status();
 }
 
@@ -567,7 +614,8 @@ static int bn_bwd_launch(const cnnk_bn_desc* d, const void* dy, const void* x, c
   const bool dz_first = MODE == 1 && dresidual && !(flags & 2);
   bwd_partial_kernel<T, MODE><<<nb, kT, 0, st>>>((const T*)dy, (const T*)x, (const T*)y, gamma, beta, save_mean,
                                                  save_invstd, m, C, part, dz_first ? (T*)dresidual : nullptr);
-  bwd_finalize_kernel<<<fin_blocks(C), kT, 0, st>>>(part, nb, C, dgamma, dbeta);
+  if (nb >= kWideFinalize) bwd_finalize_wide_kernel<<<C, kT, 0, st>>>(part, nb, C, dgamma, dbeta);
+  else bwd_finalize_kernel<<<fin_blocks(C), kT, 0, st>>>(part, nb, C, dgamma, dbeta);
   if (dz_first)
     bwd_apply_kernel<T, 3><<<row_blocks(m, C), kT, 0, st>>>((const T*)dy, (const T*)x, (const T*)y, gamma, beta,
                                                             save_mean, save_invstd, dgamma, dbeta, (T*)dx,

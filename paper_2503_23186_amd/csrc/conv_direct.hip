@@ -96,18 +96,21 @@ __global__ void __launch_bounds__(256) direct_wgrad_kernel(ConvGeom g, const T* 
   part[(size_t)blockIdx.y * nw + i] = acc;
 }
 
-// out[i] = sum_p part[p][i].  64 float4 columns x 4 partial groups per workgroup; each group sums
-// every fourth partial, the groups are combined through LDS in a fixed order (deterministic).
+// out[i] = sum_p part[p][i], deterministic.  GROUPS thread groups share the P partials of a float4 column (group g takes p = g, g+GROUPS, ...);
+// their sums are combined through LDS in group order.  More groups = more, shorter-lived threads:
+// 16 for many partials (a 64x576 gradient split 108 ways is 16 MB to read), 4 otherwise.
+template <int GROUPS>
 __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __restrict__ part,
                                                               float* __restrict__ out, int n, int P) {
-  __shared__ float4 red[4][64];
-  const int col = threadIdx.x & 63, grp = threadIdx.x >> 6;
-  const int i4 = blockIdx.x * 64 + col;   // float4 column
+  constexpr int COLS = 256 / GROUPS;
+  __shared__ float4 red[GROUPS][COLS];
+  const int col = threadIdx.x % COLS, grp = threadIdx.x / COLS;
+  const int i4 = blockIdx.x * COLS + col;   // float4 column
   const int n4 = n >> 2;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   if (i4 < n4) {
 #pragma unroll 4
-    for (int p = grp; p < P; p += 4) {
+    for (int p = grp; p < P; p += GROUPS) {
       const float4 v = *reinterpret_cast<const float4*>(part + (size_t)p * n + (size_t)i4 * 4);
       acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
     }
@@ -117,7 +120,7 @@ __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __res
   if (grp == 0 && i4 < n4) {
     float4 s = red[0][col];
 #pragma unroll
-    for (int k = 1; k < 4; ++k) { s.x += red[k][col].x; s.y += red[k][col].y; s.z += red[k][col].z; s.w += red[k][col].w; }
+    for (int k = 1; k < GROUPS; ++k) { s.x += red[k][col].x; s.y += red[k][col].y; s.z += red[k][col].z; s.w += red[k][col].w; }
     *reinterpret_cast<float4*>(out + (size_t)i4 * 4) = s;
   }
   // scalar tail (n not a multiple of 4)
@@ -184,11 +187,11 @@ int conv_direct_wgrad(const ConvGeom& g, int dtype, const void* x, const void* d
   else
     direct_wgrad_kernel<float><<<grid, 256, 0, st>>>(g, (const float*)x, (const float*)dy, part, chunk);
   if (launch_status() != CNNK_OK) return CNNK_ERR_HIP;
-  reduce_partials_kernel<<<(nw / 4 + 63) / 64 + 1, 256, 0, st>>>(part, dw, nw, P);
-  return launch_status();
+  return reduce_partials(part, dw, nw, P, st);
 }
 
 int reduce_partials(const float* part, float* out, int n, int P, hipStream_t st) {
-  reduce_partials_kernel<<<(n / 4 + 63) / 64 + 1, 256, 0, st>>>(part, out, n, P);
+  if (P >= 32) reduce_partials_kernel<16><<<(n / 4 + 15) / 16 + 1, 256, 0, st>>>(part, out, n, P);
+  else reduce_partials_kernel<4><<<(n / 4 + 63) / 64 + 1, 256, 0, st>>>(part, out, n, P);
   return launch_status();
 }

@@ -69,6 +69,22 @@ __global__ void __launch_bounds__(kThreads, OCC) igemm_kernel(IgemmArgs a) {
   const int M = a.Nimg * Hm * Wm;
   if (mt * BM >= M) return;
   const int tap0 = a.tt.cls_begin[cls], ntap = a.tt.cls_begin[cls + 1] - tap0;
+  if (ntap == 0 && !a.stats) {
+    // An output parity class that no filter tap reaches (1x1 filters with stride 2: three of the
+    // four): its values are zero.  Adding zero is a no-op; otherwise fill the tile's rows.
+    if (a.accumulate) return;
+    const int oh0 = a.tt.oh[cls], ow0 = a.tt.ow[cls];
+    for (int idx = tid; idx < BM * (BN / 8); idx += kThreads) {
+      const int row = idx / (BN / 8), ch = idx % (BN / 8);
+      const int m = mt * BM + row, co = nt * BN + ch * 8;
+      if (m >= M || co >= a.Cd) continue;
+      const int j = m % Wm, q = m / Wm;
+      const int i = q % Hm, n = q / Hm;
+      bf16_t* dp = a.dst + (((size_t)n * a.Hd + (i * a.os + oh0)) * a.Wd + (j * a.os + ow0)) * a.Cd + co;
+      *reinterpret_cast<uint4*>(dp) = make_uint4(0u, 0u, 0u, 0u);
+    }
+    return;
+  }
 
   const int kc = tid % KC, r0 = tid / KC;
   const __amdgpu_buffer_rsrc_t src_rs = make_rsrc(a.src, (unsigned)a.Nimg * a.Hs * a.Ws * a.Cs * 2u);

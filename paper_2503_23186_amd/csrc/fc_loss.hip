@@ -114,7 +114,7 @@ __global__ void __launch_bounds__(kT) logits_softmax_kernel(const T* __restrict_
 }
 
 // loss = mean(loss_n)      (single workgroup, fixed order)
-__global__ void __launch_bounds__(kT) loss_kernel(const float* __restrict__ loss_n, int N, float* __restrict__ loss) {
+__device__ __forceinline__ void loss_body(const float* __restrict__ loss_n, int N, float* __restrict__ loss) {
   __shared__ float red[kT];
   const int tid = threadIdx.x;
   float s = 0.f;
@@ -128,13 +128,17 @@ __global__ void __launch_bounds__(kT) loss_kernel(const float* __restrict__ loss
   if (tid == 0) loss[0] = red[0] / (float)N;
 }
 
+__global__ void __launch_bounds__(kT) loss_kernel(const float* __restrict__ loss_n, int N, float* __restrict__ loss) {
+  loss_body(loss_n, N, loss);
+}
+
 // One workgroup per class j: dW[j][f] = sum_n dz[n][j] * x[n][f] (threads over f), and
 // db[j] = sum_n dz[n][j] (threads over n, fixed-order tree).
 template <typename T>
-__global__ void __launch_bounds__(kT) fc_dw_db_kernel(const float* __restrict__ dz, const T* __restrict__ x, int N,
-                                                      int F, int K, float* __restrict__ dW, float* __restrict__ db) {
+__device__ __forceinline__ void fc_dw_db_body(int j, const float* __restrict__ dz, const T* __restrict__ x, int N,
+                                              int F, int K, float* __restrict__ dW, float* __restrict__ db) {
   __shared__ float red[kT];
-  const int j = blockIdx.x, tid = threadIdx.x;
+  const int tid = threadIdx.x;
   for (int f = tid; f < F; f += kT) {
     float a = 0.f;
 #pragma unroll 8
@@ -155,12 +159,12 @@ __global__ void __launch_bounds__(kT) fc_dw_db_kernel(const float* __restrict__ 
 // The same for F % 8 == 0: wave w takes the samples n = w, w+4, ..., a lane 8 consecutive features
 // (16- or 32-byte loads); the four per-wave sums are combined through LDS in wave order.
 template <typename T>
-__global__ void __launch_bounds__(kT) fc_dw_db_vec_kernel(const float* __restrict__ dz, const T* __restrict__ x,
-                                                          int N, int F, int K, float* __restrict__ dW,
-                                                          float* __restrict__ db) {
+__device__ __forceinline__ void fc_dw_db_vec_body(int j, const float* __restrict__ dz, const T* __restrict__ x,
+                                                  int N, int F, int K, float* __restrict__ dW,
+                                                  float* __restrict__ db) {
   __shared__ float part[kT / 64][512];
   __shared__ float red[kT];
-  const int j = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   for (int fb = 0; fb < F; fb += 512) {
     const int f0 = fb + lane * 8;
     float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -198,13 +202,36 @@ __global__ void __launch_bounds__(kT) fc_dw_db_vec_kernel(const float* __restric
 
 // dx[n][f] = sum_j dz[n][j] * W[j][f]
 template <typename T>
-__global__ void __launch_bounds__(kT) fc_dx_kernel(const float* __restrict__ dz, const float* __restrict__ W, int N,
-                                                   int F, int K, T* __restrict__ dx) {
-  const int f = blockIdx.x * kT + threadIdx.x, n = blockIdx.y;
+__device__ __forceinline__ void fc_dx_body(int fblk, int n, const float* __restrict__ dz,
+                                           const float* __restrict__ W, int N, int F, int K, T* __restrict__ dx) {
+  const int f = fblk * kT + threadIdx.x;
   if (f >= F) return;
   float a = 0.f;
+#pragma unroll 4
   for (int j = 0; j < K; ++j) a = fmaf(dz[(size_t)n * K + j], W[(size_t)j * F + f], a);
   Elem<T>::st(dx + (size_t)n * F + f, a);
+}
+
+// Everything behind the softmax in one launch, by workgroup role: workgroups [0, K) one class each
+// of dW and db, workgroup K the mean of the per-sample losses, the rest one (feature block, sample)
+// each of dx.  The roles are independent (all read dz and loss_n of the previous launch), each sum
+// keeps its fixed order.
+template <typename T, int VEC>
+__global__ void __launch_bounds__(kT) fc_bwd_kernel(const float* __restrict__ dz, const float* __restrict__ loss_n,
+                                                    const T* __restrict__ x, const float* __restrict__ W, int N,
+                                                    int F, int K, int fblocks, float* __restrict__ loss,
+                                                    float* __restrict__ dW, float* __restrict__ db,
+                                                    T* __restrict__ dx) {
+  const int b = blockIdx.x;
+  if (b < K) {
+    if (VEC) fc_dw_db_vec_body<T>(b, dz, x, N, F, K, dW, db);
+    else fc_dw_db_body<T>(b, dz, x, N, F, K, dW, db);
+  } else if (b == K) {
+    loss_body(loss_n, N, loss);
+  } else {
+    const int r = b - K - 1;
+    fc_dx_body<T>(r % fblocks, r / fblocks, dz, W, N, F, K, dx);
+  }
 }
 
 // *n_correct += number of samples with pred == label (integer atomic: order-independent).
@@ -251,26 +278,23 @@ extern "C" int cnnk_fc_softmax_xent(const cnnk_fc_desc* d, const void* x, const 
   const int N = d->N, F = d->F, K = d->classes;
   float* dz = (float*)ws;
   float* loss_n = dz + (size_t)N * K;
-  dim3 gx((F + kT - 1) / kT, N);
+  const int fblocks = (F + kT - 1) / kT;
+  const unsigned nblk = (unsigned)(K + 1 + fblocks * N);
   const int vec = (F % 8 == 0 && F <= 1024) ? 1 : 0;
   if (d->dtype == CNNK_BF16) {
     logits_softmax_kernel<bf16_t><<<N, kT, 0, st>>>((const bf16_t*)x, W, b, labels, N, F, K, vec, dz, loss_n, pred, probs);
-    loss_kernel<<<1, kT, 0, st>>>(loss_n, N, loss);
-    if (!backward) return launch_status();
-    if (F % 8 == 0)
-      fc_dw_db_vec_kernel<bf16_t><<<K, kT, 0, st>>>(dz, (const bf16_t*)x, N, F, K, dW, db);
+    if (!backward) loss_kernel<<<1, kT, 0, st>>>(loss_n, N, loss);
+    else if (F % 8 == 0)
+      fc_bwd_kernel<bf16_t, 1><<<nblk, kT, 0, st>>>(dz, loss_n, (const bf16_t*)x, W, N, F, K, fblocks, loss, dW, db, (bf16_t*)dx);
     else
-      fc_dw_db_kernel<bf16_t><<<K, kT, 0, st>>>(dz, (const bf16_t*)x, N, F, K, dW, db);
-    fc_dx_kernel<bf16_t><<<gx, kT, 0, st>>>(dz, W, N, F, K, (bf16_t*)dx);
+      fc_bwd_kernel<bf16_t, 0><<<nblk, kT, 0, st>>>(dz, loss_n, (const bf16_t*)x, W, N, F, K, fblocks, loss, dW, db, (bf16_t*)dx);
   } else {
     logits_softmax_kernel<float><<<N, kT, 0, st>>>((const float*)x, W, b, labels, N, F, K, vec, dz, loss_n, pred, probs);
-    loss_kernel<<<1, kT, 0, st>>>(loss_n, N, loss);
-    if (!backward) return launch_status();
-    if (F % 8 == 0)
-      fc_dw_db_vec_kernel<float><<<K, kT, 0, st>>>(dz, (const float*)x, N, F, K, dW, db);
+    if (!backward) loss_kernel<<<1, kT, 0, st>>>(loss_n, N, loss);
+    else if (F % 8 == 0)
+      fc_bwd_kernel<float, 1><<<nblk, kT, 0, st>>>(dz, loss_n, (const float*)x, W, N, F, K, fblocks, loss, dW, db, (float*)dx);
     else
-      fc_dw_db_kernel<float><<<K, kT, 0, st>>>(dz, (const float*)x, N, F, K, dW, db);
-    fc_dx_kernel<float><<<gx, kT, 0, st>>>(dz, W, N, F, K, (float*)dx);
+      fc_bwd_kernel<float, 0><<<nblk, kT, 0, st>>>(dz, loss_n, (const float*)x, W, N, F, K, fblocks, loss, dW, db, (float*)dx);
   }
   return launch_status();
 }

@@ -343,7 +343,11 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
   // on the second stream - queued behind the weight gradients there it made the main stream wait,
   // 2.45 vs 2.37 ms; (2) per-channel sums through exact 64-bit integer atomics (three fixed-point
   // limbs, 8 replicas) instead of partials + a finalising launch - same-address atomics serialise
-  // in L2 at 10-20 ns each: 3.29 ms with one copy, 2.42 vs 2.40 ms with eight.
+  // in L2 at 10-20 ns each: 3.29 ms with one copy, 2.42 vs 2.40 ms with eight; (3) the finalising
+  // reduction inside the consuming batch-norm launch (its first workgroups reduce and publish, all
+  // wait on flags with device-scope release / acquire) - the cache write-back and invalidate of
+  // those fences cost far more than the launch they save: 2.68 vs 2.33 ms; (4) the weight
+  // transpositions on the second stream beside the forward pass: no change (2.334 vs 2.334 ms).
   for (int i = n - 2; i >= 0; --i) {
     const cnnk_layer& l = L[i];
     const int g0 = n + 2 * (n - 2 - i);
