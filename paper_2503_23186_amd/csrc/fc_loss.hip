@@ -20,11 +20,11 @@ __global__ void __launch_bounds__(kT) logits_softmax_kernel(const T* __restrict_
   const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const T* xr = x + (size_t)n * F;
   if (vec) {
-    // F % 8 == 0 and F <= 1024: the sample's features stay in registers (8 consecutive per lane
+    // F % 8 == 0 and F <= 2048: the sample's features stay in registers (8 consecutive per lane
     // and 512-feature chunk), weight rows stream in as 32-byte pieces, four classes in flight
-    float xv[2][8];
+    float xv[4][8];
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
+    for (int c = 0; c < 4; ++c) {
       const int f0 = (lane + 64 * c) * 8;
       if (f0 < F) load8(xr + f0, xv[c]);
       else
@@ -38,7 +38,7 @@ __global__ void __launch_bounds__(kT) logits_softmax_kernel(const T* __restrict_
         const int j = j0 + q * (kT / 64);
         if (j < K) {
 #pragma unroll
-          for (int c = 0; c < 2; ++c) {
+          for (int c = 0; c < 4; ++c) {
             const int f0 = (lane + 64 * c) * 8;
             if (f0 < F) {
               float wv[8];
@@ -280,7 +280,7 @@ extern "C" int cnnk_fc_softmax_xent(const cnnk_fc_desc* d, const void* x, const 
   float* loss_n = dz + (size_t)N * K;
   const int fblocks = (F + kT - 1) / kT;
   const unsigned nblk = (unsigned)(K + 1 + fblocks * N);
-  const int vec = (F % 8 == 0 && F <= 1024) ? 1 : 0;
+  const int vec = (F % 8 == 0 && F <= 2048) ? 1 : 0;
   if (d->dtype == CNNK_BF16) {
     logits_softmax_kernel<bf16_t><<<N, kT, 0, st>>>((const bf16_t*)x, W, b, labels, N, F, K, vec, dz, loss_n, pred, probs);
     if (!backward) loss_kernel<<<1, kT, 0, st>>>(loss_n, N, loss);

@@ -285,7 +285,7 @@ def test_pool_fwd_bwd(K, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-@pytest.mark.parametrize("N,F,classes", [(8, 16, 100), (256, 512, 100), (33, 640, 100), (5, 2048, 10), (7, 52, 10), (3, 1024, 7)])
+@pytest.mark.parametrize("N,F,classes", [(8, 16, 100), (256, 512, 100), (33, 640, 100), (5, 2048, 10), (7, 52, 10), (3, 1024, 7), (64, 1536, 100), (4, 2056, 5)])
 def test_fc_softmax_xent(K, N, F, classes, dtype):
     rng = np.random.default_rng(41)
     x = rep(rng.standard_normal((N, F)), dtype)
