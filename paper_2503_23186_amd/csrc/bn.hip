@@ -16,10 +16,16 @@ struct RowMap {
   int rows;    // rows per workgroup pass = 256 / lanes
 };
 
-__host__ __device__ inline int reduce_blocks(size_t m, int C) {
+inline int reduce_blocks(size_t m, int C) {
   const int rows = kT / (C / 8);
   size_t nb = (m + (size_t)rows * 4 - 1) / ((size_t)rows * 4);  // at least 4 rows per thread
   if (nb > kMaxBlocks) nb = kMaxBlocks;
+  // every workgroup ends with 2*C scattered 4-byte writes of its partial sums: with many channels
+  // fewer, longer-lived workgroups are cheaper (C = 1024: 256 instead of 2048; ResNet-50
+  // b256 step 9.57 -> 9.08 ms, 128 or 512 are worse or equal)
+  size_t cap = (size_t)262144 / (size_t)C;
+  if (cap < 256) cap = 256;
+  if (nb > cap) nb = cap;
   if (nb < 1) nb = 1;
   return (int)nb;
 }
