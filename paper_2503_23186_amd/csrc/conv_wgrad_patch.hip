@@ -28,7 +28,7 @@ struct WgPatchArgs {
   float* dw;
   int N, H, W, Cin, Cout;
   int TI, TH;          // stage = TI images x TH rows x W columns = PS pixels
-  int ctiles;          // Cin / 64
+  int ctiles;          // ceil(Cin / 64)
   int tiles_per_block; // pixel stages per workgroup
   int mtiles;          // total pixel stages
   int nw;              // Cout*9*Cin: stride between the partials of consecutive pixel ranges
@@ -116,12 +116,13 @@ __global__ void __launch_bounds__(kThreads, 2) wgrad_patch_kernel(WgPatchArgs a)
     int q, pw, ti, ph;
     a.dPW.divmod(pp, &q, &pw);
     a.dPH.divmod(q, &ti, &ph);
-    const bool ok = pp < patch_px && pw >= 1 && pw <= a.W;
+    const bool ok = pp < patch_px && pw >= 1 && pw <= a.W && ct * CT + kc * 8 < a.Cin;   // ragged last channel tile
     xdh[j] = ok ? ph - 1 : -(1 << 20);   // a row shift that never passes the range test
     xti[j] = ti;
     xrel[j] = (((ti * a.H + ph - 1) * a.W + pw - 1) * a.Cin + ct * CT + kc * 8) * 2;
   }
   const int drel = ((tid >> 3) * a.Cout + kt * CT + kc * 8) * 2;
+  const bool dch_ok = kt * CT + kc * 8 < a.Cout;   // ragged last channel tile: zeros
 
   // Stages at or past t_end are loaded from the out-of-range offset (zeros, no memory traffic), so
   // the loop body is the same for every stage.
@@ -132,7 +133,7 @@ __global__ void __launch_bounds__(kThreads, 2) wgrad_patch_kernel(WgPatchArgs a)
 #pragma unroll
     for (int j = 0; j < kDyLoads; ++j) {
       const int p = (tid >> 3) + j * kRowsPerPass;
-      const unsigned off = ((int)live & (int)(m0 + p < M)) ? dbase + (unsigned)(drel + j * kRowsPerPass * a.Cout * 2) : kOobOffset;
+      const unsigned off = ((int)live & (int)(m0 + p < M) & (int)dch_ok) ? dbase + (unsigned)(drel + j * kRowsPerPass * a.Cout * 2) : kOobOffset;
       dreg[j] = buffer_load16(dy_rs, off, 0);
     }
     int q, wrem, n0, h0;
@@ -228,7 +229,7 @@ __global__ void __launch_bounds__(kThreads, 2) wgrad_patch_kernel(WgPatchArgs a)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int k = kt * CT + row_half * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-      out[((size_t)k * 9 + t) * a.Cin + c] = acc[i][r];
+      if (k < a.Cout && c < a.Cin) out[((size_t)k * 9 + t) * a.Cin + c] = acc[i][r];
     }
   }
 }
@@ -264,7 +265,10 @@ int launch_wg(const WgPatchArgs& a, dim3 grid, size_t smem, hipStream_t st) {
 bool conv_wgrad_patch_supported(const ConvGeom& g) {
   if (g_cnnk_tune[6] < 0) return false;
   if (g.R != 3 || g.S != 3 || g.stride != 1 || g.pad != 1) return false;
-  if (g.Cin % CT != 0 || g.Cout % CT != 0) return false;
+  // channel counts in whole 16-byte chunks; a ragged last 64-channel tile computes on zeros, so
+  // only shapes that waste at most a third of the tile grid are taken (160 = 2.5 tiles: yes)
+  if (g.Cin % 8 != 0 || g.Cout % 8 != 0) return false;
+  if (((g.Cin + CT - 1) / CT) * CT * 3 > g.Cin * 4 || ((g.Cout + CT - 1) / CT) * CT * 3 > g.Cout * 4) return false;
   const long M = (long)g.N * g.H * g.W;
   if (M * g.Cin * 2 >= (1L << 31) || M * g.Cout * 2 >= (1L << 31)) return false;
   int ti, th;
@@ -272,8 +276,8 @@ bool conv_wgrad_patch_supported(const ConvGeom& g) {
 }
 
 static void wg_plan(const ConvGeom& g, WgPatchArgs* a, int* splits, int cus = 256) {
-  a->ctiles = g.Cin / CT;
-  const int otiles = (g.Cout / CT) * a->ctiles;
+  a->ctiles = (g.Cin + CT - 1) / CT;
+  const int otiles = ((g.Cout + CT - 1) / CT) * a->ctiles;
   const long M = (long)g.N * g.H * g.W;
   a->mtiles = (int)((M + PS - 1) / PS);
   const int target = g_cnnk_tune[6] > 0 ? g_cnnk_tune[6] : cus;
@@ -301,7 +305,7 @@ int conv_wgrad_patch(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float
   a.dw = splits > 1 ? reinterpret_cast<float*>(ws) : dw;
   a.N = g.N; a.H = g.H; a.W = g.W; a.Cin = g.Cin; a.Cout = g.Cout;
   a.dPW.init(a.W + 2); a.dPH.init(a.TH + 2); a.dW.init(a.W); a.dTH.init(a.TH); a.dH.init(a.H);
-  const int otiles = (g.Cout / CT) * a.ctiles;
+  const int otiles = ((g.Cout + CT - 1) / CT) * a.ctiles;
   const int patch_px = a.TI * (a.TH + 2) * (a.W + 2);
   const size_t smem = (size_t)2 * (PS + patch_px) * PITCH_B;
   dim3 grid(otiles, splits);

@@ -31,6 +31,8 @@ CONV_SHAPES = [
     (2, 32, 32, 3, 64, 3, 1), (9, 4, 4, 512, 512, 3, 1), (2, 32, 32, 64, 64, 3, 1),
     (130, 4, 4, 64, 8, 3, 1), (3, 9, 9, 3, 16, 3, 2), (2, 8, 8, 3, 24, 3, 1), (2, 8, 8, 2, 128, 3, 1),
     (2, 8, 8, 3, 16, 1, 1), (3, 33, 33, 3, 64, 3, 1),
+    # channel counts that end in a ragged 64-channel tile of the 3x3 stride-1 weight-gradient kernel
+    (2, 16, 16, 160, 160, 3, 1), (4, 8, 8, 96, 160, 3, 1), (2, 16, 16, 96, 224, 3, 1),
 ]
 
 
