@@ -27,6 +27,7 @@ struct TapTable {
   int cls_begin[5];
   int dh[kMaxTaps], dw[kMaxTaps], widx[kMaxTaps];
   int Hm[4], Wm[4], oh[4], ow[4];
+  FastDiv dW[4], dH[4];   // division by Wm / Hm of each class
 };
 
 struct IgemmArgs {
@@ -39,12 +40,21 @@ struct IgemmArgs {
   int ss, os;            // source step per sub-grid index; destination step per sub-grid index
   int accumulate;
   int ntiles;
-  float* stats;          // nullable: [2][Cd][mtiles] per-tile column sums and sums of squares
+  float* stats;          // nullable: [2][Cd][mtiles * WM] per-wave column sums and sums of squares
   int mtiles;
+  int tpb;               // tiles one workgroup walks
+  FastDiv dNt;           // division by ntiles
   TapTable tt;
 };
 
-// OCC: waves per SIMD the register allocation must leave room for (workgroups per CU).
+// OCC: workgroups per CU the register allocation must leave room for.
+//
+// A workgroup walks a.tpb consecutive tiles (tile t = (pixel tile t / ntiles, channel tile
+// t % ntiles), so neighbours share their pixel rows).  The stage loads do not know about tile
+// borders: the loads of the next tile's first stages are in flight while the current tile's last
+// MFMAs and its epilogue run, which hides the prologue of every tile but the first.  The epilogue
+// is wave-local (a wave transposes its own accumulators through a private LDS strip, 8 rows at a
+// time, into 16-byte stores), so it needs no workgroup barrier and leaves the stage buffers alone.
 template <int BM, int BN, int BK, int WM, int WN, int OCC>
 __global__ void __launch_bounds__(kThreads, OCC) igemm_kernel(IgemmArgs a) {
   constexpr int LDK = BK + 8;  // padded row (elements): conflict-free 16-byte fragment reads
@@ -52,36 +62,46 @@ __global__ void __launch_bounds__(kThreads, OCC) igemm_kernel(IgemmArgs a) {
   constexpr int RPP = kThreads / KC;  // tile rows filled per pass of the workgroup
   constexpr int A_IT = (BM + RPP - 1) / RPP, B_IT = (BN + RPP - 1) / RPP;  // rows beyond the tile are skipped
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-  constexpr int LDC = BN + 8;
-  static_assert(WM * WN == 4 && A_IT >= 1 && B_IT >= 1 && TM >= 1 && TN >= 1, "tile shape");
+  constexpr int LDW = TN * 32 + 8;   // row pitch (elements) of a wave's epilogue strip
+  static_assert(WM * WN == 4 && A_IT >= 1 && B_IT >= 1 && TM >= 1 && (TN == 1 || TN == 2), "tile shape");
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t* As = reinterpret_cast<bf16_t*>(smem_raw);  // [2][BM][LDK]
   bf16_t* Bs = As + 2 * BM * LDK;                    // [2][BN][LDK]
+  bf16_t* strips = Bs + 2 * BN * LDK;                // [4 waves][8][LDW]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wn = wave / WM;
   int b = blockIdx.x;
   const int nb = gridDim.x;
-  if ((nb & 7) == 0) b = (b & 7) * (nb >> 3) + (b >> 3);  // consecutive tiles share an XCD (and its L2)
+  if ((nb & 7) == 0) b = (b & 7) * (nb >> 3) + (b >> 3);  // consecutive workgroups share an XCD (and its L2)
   const int cls = blockIdx.y;
-  const int nt = b % a.ntiles, mt = b / a.ntiles;
   const int Hm = a.tt.Hm[cls], Wm = a.tt.Wm[cls];
+  const FastDiv dWm = a.tt.dW[cls], dHm = a.tt.dH[cls];
   const int M = a.Nimg * Hm * Wm;
-  if (mt * BM >= M) return;
+  const int tiles_cls = ((M + BM - 1) / BM) * a.ntiles;
+  const int t_begin = b * a.tpb;
+  const int t_end = min(t_begin + a.tpb, tiles_cls);
+  if (t_begin >= t_end) return;
   const int tap0 = a.tt.cls_begin[cls], ntap = a.tt.cls_begin[cls + 1] - tap0;
+  const int oh = a.tt.oh[cls], ow = a.tt.ow[cls];
+  const FastDiv dNt = a.dNt;
   if (ntap == 0 && !a.stats) {
     // An output parity class that no filter tap reaches (1x1 filters with stride 2: three of the
-    // four): its values are zero.  Adding zero is a no-op; otherwise fill the tile's rows.
+    // four): its values are zero.  Adding zero is a no-op; otherwise fill the tiles' rows.
     if (a.accumulate) return;
-    const int oh0 = a.tt.oh[cls], ow0 = a.tt.ow[cls];
-    for (int idx = tid; idx < BM * (BN / 8); idx += kThreads) {
-      const int row = idx / (BN / 8), ch = idx % (BN / 8);
-      const int m = mt * BM + row, co = nt * BN + ch * 8;
-      if (m >= M || co >= a.Cd) continue;
-      const int j = m % Wm, q = m / Wm;
-      const int i = q % Hm, n = q / Hm;
-      bf16_t* dp = a.dst + (((size_t)n * a.Hd + (i * a.os + oh0)) * a.Wd + (j * a.os + ow0)) * a.Cd + co;
-      *reinterpret_cast<uint4*>(dp) = make_uint4(0u, 0u, 0u, 0u);
+    for (int t = t_begin; t < t_end; ++t) {
+      int mt, nt;
+      dNt.divmod(t, &mt, &nt);
+      for (int idx = tid; idx < BM * (BN / 8); idx += kThreads) {
+        const int row = idx / (BN / 8), ch = idx % (BN / 8);
+        const int m = mt * BM + row, co = nt * BN + ch * 8;
+        if (m >= M || co >= a.Cd) continue;
+        int q, j, n, i;
+        dWm.divmod(m, &q, &j);
+        dHm.divmod(q, &n, &i);
+        bf16_t* dp = a.dst + (((size_t)n * a.Hd + (i * a.os + oh)) * a.Wd + (j * a.os + ow)) * a.Cd + co;
+        *reinterpret_cast<uint4*>(dp) = make_uint4(0u, 0u, 0u, 0u);
+      }
     }
     return;
   }
@@ -89,29 +109,36 @@ __global__ void __launch_bounds__(kThreads, OCC) igemm_kernel(IgemmArgs a) {
   const int kc = tid % KC, r0 = tid / KC;
   const __amdgpu_buffer_rsrc_t src_rs = make_rsrc(a.src, (unsigned)a.Nimg * a.Hs * a.Ws * a.Cs * 2u);
   const __amdgpu_buffer_rsrc_t wt_rs = make_rsrc(a.wt, (unsigned)a.Cd * a.T * a.Cs * 2u);
-  // Per tile row: source coordinates at tap (0,0) and the byte offset of that pixel; a tap adds
-  // a uniform offset and two range tests, padding is an out-of-range buffer offset (reads 0).
+  // Per tile row of the tile being loaded: source coordinates at tap (0,0) and the byte offset of
+  // that pixel; a tap adds a uniform offset and two range tests, padding is an out-of-range buffer
+  // offset (reads 0).
   int a_h[A_IT], a_w[A_IT];
   unsigned a_off[A_IT];
-#pragma unroll
-  for (int it = 0; it < A_IT; ++it) {
-    const int m = mt * BM + r0 + it * RPP;
-    if (m < M && r0 + it * RPP < BM) {
-      const int j = m % Wm, q = m / Wm;
-      const int i = q % Hm, n = q / Hm;
-      a_h[it] = i * a.ss;
-      a_w[it] = j * a.ss;
-      a_off[it] = (unsigned)(((n * a.Hs + a_h[it]) * a.Ws + a_w[it]) * a.Cs + kc * 8) * 2u;
-    } else {
-      a_h[it] = -(1 << 20); a_w[it] = 0; a_off[it] = 0;
-    }
-  }
   unsigned b_off[B_IT];
+  auto set_tile = [&](int t) __attribute__((always_inline)) {
+    int mt, nt;
+    dNt.divmod(t, &mt, &nt);
 #pragma unroll
-  for (int it = 0; it < B_IT; ++it) {
-    const int row = r0 + it * RPP, ch = nt * BN + row;
-    b_off[it] = (row < BN && ch < a.Cd) ? (unsigned)(ch * a.T * a.Cs + kc * 8) * 2u : kOobOffset;
-  }
+    for (int it = 0; it < A_IT; ++it) {
+      const int m = mt * BM + r0 + it * RPP;
+      if (m < M && r0 + it * RPP < BM) {
+        int q, j, n, i;
+        dWm.divmod(m, &q, &j);
+        dHm.divmod(q, &n, &i);
+        a_h[it] = i * a.ss;
+        a_w[it] = j * a.ss;
+        a_off[it] = (unsigned)(((n * a.Hs + a_h[it]) * a.Ws + a_w[it]) * a.Cs + kc * 8) * 2u;
+      } else {
+        a_h[it] = -(1 << 20); a_w[it] = 0; a_off[it] = 0;
+      }
+    }
+#pragma unroll
+    for (int it = 0; it < B_IT; ++it) {
+      const int row = r0 + it * RPP, ch = nt * BN + row;
+      b_off[it] = (row < BN && ch < a.Cd) ? (unsigned)(ch * a.T * a.Cs + kc * 8) * 2u : kOobOffset;
+    }
+  };
+  set_tile(t_begin);
 
   f32x16_t acc[TM][TN];
 #pragma unroll
@@ -122,7 +149,8 @@ __global__ void __launch_bounds__(kThreads, OCC) igemm_kernel(IgemmArgs a) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int cchunks = (a.Cs + BK - 1) / BK;
-  const int nstage = ntap * cchunks;
+  const int nstage = ntap * cchunks;              // stages per tile
+  const int total = (t_end - t_begin) * nstage;   // stages of this workgroup
   // Two stages of global loads are kept in flight in registers (sets 0 and 1) while a third one
   // is consumed from LDS: a load issued at the top of iteration s is written to LDS at the end
   // of iteration s+1.
@@ -130,15 +158,16 @@ __global__ void __launch_bounds__(kThreads, OCC) igemm_kernel(IgemmArgs a) {
   using S0 = std::integral_constant<int, 0>;
   using S1 = std::integral_constant<int, 1>;
 
-  // Loads are issued in stage order, so the (tap, channel chunk) of the next stage is a running
-  // pair; a stage past the last one still issues its loads, all at the out-of-range offset (they
-  // return zeros without touching memory).  Unconditional loads and stores keep the main loop free
-  // of divergent joins, which lets the compiler wait for exactly the oldest loads in flight.
-  int ld_tap = 0, ld_chunk = 0;
-  auto load_stage = [&](auto SET) {
+  // Loads are issued in stage order, so (tile, tap, channel chunk) of the next stage is a running
+  // triple; a stage past the workgroup's last one still issues its loads, all at the out-of-range
+  // offset (they return zeros without touching memory).  Unconditional loads and stores keep the
+  // main loop free of divergent joins around memory operations, which lets the compiler wait for
+  // exactly the oldest loads in flight.
+  int ld_t = t_begin, ld_tap = 0, ld_chunk = 0;
+  auto load_stage = [&](auto SET) __attribute__((always_inline)) {
     constexpr int rs = decltype(SET)::value;
-    const bool live = ld_tap < ntap;
-    const int t = live ? tap0 + ld_tap : 0;
+    const bool live = ld_t < t_end;
+    const int t = ntap ? tap0 + ld_tap : 0;
     const int c0 = ld_chunk * BK;
     const int dh = a.tt.dh[t], dw = a.tt.dw[t], wi = a.tt.widx[t];
     const bool cok = live && c0 + kc * 8 < a.Cs;               // ragged last channel chunk
@@ -151,9 +180,15 @@ __global__ void __launch_bounds__(kThreads, OCC) igemm_kernel(IgemmArgs a) {
     const unsigned so = (unsigned)(wi * a.Cs + c0) * 2u;
 #pragma unroll
     for (int it = 0; it < B_IT; ++it) rb[rs][it] = buffer_load16(wt_rs, cok ? b_off[it] : kOobOffset, so);
-    if (++ld_chunk == cchunks) { ld_chunk = 0; ++ld_tap; }
+    if (++ld_chunk == cchunks) {
+      ld_chunk = 0;
+      if (++ld_tap == ntap) {
+        ld_tap = 0;
+        if (++ld_t < t_end) set_tile(ld_t);
+      }
+    }
   };
-  auto store_stage = [&](int buf, auto SET) {
+  auto store_stage = [&](int buf, auto SET) __attribute__((always_inline)) {
     constexpr int rs = decltype(SET)::value;
 #pragma unroll
     for (int it = 0; it < A_IT; ++it)
@@ -167,7 +202,7 @@ __global__ void __launch_bounds__(kThreads, OCC) igemm_kernel(IgemmArgs a) {
   // One stage of MFMAs: the operands of 16-element slice kk+1 are read from LDS between the MFMAs
   // of slice kk (two fragment sets; the scheduling directives pin the alternation, because left
   // alone the compiler reads just in time and exposes the LDS latency once per slice).
-  auto compute = [&](int cur) {
+  auto compute = [&](int cur) __attribute__((always_inline)) {
     const bf16_t* Ab = As + (cur * BM + wm * TM * 32 + (lane & 31)) * LDK + (lane >> 5) * 8;
     const bf16_t* Bb = Bs + (cur * BN + wn * TN * 32 + (lane & 31)) * LDK + (lane >> 5) * 8;
     constexpr int KK = BK / 16;
@@ -199,94 +234,104 @@ __global__ void __launch_bounds__(kThreads, OCC) igemm_kernel(IgemmArgs a) {
     }
   };
 
+  // Epilogue of tile t, wave-local.  Optional per-channel sum / sum of squares of the fp32
+  // accumulators over this wave's rows (rows beyond M hold zeros): one partial row per wave and
+  // pixel tile, reduced by a finalising kernel.  Then 8 rows x TN*32 columns at a time through the
+  // wave's LDS strip so that a lane stores 16 contiguous bytes.
+  auto epilogue = [&](int t) __attribute__((always_inline)) {
+    int mt, nt;
+    dNt.divmod(t, &mt, &nt);
+    if (a.stats) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float v = acc[i][j][r];
+            s1 += v;
+            s2 = fmaf(v, v, s2);
+          }
+        s1 += __shfl_xor(s1, 32, 64);
+        s2 += __shfl_xor(s2, 32, 64);
+        const int col = nt * BN + wn * TN * 32 + j * 32 + (lane & 31);
+        if (lane < 32 && col < a.Cd) {
+          const size_t prow = (size_t)mt * WM + wm, nrow = (size_t)a.mtiles * WM;
+          a.stats[((size_t)0 * a.Cd + col) * nrow + prow] = s1;
+          a.stats[((size_t)1 * a.Cd + col) * nrow + prow] = s2;
+        }
+      }
+    }
+    bf16_t* Cw = strips + wave * 8 * LDW;
+    constexpr int CH = TN * 4;               // 16-byte chunks per strip row
+    const int lrow = lane / CH, ch = lane % CH;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+#pragma unroll
+        for (int rho = 0; rho < 4; ++rho)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            Cw[((lane >> 5) * 4 + rho) * LDW + j * 32 + (lane & 31)] = f32_to_bf16_hw(acc[i][j][q * 4 + rho]);
+        if (lrow < 8) {
+          const int m = mt * BM + wm * TM * 32 + i * 32 + q * 8 + lrow;
+          const int co = nt * BN + wn * TN * 32 + ch * 8;
+          if (m < M && co < a.Cd) {
+            int qq, jj, n, ii;
+            dWm.divmod(m, &qq, &jj);
+            dHm.divmod(qq, &n, &ii);
+            bf16_t* dp = a.dst + (((size_t)n * a.Hd + (ii * a.os + oh)) * a.Wd + (jj * a.os + ow)) * a.Cd + co;
+            if (a.accumulate) {
+              float o[8], nw[8];
+              load8(dp, o);
+              load8(Cw + lrow * LDW + ch * 8, nw);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) o[e] += nw[e];
+              store8(dp, o);
+            } else {
+              *reinterpret_cast<uint4*>(dp) = *reinterpret_cast<const uint4*>(Cw + lrow * LDW + ch * 8);
+            }
+          }
+        }
+      }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  };
+
+  if (nstage == 0) {   // no tap at all: the tiles are zero (the accumulators are)
+    for (int t = t_begin; t < t_end; ++t) epilogue(t);
+    return;
+  }
+  int c_t = t_begin, c_stage = 0;   // tile and in-tile stage of the MFMAs
+  auto tile_end = [&]() __attribute__((always_inline)) {
+    if (++c_stage == nstage) {
+      epilogue(c_t);
+      c_stage = 0;
+      ++c_t;
+    }
+  };
   load_stage(S0{});
   load_stage(S1{});
   store_stage(0, S0{});
   __syncthreads();
-  for (int s = 0; s < nstage; s += 2) {
+  for (int s = 0; s < total; s += 2) {
     load_stage(S0{});       // stage s + 2
     compute(0);
     store_stage(1, S1{});   // stage s + 1 (zeros past the end, into the buffer nobody reads)
+    tile_end();
     __syncthreads();
-    if (s + 1 >= nstage) break;
+    if (s + 1 >= total) break;
     load_stage(S1{});       // stage s + 3
     compute(1);
     store_stage(0, S0{});   // stage s + 2
+    tile_end();
     __syncthreads();
-  }
-
-  // Optional per-channel sum / sum of squares of the fp32 accumulators over this tile's rows
-  // (rows beyond M hold zeros): one partial row per M-tile, reduced by a finalising kernel.
-  if (a.stats) {
-    float* sred = reinterpret_cast<float*>(smem_raw);  // [2][WM][BN]
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      float s1 = 0.f, s2 = 0.f;
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float v = acc[i][j][r];
-          s1 += v;
-          s2 = fmaf(v, v, s2);
-        }
-      s1 += __shfl_xor(s1, 32, 64);
-      s2 += __shfl_xor(s2, 32, 64);
-      if (lane < 32) {
-        const int col = wn * TN * 32 + j * 32 + lane;
-        sred[(0 * WM + wm) * BN + col] = s1;
-        sred[(1 * WM + wm) * BN + col] = s2;
-      }
-    }
-    __syncthreads();
-    for (int c = tid; c < BN; c += kThreads) {
-      float t1 = 0.f, t2 = 0.f;
-#pragma unroll
-      for (int w_ = 0; w_ < WM; ++w_) {
-        t1 += sred[(0 * WM + w_) * BN + c];
-        t2 += sred[(1 * WM + w_) * BN + c];
-      }
-      const int col = nt * BN + c;
-      if (col < a.Cd) {
-        a.stats[((size_t)0 * a.Cd + col) * a.mtiles + mt] = t1;
-        a.stats[((size_t)1 * a.Cd + col) * a.mtiles + mt] = t2;
-      }
-    }
-    __syncthreads();
-  }
-
-  // Epilogue: accumulators -> bf16 tile in LDS -> 16-byte coalesced rows to the destination.
-  bf16_t* Ct = reinterpret_cast<bf16_t*>(smem_raw);
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = wm * TM * 32 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        const int col = wn * TN * 32 + j * 32 + (lane & 31);
-        Ct[row * LDC + col] = f32_to_bf16_hw(acc[i][j][r]);
-      }
-  __syncthreads();
-  const int oh = a.tt.oh[cls], ow = a.tt.ow[cls];
-  for (int idx = tid; idx < BM * (BN / 8); idx += kThreads) {
-    const int row = idx / (BN / 8), ch = idx % (BN / 8);
-    const int m = mt * BM + row, co = nt * BN + ch * 8;
-    if (m >= M || co >= a.Cd) continue;
-    const int j = m % Wm, q = m / Wm;
-    const int i = q % Hm, n = q / Hm;
-    bf16_t* dp = a.dst + (((size_t)n * a.Hd + (i * a.os + oh)) * a.Wd + (j * a.os + ow)) * a.Cd + co;
-    uint4 v = *reinterpret_cast<const uint4*>(Ct + row * LDC + ch * 8);
-    if (a.accumulate) {
-      float o[8], nw[8];
-      load8(dp, o);
-      load8(Ct + row * LDC + ch * 8, nw);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) o[e] += nw[e];
-      store8(dp, o);
-    } else {
-      *reinterpret_cast<uint4*>(dp) = v;
-    }
   }
 }
 
@@ -495,9 +540,10 @@ IgemmPlan plan_igemm(long maxM, int Cd, int Cs) {
 
 template <int BM, int BN, int BK, int WM, int WN, int OCC>
 int launch_igemm(const IgemmArgs& a, long maxM, hipStream_t st) {
+  constexpr int TN = BN / WN / 32;
   constexpr size_t stage_bytes = (size_t)2 * (BM + BN) * (BK + 8) * sizeof(bf16_t);
-  constexpr size_t epi_bytes = (size_t)BM * (BN + 8) * sizeof(bf16_t);
-  constexpr size_t smem = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
+  constexpr size_t strip_bytes = (size_t)4 * 8 * (TN * 32 + 8) * sizeof(bf16_t);
+  constexpr size_t smem = stage_bytes + strip_bytes;
   static_assert(smem <= 160 * 1024, "LDS budget");
   static bool attr_done = false;
   auto kern = igemm_kernel<BM, BN, BK, WM, WN, OCC>;
@@ -511,10 +557,25 @@ int launch_igemm(const IgemmArgs& a, long maxM, hipStream_t st) {
   b.ntiles = (a.Cd + BN - 1) / BN;
   const long mtiles = (maxM + BM - 1) / BM;
   b.mtiles = (int)mtiles;
-  dim3 grid((unsigned)(mtiles * b.ntiles), a.tt.nclass);
+  b.dNt.init((unsigned)b.ntiles);
+  for (int c = 0; c < a.tt.nclass; ++c) {
+    b.tt.dW[c].init((unsigned)a.tt.Wm[c]);
+    b.tt.dH[c].init((unsigned)a.tt.Hm[c]);
+  }
+  // Tiles per workgroup: as many as still leave every CU its OCC workgroups (tune key 14 overrides).
+  const long tiles = mtiles * b.ntiles;
+  int tpb = 1;
+  for (int t = 8; t > 1; t >>= 1)
+    if ((tiles + t - 1) / t >= 256L * OCC) { tpb = t; break; }
+  if (g_cnnk_tune[14] > 0) tpb = g_cnnk_tune[14];
+  b.tpb = tpb;
+  dim3 grid((unsigned)((tiles + tpb - 1) / tpb), a.tt.nclass);
   hipLaunchKernelGGL(kern, grid, dim3(kThreads), smem, st, b);
   return launch_status();
 }
+
+// wavefront rows (WM) of the tile shape the dispatch below picks for a plan
+int igemm_wm(const IgemmPlan& p) { return p.bn == 64 && p.bm >= 128 ? 4 : 2; }
 
 int dispatch_igemm(const IgemmArgs& a, long maxM, const IgemmPlan& p, hipStream_t st) {
 #define CNNK_IGEMM_CASE(BM, BN, WM, WN, OCC)                                         \
@@ -563,8 +624,9 @@ bool conv_mfma_supported(const ConvGeom& g, int pass) {
 }
 
 size_t conv_mfma_ws(const ConvGeom& g, int pass, bool want_stats) {
-  if (pass == CNNK_PASS_FWD)   // statistics partials, sized for the finest granularity (32 rows per partial)
-    return want_stats ? align_up(((size_t)g.N * g.Ho * g.Wo + 31) / 32 * 2 * g.Cout * sizeof(float), 256) : 0;
+  if (pass == CNNK_PASS_FWD)   // statistics partials: one row per wavefront and pixel tile, at the finest 32 pixels
+                               // each; the last pixel tile is padded to whole wavefront rows (at most 8 of them)
+    return want_stats ? align_up((((size_t)g.N * g.Ho * g.Wo + 31) / 32 + 8) * 2 * g.Cout * sizeof(float), 256) : 0;
   if (pass == CNNK_PASS_DGRAD) return align_up((size_t)g.Cout * g.R * g.S * g.Cin * sizeof(bf16_t), 256);
   if (pass == CNNK_PASS_WGRAD) {
     if (conv_wgrad_patch_supported(g)) return conv_wgrad_patch_ws(g);
@@ -601,7 +663,7 @@ int conv_mfma_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y
   const IgemmPlan p = plan_igemm(M, a.Cd, a.Cs);
   int rc = dispatch_igemm(a, M, p, st);
   if (rc != CNNK_OK || !ch_sum) return rc;
-  return channel_sums_finalize(a.stats, (int)((M + p.bm - 1) / p.bm), g.Cout, ch_sum, ch_sumsq, st);
+  return channel_sums_finalize(a.stats, (int)((M + p.bm - 1) / p.bm) * igemm_wm(p), g.Cout, ch_sum, ch_sumsq, st);
 }
 
 int conv_transpose_weights_multi(TransposeTable& t, hipStream_t st) {

@@ -57,6 +57,22 @@ def test_thin_input_fma_kernels(K, shape):
         K.cnnk_tune(8, 0)
 
 
+@pytest.mark.parametrize("tpb", [2, 3, 8])
+@pytest.mark.parametrize("shape", [s for s in CONV_SHAPES if s[3] >= 8])
+def test_gathered_gemm_kernels_with_several_tiles_per_workgroup(K, shape, tpb):
+    """The gathered implicit-GEMM kernels walk several tiles per workgroup on large layers (the next
+    tile's loads are in flight during the current tile's epilogue); forced here on small shapes so
+    that tile borders, ragged last tiles and workgroups with fewer tiles than the others are hit.
+    The LDS-patch kernels are switched off so that every 3x3 shape takes this path too."""
+    K.cnnk_tune(14, tpb)
+    K.cnnk_tune(4, -1)
+    try:
+        test_conv_fwd_dgrad_wgrad(K, shape, "bf16")
+    finally:
+        K.cnnk_tune(14, 0)
+        K.cnnk_tune(4, 0)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("shape", CONV_SHAPES)
 def test_conv_fwd_dgrad_wgrad(K, shape, dtype):

@@ -68,7 +68,8 @@ def check_step(net, inp, runner, outs, tol):
     incoherent sums, so a fraction f of flipped decisions moves a gradient by about sqrt(f) of its
     norm whatever the implementation.  The oracle measures that floor itself: its walk with bf16
     stores against its pure walk.  Graded here: the loss within `tol`; every tensor no farther
-    from the pure float64 result than 1.5x the oracle's own bf16-storage walk is (plus `tol`).
+    from the pure float64 result than 1.5x (L2 norm; 2.5x for the max-norm) the oracle's own
+    bf16-storage walk is (plus `tol`).
     Element-wise bf16 parity of every layer on identical inputs is test_gpu_layers.py."""
     assert torch.equal(runner.labels.cpu(), torch.from_numpy(inp["labels"]))        # labels pass through
     for k in range(len(net.params)):
@@ -108,7 +109,9 @@ def check_step(net, inp, runner, outs, tol):
         assert e["loss"][0] <= tol, e["loss"]
         for kind in floor:
             assert e[kind][1] <= 1.5 * floor[kind][1] + tol, (kind, e[kind], floor[kind])
-            assert e[kind][0] <= 1.5 * floor[kind][0] + tol, (kind, e[kind], floor[kind])
+            # the max-norm is the single worst element of a chaotic quantity (one flipped decision
+            # late in a deep net moves it by its whole size): a wider band than for the L2 norm
+            assert e[kind][0] <= 2.5 * floor[kind][0] + tol, (kind, e[kind], floor[kind])
         safe = (top2[:, 1] - top2[:, 0]) > 4 * max(tol, e["probs"][0]) * top2[:, 1]
     assert np.array_equal(pred[safe], pure["pred"][safe])                            # argmax: bit exact
     print("argmax compared on %d of %d samples" % (int(safe.sum()), len(safe)))
