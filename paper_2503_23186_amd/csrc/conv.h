@@ -33,6 +33,11 @@ int conv_mfma_dgrad(const ConvGeom& g, const bf16_t* dy, const bf16_t* w, bf16_t
                     void* ws, hipStream_t st);
 int conv_mfma_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws,
                     hipStream_t st);
+// The same without the final reduction: *part points at *P partial gradients (each Cout*R*S*Cin
+// floats; dw itself with *P = 1 when the reduction was not split), for a caller that reduces them
+// in its own way.
+int conv_mfma_wgrad_partials(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws,
+                             const float** part, int* P, hipStream_t st);
 
 // data gradient with weights already transposed to [Cin][R*S][Cout], and the batched transposition
 constexpr int kMaxTranspose = 32;

@@ -727,9 +727,13 @@ int conv_mfma_dgrad_pt(const ConvGeom& g, const bf16_t* dy, const bf16_t* wt, bf
   return dispatch_igemm(a, maxM, plan_igemm(maxM, a.Cd, a.Cs), st);
 }
 
-int conv_mfma_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws,
-                    hipStream_t st) {
-  if (conv_wgrad_patch_supported(g)) return conv_wgrad_patch(g, x, dy, dw, ws, st);
+int conv_mfma_wgrad_partials(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws,
+                             const float** part, int* P, hipStream_t st) {
+  if (conv_wgrad_patch_supported(g)) {
+    *part = dw;
+    *P = 1;
+    return conv_wgrad_patch(g, x, dy, dw, ws, st);
+  }
   int bmk, chunk, splits;
   wgrad_plan(g, &bmk, &chunk, &splits, t_cnnk_wgrad_cus);
   WgradArgs a{};
@@ -743,7 +747,16 @@ int conv_mfma_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float*
   dim3 grid(ktiles * a.qtiles, splits);
   if (bmk == 128) hipLaunchKernelGGL((wgrad_kernel<128, 128, 2, 2>), grid, dim3(kThreads), 0, st, a);
   else hipLaunchKernelGGL((wgrad_kernel<64, 128, 1, 4>), grid, dim3(kThreads), 0, st, a);
-  if (launch_status() != CNNK_OK) return CNNK_ERR_HIP;
-  if (splits > 1) return reduce_partials(a.part, dw, g.Cout * a.Q, splits, st);
-  return CNNK_OK;
+  *part = a.part;
+  *P = splits;
+  return launch_status();
+}
+
+int conv_mfma_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws,
+                    hipStream_t st) {
+  const float* part = nullptr;
+  int P = 0;
+  const int rc = conv_mfma_wgrad_partials(g, x, dy, dw, ws, &part, &P, st);
+  if (rc != CNNK_OK || P <= 1) return rc;
+  return reduce_partials(part, dw, g.Cout * g.R * g.S * g.Cin, P, st);
 }

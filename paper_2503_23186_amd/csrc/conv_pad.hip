@@ -7,10 +7,16 @@
 
 namespace {
 
-// dst[m][0..8) = src[m][0..C) followed by zeros
-__global__ void __launch_bounds__(256) pad_channels_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst,
-                                                           size_t rows, int C) {
-  for (size_t m = (size_t)blockIdx.x * 256 + threadIdx.x; m < rows; m += (size_t)gridDim.x * 256) {
+// dst[m][0..8) = src[m][0..C) followed by zeros, for two tensors in one launch (the rows of the
+// second one follow the rows of the first in the thread index; rows1 may be 0)
+__global__ void __launch_bounds__(256) pad_channels_kernel(const bf16_t* __restrict__ src0, bf16_t* __restrict__ dst0,
+                                                           size_t rows0, const bf16_t* __restrict__ src1,
+                                                           bf16_t* __restrict__ dst1, size_t rows1, int C) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < rows0 + rows1; i += (size_t)gridDim.x * 256) {
+    const bool first = i < rows0;
+    const bf16_t* src = first ? src0 : src1;
+    bf16_t* dst = first ? dst0 : dst1;
+    const size_t m = first ? i : i - rows0;
     unsigned short v[8];
 #pragma unroll
     for (int c = 0; c < 8; ++c) v[c] = c < C ? src[m * C + c] : (unsigned short)0;
@@ -20,12 +26,29 @@ __global__ void __launch_bounds__(256) pad_channels_kernel(const bf16_t* __restr
   }
 }
 
-// dw[row][0..C) = dw8[row][0..C)
-__global__ void __launch_bounds__(256) unpad_dw_kernel(const float* __restrict__ dw8, float* __restrict__ dw, int rows,
-                                                       int C) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= rows * C) return;
-  dw[i] = dw8[(size_t)(i / C) * 8 + i % C];
+// dw[row][0..C) = sum over P partials of part[p][row][0..C) (rows of 8 padded channels; P = 1: a
+// plain copy out of the padded layout).  16 thread groups share the partials of an element, their
+// sums are added in group order (deterministic).
+__global__ void __launch_bounds__(256) reduce_unpad_kernel(const float* __restrict__ part, float* __restrict__ dw,
+                                                           int rows, int C, int P) {
+  __shared__ float red[16][16];
+  const int e = threadIdx.x & 15, grp = threadIdx.x >> 4;
+  const int i = blockIdx.x * 16 + e;            // output element
+  const size_t n8 = (size_t)rows * 8;
+  float a = 0.f;
+  if (i < rows * C) {
+    const size_t src = (size_t)(i / C) * 8 + i % C;
+#pragma unroll 4
+    for (int p = grp; p < P; p += 16) a += part[(size_t)p * n8 + src];
+  }
+  red[grp][e] = a;
+  __syncthreads();
+  if (grp == 0 && i < rows * C) {
+    float sum = red[0][e];
+#pragma unroll
+    for (int k = 1; k < 16; ++k) sum += red[k][e];
+    dw[i] = sum;
+  }
 }
 
 ConvGeom padded(const ConvGeom& g) {
@@ -63,8 +86,7 @@ int conv_pad_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y,
   bf16_t* w8 = reinterpret_cast<bf16_t*>(base + x8_bytes(g));
   void* rest = base + x8_bytes(g) + w8_bytes(g);
   const size_t px = (size_t)g.N * g.H * g.W, wr = (size_t)g.Cout * g.R * g.S;
-  pad_channels_kernel<<<pad_blocks(px), 256, 0, st>>>(x, x8, px, g.Cin);
-  pad_channels_kernel<<<pad_blocks(wr), 256, 0, st>>>(w, w8, wr, g.Cin);
+  pad_channels_kernel<<<pad_blocks(px + wr), 256, 0, st>>>(x, x8, px, w, w8, wr, g.Cin);
   if (launch_status() != CNNK_OK) return CNNK_ERR_HIP;
   return conv_mfma_fwd(padded(g), x8, w8, y, ch_sum, ch_sumsq, rest, st);
 }
@@ -75,11 +97,14 @@ int conv_pad_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* 
   float* dw8 = reinterpret_cast<float*>(base + x8_bytes(g));
   void* rest = base + x8_bytes(g) + dw8_bytes(g);
   const size_t px = (size_t)g.N * g.H * g.W;
-  pad_channels_kernel<<<pad_blocks(px), 256, 0, st>>>(x, x8, px, g.Cin);
+  pad_channels_kernel<<<pad_blocks(px), 256, 0, st>>>(x, x8, px, nullptr, nullptr, 0, g.Cin);
   if (launch_status() != CNNK_OK) return CNNK_ERR_HIP;
-  int rc = conv_mfma_wgrad(padded(g), x8, dy, dw8, rest, st);
+  // the padded problem's partial gradients, summed straight into the unpadded layout
+  const float* part = nullptr;
+  int P = 0;
+  int rc = conv_mfma_wgrad_partials(padded(g), x8, dy, dw8, rest, &part, &P, st);
   if (rc != CNNK_OK) return rc;
   const int rows = g.Cout * g.R * g.S;
-  unpad_dw_kernel<<<(rows * g.Cin + 255) / 256, 256, 0, st>>>(dw8, dw, rows, g.Cin);
+  reduce_unpad_kernel<<<(rows * g.Cin + 15) / 16, 256, 0, st>>>(part, dw, rows, g.Cin, P);
   return launch_status();
 }

@@ -244,6 +244,30 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
   float* const aux_stat = reinterpret_cast<float*>(aux_ws);              // sums hand-off of a side branch
   void* const aux_scratch = static_cast<char*>(aux_ws) + 2 * 2048 * sizeof(float);
   const size_t aux_scratch_b = aux ? aux_wsb - 2 * 2048 * sizeof(float) : 0;
+  // All weight transpositions of the data-gradient kernels in one launch (per 32 layers).  With a
+  // second stream they run there beside the classifier head, whose few small launches leave the
+  // device almost idle (tune key 12 = -1 keeps them on the main stream).
+  auto transpose_all = [&](hipStream_t s_) -> int {
+    TransposeTable t;
+    t.count = 0;
+    int r = CNNK_OK;
+    for (int i = 0; i < n; ++i) {
+      if (w.wt_off[i] == (size_t)-1) continue;
+      const cnnk_conv_desc& d = L[i].d.conv;
+      const int k = t.count++;
+      t.src[k] = static_cast<const bf16_t*>(B->param_lp[L[i].p0]);
+      t.dst[k] = reinterpret_cast<bf16_t*>(wt_region + w.wt_off[i]);
+      t.Cout[k] = d.Cout; t.T[k] = d.R * d.S; t.Cin[k] = d.Cin;
+      if (t.count == kMaxTranspose) {
+        r = conv_transpose_weights_multi(t, s_);
+        if (r != CNNK_OK) return r;
+        t.count = 0;
+      }
+    }
+    if (t.count > 0) r = conv_transpose_weights_multi(t, s_);
+    return r;
+  };
+  bool wt_forked = false;
   // ---- forward pass and loss ---------------------------------------------------------------
   for (int i = 0; i < n; ++i) {
     const cnnk_layer& l = L[i];
@@ -308,6 +332,15 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
         rc = cnnk_add(w.slot_elems[l.out], w.dtype, B->act[l.in0], B->act[l.in1], B->act[l.out], stream);
         break;
       case CNNK_OP_FC_LOSS:
+        if (aux && g_cnnk_tune[12] >= 0) {
+          if (hipEventRecord((hipEvent_t)B->ev_fork, (hipStream_t)stream) != hipSuccess ||
+              hipStreamWaitEvent(aux, (hipEvent_t)B->ev_fork, 0) != hipSuccess)
+            return CNNK_ERR_HIP;
+          rc = transpose_all(aux);
+          if (rc != CNNK_OK) return rc;
+          if (hipEventRecord((hipEvent_t)B->ev_join, aux) != hipSuccess) return CNNK_ERR_HIP;
+          wt_forked = true;
+        }
         rc = cnnk_fc_softmax_xent(&l.d.fc, B->act[l.in0], B->param[l.p0], B->param[l.p1], labels, loss, pred,
                                   B->probs, B->dact[l.in0], B->grad[l.p0], B->grad[l.p1], ws, wsb, stream);
         break;
@@ -316,25 +349,11 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
     if (rc != CNNK_OK) return rc;
   }
   // ---- backward pass ---------------------------------------------------------------------------
-  // all weight transpositions of the data-gradient kernels in one launch (per 32 layers)
-  {
-    TransposeTable t;
-    t.count = 0;
-    for (int i = 0; i < n; ++i) {
-      if (w.wt_off[i] == (size_t)-1) continue;
-      const cnnk_conv_desc& d = L[i].d.conv;
-      const int k = t.count++;
-      t.src[k] = static_cast<const bf16_t*>(B->param_lp[L[i].p0]);
-      t.dst[k] = reinterpret_cast<bf16_t*>(wt_region + w.wt_off[i]);
-      t.Cout[k] = d.Cout; t.T[k] = d.R * d.S; t.Cin[k] = d.Cin;
-      if (t.count == kMaxTranspose) {
-        rc = conv_transpose_weights_multi(t, (hipStream_t)stream);
-        if (rc != CNNK_OK) return rc;
-        t.count = 0;
-      }
-    }
-    if (t.count > 0) rc = conv_transpose_weights_multi(t, (hipStream_t)stream);
+  if (!wt_forked) {
+    rc = transpose_all((hipStream_t)stream);
     if (rc != CNNK_OK) return rc;
+  } else if (hipStreamWaitEvent((hipStream_t)stream, (hipEvent_t)B->ev_join, 0) != hipSuccess) {
+    return CNNK_ERR_HIP;
   }
   std::vector<char> written(w.slot_elems.size(), 0);
   std::vector<char> updated(w.param_elems.size(), 0);   // parameters already updated on the second stream
@@ -435,11 +454,9 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
     if (rc != CNNK_OK) return rc;
   }
   // ---- parameter update -----------------------------------------------------------------------
-  if (aux) {
-    if (hipEventRecord((hipEvent_t)B->ev_join, aux) != hipSuccess ||
-        hipStreamWaitEvent((hipStream_t)stream, (hipEvent_t)B->ev_join, 0) != hipSuccess)
-      return CNNK_ERR_HIP;
-  }
+  // With a second stream the parameters that are left (batch-norm and classifier parameters: their
+  // gradients were computed on this stream) are updated first; the wait for the tail of the other
+  // stream (the first layer's weight gradient and update) comes last, so the two overlap.
   const int g_upd = cnnk_train_step_event_groups(n) - 1;
   timer.begin(g_upd);
   SgdTable t;
@@ -460,6 +477,11 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
   }
   if (t.count > 0) rc = sgd_multi(t, lr, momentum, weight_decay, (hipStream_t)stream);
   timer.end(g_upd);
+  if (aux && rc == CNNK_OK) {
+    if (hipEventRecord((hipEvent_t)B->ev_join, aux) != hipSuccess ||
+        hipStreamWaitEvent((hipStream_t)stream, (hipEvent_t)B->ev_join, 0) != hipSuccess)
+      return CNNK_ERR_HIP;
+  }
   return rc;
 }
 
