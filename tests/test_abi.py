@@ -120,3 +120,34 @@ def test_train_step_checks_the_workspace_before_any_launch(cnnk):
     with pytest.raises(cnnk.CnnkError) as e:
         cnnk.cnnk_train_step(layers, nl, b, fake, 0.1, 0.9, 0.0, fake, fake)
     assert e.value.status == 4
+
+
+def test_epoch_loop_entry_points_reject_bad_arguments_on_the_host(cnnk):
+    """cnnk_bn_relu_infer, cnnk_count_correct and cnnk_eval_step validate before they launch."""
+    import workloads as WL
+    from paper_2503_23186_amd.runner import build_c_layers
+    d = cnnk.bn_desc(2, 4, 4, 16, cnnk.F32, 1, 1e-5, 0.1)
+    with pytest.raises(cnnk.CnnkError) as e:
+        cnnk.cnnk_bn_relu_infer(d, 256, None, 256, 256, 256, None, 256)       # no running variance
+    assert e.value.status == 1
+    odd = cnnk.bn_desc(2, 4, 4, 12, cnnk.F32, 1, 1e-5, 0.1)                    # channels not in octets
+    with pytest.raises(cnnk.CnnkError) as e:
+        cnnk.cnnk_bn_relu_infer(odd, 256, None, 256, 256, 256, 256, 256)
+    assert e.value.status == 3
+    with pytest.raises(cnnk.CnnkError) as e:
+        cnnk.cnnk_count_correct(0, 256, 256, 256)
+    assert e.value.status == 2
+    with pytest.raises(cnnk.CnnkError) as e:
+        cnnk.cnnk_count_correct(8, 256, None, 256)
+    assert e.value.status == 1
+    net = WL.mini_resnet()
+    layers = build_c_layers(net.layers, cnnk.F32)
+    b = cnnk.Buffers()
+    with pytest.raises(cnnk.CnnkError) as e:                                   # no buffers at all
+        cnnk.cnnk_eval_step(layers, len(net.layers), b, 256, 256, 256, None, 0)
+    assert e.value.status == 1
+    # forward-only classifier head: the three gradient outputs come together or not at all
+    fd = cnnk.fc_desc(4, 16, 10, cnnk.F32)
+    with pytest.raises(cnnk.CnnkError) as e:
+        cnnk.cnnk_fc_softmax_xent(fd, 256, 256, 256, 256, 256, 256, None, 256, None, 256, 256, 1 << 20)
+    assert e.value.status == 1
