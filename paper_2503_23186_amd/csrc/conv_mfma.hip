@@ -428,29 +428,34 @@ __global__ void __launch_bounds__(kThreads) wgrad_kernel(WgradArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+  // Every thread issues the same eight loads every stage; rows that do not exist (past the split's
+  // range, padding, a thread without a staging role) use the out-of-range buffer offset, which
+  // returns zeros without touching memory.  Straight-line loads let the compiler wait for exactly
+  // the loads it needs instead of draining the queue at every divergent join.
+  const __amdgpu_buffer_rsrc_t dy_rs = make_rsrc(a.dy, (unsigned)a.M * a.Cout * 2u);
+  const __amdgpu_buffer_rsrc_t x_rs = make_rsrc(a.x, (unsigned)a.N * a.H * a.W * a.Cin * 2u);
   uint4 rg[8];
-  auto load_stage = [&](int s) {
+  auto load_stage = [&](int s) __attribute__((always_inline)) {
     const int m0 = m_begin + s * BKP + po * 8;
-#pragma unroll
-    for (int p = 0; p < 8; ++p) rg[p] = make_uint4(0, 0, 0, 0);
-    if (!chan_ok) return;
     if (isA) {
 #pragma unroll
-      for (int p = 0; p < 8; ++p)
-        if (m0 + p < m_end) rg[p] = *reinterpret_cast<const uint4*>(a.dy + (size_t)(m0 + p) * a.Cout + ch0);
-    } else if (isB) {
+      for (int p = 0; p < 8; ++p) {
+        const bool ok = chan_ok && m0 + p < m_end;
+        rg[p] = buffer_load16(dy_rs, ok ? (unsigned)((m0 + p) * a.Cout + ch0) * 2u : kOobOffset, 0);
+      }
+    } else {
       int wo = m0 % a.Wo, q = m0 / a.Wo;
       int ho = q % a.Ho, n = q / a.Ho;
 #pragma unroll
       for (int p = 0; p < 8; ++p) {
         const int hi = ho * a.stride + fr - a.pad, wi = wo * a.stride + fs - a.pad;
-        if (m0 + p < m_end && (unsigned)hi < (unsigned)a.H && (unsigned)wi < (unsigned)a.W)
-          rg[p] = *reinterpret_cast<const uint4*>(a.x + (((size_t)n * a.H + hi) * a.W + wi) * a.Cin + ch0);
+        const bool ok = isB && chan_ok && m0 + p < m_end && (unsigned)hi < (unsigned)a.H && (unsigned)wi < (unsigned)a.W;
+        rg[p] = buffer_load16(x_rs, ok ? (unsigned)(((n * a.H + hi) * a.W + wi) * a.Cin + ch0) * 2u : kOobOffset, 0);
         if (++wo == a.Wo) { wo = 0; if (++ho == a.Ho) { ho = 0; ++n; } }
       }
     }
   };
-  auto store_stage = [&](int buf) {
+  auto store_stage = [&](int buf) __attribute__((always_inline)) {
     if (!(isA || isB)) return;
     bf16_t* T_ = isA ? At[buf] : Bt[buf];
     const unsigned* rw = reinterpret_cast<const unsigned*>(rg);
@@ -470,36 +475,53 @@ __global__ void __launch_bounds__(kThreads) wgrad_kernel(WgradArgs a) {
       *reinterpret_cast<uint4*>(T_ + rh * BKP + ((po ^ swz(rh)) << 3)) = hi;
     }
   };
-
-  if (nstage > 0) {
-    load_stage(0);
-    store_stage(0);
-  }
-  __syncthreads();
-  for (int s = 0; s < nstage; ++s) {
-    const int cur = s & 1;
-    if (s + 1 < nstage) load_stage(s + 1);
-#pragma unroll
-    for (int kk = 0; kk < BKP / 16; ++kk) {
-      bf16x8_t af[TM], bfr[TN];
+  // One stage of MFMAs: the operands of 16-position slice kk+1 are read from LDS between the MFMAs
+  // of slice kk (two fragment sets, alternation pinned by the scheduling directives).
+  auto compute = [&](int cur) __attribute__((always_inline)) {
+    constexpr int KK = BKP / 16;
+    bf16x8_t af[2][TM], bfr[2][TN];
+    auto read_slice = [&](int kk, int set) {
       const int chunk = kk * 2 + (lane >> 5);
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         const int row = wm * TM * 32 + i * 32 + (lane & 31);
-        af[i] = *reinterpret_cast<const bf16x8_t*>(At[cur] + row * BKP + ((chunk ^ swz(row)) << 3));
+        af[set][i] = *reinterpret_cast<const bf16x8_t*>(At[cur] + row * BKP + ((chunk ^ swz(row)) << 3));
       }
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const int row = wn * TN * 32 + j * 32 + (lane & 31);
-        bfr[j] = *reinterpret_cast<const bf16x8_t*>(Bt[cur] + row * BKP + ((chunk ^ swz(row)) << 3));
+        bfr[set][j] = *reinterpret_cast<const bf16x8_t*>(Bt[cur] + row * BKP + ((chunk ^ swz(row)) << 3));
       }
+    };
+    read_slice(0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      if (kk + 1 < KK) read_slice(kk + 1, (kk + 1) & 1);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+      if (kk + 1 < KK) {
+#pragma unroll
+        for (int q = 0; q < TM * TN; ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                    // one MFMA
+          if (q < TM + TN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
-    if (s + 1 < nstage) store_stage(cur ^ 1);
+  };
+
+  load_stage(0);
+  store_stage(0);
+  __syncthreads();
+  for (int s = 0; s < nstage; ++s) {
+    const int cur = s & 1;
+    load_stage(s + 1);        // past the last stage: zeros into the buffer nobody reads
+    compute(cur);
+    store_stage(cur ^ 1);
     __syncthreads();
   }
 
