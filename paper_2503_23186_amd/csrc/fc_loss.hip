@@ -6,17 +6,20 @@
 namespace {
 constexpr int kT = 256;
 constexpr int kMaxClasses = 4096;
+constexpr int kLT = 1024;   // threads of the logits kernel
 
-// One workgroup per sample: z = W x + b by wave-level dot products, then the softmax.
+// One workgroup per sample: z = W x + b by wave-level dot products, then the softmax.  The kernel
+// is latency-bound (a sample's 100 dot products), so the workgroup is wide: 16 wavefronts take 4
+// classes each per round.
 template <typename T>
-__global__ void __launch_bounds__(kT) logits_softmax_kernel(const T* __restrict__ x, const float* __restrict__ W,
+__global__ void __launch_bounds__(kLT) logits_softmax_kernel(const T* __restrict__ x, const float* __restrict__ W,
                                                             const float* __restrict__ b,
                                                             const int* __restrict__ labels, int N, int F, int K,
                                                             int vec, float* __restrict__ dz, float* __restrict__ loss_n,
                                                             int* __restrict__ pred, float* __restrict__ probs) {
   __shared__ float z[kMaxClasses];
-  __shared__ float red[kT / 64];
-  __shared__ int redi[kT / 64];
+  __shared__ float red[kLT / 64];
+  __shared__ int redi[kLT / 64];
   const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const T* xr = x + (size_t)n * F;
   if (vec) {
@@ -31,11 +34,11 @@ __global__ void __launch_bounds__(kT) logits_softmax_kernel(const T* __restrict_
 #pragma unroll
         for (int e = 0; e < 8; ++e) xv[c][e] = 0.f;
     }
-    for (int j0 = wave; j0 < K; j0 += 4 * (kT / 64)) {
+    for (int j0 = wave; j0 < K; j0 += 4 * (kLT / 64)) {
       float acc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int j = j0 + q * (kT / 64);
+        const int j = j0 + q * (kLT / 64);
         if (j < K) {
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
@@ -51,14 +54,14 @@ __global__ void __launch_bounds__(kT) logits_softmax_kernel(const T* __restrict_
       }
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int j = j0 + q * (kT / 64);
+        const int j = j0 + q * (kLT / 64);
         const float sq = wave_sum(acc[q]);
         if (lane == 0 && j < K) z[j] = sq + b[j];
       }
     }
   } else {
     // four classes per pass of a wave: independent dot products keep several loads in flight
-    for (int j0 = wave * 4; j0 < K; j0 += (kT / 64) * 4) {
+    for (int j0 = wave * 4; j0 < K; j0 += (kLT / 64) * 4) {
       float acc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 8
       for (int f = lane; f < F; f += 64) {
@@ -78,7 +81,7 @@ __global__ void __launch_bounds__(kT) logits_softmax_kernel(const T* __restrict_
   // max and its lowest index
   float mx = -INFINITY;
   int arg = 0x7fffffff;
-  for (int j = tid; j < K; j += kT)
+  for (int j = tid; j < K; j += kLT)
     if (z[j] > mx) { mx = z[j]; arg = j; }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
@@ -89,16 +92,16 @@ __global__ void __launch_bounds__(kT) logits_softmax_kernel(const T* __restrict_
   if (lane == 0) { red[wave] = mx; redi[wave] = arg; }
   __syncthreads();
   mx = red[0]; arg = redi[0];
-  for (int w = 1; w < kT / 64; ++w)
+  for (int w = 1; w < kLT / 64; ++w)
     if (red[w] > mx || (red[w] == mx && redi[w] < arg)) { mx = red[w]; arg = redi[w]; }
   __syncthreads();
   float se = 0.f;
-  for (int j = tid; j < K; j += kT) se += expf(z[j] - mx);
+  for (int j = tid; j < K; j += kLT) se += expf(z[j] - mx);
   se = wave_sum(se);
   if (lane == 0) red[wave] = se;
   __syncthreads();
   se = 0.f;
-  for (int w = 0; w < kT / 64; ++w) se += red[w];
+  for (int w = 0; w < kLT / 64; ++w) se += red[w];
   const float lse = mx + logf(se);
   const int lab = labels[n];
   if (tid == 0) {
@@ -106,7 +109,7 @@ __global__ void __launch_bounds__(kT) logits_softmax_kernel(const T* __restrict_
     loss_n[n] = (lab >= 0 && lab < K) ? lse - z[lab] : lse;
   }
   const float invN = 1.f / (float)N;
-  for (int j = tid; j < K; j += kT) {
+  for (int j = tid; j < K; j += kLT) {
     const float p = expf(z[j] - lse);
     if (probs) probs[(size_t)n * K + j] = p;
     dz[(size_t)n * K + j] = (p - (j == lab ? 1.f : 0.f)) * invN;
@@ -282,14 +285,14 @@ extern "C" int cnnk_fc_softmax_xent(const cnnk_fc_desc* d, const void* x, const 
   const unsigned nblk = (unsigned)(K + 1 + fblocks * N);
   const int vec = (F % 8 == 0 && F <= 2048) ? 1 : 0;
   if (d->dtype == CNNK_BF16) {
-    logits_softmax_kernel<bf16_t><<<N, kT, 0, st>>>((const bf16_t*)x, W, b, labels, N, F, K, vec, dz, loss_n, pred, probs);
+    logits_softmax_kernel<bf16_t><<<N, kLT, 0, st>>>((const bf16_t*)x, W, b, labels, N, F, K, vec, dz, loss_n, pred, probs);
     if (!backward) loss_kernel<<<1, kT, 0, st>>>(loss_n, N, loss);
     else if (F % 8 == 0)
       fc_bwd_kernel<bf16_t, 1><<<nblk, kT, 0, st>>>(dz, loss_n, (const bf16_t*)x, W, N, F, K, fblocks, loss, dW, db, (bf16_t*)dx);
     else
       fc_bwd_kernel<bf16_t, 0><<<nblk, kT, 0, st>>>(dz, loss_n, (const bf16_t*)x, W, N, F, K, fblocks, loss, dW, db, (bf16_t*)dx);
   } else {
-    logits_softmax_kernel<float><<<N, kT, 0, st>>>((const float*)x, W, b, labels, N, F, K, vec, dz, loss_n, pred, probs);
+    logits_softmax_kernel<float><<<N, kLT, 0, st>>>((const float*)x, W, b, labels, N, F, K, vec, dz, loss_n, pred, probs);
     if (!backward) loss_kernel<<<1, kT, 0, st>>>(loss_n, N, loss);
     else if (F % 8 == 0)
       fc_bwd_kernel<float, 1><<<nblk, kT, 0, st>>>(dz, loss_n, (const float*)x, W, N, F, K, fblocks, loss, dW, db, (float*)dx);
