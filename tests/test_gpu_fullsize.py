@@ -43,7 +43,18 @@ FULL_CONVS = [(256, 32, 32, 64, 64, 3, 1), (256, 16, 16, 128, 128, 3, 1), (256, 
               (256, 32, 32, 3, 64, 3, 1)]
 
 
-@pytest.mark.parametrize("shape", FULL_CONVS)
+# distinct shapes of the other configurations at their full batch: ResNet-50 b256 (1x1 bottleneck
+# GEMMs incl. K = 64 single-stage tiles and the widest layers, a strided 3x3, a strided projection),
+# WRN-28-10 b128 (160/320/640 channels: ragged 64-channel tiles; 16-channel and 3-channel inputs),
+# VGG b128 (a 3x3 stride-1 layer that changes the channel count)
+OTHER_FULL_CONVS = [(256, 32, 32, 64, 256, 1, 1), (256, 32, 32, 256, 64, 1, 1), (256, 32, 32, 128, 128, 3, 2),
+                    (256, 8, 8, 256, 1024, 1, 1), (256, 4, 4, 2048, 512, 1, 1), (256, 8, 8, 1024, 2048, 1, 2),
+                    (128, 32, 32, 160, 160, 3, 1), (128, 16, 16, 320, 320, 3, 1), (128, 8, 8, 640, 640, 3, 1),
+                    (128, 32, 32, 160, 320, 3, 2), (128, 32, 32, 16, 160, 3, 1), (128, 32, 32, 3, 16, 3, 1),
+                    (128, 16, 16, 64, 128, 3, 1)]
+
+
+@pytest.mark.parametrize("shape", FULL_CONVS + OTHER_FULL_CONVS)
 def test_conv_full_size_sampled(K, shape):
     N, H, W, Cin, Cout, R, st = shape
     pad = R // 2
@@ -109,10 +120,13 @@ def test_conv_full_size_sampled(K, shape):
     assert max_rel_err(np.array(got), np.array(want)) <= 1e-4 * 20   # fp32 sums over 2.6e5 bf16 products
 
 
-def test_bn_full_size(K):
+@pytest.mark.parametrize("shape", [(256, 32, 32, 64), (256, 8, 8, 1024), (256, 4, 4, 2048), (128, 32, 32, 160)])
+def test_bn_full_size(K, shape):
     """BN + ReLU forward (statistics from sums, as after a convolution) and backward (mask
-    recomputed from x) on the 64-channel 32x32 batch-256 tensor, whole tensor against the oracle."""
-    N, H, W, C = 256, 32, 32, 64
+    recomputed from x), whole tensor against the oracle: the 64-channel 32x32 batch-256 tensor of
+    the benchmark, the widest ResNet-50 tensors (few, long-lived reducing workgroups) and a
+    WRN tensor whose channel count does not divide the workgroup."""
+    N, H, W, C = shape
     rng = np.random.default_rng(5)
     x = rep(0.3 + 1.1 * rng.standard_normal((N, H, W, C)), "bf16")
     gamma = (1 + 0.1 * rng.standard_normal(C)).astype(np.float32).astype(np.float64)
