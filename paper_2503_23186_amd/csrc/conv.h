@@ -80,6 +80,22 @@ int conv_stem_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float*
 // ch_sum[c] = sum_b part[b][0][c], ch_sumsq[c] = sum_b part[b][1][c]  (double accumulation)
 int channel_sums_finalize(const float* part, int nb, int C, float* ch_sum, float* ch_sumsq, hipStream_t st);
 
+// When set (per host thread), the next split-K reduction of a weight gradient also applies the
+// SGD-momentum update of that parameter in the same launch (out = sum of partials is still
+// written as the gradient): g' = g + wd*w; v <- mu*v + g'; w <- w - lr*v; optional bf16 copy.
+// wait (nullable): an event the stream waits for between the weight-gradient kernel and the
+// reduction (the last reader of the old weights).  done is set when the fused launch was made;
+// callers fall back to a separate update otherwise (unsplit reductions, other reducers).
+struct SgdFuse {
+  float* w;
+  float* v;
+  void* wlp;
+  float lr, mu, wd;
+  hipEvent_t wait;
+  bool done;
+};
+extern thread_local SgdFuse* t_cnnk_sgd_fuse;
+
 extern int g_cnnk_tune[16];
 // Compute units the weight-gradient kernels size their grids for (256 = the whole device).  The
 // training step lowers it for the weight gradients it runs on its second stream, beside the rest

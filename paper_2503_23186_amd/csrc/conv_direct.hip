@@ -99,9 +99,22 @@ __global__ void __launch_bounds__(256) direct_wgrad_kernel(ConvGeom g, const T* 
 // out[i] = sum_p part[p][i], deterministic.  GROUPS thread groups share the P partials of a float4 column (group g takes p = g, g+GROUPS, ...);
 // their sums are combined through LDS in group order.  More groups = more, shorter-lived threads:
 // 16 for many partials (a 64x576 gradient split 108 ways is 16 MB to read), 4 otherwise.
-template <int GROUPS>
+struct SgdArgs {
+  float* w;
+  float* v;
+  bf16_t* wlp;
+  float lr, mu, wd;
+};
+
+__device__ __forceinline__ float sgd_apply(float wi, float vi, float gi, const SgdArgs& sg, float* vn) {
+  const float gp = fmaf(sg.wd, wi, gi);
+  *vn = fmaf(sg.mu, vi, gp);
+  return fmaf(-sg.lr, *vn, wi);
+}
+
+template <int GROUPS, bool SGD>
 __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __restrict__ part,
-                                                              float* __restrict__ out, int n, int P) {
+                                                              float* __restrict__ out, int n, int P, SgdArgs sg) {
   constexpr int COLS = 256 / GROUPS;
   __shared__ float4 red[GROUPS][COLS];
   const int col = threadIdx.x % COLS, grp = threadIdx.x / COLS;
@@ -122,6 +135,24 @@ __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __res
 #pragma unroll
     for (int k = 1; k < GROUPS; ++k) { s.x += red[k][col].x; s.y += red[k][col].y; s.z += red[k][col].z; s.w += red[k][col].w; }
     *reinterpret_cast<float4*>(out + (size_t)i4 * 4) = s;
+    if (SGD) {   // the parameter update on the gradient just summed (same arithmetic as the SGD kernel)
+      const size_t i = (size_t)i4 * 4;
+      const float4 wv = *reinterpret_cast<const float4*>(sg.w + i);
+      const float4 vv = *reinterpret_cast<const float4*>(sg.v + i);
+      float4 vn, wn;
+      wn.x = sgd_apply(wv.x, vv.x, s.x, sg, &vn.x);
+      wn.y = sgd_apply(wv.y, vv.y, s.y, sg, &vn.y);
+      wn.z = sgd_apply(wv.z, vv.z, s.z, sg, &vn.z);
+      wn.w = sgd_apply(wv.w, vv.w, s.w, sg, &vn.w);
+      *reinterpret_cast<float4*>(sg.v + i) = vn;
+      *reinterpret_cast<float4*>(sg.w + i) = wn;
+      if (sg.wlp) {
+        uint2 pk;
+        pk.x = (unsigned)f32_to_bf16(wn.x) | ((unsigned)f32_to_bf16(wn.y) << 16);
+        pk.y = (unsigned)f32_to_bf16(wn.z) | ((unsigned)f32_to_bf16(wn.w) << 16);
+        *reinterpret_cast<uint2*>(sg.wlp + i) = pk;
+      }
+    }
   }
   // scalar tail (n not a multiple of 4)
   if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
@@ -129,6 +160,13 @@ __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __res
     float a = 0.f;
     for (int p = 0; p < P; ++p) a += part[(size_t)p * n + i];
     out[i] = a;
+    if (SGD) {
+      float vn;
+      const float wn = sgd_apply(sg.w[i], sg.v[i], a, sg, &vn);
+      sg.v[i] = vn;
+      sg.w[i] = wn;
+      if (sg.wlp) sg.wlp[i] = f32_to_bf16(wn);
+    }
   }
 }
 
@@ -190,8 +228,21 @@ int conv_direct_wgrad(const ConvGeom& g, int dtype, const void* x, const void* d
   return reduce_partials(part, dw, nw, P, st);
 }
 
+thread_local SgdFuse* t_cnnk_sgd_fuse = nullptr;
+
 int reduce_partials(const float* part, float* out, int n, int P, hipStream_t st) {
-  if (P >= 32) reduce_partials_kernel<16><<<(n / 4 + 15) / 16 + 1, 256, 0, st>>>(part, out, n, P);
-  else reduce_partials_kernel<4><<<(n / 4 + 63) / 64 + 1, 256, 0, st>>>(part, out, n, P);
+  const unsigned g16 = (unsigned)((n / 4 + 15) / 16 + 1), g4 = (unsigned)((n / 4 + 63) / 64 + 1);
+  SgdFuse* f = t_cnnk_sgd_fuse;
+  if (f && !f->done && ((((size_t)f->w | (size_t)f->v | (size_t)out) & 15) == 0) && (((size_t)f->wlp & 7) == 0)) {
+    if (f->wait && hipStreamWaitEvent(st, f->wait, 0) != hipSuccess) return CNNK_ERR_HIP;
+    const SgdArgs sg{f->w, f->v, static_cast<bf16_t*>(f->wlp), f->lr, f->mu, f->wd};
+    if (P >= 32) reduce_partials_kernel<16, true><<<g16, 256, 0, st>>>(part, out, n, P, sg);
+    else reduce_partials_kernel<4, true><<<g4, 256, 0, st>>>(part, out, n, P, sg);
+    f->done = true;
+    return launch_status();
+  }
+  const SgdArgs none{nullptr, nullptr, nullptr, 0.f, 0.f, 0.f};
+  if (P >= 32) reduce_partials_kernel<16, false><<<g16, 256, 0, st>>>(part, out, n, P, none);
+  else reduce_partials_kernel<4, false><<<g4, 256, 0, st>>>(part, out, n, P, none);
   return launch_status();
 }

@@ -373,36 +373,52 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
     timer.begin(g0);
     switch (l.op) {
       case CNNK_OP_CONV: {
-        if (aux) {
-          // dy and x are final here: fork the weight gradient onto the second stream
-          if (hipEventRecord((hipEvent_t)B->ev_fork, (hipStream_t)stream) != hipSuccess ||
-              hipStreamWaitEvent(aux, (hipEvent_t)B->ev_fork, 0) != hipSuccess)
-            return CNNK_ERR_HIP;
-          t_cnnk_wgrad_cus = kAuxWgradCus;
-          rc = cnnk_conv2d_wgrad(&l.d.conv, B->act[l.in0], B->dact[l.out], B->grad[l.p0], aux_ws, aux_wsb, aux);
-          t_cnnk_wgrad_cus = 256;
-        } else {
-          rc = cnnk_conv2d_wgrad(&l.d.conv, B->act[l.in0], B->dact[l.out], B->grad[l.p0], ws, wsb, stream);
-        }
-        timer.end(g0);
-        timer.begin(g0 + 1);
-        if (rc == CNNK_OK && l.in0 != 0) {
+        // data gradient of this layer (main stream); with a second stream it is enqueued first so
+        // that the event behind it exists when the weight gradient's reduction needs it
+        auto dgrad = [&]() -> int {
+          if (l.in0 == 0) return CNNK_OK;
+          int r;
           if (w.wt_off[i] != (size_t)-1) {
-            rc = conv_mfma_dgrad_pt(make_geom(&l.d.conv), static_cast<const bf16_t*>(B->dact[l.out]),
-                                    reinterpret_cast<const bf16_t*>(wt_region + w.wt_off[i]),
-                                    static_cast<bf16_t*>(B->dact[l.in0]), written[l.in0], (hipStream_t)stream);
+            r = conv_mfma_dgrad_pt(make_geom(&l.d.conv), static_cast<const bf16_t*>(B->dact[l.out]),
+                                   reinterpret_cast<const bf16_t*>(wt_region + w.wt_off[i]),
+                                   static_cast<bf16_t*>(B->dact[l.in0]), written[l.in0], (hipStream_t)stream);
           } else {
             const void* wt = bf16 ? B->param_lp[l.p0] : (const void*)B->param[l.p0];
-            rc = cnnk_conv2d_dgrad(&l.d.conv, B->dact[l.out], wt, B->dact[l.in0], written[l.in0], ws, wsb, stream);
+            r = cnnk_conv2d_dgrad(&l.d.conv, B->dact[l.out], wt, B->dact[l.in0], written[l.in0], ws, wsb, stream);
           }
           written[l.in0] = 1;
+          return r;
+        };
+        if (!aux) {
+          rc = cnnk_conv2d_wgrad(&l.d.conv, B->act[l.in0], B->dact[l.out], B->grad[l.p0], ws, wsb, stream);
+          timer.end(g0);
+          timer.begin(g0 + 1);
+          if (rc == CNNK_OK) rc = dgrad();
+          break;
         }
-        if (aux && rc == CNNK_OK) {
-          // The update of this layer's weights follows its weight gradient on the second stream,
-          // once the data gradient above (the last reader of the weights in this step) is done.
-          if (l.in0 != 0 && (hipEventRecord((hipEvent_t)B->ev_fork, (hipStream_t)stream) != hipSuccess ||
-                             hipStreamWaitEvent(aux, (hipEvent_t)B->ev_fork, 0) != hipSuccess))
-            return CNNK_ERR_HIP;
+        // dy and x are final here: fork the weight gradient onto the second stream
+        if (hipEventRecord((hipEvent_t)B->ev_fork, (hipStream_t)stream) != hipSuccess ||
+            hipStreamWaitEvent(aux, (hipEvent_t)B->ev_fork, 0) != hipSuccess)
+          return CNNK_ERR_HIP;
+        rc = dgrad();
+        if (rc != CNNK_OK) return rc;
+        // The update of this layer's weights follows its weight gradient on the second stream, once
+        // the data gradient (the last reader of the weights in this step) is done: the event is
+        // re-recorded behind it, and the split-K reduction of the weight gradient waits for it and
+        // applies the update in the same launch (a separate launch where nothing is reduced).
+        const bool after_dgrad = l.in0 != 0;
+        if (after_dgrad && hipEventRecord((hipEvent_t)B->ev_fork, (hipStream_t)stream) != hipSuccess)
+          return CNNK_ERR_HIP;
+        SgdFuse fuse{B->param[l.p0], B->mom[l.p0], (bf16 && B->param_lp) ? B->param_lp[l.p0] : nullptr,
+                     lr, momentum, weight_decay, after_dgrad ? (hipEvent_t)B->ev_fork : nullptr, false};
+        t_cnnk_sgd_fuse = &fuse;
+        t_cnnk_wgrad_cus = kAuxWgradCus;
+        rc = cnnk_conv2d_wgrad(&l.d.conv, B->act[l.in0], B->dact[l.out], B->grad[l.p0], aux_ws, aux_wsb, aux);
+        t_cnnk_wgrad_cus = 256;
+        t_cnnk_sgd_fuse = nullptr;
+        if (rc != CNNK_OK) return rc;
+        if (!fuse.done) {
+          if (after_dgrad && hipStreamWaitEvent(aux, (hipEvent_t)B->ev_fork, 0) != hipSuccess) return CNNK_ERR_HIP;
           SgdTable t1;
           t1.count = 1;
           t1.w[0] = B->param[l.p0];
@@ -411,8 +427,8 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
           t1.wlp[0] = (bf16 && B->param_lp) ? B->param_lp[l.p0] : nullptr;
           t1.n[0] = w.param_elems[l.p0];
           rc = sgd_multi(t1, lr, momentum, weight_decay, aux);
-          updated[l.p0] = 1;
         }
+        updated[l.p0] = 1;
         break;
       }
       case CNNK_OP_BN: {
