@@ -70,6 +70,16 @@ size_t conv_pad_ws(const ConvGeom& g, int pass, bool want_stats);
 int conv_pad_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y, float* ch_sum, float* ch_sumsq,
                  void* ws, hipStream_t st);
 int conv_pad_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws, hipStream_t st);
+// The forward and the weight-gradient call of such a layer both need the 8-channel copy of x.  When
+// set (per host thread), the forward call writes it to buf and sets valid, and a weight-gradient
+// call that finds valid set reads it there instead of padding x again (the caller vouches that x
+// and buf are unchanged in between).
+size_t conv_pad_x8_bytes(const ConvGeom& g);
+struct X8Cache {
+  bf16_t* buf;
+  bool valid;
+};
+extern thread_local X8Cache* t_cnnk_x8_cache;
 
 // thin-input (stem) kernels, bf16 storage
 bool conv_stem_supported(const ConvGeom& g);

@@ -68,6 +68,9 @@ size_t dw8_bytes(const ConvGeom& g) { return align_up((size_t)g.Cout * g.R * g.S
 
 }  // namespace
 
+thread_local X8Cache* t_cnnk_x8_cache = nullptr;
+size_t conv_pad_x8_bytes(const ConvGeom& g) { return x8_bytes(g); }
+
 bool conv_pad_supported(const ConvGeom& g) {
   return g.Cin < 8 && conv_mfma_supported(padded(g), CNNK_PASS_FWD);
 }
@@ -82,10 +85,12 @@ size_t conv_pad_ws(const ConvGeom& g, int pass, bool want_stats) {
 int conv_pad_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y, float* ch_sum, float* ch_sumsq,
                  void* ws, hipStream_t st) {
   char* base = static_cast<char*>(ws);
-  bf16_t* x8 = reinterpret_cast<bf16_t*>(base);
+  X8Cache* cache = t_cnnk_x8_cache;
+  bf16_t* x8 = cache ? cache->buf : reinterpret_cast<bf16_t*>(base);
   bf16_t* w8 = reinterpret_cast<bf16_t*>(base + x8_bytes(g));
   void* rest = base + x8_bytes(g) + w8_bytes(g);
   const size_t px = (size_t)g.N * g.H * g.W, wr = (size_t)g.Cout * g.R * g.S;
+  if (cache) cache->valid = true;
   pad_channels_kernel<<<pad_blocks(px + wr), 256, 0, st>>>(x, x8, px, w, w8, wr, g.Cin);
   if (launch_status() != CNNK_OK) return CNNK_ERR_HIP;
   return conv_mfma_fwd(padded(g), x8, w8, y, ch_sum, ch_sumsq, rest, st);
@@ -93,12 +98,15 @@ int conv_pad_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y,
 
 int conv_pad_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws, hipStream_t st) {
   char* base = static_cast<char*>(ws);
-  bf16_t* x8 = reinterpret_cast<bf16_t*>(base);
+  const X8Cache* cache = (t_cnnk_x8_cache && t_cnnk_x8_cache->valid) ? t_cnnk_x8_cache : nullptr;
+  bf16_t* x8 = cache ? cache->buf : reinterpret_cast<bf16_t*>(base);
   float* dw8 = reinterpret_cast<float*>(base + x8_bytes(g));
   void* rest = base + x8_bytes(g) + dw8_bytes(g);
   const size_t px = (size_t)g.N * g.H * g.W;
-  pad_channels_kernel<<<pad_blocks(px), 256, 0, st>>>(x, x8, px, nullptr, nullptr, 0, g.Cin);
-  if (launch_status() != CNNK_OK) return CNNK_ERR_HIP;
+  if (!cache) {
+    pad_channels_kernel<<<pad_blocks(px), 256, 0, st>>>(x, x8, px, nullptr, nullptr, 0, g.Cin);
+    if (launch_status() != CNNK_OK) return CNNK_ERR_HIP;
+  }
   // the padded problem's partial gradients, summed straight into the unpadded layout
   const float* part = nullptr;
   int P = 0;

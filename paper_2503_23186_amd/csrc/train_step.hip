@@ -21,6 +21,8 @@ struct Walk {
   size_t ws = 0;
   size_t wt_bytes = 0;               // transposed bf16 weights of every conv whose data gradient runs on MFMA
   std::vector<size_t> wt_off;        // per layer: offset into that region, or (size_t)-1
+  int x8_layer = -1;                 // first-layer convolution with fewer than 8 input channels, if any:
+  size_t x8_off = 0;                 // its 8-channel copy of the network input lives in the same region
   int dtype = -1;
 };
 
@@ -73,6 +75,11 @@ int walk_layers(const cnnk_layer* L, int n, int n_slots, int n_params, Walk* w) 
         if (dgrad_pretransposed(l)) {
           w->wt_off[i] = w->wt_bytes;
           w->wt_bytes += align_up((size_t)d.Cout * d.R * d.S * d.Cin * sizeof(bf16_t), 256);
+        }
+        if (w->x8_layer < 0 && l.in0 == 0 && d.dtype == CNNK_BF16 && conv_pad_supported(make_geom(&d))) {
+          w->x8_layer = i;
+          w->x8_off = w->wt_bytes;
+          w->wt_bytes += conv_pad_x8_bytes(make_geom(&d));
         }
         break;
       }
@@ -268,6 +275,7 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
     return r;
   };
   bool wt_forked = false;
+  bool x8_valid = false;   // the forward pass left the first layer's 8-channel input copy in place
   // ---- forward pass and loss ---------------------------------------------------------------
   for (int i = 0; i < n; ++i) {
     const cnnk_layer& l = L[i];
@@ -307,8 +315,13 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
             if (stat_slot[k] < 0) sb = k;
         }
         float* ssum = sb >= 0 ? stat_base + (size_t)sb * 4096 : nullptr;
+        // the 8-channel copy of the network input is kept for this layer's weight gradient
+        X8Cache x8c{reinterpret_cast<bf16_t*>(wt_region + w.x8_off), false};
+        if (i == w.x8_layer) t_cnnk_x8_cache = &x8c;
         rc = cnnk_conv2d_fwd(&l.d.conv, B->act[l.in0], wt, B->act[l.out], ssum, ssum ? ssum + 2048 : nullptr, ws, wsb,
                              stream);
+        t_cnnk_x8_cache = nullptr;
+        if (i == w.x8_layer) x8_valid = x8c.valid;
         if (sb >= 0) stat_slot[sb] = l.out;
         break;
       }
@@ -390,7 +403,10 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
           return r;
         };
         if (!aux) {
+          X8Cache x8c{reinterpret_cast<bf16_t*>(wt_region + w.x8_off), x8_valid};
+          if (i == w.x8_layer && x8_valid) t_cnnk_x8_cache = &x8c;
           rc = cnnk_conv2d_wgrad(&l.d.conv, B->act[l.in0], B->dact[l.out], B->grad[l.p0], ws, wsb, stream);
+          t_cnnk_x8_cache = nullptr;
           timer.end(g0);
           timer.begin(g0 + 1);
           if (rc == CNNK_OK) rc = dgrad();
@@ -413,7 +429,10 @@ extern "C" int cnnk_train_step(const cnnk_layer* L, int n, const cnnk_buffers* B
                      lr, momentum, weight_decay, after_dgrad ? (hipEvent_t)B->ev_fork : nullptr, false};
         t_cnnk_sgd_fuse = &fuse;
         t_cnnk_wgrad_cus = kAuxWgradCus;
+        X8Cache x8c{reinterpret_cast<bf16_t*>(wt_region + w.x8_off), x8_valid};
+        if (i == w.x8_layer && x8_valid) t_cnnk_x8_cache = &x8c;
         rc = cnnk_conv2d_wgrad(&l.d.conv, B->act[l.in0], B->dact[l.out], B->grad[l.p0], aux_ws, aux_wsb, aux);
+        t_cnnk_x8_cache = nullptr;
         t_cnnk_wgrad_cus = 256;
         t_cnnk_sgd_fuse = nullptr;
         if (rc != CNNK_OK) return rc;
