@@ -92,7 +92,18 @@ __global__ void __launch_bounds__(kT) gap_fwd_kernel(const T* __restrict__ x, T*
   float acc[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-  for (int p = 0; p < HW; ++p) {
+  // eight positions' loads in flight at a time; the additions keep the order p = 0, 1, 2, ...
+  int p = 0;
+  for (; p + 8 <= HW; p += 8) {
+    float v[8][8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) load8(x + (n * HW + p + k) * C + c8 * 8, v[k]);
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += v[k][e];
+  }
+  for (; p < HW; ++p) {
     float v[8];
     load8(x + (n * HW + p) * C + c8 * 8, v);
 #pragma unroll
