@@ -3,8 +3,11 @@
 
 A step is one pass of the whole hot path (forward, loss, backward, SGD-momentum update) over one
 batch of seeded synthetic CIFAR-100-shaped data, resident in HBM before the timed region starts.
-Workload: BASELINE configs[2], ResNet-18 adapted to 32x32 inputs, bf16 storage / fp32 accumulate,
-batch 256.  Prints ONE JSON line (see README for the fields).
+Workload: ResNet-18 adapted to 32x32 inputs, 100 classes, bf16 storage / fp32 accumulate, batch 256
+(--config picks another network).  Prints ONE JSON line: metric / value (images/s) / ms_per_step,
+`roofline` for the call class with the largest time per step (measured with HIP events recorded
+on the launch stream around every entry-point call), `cpu_baseline` (the fp64 oracle timed on a
+bounded sample on the host cores) and `validation_pass` (the inference-mode forward).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu-baseline]
 """
