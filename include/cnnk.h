@@ -61,7 +61,8 @@ const char* cnnk_version(void);
  * stride-1 LDS-patch kernels (4 = -1 switches them off); 6 = target number of workgroups of
  * the 3x3 stride-1 weight-gradient kernel (-1 switches it off); 7 = -1 switches off the pixel
  * permutation that keeps narrow images (W < 16) free of LDS bank conflicts; 8 = -1 keeps convolutions with
- * fewer than 8 input channels on the plain-FMA kernels; 9 = -1 makes cnnk_train_step hand y to
+ * fewer than 8 input channels on the plain-FMA kernels; 11 = -1 keeps the first layer's forward
+ * pass on the padded-input path; 9 = -1 makes cnnk_train_step hand y to
  * every batch-norm backward call (no mask recomputation); 12 = -1 keeps the weight transposes of
  * the data-gradient kernels on the main stream when cnnk_train_step has a second one; 14 = tiles that one workgroup of the
  * gathered implicit-GEMM kernels walks (0: as many as still fill every CU); 13 = pixel tiles that one workgroup of

@@ -81,6 +81,13 @@ struct X8Cache {
 };
 extern thread_local X8Cache* t_cnnk_x8_cache;
 
+// first layer (3 input channels, 3x3, stride 1, pad 1, at most 64 output channels): forward on MFMA
+// without operand staging
+bool conv_first_supported(const ConvGeom& g);
+size_t conv_first_ws(const ConvGeom& g);
+int conv_first_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y, float* ch_sum, float* ch_sumsq,
+                   void* ws, hipStream_t st);
+
 // thin-input (stem) kernels, bf16 storage
 bool conv_stem_supported(const ConvGeom& g);
 size_t conv_stem_wgrad_ws(const ConvGeom& g);

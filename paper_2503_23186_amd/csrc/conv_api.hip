@@ -25,6 +25,9 @@ static bool use_mfma(const cnnk_conv_desc* d, const ConvGeom& g, int pass) {
 static bool use_pad(const cnnk_conv_desc* d, const ConvGeom& g, int pass) {
   return d->dtype == CNNK_BF16 && pass != CNNK_PASS_DGRAD && g_cnnk_tune[8] >= 0 && conv_pad_supported(g);
 }
+static bool use_first(const cnnk_conv_desc* d, const ConvGeom& g) {   // forward only
+  return d->dtype == CNNK_BF16 && g_cnnk_tune[8] >= 0 && g_cnnk_tune[11] >= 0 && conv_first_supported(g);
+}
 static bool use_stem(const cnnk_conv_desc* d, const ConvGeom& g, int pass) {
   return d->dtype == CNNK_BF16 && !conv_mfma_supported(g, pass) && !use_pad(d, g, pass) && conv_stem_supported(g);
 }
@@ -38,6 +41,7 @@ extern "C" size_t cnnk_conv2d_workspace_bytes(const cnnk_conv_desc* d, int pass)
     b = (g.Cout % 8 == 0 && g.Cout <= 2048) ? channel_stats_ws((size_t)g.N * g.Ho * g.Wo, g.Cout) : 0;
     if (use_mfma(d, g, pass)) { const size_t m = conv_mfma_ws(g, pass, true); if (m > b) b = m; }
     if (use_pad(d, g, pass)) { const size_t m = conv_pad_ws(g, pass, true); if (m > b) b = m; }
+    if (use_first(d, g)) { const size_t m = conv_first_ws(g); if (m > b) b = m; }
   } else if (pass == CNNK_PASS_DGRAD) {
     b = use_mfma(d, g, pass) ? conv_mfma_ws(g, pass, false) : 0;
   } else if (pass == CNNK_PASS_WGRAD) {
@@ -62,6 +66,8 @@ extern "C" int cnnk_conv2d_fwd(const cnnk_conv_desc* d, const void* x, const voi
   hipStream_t st = (hipStream_t)stream;
   if (use_mfma(d, g, CNNK_PASS_FWD))
     return conv_mfma_fwd(g, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, ch_sum, ch_sumsq, ws, st);
+  if (use_first(d, g))
+    return conv_first_fwd(g, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, ch_sum, ch_sumsq, ws, st);
   if (use_pad(d, g, CNNK_PASS_FWD)) {
     if (!ws || ws_bytes < cnnk_conv2d_workspace_bytes(d, CNNK_PASS_FWD)) return CNNK_ERR_WORKSPACE;
     return conv_pad_fwd(g, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, ch_sum, ch_sumsq, ws, st);

@@ -275,6 +275,9 @@ __global__ void __launch_bounds__(kThreads, OCC) igemm_kernel(IgemmArgs a) {
 #pragma unroll
           for (int j = 0; j < TN; ++j)
             Cw[((lane >> 5) * 4 + rho) * LDW + j * 32 + (lane & 31)] = f32_to_bf16_hw(acc[i][j][q * 4 + rho]);
+        // the 16-byte reads below go through another type than the 2-byte writes above: tell the
+        // compiler that they touch the same memory (the hardware keeps a wave's LDS operations in order)
+        asm volatile("" ::: "memory");
         if (lrow < 8) {
           const int m = mt * BM + wm * TM * 32 + i * 32 + q * 8 + lrow;
           const int co = nt * BN + wn * TN * 32 + ch * 8;
@@ -295,6 +298,7 @@ __global__ void __launch_bounds__(kThreads, OCC) igemm_kernel(IgemmArgs a) {
             }
           }
         }
+        asm volatile("" ::: "memory");   // ... and the next pass's writes stay behind these reads
       }
 #pragma unroll
     for (int i = 0; i < TM; ++i)

@@ -315,6 +315,9 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
 #pragma unroll
           for (int j = 0; j < TN; ++j)
             Cw[((lane >> 5) * 4 + rho) * LDW + j * 32 + (lane & 31)] = f32_to_bf16_hw(acc[i][j][q * 4 + rho]);
+        // the 16-byte reads below go through another type than the 2-byte writes above: tell the
+        // compiler that they touch the same memory (the hardware keeps a wave's LDS operations in order)
+        asm volatile("" ::: "memory");
         const int lrow = lane >> 3, ch = lane & 7;
         const int row = wm * TM * 32 + i * 32 + q * 8 + lrow;
         const int m = mbase + tile_pixel(row, a.perm), co = nt * BN + wn * TN * 32 + ch * 8;
@@ -332,6 +335,7 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
             *reinterpret_cast<uint4*>(dp) = v;
           }
         }
+        asm volatile("" ::: "memory");   // ... and the next pass's writes stay behind these reads
       }
   };
 
