@@ -87,6 +87,9 @@ bool conv_first_supported(const ConvGeom& g);
 size_t conv_first_ws(const ConvGeom& g);
 int conv_first_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y, float* ch_sum, float* ch_sumsq,
                    void* ws, hipStream_t st);
+bool conv_first_wgrad_supported(const ConvGeom& g);   // additionally W % 16 == 0
+size_t conv_first_wgrad_ws(const ConvGeom& g);
+int conv_first_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws, hipStream_t st);
 
 // thin-input (stem) kernels, bf16 storage
 bool conv_stem_supported(const ConvGeom& g);

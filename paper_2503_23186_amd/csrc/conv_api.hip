@@ -28,6 +28,9 @@ static bool use_pad(const cnnk_conv_desc* d, const ConvGeom& g, int pass) {
 static bool use_first(const cnnk_conv_desc* d, const ConvGeom& g) {   // forward only
   return d->dtype == CNNK_BF16 && g_cnnk_tune[8] >= 0 && g_cnnk_tune[11] >= 0 && conv_first_supported(g);
 }
+static bool use_first_wgrad(const cnnk_conv_desc* d, const ConvGeom& g) {
+  return d->dtype == CNNK_BF16 && g_cnnk_tune[8] >= 0 && g_cnnk_tune[11] >= 0 && conv_first_wgrad_supported(g);
+}
 static bool use_stem(const cnnk_conv_desc* d, const ConvGeom& g, int pass) {
   return d->dtype == CNNK_BF16 && !conv_mfma_supported(g, pass) && !use_pad(d, g, pass) && conv_stem_supported(g);
 }
@@ -46,6 +49,7 @@ extern "C" size_t cnnk_conv2d_workspace_bytes(const cnnk_conv_desc* d, int pass)
     b = use_mfma(d, g, pass) ? conv_mfma_ws(g, pass, false) : 0;
   } else if (pass == CNNK_PASS_WGRAD) {
     b = use_mfma(d, g, pass) ? conv_mfma_ws(g, pass, false)
+        : use_first_wgrad(d, g) ? conv_first_wgrad_ws(g)
         : use_pad(d, g, pass) ? conv_pad_ws(g, pass, false)
         : use_stem(d, g, pass) ? conv_stem_wgrad_ws(g) : conv_direct_wgrad_ws(g);
   }
@@ -106,6 +110,7 @@ extern "C" int cnnk_conv2d_wgrad(const cnnk_conv_desc* d, const void* x, const v
   if (need && (!ws || ws_bytes < need)) return CNNK_ERR_WORKSPACE;
   if (use_mfma(d, g, CNNK_PASS_WGRAD))
     return conv_mfma_wgrad(g, (const bf16_t*)x, (const bf16_t*)dy, dw, ws, st);
+  if (use_first_wgrad(d, g)) return conv_first_wgrad(g, (const bf16_t*)x, (const bf16_t*)dy, dw, ws, st);
   if (use_pad(d, g, CNNK_PASS_WGRAD)) return conv_pad_wgrad(g, (const bf16_t*)x, (const bf16_t*)dy, dw, ws, st);
   if (use_stem(d, g, CNNK_PASS_WGRAD)) return conv_stem_wgrad(g, (const bf16_t*)x, (const bf16_t*)dy, dw, ws, st);
   return conv_direct_wgrad(g, d->dtype, x, dy, dw, ws, st);

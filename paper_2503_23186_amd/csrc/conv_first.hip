@@ -152,6 +152,131 @@ __global__ void __launch_bounds__(kT) first_fwd_kernel(FirstArgs a) {
     }
 }
 
+// ---- weight gradient ---------------------------------------------------------------------------
+// dw[k][q] = sum over pixels of dy[p][k] * A[p][q], q = (tap, channel) as in the forward pass, as
+// the MFMA product A^T (32 x pixels) * dy (pixels x 64): both fragments want eight consecutive
+// PIXELS per lane, which for a lane's fixed column is a gather of 2-byte elements - from the
+// cache-resident image for A, and for dy 32 adjacent lanes read 64 contiguous bytes of a pixel's
+// channel row, so every line of dy still comes from memory once.  No LDS staging.  A wavefront
+// walks whole image rows (16 pixels per MFMA step, so W % 16 == 0), workgroups write fp32 partials
+// in accumulator layout, a second kernel sums them into dw[k][r][s][c] (and may apply the SGD
+// update of the parameter in the same launch).
+struct FirstWgArgs {
+  const bf16_t* x;
+  const bf16_t* dy;
+  float* part;       // [workgroups][TN][16][64]
+  int N, H, W, Cout, rows, rows_per_wave;
+  FastDiv dH;
+};
+
+template <int TN>
+__global__ void __launch_bounds__(kT) first_wgrad_kernel(FirstWgArgs a) {
+  __shared__ float red[kT / 64][TN][16][64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kg = lane >> 5, l31 = lane & 31;
+  // this lane's column of A: q = l31 = r*9 + s*3 + c
+  const int fr = (l31 * 57) >> 9, jj = l31 - fr * 9, fs = (jj * 11) >> 5;
+  const bool qok = l31 < 27;
+  f32x16_t acc[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+
+  const int row_begin = (blockIdx.x * (kT / 64) + wave) * a.rows_per_wave;
+  const int row_end = min(row_begin + a.rows_per_wave, a.rows);
+  for (int R = row_begin; R < row_end; ++R) {      // image row R = n*H + h
+    int n, h;
+    a.dH.divmod(R, &n, &h);
+    const int hh = h + fr - 1;
+    const bool rok = qok && (unsigned)hh < (unsigned)a.H;
+    const long xbase = ((long)(R + fr - 1) * a.W + fs - 1) * 3 + (jj - fs * 3);   // element index at w = 0 (used only when in range)
+    const bf16_t* dyrow = a.dy + (size_t)R * a.W * a.Cout + l31;
+    for (int w0 = 0; w0 < a.W; w0 += 16) {
+      bf16_t va[8], vb[TN][8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int wc = w0 + kg * 8 + e;
+        const bool ok = rok && (unsigned)(wc + fs - 1) < (unsigned)a.W;
+        va[e] = ok ? a.x[xbase + (long)wc * 3] : (bf16_t)0;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          vb[j][e] = (j * 32 + l31 < a.Cout) ? dyrow[(size_t)wc * a.Cout + j * 32] : (bf16_t)0;
+      }
+      const bf16x8_t af = pack8(va);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, pack8(vb[j]), acc[j], 0, 0, 0);
+    }
+  }
+  // four wavefront accumulators -> one partial per workgroup (accumulator layout kept)
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) red[wave][j][r][lane] = acc[j][r];
+  __syncthreads();
+  for (int i = tid; i < TN * 16 * 64; i += kT) {
+    const float* p0 = &red[0][0][0][0] + i;
+    float t = p0[0];
+#pragma unroll
+    for (int w_ = 1; w_ < kT / 64; ++w_) t += p0[(size_t)w_ * TN * 16 * 64];
+    a.part[(size_t)blockIdx.x * TN * 16 * 64 + i] = t;
+  }
+}
+
+struct FirstSgd {
+  float* w;
+  float* v;
+  bf16_t* wlp;
+  float lr, mu, wd;
+};
+
+// dw[k*27 + q] = sum over P workgroup partials; 16 thread groups share the partials of an element,
+// their sums are added in group order.  SGD: also g' = g + wd*w; v <- mu*v + g'; w <- w - lr*v.
+template <bool SGD>
+__global__ void __launch_bounds__(256) first_wgrad_reduce_kernel(const float* __restrict__ part,
+                                                                 float* __restrict__ dw, int Cout, int TN, int P,
+                                                                 FirstSgd sg) {
+  __shared__ float red[16][16];
+  const int e = threadIdx.x & 15, grp = threadIdx.x >> 4;
+  const int i = blockIdx.x * 16 + e;            // output element k*27 + q
+  float acc = 0.f;
+  if (i < Cout * 27) {
+    const int k = i / 27, q = i - k * 27;
+    // accumulator layout: row q = (r/4)*8 + (lane/32)*4 + r%4, column k%32 = lane%32
+    const int r = (q >> 3) * 4 + (q & 3), ln = ((q >> 2) & 1) * 32 + (k & 31);
+    const size_t src = ((size_t)(k >> 5) * 16 + r) * 64 + ln, stride = (size_t)TN * 16 * 64;
+#pragma unroll 4
+    for (int p = grp; p < P; p += 16) acc += part[(size_t)p * stride + src];
+  }
+  red[grp][e] = acc;
+  __syncthreads();
+  if (grp == 0 && i < Cout * 27) {
+    float g = red[0][e];
+#pragma unroll
+    for (int k_ = 1; k_ < 16; ++k_) g += red[k_][e];
+    dw[i] = g;
+    if (SGD) {
+      const float wi = sg.w[i];
+      const float gp = fmaf(sg.wd, wi, g);
+      const float vn = fmaf(sg.mu, sg.v[i], gp);
+      const float wn = fmaf(-sg.lr, vn, wi);
+      sg.v[i] = vn;
+      sg.w[i] = wn;
+      if (sg.wlp) sg.wlp[i] = f32_to_bf16(wn);
+    }
+  }
+}
+
+inline int first_wg_rows_per_wave(const ConvGeom& g) {
+  const int rows = g.N * g.H;
+  int rpw = (rows + 2047) / 2048;          // about 2048 wavefronts on the device
+  return rpw < 1 ? 1 : rpw;
+}
+inline int first_wg_blocks(const ConvGeom& g) {
+  const int rows = g.N * g.H, per_block = first_wg_rows_per_wave(g) * (kT / 64);
+  return (rows + per_block - 1) / per_block;
+}
+
 }  // namespace
 
 bool conv_first_supported(const ConvGeom& g) {
@@ -184,4 +309,37 @@ int conv_first_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* 
   if (launch_status() != CNNK_OK) return CNNK_ERR_HIP;
   if (!ch_sum) return CNNK_OK;
   return channel_sums_finalize(a.stats, a.nblocks, g.Cout, ch_sum, ch_sumsq, st);
+}
+
+bool conv_first_wgrad_supported(const ConvGeom& g) { return conv_first_supported(g) && g.W % 16 == 0; }
+
+size_t conv_first_wgrad_ws(const ConvGeom& g) {
+  const int TN = g.Cout <= 32 ? 1 : 2;
+  return align_up((size_t)first_wg_blocks(g) * TN * 16 * 64 * sizeof(float), 256);
+}
+
+int conv_first_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws, hipStream_t st) {
+  FirstWgArgs a{};
+  a.x = x; a.dy = dy;
+  a.part = reinterpret_cast<float*>(ws);
+  a.N = g.N; a.H = g.H; a.W = g.W; a.Cout = g.Cout;
+  a.rows = g.N * g.H;
+  a.rows_per_wave = first_wg_rows_per_wave(g);
+  a.dH.init((unsigned)g.H);
+  const int TN = g.Cout <= 32 ? 1 : 2, nblk = first_wg_blocks(g);
+  if (TN == 1) first_wgrad_kernel<1><<<nblk, kT, 0, st>>>(a);
+  else first_wgrad_kernel<2><<<nblk, kT, 0, st>>>(a);
+  if (launch_status() != CNNK_OK) return CNNK_ERR_HIP;
+  const unsigned rblk = (unsigned)((g.Cout * 27 + 15) / 16);
+  SgdFuse* f = t_cnnk_sgd_fuse;
+  if (f && !f->done) {
+    if (f->wait && hipStreamWaitEvent(st, f->wait, 0) != hipSuccess) return CNNK_ERR_HIP;
+    const FirstSgd sg{f->w, f->v, static_cast<bf16_t*>(f->wlp), f->lr, f->mu, f->wd};
+    first_wgrad_reduce_kernel<true><<<rblk, 256, 0, st>>>(a.part, dw, g.Cout, TN, nblk, sg);
+    f->done = true;
+  } else {
+    const FirstSgd none{nullptr, nullptr, nullptr, 0.f, 0.f, 0.f};
+    first_wgrad_reduce_kernel<false><<<rblk, 256, 0, st>>>(a.part, dw, g.Cout, TN, nblk, none);
+  }
+  return launch_status();
 }
