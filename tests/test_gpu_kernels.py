@@ -57,6 +57,17 @@ def test_thin_input_fma_kernels(K, shape):
         K.cnnk_tune(8, 0)
 
 
+@pytest.mark.parametrize("shape", [s for s in CONV_SHAPES if s[3] == 3 and s[5] == 3 and s[6] == 1])
+def test_first_layer_on_the_padded_input_path(K, shape):
+    """3-channel 3x3 stride-1 layers normally take the dedicated first-layer kernels; the padded-input
+    path behind them (used for other thin inputs) is kept covered for these shapes too."""
+    K.cnnk_tune(11, -1)
+    try:
+        test_conv_fwd_dgrad_wgrad(K, shape, "bf16")
+    finally:
+        K.cnnk_tune(11, 0)
+
+
 @pytest.mark.parametrize("tpb", [2, 3, 8])
 @pytest.mark.parametrize("shape", [s for s in CONV_SHAPES if s[3] >= 8])
 def test_gathered_gemm_kernels_with_several_tiles_per_workgroup(K, shape, tpb):
