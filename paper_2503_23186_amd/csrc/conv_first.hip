@@ -230,40 +230,43 @@ struct FirstSgd {
   float lr, mu, wd;
 };
 
-// dw[k*27 + q] = sum over P workgroup partials; 16 thread groups share the partials of an element,
-// their sums are added in group order.  SGD: also g' = g + wd*w; v <- mu*v + g'; w <- w - lr*v.
+// dw[k*27 + q] = sum over P workgroup partials.  A thread owns one element of the accumulator
+// layout (adjacent threads read adjacent floats of every partial), 16 thread groups share the
+// partials of an element and their sums are added in group order; the element's (k, q) is decoded
+// only for the final store.  SGD: also g' = g + wd*w; v <- mu*v + g'; w <- w - lr*v.
 template <bool SGD>
 __global__ void __launch_bounds__(256) first_wgrad_reduce_kernel(const float* __restrict__ part,
                                                                  float* __restrict__ dw, int Cout, int TN, int P,
                                                                  FirstSgd sg) {
   __shared__ float red[16][16];
   const int e = threadIdx.x & 15, grp = threadIdx.x >> 4;
-  const int i = blockIdx.x * 16 + e;            // output element k*27 + q
+  const int a = blockIdx.x * 16 + e;            // accumulator element: ((j*16 + r)*64 + lane)
+  const int total = TN * 16 * 64;
   float acc = 0.f;
-  if (i < Cout * 27) {
-    const int k = i / 27, q = i - k * 27;
-    // accumulator layout: row q = (r/4)*8 + (lane/32)*4 + r%4, column k%32 = lane%32
-    const int r = (q >> 3) * 4 + (q & 3), ln = ((q >> 2) & 1) * 32 + (k & 31);
-    const size_t src = ((size_t)(k >> 5) * 16 + r) * 64 + ln, stride = (size_t)TN * 16 * 64;
+  if (a < total) {
 #pragma unroll 4
-    for (int p = grp; p < P; p += 16) acc += part[(size_t)p * stride + src];
+    for (int p = grp; p < P; p += 16) acc += part[(size_t)p * total + a];
   }
   red[grp][e] = acc;
   __syncthreads();
-  if (grp == 0 && i < Cout * 27) {
-    float g = red[0][e];
+  if (grp != 0 || a >= total) return;
+  float g = red[0][e];
 #pragma unroll
-    for (int k_ = 1; k_ < 16; ++k_) g += red[k_][e];
-    dw[i] = g;
-    if (SGD) {
-      const float wi = sg.w[i];
-      const float gp = fmaf(sg.wd, wi, g);
-      const float vn = fmaf(sg.mu, sg.v[i], gp);
-      const float wn = fmaf(-sg.lr, vn, wi);
-      sg.v[i] = vn;
-      sg.w[i] = wn;
-      if (sg.wlp) sg.wlp[i] = f32_to_bf16(wn);
-    }
+  for (int k_ = 1; k_ < 16; ++k_) g += red[k_][e];
+  // accumulator layout: row q = (r/4)*8 + (lane/32)*4 + r%4, column k = j*32 + lane%32
+  const int ln = a & 63, r = (a >> 6) & 15, j = a >> 10;
+  const int q = (r >> 2) * 8 + (ln >> 5) * 4 + (r & 3), k = j * 32 + (ln & 31);
+  if (q >= 27 || k >= Cout) return;
+  const int i = k * 27 + q;
+  dw[i] = g;
+  if (SGD) {
+    const float wi = sg.w[i];
+    const float gp = fmaf(sg.wd, wi, g);
+    const float vn = fmaf(sg.mu, sg.v[i], gp);
+    const float wn = fmaf(-sg.lr, vn, wi);
+    sg.v[i] = vn;
+    sg.w[i] = wn;
+    if (sg.wlp) sg.wlp[i] = f32_to_bf16(wn);
   }
 }
 
@@ -330,7 +333,7 @@ int conv_first_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float
   if (TN == 1) first_wgrad_kernel<1><<<nblk, kT, 0, st>>>(a);
   else first_wgrad_kernel<2><<<nblk, kT, 0, st>>>(a);
   if (launch_status() != CNNK_OK) return CNNK_ERR_HIP;
-  const unsigned rblk = (unsigned)((g.Cout * 27 + 15) / 16);
+  const unsigned rblk = (unsigned)(TN * 16 * 64 / 16);
   SgdFuse* f = t_cnnk_sgd_fuse;
   if (f && !f->done) {
     if (f->wait && hipStreamWaitEvent(st, f->wait, 0) != hipSuccess) return CNNK_ERR_HIP;
