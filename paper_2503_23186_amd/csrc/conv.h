@@ -63,6 +63,9 @@ int conv_patch_dgrad(const ConvGeom& g, const bf16_t* dy, const bf16_t* wt, bf16
 bool conv_wgrad_patch_supported(const ConvGeom& g);
 size_t conv_wgrad_patch_ws(const ConvGeom& g);
 int conv_wgrad_patch(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws, hipStream_t st);
+// the same partial sums with the operand tiles loaded straight into LDS (conv_wgrad_dma.hip)
+int conv_wgrad_dma_launch(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* part, int TI, int TH, int ctiles,
+                          int tiles_per_block, int mtiles, int nw, int otiles, int splits, hipStream_t st);
 
 // fewer than 8 input channels: zero-pad to 8 in the workspace, then the MFMA kernels
 bool conv_pad_supported(const ConvGeom& g);

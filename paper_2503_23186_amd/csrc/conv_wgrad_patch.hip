@@ -311,7 +311,9 @@ int conv_wgrad_patch(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float
   dim3 grid(otiles, splits);
   const int pl = (patch_px + kRowsPerPass - 1) / kRowsPerPass;
   int rc;
-  if (pl <= 4) rc = launch_wg<4>(a, grid, smem, st);
+  if (g_cnnk_tune[10] >= 0)   // -1: the register-staged kernel of this file
+    rc = conv_wgrad_dma_launch(g, x, dy, a.dw, a.TI, a.TH, a.ctiles, a.tiles_per_block, a.mtiles, a.nw, otiles, splits, st);
+  else if (pl <= 4) rc = launch_wg<4>(a, grid, smem, st);
   else rc = launch_wg<5>(a, grid, smem, st);
   if (rc != CNNK_OK || splits == 1) return rc;
   return reduce_partials(a.dw, dw, a.nw, splits, st);

@@ -136,15 +136,17 @@ WG_SHAPES = [(4, 8, 8, 64, 128), (3, 16, 16, 64, 64), (2, 32, 32, 128, 64), (18,
              (1, 32, 32, 64, 64)]
 
 
+@pytest.mark.parametrize("staging", [0, -1])
 @pytest.mark.parametrize("target", [1, 4, 0])
 @pytest.mark.parametrize("shape", WG_SHAPES)
-def test_conv_wgrad_patch_kernel(K, shape, target):
-    """3x3 stride-1 weight gradient through the LDS-patch kernel: one workgroup per output tile
-    (plain stores), a few (atomic accumulation), and the default split."""
+def test_conv_wgrad_patch_kernel(K, shape, target, staging):
+    """3x3 stride-1 weight gradient through the LDS-patch kernels (tiles loaded straight into LDS,
+    and staged through registers): one workgroup per output tile (plain stores), a few (partial
+    sums), and the default split."""
     N, H, W, Cin, Cout = shape
     x, w, dy, pad = conv_inputs((N, H, W, Cin, Cout, 3, 1), "bf16", 17)
     d = K.conv_desc(N, H, W, Cin, Cout, 3, 3, 1, 1, K.BF16)
-    K.cnnk_tune(6, target)
+    K.cnnk_tune(6, target); K.cnnk_tune(10, staging)
     try:
         dw_ref = ref.conv2d_wgrad(x, dy, w.shape, 1, 1)
         gdw = torch.full(w.shape, 9.0, dtype=torch.float32, device="cuda:0")
@@ -153,7 +155,7 @@ def test_conv_wgrad_patch_kernel(K, shape, target):
         torch.cuda.synchronize()
         assert max_rel_err(host(gdw), dw_ref) <= 1e-4
     finally:
-        K.cnnk_tune(6, 0)
+        K.cnnk_tune(6, 0); K.cnnk_tune(10, 0)
 
 
 PATCH_TILES = [(256, 128), (256, 64), (128, 128), (128, 64)]
