@@ -17,6 +17,8 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int CK = 32;          // channels per chunk
 
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+
 constexpr int kPxPerLoad = kThreads / (CK / 8);  // patch pixels staged per 16-byte load of the workgroup
 
 struct PatchArgs {
@@ -86,7 +88,7 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const int PW = a.W + 2, PH = a.TH + 2;
   const int patch_px = a.TI * PH * PW;
-  const int patch_bytes = patch_px * 64;
+  const int patch_bytes = max(patch_px * 64, 4 * 32 * 72);   // at least the epilogue's four transposition strips
   unsigned char* Pb = smem_raw;                      // [2][patch_px][64 B]
   unsigned char* Bb = smem_raw + 2 * patch_bytes;    // [2][3][BN][64 B]
 
@@ -104,29 +106,44 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   const __amdgpu_buffer_rsrc_t wt_rs = make_rsrc(a.wt, (unsigned)a.Cd * 9u * a.Cs * 2u);
 
   const int kc = tid & 3;
-  // global byte offset of each staged patch chunk of a pixel tile (kOobOffset: zero fill; a tile
-  // past the workgroup's range is all zero fill)
-  auto patch_offsets = [&](int mtile, unsigned* off) __attribute__((always_inline)) {
-    const int m0 = mtile * BM;
-    int q0, hh, n0, h0;
-    a.dW.divmod(m0, &q0, &hh);
-    a.dH.divmod(q0, &n0, &h0);
+  // Patch addressing.  What a thread loads for patch position pp = tid/4 + 64*j is the same for
+  // every tile up to the tile's origin: a byte offset relative to the tile's first pixel (prel),
+  // and whether the position is real data - never (padding column, or a padding row of a tile of
+  // whole images), always (interior row), or only if the band of rows has a row above / below it
+  // inside the image (pcls: bit j interior, bit 8+j row above, bit 16+j row below).  A tile then
+  // costs two scalar conditions instead of two divisions per position.  Images past the end of
+  // the batch (ragged last tile of whole images) lie past the end of the buffer and read as zeros.
+  int prel[PL];
+  unsigned pcls = 0;
 #pragma unroll
-    for (int j = 0; j < PL; ++j) {
-      const int pp = (tid >> 2) + j * (kThreads / 4);
-      off[j] = kOobOffset;
-      if (pp < patch_px && mtile < mt_end) {
-        int q, pw, ti, ph;
-        a.dPW.divmod(pp, &q, &pw);
-        a.dPH.divmod(q, &ti, &ph);
-        const int n = n0 + ti, hs = h0 + ph - 1, ws = pw - 1;
-        if (n < a.N && (unsigned)hs < (unsigned)a.H && (unsigned)ws < (unsigned)a.W)
-          off[j] = (unsigned)(((n * a.H + hs) * a.W + ws) * a.Cs + kc * 8) * 2u;
-      }
+  for (int j = 0; j < PL; ++j) {
+    const int pp = (tid >> 2) + j * (kThreads / 4);
+    int q, pw, ti, ph;
+    a.dPW.divmod(pp, &q, &pw);
+    a.dPH.divmod(q, &ti, &ph);
+    if (pp < patch_px && pw >= 1 && pw <= a.W) {
+      if (ph >= 1 && ph <= a.TH) pcls |= 1u << j;
+      else if (a.TI == 1) pcls |= (ph == 0 ? 0x100u : 0x10000u) << j;
     }
+    prel[j] = (((ti * a.H + ph - 1) * a.W + pw - 1) * a.Cs + kc * 8) * 2;
+  }
+  // the positions that are real data in pixel tile `mtile` (bit j), and the byte offset of its origin
+  auto tile_mask = [&](int mtile, unsigned* base) __attribute__((always_inline)) {
+    const int m0 = mtile * BM;
+    int q0, wrem, n0, h0;
+    a.dW.divmod(m0, &q0, &wrem);
+    a.dH.divmod(q0, &n0, &h0);
+    *base = (unsigned)m0 * (unsigned)a.Cs * 2u;
+    if (mtile >= mt_end) return 0u;        // past the workgroup's range: all zero fill
+    const unsigned sel = 0xffu | (h0 > 0 ? 0xff00u : 0u) | (h0 + a.TH < a.H ? 0xff0000u : 0u);
+    const unsigned v = pcls & sel;
+    return (v | (v >> 8) | (v >> 16)) & 0xffu;
   };
-  unsigned poff[PL];
-  patch_offsets(mt, poff);
+  unsigned cbase, nbase;                   // current tile and the one after it
+  unsigned cmask = tile_mask(mt, &cbase), nmask = tile_mask(mt + 1, &nbase);
+  auto patch_off = [&](unsigned mask, unsigned base, int j) __attribute__((always_inline)) {
+    return (mask >> j) & 1u ? base + (unsigned)prel[j] : kOobOffset;
+  };
   // its LDS byte offset inside a patch buffer is pst0 + j * 64 rows (the swizzle repeats every 16 rows)
   const int pst0 = swz_off(tid >> 2, kc);
   const int r0 = tid >> 2;  // weight row of this thread inside a 64-row pass
@@ -165,23 +182,14 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   uint4 preg[PL];
   uint4 rb[2][3][B_IT];
 
-  auto load_patch = [&](const unsigned* off, int chunk) {
-#pragma unroll
-    for (int j = 0; j < PL; ++j) preg[j] = buffer_load16(src_rs, off[j], (unsigned)chunk * (CK * 2));
-  };
   // the chunk after chunk c of the current tile: c + 1, or chunk 0 of the next tile
   int c_in_tile = 0;
   auto load_next_patch = [&]() __attribute__((always_inline)) {
-    if (c_in_tile + 1 == nchunks) {
-      unsigned nxt[PL];     // computed here rather than kept: registers are scarce in the main loop
-      patch_offsets(mt + 1, nxt);
+    const bool last = c_in_tile + 1 == nchunks;
+    const unsigned so = (unsigned)__builtin_amdgcn_readfirstlane(last ? 0 : (c_in_tile + 1) * (CK * 2));
+    const unsigned base = last ? nbase : cbase, mask = last ? nmask : cmask;
 #pragma unroll
-      for (int j = 0; j < PL; ++j) preg[j] = buffer_load16(src_rs, nxt[j], 0u);
-    } else {
-      const unsigned so = (unsigned)__builtin_amdgcn_readfirstlane((c_in_tile + 1) * (CK * 2));
-#pragma unroll
-      for (int j = 0; j < PL; ++j) preg[j] = buffer_load16(src_rs, poff[j], so);
-    }
+    for (int j = 0; j < PL; ++j) preg[j] = buffer_load16(src_rs, patch_off(mask, base, j), so);
   };
   auto store_patch = [&](int buf) {
 #pragma unroll
@@ -280,7 +288,7 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   // per-channel sums of the fp32 accumulators over this wave's 64 rows (one partial row per wave:
   // mtiles * WM rows in all, reduced by a finalising kernel), then eight passes of 8 rows x 64
   // columns through LDS so that every lane stores 16 contiguous bytes.
-  auto epilogue = [&](int mtile) __attribute__((always_inline)) {
+  auto epilogue = [&](int mtile, int par) __attribute__((always_inline)) {
     if (a.stats) {
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
@@ -303,40 +311,71 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
         }
       }
     }
-    constexpr int LDW = TN * 32 + 8;
-    bf16_t* Cw = reinterpret_cast<bf16_t*>(smem_raw + 2 * patch_bytes + 6 * BN * 64) + wave * 8 * LDW;
+    // Transposition through LDS so that a lane stores 16 contiguous bytes (8 channels of a pixel).
+    // A lane of the accumulator layout holds one column (channel) and, per register quad, four
+    // consecutive rows: the quad goes out as one 8-byte write into a [channel][row] strip, and the
+    // transposing LDS read hands each lane four consecutive channels of one row back.  Per 32x32
+    // tile: 4 writes, 4 reads, 2 stores; the stores of a tile are issued behind the LDS traffic of
+    // the next one.  The strip lives in the patch buffer of the chunk just finished (every wave is
+    // past the barrier behind its last read, and the buffer is not refilled before two more barriers).
+    constexpr int SP = 72;   // strip pitch in bytes per channel: 32 rows + 8 bytes, keeps writes and reads off shared banks
+    unsigned char* S = Pb + par * patch_bytes + wave * (32 * SP);
     const int mbase = mtile * BM;
+    const int g4 = lane >> 4, i16 = lane & 15;
+    const int wr_off = (lane & 31) * SP + (lane >> 5) * 8;
+    const int rd_off = (g4 * 8 + (i16 >> 2)) * SP + (i16 & 3) * 8;
+    uint4 pend[2];
+    int pend_i = 0, pend_j = 0;
+    auto flush = [&](int i, int j) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-#pragma unroll
-        for (int rho = 0; rho < 4; ++rho)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            Cw[((lane >> 5) * 4 + rho) * LDW + j * 32 + (lane & 31)] = f32_to_bf16_hw(acc[i][j][q * 4 + rho]);
-        // the 16-byte reads below go through another type than the 2-byte writes above: tell the
-        // compiler that they touch the same memory (the hardware keeps a wave's LDS operations in order)
-        asm volatile("" ::: "memory");
-        const int lrow = lane >> 3, ch = lane & 7;
-        const int row = wm * TM * 32 + i * 32 + q * 8 + lrow;
-        const int m = mbase + tile_pixel(row, a.perm), co = nt * BN + wn * TN * 32 + ch * 8;
-        const uint4 v = *reinterpret_cast<const uint4*>(Cw + lrow * LDW + ch * 8);
+      for (int rb = 0; rb < 2; ++rb) {
+        const int row = wm * TM * 32 + i * 32 + rb * 16 + i16;
+        const int m = mbase + tile_pixel(row, a.perm), co = nt * BN + wn * TN * 32 + j * 32 + g4 * 8;
         if (m < M && co < a.Cd) {
           bf16_t* dp = a.dst + (size_t)m * a.Cd + co;
           if (a.accumulate) {
             float o[8], nw[8];
             load8(dp, o);
-            load8(Cw + lrow * LDW + ch * 8, nw);
+            unpack8(pend[rb], nw);
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] += nw[e];
             store8(dp, o);
           } else {
-            *reinterpret_cast<uint4*>(dp) = v;
+            *reinterpret_cast<uint4*>(dp) = pend[rb];
           }
         }
-        asm volatile("" ::: "memory");   // ... and the next pass's writes stay behind these reads
       }
+    };
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          uint2 v;
+          v.x = pack_bf16x2(acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1]);
+          v.y = pack_bf16x2(acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
+          *reinterpret_cast<uint2*>(S + wr_off + q * 16) = v;
+        }
+        // the reads below go through another type than the writes above: tell the compiler that
+        // they touch the same memory (the hardware keeps a wave's LDS operations in order)
+        asm volatile("" ::: "memory");
+        uint4 cur[2];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+          const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (s16x4_t __attribute__((address_space(3)))*)(S + rd_off + rb * 32));
+          const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (s16x4_t __attribute__((address_space(3)))*)(S + rd_off + 4 * SP + rb * 32));
+          const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
+          cur[rb] = uint4{l2.x, l2.y, h2.x, h2.y};
+        }
+        asm volatile("" ::: "memory");   // ... and the next tile's writes stay behind these reads
+        if (i + j > 0) flush(pend_i, pend_j);
+        pend[0] = cur[0]; pend[1] = cur[1];
+        pend_i = i; pend_j = j;
+      }
+    flush(pend_i, pend_j);
   };
 
   using I0 = std::integral_constant<int, 0>;
@@ -350,7 +389,7 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
     step(PARC, std::integral_constant<int, 1>{});
     step(PARC, std::integral_constant<int, 2>{});
     if (c_in_tile + 1 == nchunks) {
-      epilogue(mt);
+      epilogue(mt, decltype(PARC)::value);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -359,13 +398,15 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
           for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
       ++mt;
       c_in_tile = 0;
-      patch_offsets(mt, poff);
+      cbase = nbase; cmask = nmask;
+      nmask = tile_mask(mt + 1, &nbase);
     } else {
       ++c_in_tile;
     }
   };
 
-  load_patch(poff, 0);
+#pragma unroll
+  for (int j = 0; j < PL; ++j) preg[j] = buffer_load16(src_rs, patch_off(cmask, cbase, j), 0u);
   load_w(0, I0{}, I0{});
   load_w(0, I1{}, I1{});
   store_patch(0);
@@ -398,8 +439,9 @@ bool tile_geometry(const ConvGeom& g, int bm, int max_px, int* ti, int* th) {
 
 template <int BM, int BN>
 size_t patch_smem(int patch_px) {
-  // two patch buffers, two weight buffers of three taps, 8 rows x 72 columns of epilogue staging per wave
-  return (size_t)2 * patch_px * 64 + (size_t)6 * BN * 64 + (size_t)4 * 8 * 72 * sizeof(bf16_t);
+  // two patch buffers (each at least the 9 KB the epilogue's transposition strips need), two weight
+  // buffers of three taps
+  return (size_t)2 * (patch_px * 64 < 4 * 32 * 72 ? 4 * 32 * 72 : patch_px * 64) + (size_t)6 * BN * 64;
 }
 
 template <int BM, int BN, int WM, int WN, int OCC, int PL>
