@@ -18,7 +18,8 @@ struct RowMap {
 
 inline int reduce_blocks(size_t m, int C) {
   const int rows = kT / (C / 8);
-  size_t nb = (m + (size_t)rows * 4 - 1) / ((size_t)rows * 4);  // at least 4 rows per thread
+  // at least 8 rows per thread (ResNet-18 b256 step: 2.215 ms with 4, 2.195 with 8, 2.27 with 16)
+  size_t nb = (m + (size_t)rows * 8 - 1) / ((size_t)rows * 8);
   if (nb > kMaxBlocks) nb = kMaxBlocks;
   // every workgroup ends with 2*C scattered 4-byte writes of its partial sums: with many channels
   // fewer, longer-lived workgroups are cheaper (C = 1024: 256 instead of 2048; ResNet-50
