@@ -275,15 +275,19 @@ int conv_wgrad_dma_launch(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, 
   a.dPW.init(a.W + 2); a.dPH.init(a.TH + 2); a.dW.init(a.W); a.dTH.init(a.TH); a.dH.init(a.H);
   const int patch_px = TI * (TH + 2) * (g.W + 2);
   dim3 grid(otiles, splits);
-  auto launch = [&](auto kern, int stage_b, int nbuf) {
+  auto launch = [&](auto kern, int stage_b, int nbuf, bool* attr_done) {
     const int smem = nbuf * stage_b;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
-        hipSuccess)
-      return (int)CNNK_ERR_HIP;
+    if (!*attr_done) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
+          hipSuccess)
+        return (int)CNNK_ERR_HIP;
+      *attr_done = true;
+    }
     hipLaunchKernelGGL(kern, grid, dim3(kThreads), smem, st, a);
     return launch_status();
   };
-  if (patch_px <= 4 * 64) return launch(wgrad_dma_kernel<4, 3>, 2 * DY_PLANE + 2 * 4 * 64 * ROW_B, 3);
-  if (patch_px <= 5 * 64) return launch(wgrad_dma_kernel<5, 2>, 2 * DY_PLANE + 2 * 5 * 64 * ROW_B, 2);
+  static bool attr43 = false, attr52 = false;
+  if (patch_px <= 4 * 64) return launch(wgrad_dma_kernel<4, 3>, 2 * DY_PLANE + 2 * 4 * 64 * ROW_B, 3, &attr43);
+  if (patch_px <= 5 * 64) return launch(wgrad_dma_kernel<5, 2>, 2 * DY_PLANE + 2 * 5 * 64 * ROW_B, 2, &attr52);
   return CNNK_ERR_UNSUPPORTED;
 }
