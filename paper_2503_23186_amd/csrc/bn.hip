@@ -74,13 +74,45 @@ __device__ __forceinline__ void finalize_sums(const float* __restrict__ part, in
   double s1 = 0.0, s2 = 0.0;
   const float* p1 = part + ((size_t)0 * C + c) * nb;
   const float* p2 = part + ((size_t)1 * C + c) * nb;
-#pragma unroll 4
-  for (int b = lane; b < nb; b += 64) {
-    s1 += (double)p1[b];
-    s2 += (double)p2[b];
+  // eight partials per round, all loads issued before the first add (an index past the end
+  // re-reads the lane's first partial and counts as zero); same order of additions as a plain loop
+  for (int b0 = lane; b0 < nb; b0 += 8 * 64) {
+    float v1[8], v2[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int b = b0 + k * 64 < nb ? b0 + k * 64 : lane;
+      v1[k] = p1[b];
+      v2[k] = p2[b];
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const bool in = b0 + k * 64 < nb;
+      s1 += in ? (double)v1[k] : 0.0;
+      s2 += in ? (double)v2[k] : 0.0;
+    }
   }
   *s1_out = wave_sum_f64(s1);
   *s2_out = wave_sum_f64(s2);
+}
+
+// Row walk of the reductions and of the element-wise kernels: a thread owns one octet of
+// channels (o = tid % (C/8)) for the whole launch, keeps that octet's coefficients in registers, and
+// walks rows blockIdx.x*rows + tid/(C/8), +gridDim.x*rows, ... four rows in flight.  No per-vector
+// index arithmetic beyond one multiply-add, no per-vector coefficient loads.
+template <typename T, typename F>
+__device__ __forceinline__ void for_rows4(size_t m, int C, int lanes, int rows, F body) {
+  const int tid = threadIdx.x, o = tid % lanes, rl = tid / lanes;
+  if (rl >= rows) return;
+  const size_t step = (size_t)gridDim.x * rows;
+  size_t r = (size_t)blockIdx.x * rows + rl;
+  for (; r + 3 * step < m; r += 4 * step) {
+    const size_t i0 = r * C + o * 8, d = step * C;
+    body(i0, i0 + d, i0 + 2 * d, i0 + 3 * d, std::integral_constant<int, 4>{});
+  }
+  for (; r < m; r += step) {
+    const size_t i0 = r * C + o * 8;
+    body(i0, i0, i0, i0, std::integral_constant<int, 1>{});
+  }
 }
 
 // Partial sums of (x - shift) and (x - shift)^2 with shift = x[0][c] (keeps fp32 sums benign).
@@ -95,17 +127,26 @@ __global__ void __launch_bounds__(kT) stats_partial_kernel(const T* __restrict__
   if (rl < rows) {
     float sh[8];
     load8(x + o * 8, sh);
-#pragma unroll 4
-    for (size_t r = (size_t)blockIdx.x * rows + rl; r < m; r += (size_t)gridDim.x * rows) {
-      float v[8];
-      load8(x + r * C + o * 8, v);
+    // four rows per round, all loads issued before the first use (a plain row loop is compiled to
+    // one load in flight per thread)
+    for_rows4<T>(m, C, lanes, rows, [&](size_t i0, size_t i1, size_t i2, size_t i3, auto NN) {
+      constexpr int n = decltype(NN)::value;
+      const size_t idx[4] = {i0, i1, i2, i3};
+      float v[4][8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float d = v[e] - sh[e];
-        acc[0][e] += d;
-        acc[1][e] = fmaf(d, d, acc[1][e]);
+      for (int k = 0; k < 4; ++k)
+        if (k < n) load8(x + idx[k], v[k]);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if (k >= n) break;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float d = v[k][e] - sh[e];
+          acc[0][e] += d;
+          acc[1][e] = fmaf(d, d, acc[1][e]);
+        }
       }
-    }
+    });
   }
   block_reduce_store<2>(acc, lanes, rows, C, part);
 }
@@ -163,10 +204,20 @@ __device__ __forceinline__ void finalize_sums_wide(const float* __restrict__ par
   const float* p1 = part + ((size_t)0 * C + c) * nb;
   const float* p2 = part + ((size_t)1 * C + c) * nb;
   double s1 = 0.0, s2 = 0.0;
-#pragma unroll 4
-  for (int b = tid; b < nb; b += kT) {
-    s1 += (double)p1[b];
-    s2 += (double)p2[b];
+  for (int b0 = tid; b0 < nb; b0 += 8 * kT) {   // eight partials per round, as above
+    float v1[8], v2[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int b = b0 + k * kT < nb ? b0 + k * kT : tid;
+      v1[k] = p1[b];
+      v2[k] = p2[b];
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const bool in = b0 + k * kT < nb;
+      s1 += in ? (double)v1[k] : 0.0;
+      s2 += in ? (double)v2[k] : 0.0;
+    }
   }
   s1 = wave_sum_f64(s1);
   s2 = wave_sum_f64(s2);
@@ -194,26 +245,6 @@ __global__ void __launch_bounds__(kT) sums_finalize_wide_kernel(const float* __r
 __device__ __forceinline__ void bn_scale_bias(float g, float b, float mu, float is, float* sc, float* bi) {
   *sc = g * is;
   *bi = fmaf(-mu, *sc, b);
-}
-
-// The element-wise kernels use the row mapping of the reductions: a thread owns one octet of
-// channels (o = tid % (C/8)) for the whole launch, keeps that octet's coefficients in registers, and
-// walks rows blockIdx.x*rows + tid/(C/8), +gridDim.x*rows, ... four rows in flight.  No per-vector
-// index arithmetic beyond one multiply-add, no per-vector coefficient loads.
-template <typename T, typename F>
-__device__ __forceinline__ void for_rows4(size_t m, int C, int lanes, int rows, F body) {
-  const int tid = threadIdx.x, o = tid % lanes, rl = tid / lanes;
-  if (rl >= rows) return;
-  const size_t step = (size_t)gridDim.x * rows;
-  size_t r = (size_t)blockIdx.x * rows + rl;
-  for (; r + 3 * step < m; r += 4 * step) {
-    const size_t i0 = r * C + o * 8, d = step * C;
-    body(i0, i0 + d, i0 + 2 * d, i0 + 3 * d, std::integral_constant<int, 4>{});
-  }
-  for (; r < m; r += step) {
-    const size_t i0 = r * C + o * 8;
-    body(i0, i0, i0, i0, std::integral_constant<int, 1>{});
-  }
 }
 
 template <typename T>
@@ -359,30 +390,40 @@ __global__ void __launch_bounds__(kT) bwd_partial_kernel(const T* __restrict__ d
 #pragma unroll
       for (int e = 0; e < 8; ++e) bn_scale_bias(ga[e], be[e], mu[e], is[e], &sc[e], &bi[e]);
     }
-#pragma unroll 4
-    for (size_t r = (size_t)blockIdx.x * rows + rl; r < m; r += (size_t)gridDim.x * rows) {
-      float g[8], xv[8];
-      load8(dy + r * C + o * 8, g);
-      load8(x + r * C + o * 8, xv);
-      if (MODE == 1) {
-        float yv[8];
-        load8(y + r * C + o * 8, yv);
+    // four rows per round, all loads issued before the first use (a plain row loop is compiled to
+    // one load in flight per thread)
+    for_rows4<T>(m, C, lanes, rows, [&](size_t i0, size_t i1, size_t i2, size_t i3, auto NN) {
+      constexpr int n = decltype(NN)::value;
+      const size_t idx[4] = {i0, i1, i2, i3};
+      float g[4][8], xv[4][8], yv[4][8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) g[e] = yv[e] > 0.f ? g[e] : 0.f;
-      }
-      if (MODE == 2) {
+      for (int k = 0; k < 4; ++k)
+        if (k < n) {
+          load8(dy + idx[k], g[k]);
+          load8(x + idx[k], xv[k]);
+          if (MODE == 1) load8(y + idx[k], yv[k]);
+        }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) g[e] = fmaf(xv[e], sc[e], bi[e]) > 0.f ? g[e] : 0.f;
-      }
-      // the masked gradient is exact in the storage type (dy or 0): written here, it spares the
-      // element-wise pass the reads of dy and y
-      if (dz_out) store8(dz_out + r * C + o * 8, g);
+      for (int k = 0; k < 4; ++k) {
+        if (k >= n) break;
+        if (MODE == 1) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        acc[0][e] += g[e];
-        acc[1][e] = fmaf(g[e], (xv[e] - mu[e]) * is[e], acc[1][e]);
+          for (int e = 0; e < 8; ++e) g[k][e] = yv[k][e] > 0.f ? g[k][e] : 0.f;
+        }
+        if (MODE == 2) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) g[k][e] = fmaf(xv[k][e], sc[e], bi[e]) > 0.f ? g[k][e] : 0.f;
+        }
+        // the masked gradient is exact in the storage type (dy or 0): written here, it spares the
+        // element-wise pass the reads of dy and y
+        if (dz_out) store8(dz_out + idx[k], g[k]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          acc[0][e] += g[k][e];
+          acc[1][e] = fmaf(g[k][e], (xv[k][e] - mu[e]) * is[e], acc[1][e]);
+        }
       }
-    }
+    });
   }
   block_reduce_store<2>(acc, lanes, rows, C, part);
 }

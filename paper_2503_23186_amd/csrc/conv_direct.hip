@@ -121,11 +121,29 @@ __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __res
   const int i4 = blockIdx.x * COLS + col;   // float4 column
   const int n4 = n >> 2;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  // weight and momentum of the fused update are fetched under the partial sums
+  float4 wv = make_float4(0.f, 0.f, 0.f, 0.f), vv = wv;
+  if (SGD && grp == 0 && i4 < n4) {
+    wv = *reinterpret_cast<const float4*>(sg.w + (size_t)i4 * 4);
+    vv = *reinterpret_cast<const float4*>(sg.v + (size_t)i4 * 4);
+  }
   if (i4 < n4) {
-#pragma unroll 4
-    for (int p = grp; p < P; p += GROUPS) {
-      const float4 v = *reinterpret_cast<const float4*>(part + (size_t)p * n + (size_t)i4 * 4);
-      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    // eight partials per round, all loads issued before the first add (a partial past the end
+    // re-reads this thread's first one and counts as zero): the sum is a chain of memory
+    // latencies otherwise.  Same order of additions as a plain loop.
+    const float* base = part + (size_t)i4 * 4;
+    for (int p0 = grp; p0 < P; p0 += 8 * GROUPS) {
+      float4 v[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int p = p0 + k * GROUPS;
+        v[k] = *reinterpret_cast<const float4*>(base + (size_t)(p < P ? p : grp) * n);
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const bool in = p0 + k * GROUPS < P;
+        acc.x += in ? v[k].x : 0.f; acc.y += in ? v[k].y : 0.f; acc.z += in ? v[k].z : 0.f; acc.w += in ? v[k].w : 0.f;
+      }
     }
   }
   red[grp][col] = acc;
@@ -137,8 +155,6 @@ __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __res
     *reinterpret_cast<float4*>(out + (size_t)i4 * 4) = s;
     if (SGD) {   // the parameter update on the gradient just summed (same arithmetic as the SGD kernel)
       const size_t i = (size_t)i4 * 4;
-      const float4 wv = *reinterpret_cast<const float4*>(sg.w + i);
-      const float4 vv = *reinterpret_cast<const float4*>(sg.v + i);
       float4 vn, wn;
       wn.x = sgd_apply(wv.x, vv.x, s.x, sg, &vn.x);
       wn.y = sgd_apply(wv.y, vv.y, s.y, sg, &vn.y);

@@ -38,8 +38,17 @@ __global__ void __launch_bounds__(256) reduce_unpad_kernel(const float* __restri
   float a = 0.f;
   if (i < rows * C) {
     const size_t src = (size_t)(i / C) * 8 + i % C;
-#pragma unroll 4
-    for (int p = grp; p < P; p += 16) a += part[(size_t)p * n8 + src];
+    // eight partials per round, all loads issued before the first add
+    for (int p0 = grp; p0 < P; p0 += 8 * 16) {
+      float v[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int p = p0 + k * 16;
+        v[k] = part[(size_t)(p < P ? p : grp) * n8 + src];
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) a += p0 + k * 16 < P ? v[k] : 0.f;
+    }
   }
   red[grp][e] = a;
   __syncthreads();
