@@ -29,28 +29,32 @@ __global__ void __launch_bounds__(kLT) logits_softmax_kernel(const T* __restrict
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       const int f0 = (lane + 64 * c) * 8;
-      if (f0 < F) load8(xr + f0, xv[c]);
-      else
+      if (c * 512 < F) load8(xr + (f0 < F ? f0 : 0), xv[c]);   // uniform condition: the chunks load together
+      if (f0 >= F)
 #pragma unroll
         for (int e = 0; e < 8; ++e) xv[c][e] = 0.f;
     }
     for (int j0 = wave; j0 < K; j0 += 4 * (kLT / 64)) {
       float acc[4] = {0.f, 0.f, 0.f, 0.f};
+      // Unconditional loads, so that the four classes' weight pieces are in flight together (under
+      // per-lane conditions the compiler waits for every load before it issues the next): a class
+      // past the end re-reads the last one (its logit is not stored), a lane past the end of the
+      // features reads the row's start against features that are zero.
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int j = j0 + q * (kLT / 64);
-        if (j < K) {
+      for (int c = 0; c < 4; ++c) {
+        if (c * 512 >= F) break;           // uniform
+        const int f0 = (lane + 64 * c) * 8;
+        const int fl = f0 < F ? f0 : 0;
+        float wv[4][8];
 #pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            const int f0 = (lane + 64 * c) * 8;
-            if (f0 < F) {
-              float wv[8];
-              load8(W + (size_t)j * F + f0, wv);
-#pragma unroll
-              for (int e = 0; e < 8; ++e) acc[q] = fmaf(xv[c][e], wv[e], acc[q]);
-            }
-          }
+        for (int q = 0; q < 4; ++q) {
+          const int j = min(j0 + q * (kLT / 64), K - 1);
+          load8(W + (size_t)j * F + fl, wv[q]);
         }
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[q] = fmaf(xv[c][e], wv[q][e], acc[q]);
       }
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
