@@ -74,22 +74,26 @@ __device__ __forceinline__ void finalize_sums(const float* __restrict__ part, in
   double s1 = 0.0, s2 = 0.0;
   const float* p1 = part + ((size_t)0 * C + c) * nb;
   const float* p2 = part + ((size_t)1 * C + c) * nb;
-  // eight partials per round, all loads issued before the first add (an index past the end
-  // re-reads the lane's first partial and counts as zero); same order of additions as a plain loop
-  for (int b0 = lane; b0 < nb; b0 += 8 * 64) {
+  // up to eight partials per round, all loads issued before the first add (an index past the end
+  // is not loaded and adds zero); same order of additions as a plain loop
+  const int rounds = (nb + 63) / 64;
+  for (int k0 = 0; k0 < rounds; k0 += 8) {
     float v1[8], v2[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
-      const int b = b0 + k * 64 < nb ? b0 + k * 64 : lane;
-      v1[k] = p1[b];
-      v2[k] = p2[b];
+      const int b = lane + (k0 + k) * 64;
+      v1[k] = v2[k] = 0.f;
+      if (b < nb) {
+        v1[k] = p1[b];
+        v2[k] = p2[b];
+      }
     }
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const bool in = b0 + k * 64 < nb;
-      s1 += in ? (double)v1[k] : 0.0;
-      s2 += in ? (double)v2[k] : 0.0;
-    }
+    for (int k = 0; k < 8; ++k)
+      if (k0 + k < rounds) {
+        s1 += (double)v1[k];
+        s2 += (double)v2[k];
+      }
   }
   *s1_out = wave_sum_f64(s1);
   *s2_out = wave_sum_f64(s2);
@@ -204,20 +208,24 @@ __device__ __forceinline__ void finalize_sums_wide(const float* __restrict__ par
   const float* p1 = part + ((size_t)0 * C + c) * nb;
   const float* p2 = part + ((size_t)1 * C + c) * nb;
   double s1 = 0.0, s2 = 0.0;
-  for (int b0 = tid; b0 < nb; b0 += 8 * kT) {   // eight partials per round, as above
+  const int rounds = (nb + kT - 1) / kT;       // up to eight partials per round, as above
+  for (int k0 = 0; k0 < rounds; k0 += 8) {
     float v1[8], v2[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
-      const int b = b0 + k * kT < nb ? b0 + k * kT : tid;
-      v1[k] = p1[b];
-      v2[k] = p2[b];
+      const int b = tid + (k0 + k) * kT;
+      v1[k] = v2[k] = 0.f;
+      if (b < nb) {
+        v1[k] = p1[b];
+        v2[k] = p2[b];
+      }
     }
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const bool in = b0 + k * kT < nb;
-      s1 += in ? (double)v1[k] : 0.0;
-      s2 += in ? (double)v2[k] : 0.0;
-    }
+    for (int k = 0; k < 8; ++k)
+      if (k0 + k < rounds) {
+        s1 += (double)v1[k];
+        s2 += (double)v2[k];
+      }
   }
   s1 = wave_sum_f64(s1);
   s2 = wave_sum_f64(s2);

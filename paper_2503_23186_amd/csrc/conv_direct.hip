@@ -128,22 +128,22 @@ __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __res
     vv = *reinterpret_cast<const float4*>(sg.v + (size_t)i4 * 4);
   }
   if (i4 < n4) {
-    // eight partials per round, all loads issued before the first add (a partial past the end
-    // re-reads this thread's first one and counts as zero): the sum is a chain of memory
-    // latencies otherwise.  Same order of additions as a plain loop.
+    // up to eight partials per round, all loads issued before the first add: the sum is a chain of
+    // memory latencies otherwise (a partial past the end is not loaded and adds zero).  Same order
+    // of additions as a plain loop.
     const float* base = part + (size_t)i4 * 4;
-    for (int p0 = grp; p0 < P; p0 += 8 * GROUPS) {
+    const int rounds = (P + GROUPS - 1) / GROUPS;
+    for (int k0 = 0; k0 < rounds; k0 += 8) {
       float4 v[8];
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
-        const int p = p0 + k * GROUPS;
-        v[k] = *reinterpret_cast<const float4*>(base + (size_t)(p < P ? p : grp) * n);
+        const int p = grp + (k0 + k) * GROUPS;
+        v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (p < P) v[k] = *reinterpret_cast<const float4*>(base + (size_t)p * n);
       }
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        const bool in = p0 + k * GROUPS < P;
-        acc.x += in ? v[k].x : 0.f; acc.y += in ? v[k].y : 0.f; acc.z += in ? v[k].z : 0.f; acc.w += in ? v[k].w : 0.f;
-      }
+      for (int k = 0; k < 8; ++k)
+        if (k0 + k < rounds) { acc.x += v[k].x; acc.y += v[k].y; acc.z += v[k].z; acc.w += v[k].w; }
     }
   }
   red[grp][col] = acc;

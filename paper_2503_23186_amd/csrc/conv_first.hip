@@ -244,17 +244,20 @@ __global__ void __launch_bounds__(256) first_wgrad_reduce_kernel(const float* __
   const int total = TN * 16 * 64;
   float acc = 0.f;
   if (a < total) {
-    // sixteen partials per round, all loads issued before the first add (a partial past the end
-    // re-reads the first one and counts as zero); same order of additions as a plain loop
-    for (int p0 = grp; p0 < P; p0 += 16 * 16) {
+    // up to sixteen partials per round, all loads issued before the first add (a partial past the
+    // end is not loaded and adds zero); same order of additions as a plain loop
+    const int rounds = (P + 15) / 16;
+    for (int k0 = 0; k0 < rounds; k0 += 16) {
       float v[16];
 #pragma unroll
       for (int k = 0; k < 16; ++k) {
-        const int p = p0 + k * 16;
-        v[k] = part[(size_t)(p < P ? p : grp) * total + a];
+        const int p = grp + (k0 + k) * 16;
+        v[k] = 0.f;
+        if (p < P) v[k] = part[(size_t)p * total + a];
       }
 #pragma unroll
-      for (int k = 0; k < 16; ++k) acc += p0 + k * 16 < P ? v[k] : 0.f;
+      for (int k = 0; k < 16; ++k)
+        if (k0 + k < rounds) acc += v[k];
     }
   }
   red[grp][e] = acc;

@@ -38,16 +38,20 @@ __global__ void __launch_bounds__(256) reduce_unpad_kernel(const float* __restri
   float a = 0.f;
   if (i < rows * C) {
     const size_t src = (size_t)(i / C) * 8 + i % C;
-    // eight partials per round, all loads issued before the first add
-    for (int p0 = grp; p0 < P; p0 += 8 * 16) {
+    // up to eight partials per round, all loads issued before the first add (a partial past the end
+    // is not loaded and adds zero)
+    const int rounds = (P + 15) / 16;
+    for (int k0 = 0; k0 < rounds; k0 += 8) {
       float v[8];
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
-        const int p = p0 + k * 16;
-        v[k] = part[(size_t)(p < P ? p : grp) * n8 + src];
+        const int p = grp + (k0 + k) * 16;
+        v[k] = 0.f;
+        if (p < P) v[k] = part[(size_t)p * n8 + src];
       }
 #pragma unroll
-      for (int k = 0; k < 8; ++k) a += p0 + k * 16 < P ? v[k] : 0.f;
+      for (int k = 0; k < 8; ++k)
+        if (k0 + k < rounds) a += v[k];
     }
   }
   red[grp][e] = a;
