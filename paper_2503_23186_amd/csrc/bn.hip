@@ -428,10 +428,12 @@ __global__ void __launch_bounds__(kT) bwd_partial_kernel(const T* __restrict__ d
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           acc[0][e] += g[k][e];
-          acc[1][e] = fmaf(g[k][e], (xv[k][e] - mu[e]) * is[e], acc[1][e]);
+          acc[1][e] = fmaf(g[k][e], xv[k][e] - mu[e], acc[1][e]);   // times invstd once, below
         }
       }
     });
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[1][e] *= is[e];
   }
   block_reduce_store<2>(acc, lanes, rows, C, part);
 }
@@ -480,7 +482,7 @@ __global__ void __launch_bounds__(kT) bwd_apply_kernel(const T* __restrict__ dy,
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       a[e] = ga[e] * is[e];
-      dgm[e] = dg[e] * inv_m;
+      dgm[e] = dg[e] * inv_m * is[e];   // xhat * dgamma / m = (x - mu) * (invstd * dgamma / m)
       dbm[e] = db[e] * inv_m;
     }
     if (MODE == 2) {
@@ -515,8 +517,7 @@ __global__ void __launch_bounds__(kT) bwd_apply_kernel(const T* __restrict__ dy,
       }
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const float xh = (xv[k][e] - mu[e]) * is[e];
-        out[e] = a[e] * (g[k][e] - fmaf(xh, dgm[e], dbm[e]));
+        out[e] = a[e] * (g[k][e] - fmaf(xv[k][e] - mu[e], dgm[e], dbm[e]));
       }
       if (flags & 1) {
         float old[8];
