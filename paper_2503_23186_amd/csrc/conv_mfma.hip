@@ -366,9 +366,17 @@ __global__ void __launch_bounds__(256) transpose_weights_multi_kernel(TransposeT
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
   const bf16_t* src = t.src[k];
   bf16_t* dst = t.dst[k];
+  // unconditional loads (an element outside the tensor reads element 0 and is never written out),
+  // so that the four are in flight together
+  bf16_t v[4];
 #pragma unroll
-  for (int r = ty; r < 32; r += 8)
-    if (k0 + r < Cout && c0 + tx < Cin) tile[r][tx] = src[((size_t)(k0 + r) * T + tap) * Cin + c0 + tx];
+  for (int q = 0; q < 4; ++q) {
+    const int r = ty + q * 8;
+    const bool ok = k0 + r < Cout && c0 + tx < Cin;
+    v[q] = src[ok ? ((size_t)(k0 + r) * T + tap) * Cin + c0 + tx : (size_t)0];
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q) tile[ty + q * 8][tx] = v[q];
   __syncthreads();
 #pragma unroll
   for (int r = ty; r < 32; r += 8)
