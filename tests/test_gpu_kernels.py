@@ -137,7 +137,7 @@ WG_SHAPES = [(4, 8, 8, 64, 128), (3, 16, 16, 64, 64), (2, 32, 32, 128, 64), (18,
 
 
 @pytest.mark.parametrize("staging", [0, -1])
-@pytest.mark.parametrize("target", [1, 4, 0])
+@pytest.mark.parametrize("target", [1, 2, 3, 4, 0])   # 2, 3: fewer partials than the reduce has thread groups
 @pytest.mark.parametrize("shape", WG_SHAPES)
 def test_conv_wgrad_patch_kernel(K, shape, target, staging):
     """3x3 stride-1 weight gradient through the LDS-patch kernels (tiles loaded straight into LDS,
