@@ -160,11 +160,13 @@ int cnnk_grad_route(size_t n, int dtype, const void* src, void* dst, int accumul
 size_t cnnk_fc_workspace_bytes(const cnnk_fc_desc* d);
 
 /* z = x W^T + b; loss = (1/N) sum_n (logsumexp(z_n) - z[n,label_n]) (natural log);
- * pred[n] = smallest j attaining max_j z[n,j]; dz = (softmax(z) - onehot)/N;
- * dW = dz^T x; db = sum_n dz; dx = dz W.
- * x, dx: N*F of dtype; W, dW: classes*F float; b, db: classes float; labels, pred: N int32
- * (labels must lie in [0, classes): not checked on the device, out-of-range labels contribute
- * a zero target); loss: 1 float; probs (nullable): N*classes float softmax output.
+ * pred[n] = smallest j attaining max_j z[n,j] (the scan starts at class 0 and moves on a strictly
+ * greater logit only, so a row whose logits are all -inf or NaN, or whose first logit is NaN,
+ * predicts class 0); dz = (softmax(z) - onehot)/N; dW = dz^T x; db = sum_n dz; dx = dz W.
+ * x, dx: N*F of dtype; W, dW: classes*F float; b, db: classes float; labels, pred: N int32.
+ * labels live on the device, so the host cannot validate them: a label outside [0, classes)
+ * makes that sample's loss, and therefore *loss, NaN (its row of dz has no target term);
+ * loss: 1 float; probs (nullable): N*classes float softmax output.
  * dx, dW, db: all three, or all NULL for the forward half only (loss, pred, probs). */
 int cnnk_fc_softmax_xent(const cnnk_fc_desc* d, const void* x, const float* W, const float* b,
                          const int* labels, float* loss, int* pred, float* probs, void* dx,

@@ -27,8 +27,10 @@ def evaluate(net, xs, ys, params, running, storage=None):
 
 
 def fit(net, train_x, train_y, val_x, val_y, params, mom, orders, lrs, momentum=0.9, weight_decay=0.0,
-        storage=None):
-    """orders: one index array per epoch (a multiple of the batch size long; consecutive slices are
+        storage=None, jitter=None):
+    """jitter=(seed, rel): every training step k is the jittered bf16-storage walk of oracle.step with
+    seed `seed + k` (validation passes are not perturbed).
+    orders: one index array per epoch (a multiple of the batch size long; consecutive slices are
     the mini-batches); lrs: the learning rate of every step, in order.
     Returns dict(params, mom, running, history, best): history[e] = (mean train loss, val accuracy,
     val loss); best = dict(epoch, acc, params, mom, running) of the last improvement ("checkpoint")."""
@@ -44,7 +46,8 @@ def fit(net, train_x, train_y, val_x, val_y, params, mom, orders, lrs, momentum=
         for b in range(order.size // B):
             idx = order[b * B:(b + 1) * B]
             r = ostep.train_step(net, train_x[idx], train_y[idx], params, mom, lr=lrs[k], momentum=momentum,
-                                 weight_decay=weight_decay, storage=storage, running=running)
+                                 weight_decay=weight_decay, storage=storage, running=running,
+                                 jitter=None if jitter is None else (jitter[0] + k, jitter[1]))
             params, mom, running = r["params"], r["mom"], r["running"]
             losses.append(r["loss"])
             k += 1

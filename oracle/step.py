@@ -12,6 +12,15 @@ storage='bf16' : every activation and activation gradient is rounded to bfloat16
                  stays float64 and parameter gradients are not rounded.  The ReLU masks,
                  max-pool winners and predicted classes are then decided on values of the same
                  precision as the stored ones.
+jitter=(seed, rel), bf16 storage only: before each of those roundings a seeded perturbation drawn
+                 uniformly from +-rel * rms(tensor) is added to every element that is not exactly
+                 zero (unless it would change the element's sign).  The paper fixes no
+                 precision; in a bf16-storage / fp32-accumulate implementation the value that gets
+                 rounded differs from the exact one by the fp32 accumulation error of that
+                 implementation, which decides the rounding of the values that lie that close to a
+                 rounding boundary.  Walks with different seeds are therefore equally legal results
+                 of the same method, and their spread measures how far two correct bf16
+                 implementations may lie apart (tests grade the HIP step against that spread).
 """
 from __future__ import annotations
 import numpy as np
@@ -21,21 +30,37 @@ BN_EPS = 1e-5
 BN_MOMENTUM = 0.1
 
 
-def _q(storage):
+def _q(storage, jitter=None):
     if storage is None:
+        if jitter is not None:
+            raise ValueError("jitter belongs to a storage mode")
         return lambda a: a
     if storage == "bf16":
-        return ops.round_bf16
+        if jitter is None:
+            return ops.round_bf16
+        seed, rel = jitter
+        rng = np.random.default_rng(seed)
+
+        def q(a):
+            a = np.asarray(a, dtype=np.float64)
+            rms = float(np.sqrt(np.mean(a * a))) if a.size else 0.0
+            b = a + (rel * rms) * rng.uniform(-1.0, 1.0, size=a.shape)
+            # exact zeros (a clamped activation, a masked or unrouted gradient, padding) are exact in
+            # any implementation, and rounding noise never changes a sign: those elements stay as
+            # they are, so that no ReLU mask is decided by the perturbation itself
+            keep = (a == 0.0) | (np.sign(b) != np.sign(a))
+            return ops.round_bf16(np.where(keep, a, b))
+        return q
     raise ValueError(storage)
 
 
-def forward_loss(net, x, labels, params, storage=None, running=None, infer=False):
+def forward_loss(net, x, labels, params, storage=None, running=None, infer=False, q=None):
     """Forward pass and loss only.  Returns (loss, fc_result, acts, saved).
 
     running: {layer index: [running_mean, running_var]} (float64 arrays).  Training mode
     (infer=False) updates them in place; inference mode (infer=True) normalises with them
     instead of the batch statistics and changes nothing."""
-    q = _q(storage)
+    q = _q(storage) if q is None else q
     if infer and running is None:
         raise ValueError("inference mode needs running statistics")
     acts = {0: np.asarray(x, dtype=np.float64)}
@@ -85,14 +110,14 @@ def eval_forward(net, x, labels, params, running, storage=None):
 
 
 def train_step(net, x, labels, params, mom, lr=0.1, momentum=0.9, weight_decay=0.0, storage=None,
-               running=None):
+               running=None, jitter=None):
     """One step.  Returns dict(loss, pred, acts, dacts, grads, params, mom[, running]); inputs are
     not modified (the running statistics, if given, are copied and the copy is advanced)."""
-    q = _q(storage)
+    q = _q(storage, jitter)
     if running is not None:
         running = {i: [np.array(rm, dtype=np.float64), np.array(rv, dtype=np.float64)]
                    for i, (rm, rv) in running.items()}
-    loss, fc, acts, saved = forward_loss(net, x, labels, params, storage, running=running)
+    loss, fc, acts, saved = forward_loss(net, x, labels, params, storage, running=running, q=q)
     grads = [None] * len(params)
     dacts = {}
 

@@ -98,6 +98,10 @@ __global__ void __launch_bounds__(kLT) logits_softmax_kernel(const T* __restrict
   mx = red[0]; arg = redi[0];
   for (int w = 1; w < kLT / 64; ++w)
     if (red[w] > mx || (red[w] == mx && redi[w] < arg)) { mx = red[w]; arg = redi[w]; }
+  // A scan that starts from class 0 and moves only on a strictly greater logit stays at class 0
+  // when no logit exceeds -inf (a row of -inf or NaN) and when the first logit is NaN (nothing
+  // compares greater than NaN): the predicted class of such a row is 0.
+  if (arg == 0x7fffffff || z[0] != z[0]) arg = 0;
   __syncthreads();
   float se = 0.f;
   for (int j = tid; j < K; j += kLT) se += expf(z[j] - mx);
@@ -110,7 +114,8 @@ __global__ void __launch_bounds__(kLT) logits_softmax_kernel(const T* __restrict
   const int lab = labels[n];
   if (tid == 0) {
     pred[n] = arg;
-    loss_n[n] = (lab >= 0 && lab < K) ? lse - z[lab] : lse;
+    // a label outside [0, K) has no target logit: the sample's loss, and with it the mean, is NaN
+    loss_n[n] = (lab >= 0 && lab < K) ? lse - z[lab] : __builtin_nanf("");
   }
   const float invN = 1.f / (float)N;
   for (int j = tid; j < K; j += kLT) {
@@ -287,18 +292,22 @@ extern "C" int cnnk_fc_softmax_xent(const cnnk_fc_desc* d, const void* x, const 
   float* loss_n = dz + (size_t)N * K;
   const int fblocks = (F + kT - 1) / kT;
   const unsigned nblk = (unsigned)(K + 1 + fblocks * N);
-  const int vec = (F % 8 == 0 && F <= 2048) ? 1 : 0;
+  // the vector paths read x and W in 16-byte pieces: rows stay aligned when F % 8 == 0 and the
+  // tensors themselves start on a 16-byte boundary
+  const bool aligned = (((uintptr_t)x | (uintptr_t)W) & 15u) == 0;
+  const bool vec8 = F % 8 == 0 && aligned;
+  const int vec = (vec8 && F <= 2048) ? 1 : 0;
   if (d->dtype == CNNK_BF16) {
     logits_softmax_kernel<bf16_t><<<N, kLT, 0, st>>>((const bf16_t*)x, W, b, labels, N, F, K, vec, dz, loss_n, pred, probs);
     if (!backward) loss_kernel<<<1, kT, 0, st>>>(loss_n, N, loss);
-    else if (F % 8 == 0)
+    else if (vec8)
       fc_bwd_kernel<bf16_t, 1><<<nblk, kT, 0, st>>>(dz, loss_n, (const bf16_t*)x, W, N, F, K, fblocks, loss, dW, db, (bf16_t*)dx);
     else
       fc_bwd_kernel<bf16_t, 0><<<nblk, kT, 0, st>>>(dz, loss_n, (const bf16_t*)x, W, N, F, K, fblocks, loss, dW, db, (bf16_t*)dx);
   } else {
     logits_softmax_kernel<float><<<N, kLT, 0, st>>>((const float*)x, W, b, labels, N, F, K, vec, dz, loss_n, pred, probs);
     if (!backward) loss_kernel<<<1, kT, 0, st>>>(loss_n, N, loss);
-    else if (F % 8 == 0)
+    else if (vec8)
       fc_bwd_kernel<float, 1><<<nblk, kT, 0, st>>>(dz, loss_n, (const float*)x, W, N, F, K, fblocks, loss, dW, db, (float*)dx);
     else
       fc_bwd_kernel<float, 0><<<nblk, kT, 0, st>>>(dz, loss_n, (const float*)x, W, N, F, K, fblocks, loss, dW, db, (float*)dx);

@@ -1,13 +1,17 @@
 """Full-size parity: the benchmark workload's shapes, in the launch configuration bench.py times.
 
-The oracle cannot walk batch 256 inside a test, so:
-  * the hot kernels run at their full ResNet-18 batch-256 shapes and are checked on sampled
-    outputs that the oracle computes one by one (its own routines on cropped operands), BN on
-    the whole tensor;
-  * the whole step (two streams, as bench.py runs it) is checked against a small fixture that
-    tests/golden/make_resnet18_b256_fixture.py wrote from the oracle alone: the loss, and per
-    tensor the norm and 24 sampled values of the float64 walk plus the oracle's own bf16-storage
-    walk, which measures the floor any bf16 implementation sits on (see test_gpu_step.py).
+  * every convolution shape of the benchmark (ResNet-18, batch 256) on seeded inputs: the whole y,
+    the per-channel sums, the whole dx and the whole dw against the oracle, element by element;
+  * the distinct shapes of the other configurations at their full batch: the whole y and the sums,
+    dx and dw on sampled outputs that the oracle computes one by one (its own routines on cropped
+    operands; the oracle's definition-order loops need minutes per whole gradient at these sizes);
+  * every layer of the benchmark network at batch 256, and of the VGG-style network at batch 128,
+    run on the tensors of the oracle's own bf16-storage walk and compared on whole outputs
+    (activations, activation gradients, parameter gradients; test_gpu_layers.py's case at full
+    batch), so that both sides take every decision on identical inputs;
+  * batch norm on whole full-size tensors;
+  * the whole two-stream step against a fixture that tests/golden/make_resnet18_b256_fixture.py
+    wrote from the oracle alone (a chaining check at full size: loss, per-tensor norms).
 """
 import json
 import os
@@ -54,8 +58,7 @@ OTHER_FULL_CONVS = [(256, 32, 32, 64, 256, 1, 1), (256, 32, 32, 256, 64, 1, 1), 
                     (128, 16, 16, 64, 128, 3, 1)]
 
 
-@pytest.mark.parametrize("shape", FULL_CONVS + OTHER_FULL_CONVS)
-def test_conv_full_size_sampled(K, shape):
+def _full_conv_case(K, shape, whole_gradients):
     N, H, W, Cin, Cout, R, st = shape
     pad = R // 2
     rng = np.random.default_rng(77)
@@ -70,24 +73,28 @@ def test_conv_full_size_sampled(K, shape):
     gy = torch.empty((N, Ho, Wo, Cout), dtype=torch.bfloat16, device="cuda:0")
     gdx = torch.empty((N, H, W, Cin), dtype=torch.bfloat16, device="cuda:0")
     gdw = torch.empty((Cout, R, R, Cin), dtype=torch.float32, device="cuda:0")
-    K.cnnk_conv2d_fwd(d, gx, gw, gy, None, None, ws, nb)
+    s1 = torch.zeros(Cout, device="cuda:0"); s2 = torch.zeros(Cout, device="cuda:0")
+    K.cnnk_conv2d_fwd(d, gx, gw, gy, s1, s2, ws, nb)
+    torch.cuda.synchronize()
+    stats = host(s1), host(s2)
     K.cnnk_conv2d_wgrad(d, gx, gdy, gdw, ws, nb)
     K.cnnk_conv2d_dgrad(d, gdy, gw, gdx, 0, ws, nb)
     torch.cuda.synchronize()
     y, dx, dw = host(gy), host(gdx), host(gdw)
+
+    # forward: every output element (one bf16 rounding of the fp32 accumulator), and the per-channel
+    # sums of the accumulators that the following batch norm consumes
+    y_ref = ref.conv2d_fwd(x, w, st, pad)
+    assert max_rel_err(y, y_ref) <= 4e-3
+    assert max_rel_err(stats[0], y_ref.reshape(-1, Cout).sum(0)) <= 1e-4
+    assert max_rel_err(stats[1], (y_ref ** 2).reshape(-1, Cout).sum(0)) <= 1e-4
+    del y_ref
+    if whole_gradients:
+        assert max_rel_err(dx, ref.conv2d_dgrad(dy, w, x.shape, st, pad)) <= 4e-3
+        # fp32 sums of up to 2.6e5 products, split over workgroups and reduced in a fixed order
+        assert max_rel_err(dw, ref.conv2d_wgrad(x, dy, w.shape, st, pad)) <= 1e-4
+        return
     xp = np.pad(x, ((0, 0), (pad, pad), (pad, pad), (0, 0)))
-
-    # forward: one output pixel (all channels) = the oracle's convolution of the R x R window
-    got, want = [], []
-    for _ in range(96):
-        n, ho, wo = int(rng.integers(N)), int(rng.integers(Ho)), int(rng.integers(Wo))
-        if _ < 8:   # corners and edges first
-            n, ho, wo = [0, N - 1][_ & 1], [0, Ho - 1][(_ >> 1) & 1], [0, Wo - 1][(_ >> 2) & 1]
-        win = xp[n:n + 1, ho * st:ho * st + R, wo * st:wo * st + R, :]
-        want.append(ref.conv2d_fwd(win, w, 1, 0)[0, 0, 0, :])
-        got.append(y[n, ho, wo, :])
-    assert max_rel_err(np.array(got), np.array(want)) <= 1e-2
-
     # data gradient: one input pixel (all channels) needs the dy positions that its R x R
     # neighbourhood of outputs covers: the oracle's dgrad on that crop, embedded with its offset
     got, want = [], []
@@ -107,8 +114,7 @@ def test_conv_full_size_sampled(K, shape):
         dxc = ref.conv2d_dgrad(dyc, w, (1, hh, ww, Cin), st, 0)
         want.append(dxc[0, h - r0, wi - c0, :])
         got.append(dx[n, h, wi, :])
-    assert max_rel_err(np.array(got), np.array(want)) <= 1e-2
-
+    assert max_rel_err(np.array(got), np.array(want)) <= 4e-3
     # weight gradient: one (k, c) pair (all taps) = the oracle's wgrad on single-channel slices,
     # a reduction over all N*Ho*Wo positions
     got, want = [], []
@@ -117,7 +123,38 @@ def test_conv_full_size_sampled(K, shape):
         dwk = ref.conv2d_wgrad(x[..., c:c + 1], dy[..., k:k + 1], (1, R, R, 1), st, pad)
         want.append(dwk[0, :, :, 0])
         got.append(dw[k, :, :, c])
-    assert max_rel_err(np.array(got), np.array(want)) <= 1e-4 * 20   # fp32 sums over 2.6e5 bf16 products
+    assert max_rel_err(np.array(got), np.array(want)) <= 1e-4
+    del xp
+
+
+@pytest.mark.parametrize("shape", FULL_CONVS)
+def test_conv_full_size_whole_tensors(K, shape):
+    """The benchmark's convolution shapes at batch 256, in the launch configuration the library
+    picks there (the 3x3 stride-1 kernels walk two pixel tiles per workgroup only at this size):
+    every element of y, dx and dw, and the per-channel sums."""
+    _full_conv_case(K, shape, whole_gradients=True)
+
+
+@pytest.mark.parametrize("shape", OTHER_FULL_CONVS)
+def test_conv_full_size_other_configurations(K, shape):
+    """The other configurations' distinct shapes at their full batch: every element of y and the
+    per-channel sums; dx and dw on sampled outputs."""
+    _full_conv_case(K, shape, whole_gradients=False)
+
+
+def test_every_layer_of_the_benchmark_step_at_batch_256():
+    """ResNet-18 at batch 256 (the benchmark workload): the oracle walks the whole step with bf16
+    stores, every layer's HIP kernels then run on the oracle's tensors and whole outputs are
+    compared (activations, activation gradients and parameter gradients within one bf16 unit in
+    the last place / 2e-4 for fp32 sums; pool winners and masked residual gradients bit exact)."""
+    from test_gpu_layers import layerwise_case
+    layerwise_case("resnet18_b256", WL.build_config(3), 3)
+
+
+def test_every_layer_of_the_vgg_step_at_batch_128():
+    """The VGG-style configuration at its full batch, same check (its max-pool layers included)."""
+    from test_gpu_layers import layerwise_case
+    layerwise_case("vgg_b128", WL.build_config(2), 2)
 
 
 @pytest.mark.parametrize("shape", [(256, 32, 32, 64), (256, 8, 8, 1024), (256, 4, 4, 2048), (128, 32, 32, 160)])
@@ -154,7 +191,12 @@ def test_bn_full_size(K, shape):
 
 
 def test_step_full_size_against_fixture():
-    """One step of the benchmark workload exactly as bench.py runs it (config 3, two streams)."""
+    """One step of the benchmark workload exactly as bench.py runs it (config 3, two streams): a
+    check of the chaining at full size (tape order, forks, accumulation, the second stream).  The
+    fixture holds, per tensor, the norm of the oracle's float64 result and the relative L2 distance
+    f of the oracle's own bf16-storage walk from it.  A result within f of the float64 one has a
+    norm within f of its norm (triangle inequality), so the HIP step's norms are graded at
+    f + 2e-2, the loss at 2e-2.  Element-wise parity at this size is the layer-wise test above."""
     from paper_2503_23186_amd import StepRunner
     with open(GOLDEN) as f:
         G = json.load(f)
@@ -176,21 +218,13 @@ def test_step_full_size_against_fixture():
         buf = {"act": run.act, "dact": run.dact, "grad": run.grad}[kind][idx]
         flat = buf.reshape(-1)
         assert flat.numel() == t["size"], name
-        pos = torch.tensor(t["pos"], device=flat.device)
-        got = flat[pos].to(torch.float64).cpu().numpy()
-        pure, emu = np.array(t["pure"]), np.array(t["bf16_storage"])
-        norm = float(torch.linalg.vector_norm(flat.to(torch.float32)).item())
-        # the norm over the whole tensor, and the sampled values, no farther from the float64 walk
-        # than 1.5x the oracle's own bf16-storage walk (plus the bf16 bar)
-        floor = t["floor_l2"]
+        assert bool(torch.isfinite(flat).all()), name
+        norm = float(torch.linalg.vector_norm(flat.to(torch.float64)).item())
         nerr = abs(norm / max(t["l2"], 1e-300) - 1.0)
-        scale = max(t["max"], 1e-300)
-        serr = float(np.max(np.abs(got - pure))) / scale
-        sfloor = float(np.max(np.abs(emu - pure))) / scale
-        worst[kind] = max(worst.get(kind, 0.0), nerr)
-        assert nerr <= 1.5 * floor + 2e-2, (name, nerr, floor)
-        assert serr <= 1.5 * sfloor + 4.0 * floor * (t["l2"] / np.sqrt(t["size"])) / scale + 2e-2, (name, serr, sfloor)
-    print("worst norm deviation per class:", {k: "%.1e" % v for k, v in worst.items()})
+        worst[kind] = max(worst.get(kind, 0.0), nerr - t["floor_l2"])
+        assert nerr <= t["floor_l2"] + 2e-2, (name, nerr, t["floor_l2"])
+    print("worst norm deviation beyond the oracle's own bf16 distance, per class:",
+          {k: "%.1e" % v for k, v in worst.items()})
 
 
 def test_conv_beyond_2gib_falls_back(K):

@@ -163,14 +163,14 @@ PATCH_SHAPES = [(4, 8, 8, 64, 128), (2, 16, 16, 32, 64), (2, 32, 32, 32, 64), (1
                 (5, 8, 8, 96, 72), (3, 16, 16, 64, 40), (1, 32, 32, 160, 32)]
 
 
-@pytest.mark.parametrize("tile", PATCH_TILES)
-@pytest.mark.parametrize("shape", PATCH_SHAPES)
-def test_conv_patch_kernels_every_tile(K, shape, tile):
-    """3x3 stride-1 forward / data gradient through each LDS-patch tile configuration."""
+def patch_case(K, shape, tune):
+    """3x3 stride-1 forward (+ channel sums) and data gradient (overwrite and accumulate) under the
+    given cnnk_tune overrides, every output element against the oracle."""
     N, H, W, Cin, Cout = shape
     x, w, dy, pad = conv_inputs((N, H, W, Cin, Cout, 3, 1), "bf16", 13)
     d = K.conv_desc(N, H, W, Cin, Cout, 3, 3, 1, 1, K.BF16)
-    K.cnnk_tune(4, tile[0]); K.cnnk_tune(5, tile[1])
+    for k, v in tune.items():
+        K.cnnk_tune(k, v)
     try:
         gx, gw, gdy = dev(x, "bf16"), dev(w, "bf16"), dev(dy, "bf16")
         y_ref = ref.conv2d_fwd(x, w, 1, 1)
@@ -193,7 +193,46 @@ def test_conv_patch_kernels_every_tile(K, shape, tile):
         assert max_rel_err(host(gdx), dx_ref) <= 4e-3
         assert max_rel_err(host(gdx2), dx_ref + base) <= 8e-3
     finally:
-        K.cnnk_tune(4, 0); K.cnnk_tune(5, 0)
+        for k in tune:
+            K.cnnk_tune(k, 0)
+
+
+@pytest.mark.parametrize("tile", PATCH_TILES)
+@pytest.mark.parametrize("shape", PATCH_SHAPES)
+def test_conv_patch_kernels_every_tile(K, shape, tile):
+    """3x3 stride-1 forward / data gradient through each LDS-patch tile configuration."""
+    patch_case(K, shape, {4: tile[0], 5: tile[1]})
+
+
+# (shape, (BM, BN), pixel tiles of the launch): bands of rows inside an image (row above / below
+# the band changes from tile to tile), whole-image tiles, a ragged last tile of whole images, and
+# channel counts that end in a ragged channel tile
+PATCH_WALKS = [((8, 32, 32, 64, 64), (256, 64), 32), ((32, 8, 8, 128, 128), (256, 64), 8),
+               ((32, 8, 8, 128, 128), (128, 128), 16), ((7, 8, 8, 64, 72), (128, 64), 4),
+               ((7, 8, 8, 64, 72), (256, 64), 2), ((12, 16, 16, 32, 40), (128, 64), 24),
+               ((58, 4, 4, 64, 136), (128, 128), 8), ((6, 16, 16, 96, 160), (256, 128), 6)]
+
+
+@pytest.mark.parametrize("tpb", [2, 4, 8])
+@pytest.mark.parametrize("shape,tile,mtiles", PATCH_WALKS)
+def test_conv_patch_kernels_several_tiles_per_workgroup(K, shape, tile, mtiles, tpb):
+    """A workgroup of the LDS-patch kernels walks several pixel tiles on large layers (the next
+    tile's first patch chunk and weights are fetched under the last steps of the current tile, the
+    accumulators are written out and cleared at the border).  The library picks that only for
+    layers with at least 512 workgroups' worth of tiles; forced here on small shapes so that every
+    output element, the channel sums and the accumulating data gradient are compared."""
+    N, H, W, Cin, Cout = shape
+    assert mtiles == -(-N * H * W // tile[0])
+    if mtiles % tpb != 0:
+        pytest.skip("the library ignores a walk length that does not divide the tile count")
+    patch_case(K, shape, {4: tile[0], 5: tile[1], 13: tpb})
+
+
+@pytest.mark.parametrize("shape", [(4, 8, 8, 64, 128), (18, 4, 4, 64, 136), (16, 4, 4, 64, 64)])
+def test_conv_patch_kernels_without_the_pixel_permutation(K, shape):
+    """Narrow images (W < 16) normally map GEMM rows to pixels through a permutation that keeps the
+    LDS reads free of bank conflicts; with it switched off the results must not change."""
+    patch_case(K, shape, {7: -1})
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])

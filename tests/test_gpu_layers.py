@@ -30,13 +30,20 @@ NETS = [
 
 @pytest.mark.parametrize("name,make,cid", NETS, ids=[n[0] for n in NETS])
 def test_every_layer_on_oracle_inputs(name, make, cid):
+    layerwise_case(name, make(), cid)
+
+
+def layerwise_case(name, net, cid):
+    """Walks `net` with the oracle, then runs every layer's HIP kernels on the oracle's tensors and
+    compares whole outputs (also used at the benchmark's full batch by test_gpu_fullsize.py)."""
     from paper_2503_23186_amd import cnnk as K
-    net = make()
     dtype = net.dtype
     dt = K.BF16 if dtype == "bf16" else K.F32
     st = "bf16" if dtype == "bf16" else None
     q = ref.round_bf16 if dtype == "bf16" else (lambda a: a)
-    out_tol = 1e-2 if dtype == "bf16" else 1e-5    # one bf16 unit in the last place of the largest element
+    # bf16 outputs: both sides round (nearly) the same value once, so they differ by at most one
+    # unit in the last place of an element, 2^-8 of the largest one
+    out_tol = 4e-3 if dtype == "bf16" else 1e-5
     acc_tol = 2e-4 if dtype == "bf16" else 2e-5
     inp = WL.make_inputs(net, cid, perturb_bn=True)
     o = oracle.train_step(net, inp["x"], inp["labels"], inp["params"], inp["mom"], storage=st)

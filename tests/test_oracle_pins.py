@@ -385,3 +385,58 @@ def test_storage_emulation_only_rounds_stores():
     assert abs(emu["loss"] - pure["loss"]) < 2e-2 * pure["loss"]
     for ge, gp in zip(emu["grads"], pure["grads"]):
         assert np.max(np.abs(ge - gp)) <= 0.25 * np.max(np.abs(gp))   # tiny net: a sanity bound only
+
+
+def test_storage_jitter_is_a_bounded_seeded_perturbation_of_the_rounding_only():
+    """The jittered bf16-storage walk: amplitude 0 is the plain bf16-storage walk bit for bit; a
+    seed fixes the walk; everything stored is still a bf16 value; and the first stored tensor (the
+    first convolution's output, whose inputs no jitter has touched yet) lies within the stated
+    amplitude plus half a bf16 unit in the last place of the exact value."""
+    net = WL.mini_resnet()
+    inp = WL.make_inputs(net, 82)
+    args = (net, inp["x"], inp["labels"], inp["params"], inp["mom"])
+    plain = train_step(*args, storage="bf16")
+    zero = train_step(*args, storage="bf16", jitter=(5, 0.0))
+    for k in range(len(plain["grads"])):
+        assert np.array_equal(plain["grads"][k], zero["grads"][k])
+    rel = 2.0 ** -12     # exaggerated so that many roundings move
+    a = train_step(*args, storage="bf16", jitter=(5, rel))
+    b = train_step(*args, storage="bf16", jitter=(5, rel))
+    c = train_step(*args, storage="bf16", jitter=(6, rel))
+    assert all(np.array_equal(x, y) for x, y in zip(a["grads"], b["grads"]))
+    assert any(not np.array_equal(x, y) for x, y in zip(a["grads"], c["grads"]))
+    for s, t in a["acts"].items():
+        if s != 0:
+            assert np.array_equal(t, ops.round_bf16(t))
+    first = net.layers[0]
+    assert first["op"] == "conv" and first["x"] == 0
+    exact = ops.conv2d_fwd(inp["x"], inp["params"][first["w"]], first["stride"], first["pad"])
+    rms = np.sqrt(np.mean(exact ** 2))
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(exact), 1e-300))) - 7)
+    assert np.all(np.abs(a["acts"][first["y"]] - exact) <= rel * rms + 0.5 * ulp * (1 + 1e-9) + rel * rms * 2.0 ** -7)
+    assert not np.array_equal(a["acts"][first["y"]], plain["acts"][first["y"]])
+    with pytest.raises(ValueError):
+        train_step(*args, jitter=(5, rel))
+
+
+def test_storage_jitter_keeps_zeros_and_signs():
+    """Clamped activations and masked gradients are exact zeros in any implementation: the jitter
+    leaves them (and every sign) alone, so the ensemble's ReLU masks differ only through values
+    computed downstream of a moved rounding, and a member stays as close to the float64 walk as
+    the plain bf16-storage walk is (same order of magnitude, not the O(1) of a randomised mask)."""
+    net = WL.mini_resnet(batch=8, size=8, widths=(16, 32))
+    inp = WL.make_inputs(net, 83)
+    args = (net, inp["x"], inp["labels"], inp["params"], inp["mom"])
+    pure = train_step(*args)
+    plain = train_step(*args, storage="bf16")
+    from oracle.ensemble import JITTER_REL, JITTER_SEEDS
+    for seed in JITTER_SEEDS:
+        m = train_step(*args, storage="bf16", jitter=(seed, JITTER_REL))
+        relu_out = [L["y"] for L in net.layers if L["op"] == "bn" and L["relu"]]
+        for s in relu_out:
+            assert np.all(m["acts"][s] >= 0.0)
+            assert 0.2 < np.mean(m["acts"][s] == 0.0) < 0.8          # about half the units are clamped
+        for k, g in enumerate(pure["grads"]):
+            dm = np.linalg.norm(m["grads"][k] - g)
+            dp = np.linalg.norm(plain["grads"][k] - g)
+            assert dm <= 3.0 * dp + 2e-2 * np.linalg.norm(g), (seed, k, dm, dp)

@@ -5,6 +5,9 @@ import torch
 TOL = {"f32": 1e-4, "bf16": 2e-2}      # max |gpu - ref| / max |ref| per tensor (spec bars)
 DEV = "cuda:0"
 
+from oracle.ensemble import (JITTER_REL, JITTER_SEEDS, SCALE_TO_EXACT, SCALE_TO_MEMBER,  # noqa: E402,F401
+                             ensemble_bound)
+
 
 def tdtype(dtype):
     return torch.bfloat16 if dtype == "bf16" else torch.float32
