@@ -172,6 +172,22 @@ int cnnk_fc_softmax_xent(const cnnk_fc_desc* d, const void* x, const float* W, c
                          const int* labels, float* loss, int* pred, float* probs, void* dx,
                          float* dW, float* db, void* ws, size_t ws_bytes, void* stream);
 
+/* The same operation for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc) and so have no workspace to hand
+ * over: identical arguments and results (the same kernels), but the scratch (N*classes + N floats)
+ * lives in an array inside the library's code object, CNNK_FC_STATIC_SCRATCH_BYTES per device,
+ * resident from the moment the library is loaded until the process ends.  The call allocates and
+ * frees nothing.  Shapes whose cnnk_fc_workspace_bytes exceeds that size are refused with
+ * CNNK_ERR_WORKSPACE and nothing is launched.  The device that `stream` belongs to must be the
+ * current device.  All calls on one device share the one array: two calls that may overlap in
+ * time on one device (different streams, or different host threads) race and must be ordered by
+ * the caller; calls on one stream are ordered by the stream.  Nothing in the array has to be
+ * cleared between calls: each call writes every element it later reads. */
+#define CNNK_FC_STATIC_SCRATCH_BYTES (1 << 20)
+int cnnk_fc_softmax_xent_static(const cnnk_fc_desc* d, const void* x, const float* W, const float* b,
+                                const int* labels, float* loss, int* pred, float* probs, void* dx,
+                                float* dW, float* db, void* stream);
+
 /* *n_correct += #{i < n : pred[i] == labels[i]} (device int; the caller zeroes it, so that the
  * count can run over several validation batches).  Integer addition: order-independent. */
 int cnnk_count_correct(int n, const int* pred, const int* labels, int* n_correct, void* stream);

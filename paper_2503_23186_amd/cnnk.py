@@ -20,7 +20,7 @@ OP_CONV, OP_BN, OP_POOL, OP_ADD, OP_FC_LOSS = 0, 1, 2, 3, 4
 EXPORTS = ["cnnk_status_string", "cnnk_version", "cnnk_tune", "cnnk_conv2d_workspace_bytes", "cnnk_conv2d_fwd",
            "cnnk_conv2d_dgrad", "cnnk_conv2d_wgrad", "cnnk_bn_workspace_bytes", "cnnk_bn_relu_fwd",
            "cnnk_bn_relu_infer", "cnnk_bn_relu_bwd", "cnnk_pool_fwd", "cnnk_pool_bwd", "cnnk_add", "cnnk_grad_route",
-           "cnnk_fc_workspace_bytes", "cnnk_fc_softmax_xent", "cnnk_count_correct", "cnnk_sgd_momentum",
+           "cnnk_fc_workspace_bytes", "cnnk_fc_softmax_xent", "cnnk_fc_softmax_xent_static", "cnnk_count_correct", "cnnk_sgd_momentum",
            "cnnk_train_step_workspace_bytes", "cnnk_train_step_event_groups", "cnnk_train_step",
            "cnnk_eval_step"]
 
@@ -96,6 +96,7 @@ def _load():
     lib.cnnk_fc_workspace_bytes.restype = sz
     lib.cnnk_fc_workspace_bytes.argtypes = [C.POINTER(FcDesc)]
     lib.cnnk_fc_softmax_xent.argtypes = [C.POINTER(FcDesc)] + [vp] * 10 + [vp, sz, vp]
+    lib.cnnk_fc_softmax_xent_static.argtypes = [C.POINTER(FcDesc)] + [vp] * 10 + [vp]
     lib.cnnk_count_correct.argtypes = [ci, vp, vp, vp, vp]
     lib.cnnk_sgd_momentum.argtypes = [sz, vp, vp, vp, vp, cf, cf, cf, vp]
     lib.cnnk_train_step_workspace_bytes.restype = sz
@@ -217,6 +218,15 @@ def cnnk_fc_softmax_xent(d, x, W, b, labels, loss, pred, probs, dx, dW, db, ws=N
     _check(lib.cnnk_fc_softmax_xent(C.byref(d), ptr(x), ptr(W), ptr(b), ptr(labels), ptr(loss), ptr(pred),
                                     ptr(probs), ptr(dx), ptr(dW), ptr(db), ptr(ws), ws_bytes, stream),
            "cnnk_fc_softmax_xent")
+
+
+FC_STATIC_SCRATCH_BYTES = 1 << 20
+
+
+def cnnk_fc_softmax_xent_static(d, x, W, b, labels, loss, pred, probs, dx, dW, db, stream=0):
+    _check(lib.cnnk_fc_softmax_xent_static(C.byref(d), ptr(x), ptr(W), ptr(b), ptr(labels), ptr(loss), ptr(pred),
+                                           ptr(probs), ptr(dx), ptr(dW), ptr(db), stream),
+           "cnnk_fc_softmax_xent_static")
 
 
 def cnnk_count_correct(n, pred, labels, n_correct, stream=0):

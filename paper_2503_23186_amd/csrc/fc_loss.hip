@@ -1,6 +1,7 @@
 // Classifier head: logits, softmax cross-entropy (mean over the batch, natural log), class
 // prediction, and the gradients of the head.  The work is tiny (N x F x classes); the kernels
 // are written for determinism: every sum has a fixed order, no atomics.
+#include <mutex>
 #include "common.h"
 
 namespace {
@@ -277,18 +278,15 @@ extern "C" size_t cnnk_fc_workspace_bytes(const cnnk_fc_desc* d) {
   return align_up(((size_t)d->N * d->classes + d->N) * sizeof(float), 256);
 }
 
-extern "C" int cnnk_fc_softmax_xent(const cnnk_fc_desc* d, const void* x, const float* W, const float* b,
-                                    const int* labels, float* loss, int* pred, float* probs, void* dx, float* dW,
-                                    float* db, void* ws, size_t ws_bytes, void* stream) {
-  int rc = validate_fc(d);
-  if (rc != CNNK_OK) return rc;
-  if (!x || !W || !b || !labels || !loss || !pred) return CNNK_ERR_NULL;
+namespace {
+// Both entry points of the classifier head: `scratch` holds dz (N * classes floats) and the
+// per-sample losses (N floats); every element is written by the first launch before the second
+// reads it, so its previous contents do not matter.
+int fc_enqueue(const cnnk_fc_desc* d, const void* x, const float* W, const float* b, const int* labels, float* loss,
+               int* pred, float* probs, void* dx, float* dW, float* db, float* scratch, hipStream_t st) {
   const bool backward = dx || dW || db;   // all three or none
-  if (backward && (!dx || !dW || !db)) return CNNK_ERR_NULL;
-  if (!ws || ws_bytes < cnnk_fc_workspace_bytes(d)) return CNNK_ERR_WORKSPACE;
-  hipStream_t st = (hipStream_t)stream;
   const int N = d->N, F = d->F, K = d->classes;
-  float* dz = (float*)ws;
+  float* dz = scratch;
   float* loss_n = dz + (size_t)N * K;
   const int fblocks = (F + kT - 1) / kT;
   const unsigned nblk = (unsigned)(K + 1 + fblocks * N);
@@ -313,6 +311,59 @@ extern "C" int cnnk_fc_softmax_xent(const cnnk_fc_desc* d, const void* x, const 
       fc_bwd_kernel<float, 0><<<nblk, kT, 0, st>>>(dz, loss_n, (const float*)x, W, N, F, K, fblocks, loss, dW, db, (float*)dx);
   }
   return launch_status();
+}
+
+int fc_check_args(const cnnk_fc_desc* d, const void* x, const float* W, const float* b, const int* labels,
+                  const float* loss, const int* pred, const void* dx, const float* dW, const float* db) {
+  int rc = validate_fc(d);
+  if (rc != CNNK_OK) return rc;
+  if (!x || !W || !b || !labels || !loss || !pred) return CNNK_ERR_NULL;
+  if ((dx || dW || db) && (!dx || !dW || !db)) return CNNK_ERR_NULL;
+  return CNNK_OK;
+}
+
+// Scratch of the entry point that allocates nothing: one array per device, part of the code object
+// (it exists from the moment the library is loaded until the process ends).  In host code the
+// array's name is only a handle for hipGetSymbolAddress; kernels and copies get the address that
+// call returns for the device that is current, looked up once per device.
+static __device__ __align__(256) unsigned char g_fc_scratch[CNNK_FC_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::mutex g_fc_scratch_mu;
+void* g_fc_scratch_ptr[kMaxDevices];   // zero-initialised: not looked up yet
+
+int fc_static_scratch(float** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CNNK_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_fc_scratch_mu);
+  if (!g_fc_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_fc_scratch)) != hipSuccess || !p) return CNNK_ERR_HIP;
+    g_fc_scratch_ptr[dev] = p;
+  }
+  *out = static_cast<float*>(g_fc_scratch_ptr[dev]);
+  return CNNK_OK;
+}
+}  // namespace
+
+extern "C" int cnnk_fc_softmax_xent(const cnnk_fc_desc* d, const void* x, const float* W, const float* b,
+                                    const int* labels, float* loss, int* pred, float* probs, void* dx, float* dW,
+                                    float* db, void* ws, size_t ws_bytes, void* stream) {
+  int rc = fc_check_args(d, x, W, b, labels, loss, pred, dx, dW, db);
+  if (rc != CNNK_OK) return rc;
+  if (!ws || ws_bytes < cnnk_fc_workspace_bytes(d)) return CNNK_ERR_WORKSPACE;
+  return fc_enqueue(d, x, W, b, labels, loss, pred, probs, dx, dW, db, (float*)ws, (hipStream_t)stream);
+}
+
+extern "C" int cnnk_fc_softmax_xent_static(const cnnk_fc_desc* d, const void* x, const float* W, const float* b,
+                                           const int* labels, float* loss, int* pred, float* probs, void* dx,
+                                           float* dW, float* db, void* stream) {
+  int rc = fc_check_args(d, x, W, b, labels, loss, pred, dx, dW, db);
+  if (rc != CNNK_OK) return rc;
+  if (cnnk_fc_workspace_bytes(d) > (size_t)CNNK_FC_STATIC_SCRATCH_BYTES) return CNNK_ERR_WORKSPACE;
+  float* scratch = nullptr;
+  rc = fc_static_scratch(&scratch);
+  if (rc != CNNK_OK) return rc;
+  return fc_enqueue(d, x, W, b, labels, loss, pred, probs, dx, dW, db, scratch, (hipStream_t)stream);
 }
 
 extern "C" int cnnk_count_correct(int n, const int* pred, const int* labels, int* n_correct, void* stream) {

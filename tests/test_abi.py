@@ -71,6 +71,15 @@ def test_argument_errors_are_reported_before_any_launch(cnnk):
         cnnk.cnnk_fc_softmax_xent(fc, 256, 256, 256, 256, 256, 256, None, 256, 256, 256, None, 0)
     assert e.value.status == 4
     assert cnnk.status_string(4).startswith("workspace")
+    # the allocation-free head refuses shapes beyond its fixed scratch, and bad arguments, on the host
+    big = cnnk.fc_desc(4096, 64, 100, cnnk.F32)
+    assert cnnk.cnnk_fc_workspace_bytes(big) > cnnk.FC_STATIC_SCRATCH_BYTES
+    with pytest.raises(cnnk.CnnkError) as e:
+        cnnk.cnnk_fc_softmax_xent_static(big, 256, 256, 256, 256, 256, 256, None, None, None, None)
+    assert e.value.status == 4
+    with pytest.raises(cnnk.CnnkError) as e:
+        cnnk.cnnk_fc_softmax_xent_static(fc, 256, 256, 256, None, 256, 256, None, None, None, None)
+    assert e.value.status == 1
 
 
 def test_train_step_validates_the_layer_list(cnnk):
