@@ -6,7 +6,8 @@ batch of seeded synthetic CIFAR-100-shaped data, resident in HBM before the time
 Workload: ResNet-18 adapted to 32x32 inputs, 100 classes, bf16 storage / fp32 accumulate, batch 256
 (--config picks another network).  Prints ONE JSON line: metric / value (images/s) / ms_per_step,
 `roofline` for the call class with the largest time per step (measured with HIP events recorded
-on the launch stream around every entry-point call), `cpu_baseline` (the fp64 oracle timed on a
+on the launch stream around every entry-point call, in extra single-stream steps that two marker
+launches bracket in a kernel trace), `cpu_baseline` (the fp64 oracle timed on a
 bounded sample on the host cores) and `validation_pass` (the inference-mode forward).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu-baseline]
@@ -20,12 +21,20 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
-# counters read for a plain copy of known size (summary and commands under profiles/); None for a
-# class that was not measured.
+# HBM bytes per launch of the roofline class, from two `rocprofv3 --pmc` runs of this very script
+# (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for the calibration copy
+# below (a plain copy kernel of known size in the same run); commands, raw counter means and the
+# scale factors are in profiles/.  None for a class that was not measured.
 MEASURED_TRAFFIC_BYTES = {
     "conv3x3 s1 64->64 @32 fwd+dgrad (patch_kernel)": 66294 * 1024,
 }
+# Launches that exist to be found in a profiler's kernel trace (all through cnnk_grad_route, a plain
+# copy kernel of the library, whose grid is its element count / 2048): one copy of CAL_ELEMS bf16
+# values before the warm-up (256 MiB read, 256 MiB written: the known size that calibrates the
+# traffic counters), and two small copies that bracket the steps timed per call, so that a trace
+# can be cut to exactly the launches that `roofline` is computed from.
+CAL_ELEMS = 128 << 20
+MARK_BEGIN_ELEMS, MARK_END_ELEMS = 2048 * 777 - 8, 2048 * 778 - 8
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
@@ -118,6 +127,11 @@ def main():
     lr, mu, wd = 0.1, 0.9, 0.0
     stream = torch.cuda.current_stream().cuda_stream
 
+    from paper_2503_23186_amd import cnnk as _cnnk
+    cal = torch.zeros(2 * CAL_ELEMS, dtype=torch.bfloat16, device="cuda:0")
+    _cnnk.cnnk_grad_route(CAL_ELEMS, _cnnk.BF16, cal, cal[CAL_ELEMS:], 0, stream)
+    torch.cuda.synchronize()
+
     for _ in range(args.warmup):
         run.step(lr, mu, wd, stream)
     torch.cuda.synchronize()
@@ -136,10 +150,13 @@ def main():
     acc = {}
     empty = []
     nt = max(args.timed_steps, 1)
+    mean_times = None
+    _cnnk.cnnk_grad_route(MARK_BEGIN_ELEMS, _cnnk.BF16, cal, cal[CAL_ELEMS:], 0, stream)
     for _ in range(nt):
         run.step(lr, mu, wd, stream)
         torch.cuda.synchronize()
         times = run.group_times_ms()
+        mean_times = times if mean_times is None else [a + b for a, b in zip(mean_times, times)]
         for g, li, phase in run.group_table():
             if phase == "none":
                 # an empty event pair (a layer without a second backward call): what two event
@@ -156,11 +173,15 @@ def main():
             a = acc.setdefault(key, dict(ms=0.0, calls=0, flops=fl, bytes=by, op=L["op"]))
             a["ms"] += times[g]
             a["calls"] += 1
+    _cnnk.cnnk_grad_route(MARK_END_ELEMS, _cnnk.BF16, cal, cal[CAL_ELEMS:], 0, stream)
+    torch.cuda.synchronize()
+    del cal
     run.enable_timing(False)
     # Every timed call sits between two event records of its own; the pair costs a few microseconds
     # even when empty.  That overhead, measured on the empty pairs of the same steps, is taken off
     # each call so that the durations are the kernels' (they then agree with a kernel trace).
     ev_overhead = float(np.median(empty)) if empty else 0.0
+    mean_times = [t / nt for t in mean_times]
     rows = []
     for key, a in acc.items():
         avg = max(a["ms"] / a["calls"] - ev_overhead, 1e-6)
@@ -202,8 +223,24 @@ def main():
                                    frac_of_hbm_peak=round(ew_bytes / ew_ms / 1e6 / PEAK_HBM_GBS, 4) if ew_ms else None,
                                    ms_per_step=round(ew_ms, 4))
 
+    # ---- what the paper's scheduler would choose for 8 such devices, from the measured times ----
+    # (Section III-B/III-C on the host: t_comp = the per-call times above, t_comm from byte counts;
+    # a model's prediction, not a measurement: nothing here runs on more than one GPU)
+    from paper_2503_23186_amd import asa
+    prof_rows = []
+    for g, li, phase in run.group_table():
+        if phase != "none":
+            prof_rows.append((li, phase, max(mean_times[g] - ev_overhead, 0.0)))
+    comps = asa.components_from_tape(net.layers, prof_rows, net.dtype)
+    cluster = asa.Cluster(K=8, mem=288e9, bw=153e9, lat=5e-6, d=2)   # xGMI: a ring is bound by one 153 GB/s link
+    plan = asa.solve(comps, cluster)
+    kinds = [s[0] for s in plan.assignment]
+    asa_out = dict(devices=8, components=len(comps), predicted_ms_per_step=round(plan.time * 1e3, 4),
+                   single_device_ms=round(sum(c.t for c in comps) * 1e3, 4),
+                   strategies={k: kinds.count(k) for k in ("DP", "HP", "MP")},
+                   basis="cost model of the paper's scheduler over this run's measured per-call times; prediction only")
+
     # ---- the validation pass of the epoch loop (inference-mode forward), reported beside the step ----
-    from paper_2503_23186_amd import cnnk as _cnnk
     for _ in range(3):
         _cnnk.cnnk_eval_step(run.c_layers, len(net.layers), run.buffers, run.labels, run.loss, run.pred, None, stream)
     torch.cuda.synchronize()
@@ -245,6 +282,7 @@ def main():
                    "config_id": args.config, "global_batch": net.batch, "loss": round(loss, 5)},
         "roofline": roof,
         "cpu_baseline": cpu,
+        "asa_plan": asa_out,
         "validation_pass": {"ms_per_batch": round(eval_ms, 4), "images_per_s": round(net.batch / (eval_ms * 1e-3), 1)},
     }
     print(json.dumps(out))

@@ -19,6 +19,11 @@
  *  - Errors are return codes.  Arguments are validated on the host before anything is
  *    enqueued: a call that returns an error other than CNNK_ERR_HIP has launched nothing.
  *  - Outputs must not alias inputs unless stated.
+ *  - Threads and streams: every entry point may be called from any host thread; calls that share
+ *    device buffers or a workspace must be ordered by the caller (same stream, or events).  The
+ *    library keeps no state between calls apart from cnnk_tune's table (process-wide, not
+ *    thread-safe) and, inside cnnk_train_step only, per-thread context that the step hands to the
+ *    convolution calls it makes (invisible to other threads and to direct callers).
  *  - Workspace (`ws`, `ws_bytes`): scratch device memory, at least the size the matching
  *    *_workspace_bytes query returns (may be NULL when that is 0), 256-byte aligned.
  *    Contents are undefined on entry and on return.
@@ -59,10 +64,9 @@ const char* cnnk_version(void);
  * (unsupported combinations make the conv calls return CNNK_ERR_UNSUPPORTED); 3 = target
  * number of workgroups of the weight-gradient kernel; 4/5 = pixel / channel tile of the 3x3
  * stride-1 LDS-patch kernels (4 = -1 switches them off); 6 = target number of workgroups of
- * the 3x3 stride-1 weight-gradient kernel (-1 switches it off); 10 = -1 makes that kernel stage
- * its tiles through registers instead of loading them straight into LDS; 7 = -1 switches off the pixel
+ * the 3x3 stride-1 weight-gradient kernel (-1 switches it off); 10 = unused; 7 = -1 switches off the pixel
  * permutation that keeps narrow images (W < 16) free of LDS bank conflicts; 8 = -1 keeps convolutions with
- * fewer than 8 input channels on the plain-FMA kernels; 11 = -1 keeps the first layer's forward
+ * fewer than 8 input channels on the direct (plain-FMA) kernels; 11 = -1 keeps the first layer's forward
  * pass on the padded-input path; 9 = -1 makes cnnk_train_step hand y to
  * every batch-norm backward call (no mask recomputation); 12 = -1 keeps the weight transposes of
  * the data-gradient kernels on the main stream when cnnk_train_step has a second one; 14 = tiles that one workgroup of the
@@ -198,6 +202,18 @@ int cnnk_count_correct(int n, const int* pred, const int* labels, int* n_correct
  * w_bf16 (nullable): n bfloat16 values refreshed with the rounded new w. */
 int cnnk_sgd_momentum(size_t n, float* w, float* v, const float* g, void* w_bf16, float lr,
                       float momentum, float weight_decay, void* stream);
+
+/* w_bf16[i] = round-to-nearest-even bfloat16 of w[i], n values: the first bf16 copy of fp32 master
+ * weights (cnnk_sgd_momentum refreshes the copy after every update). */
+int cnnk_round_bf16(size_t n, const float* w, void* w_bf16, void* stream);
+
+/* Mini-batch assembly (Algorithm 1, "for each mini-batch"): dst row i = src row idx[i] for
+ * i < n_rows; rows are row_bytes bytes (a multiple of 4; src and dst 4-byte aligned), idx holds
+ * n_rows int64 row numbers on the device.  The indices are device data and cannot be validated on
+ * the host: a row number outside [0, n_src_rows) is never dereferenced; its destination row is
+ * zero-filled and *bad_index (device int, nullable, zeroed by the caller) is set to 1. */
+int cnnk_gather_rows(int n_rows, long long n_src_rows, size_t row_bytes, const void* src,
+                     const long long* idx, void* dst, int* bad_index, void* stream);
 
 /* ---- the whole step over a layer list ------------------------------------------------------ */
 

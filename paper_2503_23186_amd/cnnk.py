@@ -20,7 +20,7 @@ OP_CONV, OP_BN, OP_POOL, OP_ADD, OP_FC_LOSS = 0, 1, 2, 3, 4
 EXPORTS = ["cnnk_status_string", "cnnk_version", "cnnk_tune", "cnnk_conv2d_workspace_bytes", "cnnk_conv2d_fwd",
            "cnnk_conv2d_dgrad", "cnnk_conv2d_wgrad", "cnnk_bn_workspace_bytes", "cnnk_bn_relu_fwd",
            "cnnk_bn_relu_infer", "cnnk_bn_relu_bwd", "cnnk_pool_fwd", "cnnk_pool_bwd", "cnnk_add", "cnnk_grad_route",
-           "cnnk_fc_workspace_bytes", "cnnk_fc_softmax_xent", "cnnk_fc_softmax_xent_static", "cnnk_count_correct", "cnnk_sgd_momentum",
+           "cnnk_fc_workspace_bytes", "cnnk_fc_softmax_xent", "cnnk_fc_softmax_xent_static", "cnnk_count_correct", "cnnk_sgd_momentum", "cnnk_round_bf16", "cnnk_gather_rows",
            "cnnk_train_step_workspace_bytes", "cnnk_train_step_event_groups", "cnnk_train_step",
            "cnnk_eval_step"]
 
@@ -99,6 +99,8 @@ def _load():
     lib.cnnk_fc_softmax_xent_static.argtypes = [C.POINTER(FcDesc)] + [vp] * 10 + [vp]
     lib.cnnk_count_correct.argtypes = [ci, vp, vp, vp, vp]
     lib.cnnk_sgd_momentum.argtypes = [sz, vp, vp, vp, vp, cf, cf, cf, vp]
+    lib.cnnk_round_bf16.argtypes = [sz, vp, vp, vp]
+    lib.cnnk_gather_rows.argtypes = [ci, C.c_longlong, sz, vp, vp, vp, vp, vp]
     lib.cnnk_train_step_workspace_bytes.restype = sz
     lib.cnnk_train_step_workspace_bytes.argtypes = [C.POINTER(Layer), ci]
     lib.cnnk_train_step_event_groups.argtypes = [ci]
@@ -236,6 +238,15 @@ def cnnk_count_correct(n, pred, labels, n_correct, stream=0):
 def cnnk_sgd_momentum(n, w, v, g, w_bf16, lr, momentum, weight_decay=0.0, stream=0):
     _check(lib.cnnk_sgd_momentum(n, ptr(w), ptr(v), ptr(g), ptr(w_bf16), lr, momentum, weight_decay, stream),
            "cnnk_sgd_momentum")
+
+
+def cnnk_round_bf16(n, w, w_bf16, stream=0):
+    _check(lib.cnnk_round_bf16(n, ptr(w), ptr(w_bf16), stream), "cnnk_round_bf16")
+
+
+def cnnk_gather_rows(n_rows, n_src_rows, row_bytes, src, idx, dst, bad_index=None, stream=0):
+    _check(lib.cnnk_gather_rows(int(n_rows), int(n_src_rows), int(row_bytes), ptr(src), ptr(idx), ptr(dst),
+                                ptr(bad_index), stream), "cnnk_gather_rows")
 
 
 def cnnk_train_step_workspace_bytes(layers, n_layers):

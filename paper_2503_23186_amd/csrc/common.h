@@ -119,5 +119,3 @@ static inline size_t elem_size(int dtype) { return dtype == CNNK_BF16 ? 2 : 4; }
 static inline int launch_status() { return hipGetLastError() == hipSuccess ? CNNK_OK : CNNK_ERR_HIP; }
 
 int cnnk_validate_conv(const cnnk_conv_desc* d);
-
-// Entry points implemented per file, dispatched by the C ABI in api.cpp

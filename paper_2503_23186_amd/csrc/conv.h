@@ -73,6 +73,7 @@ size_t conv_pad_ws(const ConvGeom& g, int pass, bool want_stats);
 int conv_pad_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y, float* ch_sum, float* ch_sumsq,
                  void* ws, hipStream_t st);
 int conv_pad_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws, hipStream_t st);
+// Hook 1 of 3 (see "Hooks between cnnk_train_step and the convolution entry points" below).
 // The forward and the weight-gradient call of such a layer both need the 8-channel copy of x.  When
 // set (per host thread), the forward call writes it to buf and sets valid, and a weight-gradient
 // call that finds valid set reads it there instead of padding x again (the caller vouches that x
@@ -94,16 +95,23 @@ bool conv_first_wgrad_supported(const ConvGeom& g);   // additionally W % 16 == 
 size_t conv_first_wgrad_ws(const ConvGeom& g);
 int conv_first_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws, hipStream_t st);
 
-// thin-input (stem) kernels, bf16 storage
-bool conv_stem_supported(const ConvGeom& g);
-size_t conv_stem_wgrad_ws(const ConvGeom& g);
-int conv_stem_fwd(const ConvGeom& g, const bf16_t* x, const bf16_t* w, bf16_t* y, hipStream_t st);
-int conv_stem_wgrad(const ConvGeom& g, const bf16_t* x, const bf16_t* dy, float* dw, void* ws, hipStream_t st);
-
 // ch_sum[c] = sum_b part[b][0][c], ch_sumsq[c] = sum_b part[b][1][c]  (double accumulation)
 int channel_sums_finalize(const float* part, int nb, int C, float* ch_sum, float* ch_sumsq, hipStream_t st);
 
-// When set (per host thread), the next split-K reduction of a weight gradient also applies the
+// ---- Hooks between cnnk_train_step and the convolution entry points -----------------------------
+// cnnk_train_step calls the public entry points (cnnk_conv2d_fwd / _wgrad) and passes three extra
+// pieces of context through the per-thread pointers below (t_cnnk_x8_cache above, t_cnnk_sgd_fuse,
+// t_cnnk_wgrad_cus).  Contract, the same for all three: the step sets the pointer immediately
+// before ONE entry-point call on the same host thread and resets it to its neutral value (nullptr /
+// 256) right after that call returns, whatever the call's status; an entry point reads it once, at
+// entry.  Outside cnnk_train_step the values are always neutral, so a direct caller of the C ABI
+// never sees them, and calls from other host threads are unaffected (thread_local).  The library
+// keeps no other state between calls except two process-wide tables that are written once or by
+// an explicit call: the "dynamic LDS size already raised" flag of each kernel launcher (set on the
+// first launch; harmless to set twice, so unsynchronised first launches from two threads are
+// benign) and the cnnk_tune table (explicitly documented as not thread-safe).
+//
+// Hook 2 of 3.  When set (per host thread), the next split-K reduction of a weight gradient also applies the
 // SGD-momentum update of that parameter in the same launch (out = sum of partials is still
 // written as the gradient): g' = g + wd*w; v <- mu*v + g'; w <- w - lr*v; optional bf16 copy.
 // wait (nullable): an event the stream waits for between the weight-gradient kernel and the
@@ -120,7 +128,7 @@ struct SgdFuse {
 extern thread_local SgdFuse* t_cnnk_sgd_fuse;
 
 extern int g_cnnk_tune[16];
-// Compute units the weight-gradient kernels size their grids for (256 = the whole device).  The
+// Hook 3 of 3.  Compute units the weight-gradient kernels size their grids for (256 = the whole device).  The
 // training step lowers it for the weight gradients it runs on its second stream, beside the rest
 // of the backward pass: fewer, longer-lived workgroups leave the other stream room to run.
 // Workspace sizes are always computed for the whole device (the upper bound).

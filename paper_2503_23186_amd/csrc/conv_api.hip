@@ -31,9 +31,6 @@ static bool use_first(const cnnk_conv_desc* d, const ConvGeom& g) {   // forward
 static bool use_first_wgrad(const cnnk_conv_desc* d, const ConvGeom& g) {
   return d->dtype == CNNK_BF16 && g_cnnk_tune[8] >= 0 && g_cnnk_tune[11] >= 0 && conv_first_wgrad_supported(g);
 }
-static bool use_stem(const cnnk_conv_desc* d, const ConvGeom& g, int pass) {
-  return d->dtype == CNNK_BF16 && !conv_mfma_supported(g, pass) && !use_pad(d, g, pass) && conv_stem_supported(g);
-}
 
 extern "C" size_t cnnk_conv2d_workspace_bytes(const cnnk_conv_desc* d, int pass) {
   if (cnnk_validate_conv(d) != CNNK_OK) return 0;
@@ -50,8 +47,7 @@ extern "C" size_t cnnk_conv2d_workspace_bytes(const cnnk_conv_desc* d, int pass)
   } else if (pass == CNNK_PASS_WGRAD) {
     b = use_mfma(d, g, pass) ? conv_mfma_ws(g, pass, false)
         : use_first_wgrad(d, g) ? conv_first_wgrad_ws(g)
-        : use_pad(d, g, pass) ? conv_pad_ws(g, pass, false)
-        : use_stem(d, g, pass) ? conv_stem_wgrad_ws(g) : conv_direct_wgrad_ws(g);
+        : use_pad(d, g, pass) ? conv_pad_ws(g, pass, false) : conv_direct_wgrad_ws(g);
   }
   return align_up(b, 256);
 }
@@ -76,10 +72,7 @@ extern "C" int cnnk_conv2d_fwd(const cnnk_conv_desc* d, const void* x, const voi
     if (!ws || ws_bytes < cnnk_conv2d_workspace_bytes(d, CNNK_PASS_FWD)) return CNNK_ERR_WORKSPACE;
     return conv_pad_fwd(g, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, ch_sum, ch_sumsq, ws, st);
   }
-  if (use_stem(d, g, CNNK_PASS_FWD))
-    rc = conv_stem_fwd(g, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, st);
-  else
-    rc = conv_direct_fwd(g, d->dtype, x, w, y, st);
+  rc = conv_direct_fwd(g, d->dtype, x, w, y, st);
   if (rc != CNNK_OK) return rc;
   if (ch_sum) rc = channel_stats(d->dtype, y, (size_t)g.N * g.Ho * g.Wo, g.Cout, ch_sum, ch_sumsq, ws, st);
   return rc;
@@ -112,7 +105,6 @@ extern "C" int cnnk_conv2d_wgrad(const cnnk_conv_desc* d, const void* x, const v
     return conv_mfma_wgrad(g, (const bf16_t*)x, (const bf16_t*)dy, dw, ws, st);
   if (use_first_wgrad(d, g)) return conv_first_wgrad(g, (const bf16_t*)x, (const bf16_t*)dy, dw, ws, st);
   if (use_pad(d, g, CNNK_PASS_WGRAD)) return conv_pad_wgrad(g, (const bf16_t*)x, (const bf16_t*)dy, dw, ws, st);
-  if (use_stem(d, g, CNNK_PASS_WGRAD)) return conv_stem_wgrad(g, (const bf16_t*)x, (const bf16_t*)dy, dw, ws, st);
   return conv_direct_wgrad(g, d->dtype, x, dy, dw, ws, st);
 }
 

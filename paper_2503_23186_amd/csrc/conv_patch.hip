@@ -94,8 +94,10 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wn = wave / WM;
-  int b = blockIdx.x;
-  const int nb = gridDim.x;
+  // The grid is (pixel-tile groups, channel tiles), walked as one linear index; the second
+  // dimension only makes layers with the same number of workgroups tell apart in a kernel trace.
+  int b = blockIdx.y * gridDim.x + blockIdx.x;
+  const int nb = gridDim.x * gridDim.y;
   if ((nb & 7) == 0) b = (b & 7) * (nb >> 3) + (b >> 3);  // consecutive tiles share an XCD
   const int nt = b % a.ntiles;
   int mt = (b / a.ntiles) * a.tpb;            // current pixel tile; the workgroup walks tpb of them
@@ -464,7 +466,7 @@ int launch_patch(PatchArgs& a, hipStream_t st) {
     if (a.mtiles % t == 0 && (long)a.ntiles * (a.mtiles / t) >= 512) a.tpb = t;
   if (g_cnnk_tune[13] > 0 && a.mtiles % g_cnnk_tune[13] == 0) a.tpb = g_cnnk_tune[13];
   const size_t smem = patch_smem<BM, BN>(a.TI * (a.TH + 2) * (a.W + 2));
-  hipLaunchKernelGGL(kern, dim3((unsigned)(a.mtiles / a.tpb * a.ntiles)), dim3(kThreads), smem, st, a);
+  hipLaunchKernelGGL(kern, dim3((unsigned)(a.mtiles / a.tpb), (unsigned)a.ntiles), dim3(kThreads), smem, st, a);
   return launch_status();
 }
 

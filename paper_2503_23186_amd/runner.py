@@ -139,9 +139,16 @@ class StepRunner:
         for k, (p, v) in enumerate(zip(params, mom)):
             self.param[k].copy_(torch.from_numpy(np.ascontiguousarray(p, dtype=np.float32)).to(self.dev))
             self.mom[k].copy_(torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to(self.dev))
-            if self.param_lp[k] is not None:
-                self.param_lp[k].copy_(self.param[k])
+        self.refresh_low_precision()
         torch.cuda.synchronize()
+
+    def refresh_low_precision(self):
+        """bf16 copies of the convolution weights from the fp32 masters (the step's update kernel
+        keeps them current afterwards)."""
+        s = torch.cuda.current_stream().cuda_stream
+        for k, lp in enumerate(self.param_lp):
+            if lp is not None:
+                cnnk.cnnk_round_bf16(lp.numel(), self.param[k], lp, s)
 
     def step(self, lr=0.1, momentum=0.9, weight_decay=0.0, stream=None):
         s = torch.cuda.current_stream().cuda_stream if stream is None else stream

@@ -72,6 +72,7 @@ class Trainer:
                               keep_probs=False, two_streams=two_streams)
         self.batch = self.run.N
         self.n_correct = torch.zeros(1, dtype=torch.int32, device=self.run.dev)
+        self.bad_index = torch.zeros(1, dtype=torch.int32, device=self.run.dev)   # set by a batch gather
         self.epoch = 0          # epochs completed
         self.step = 0           # steps completed
         self.best_acc = -1.0
@@ -92,10 +93,7 @@ class Trainer:
         torch.cuda.synchronize()
 
     def _refresh_low_precision(self):
-        r = self.run
-        for k, lp in enumerate(r.param_lp):
-            if lp is not None:
-                lp.copy_(r.param[k])
+        self.run.refresh_low_precision()
 
     def to_device(self, x, y):
         """A host data set (float NHWC, int labels) as device tensors of the storage dtype."""
@@ -107,8 +105,10 @@ class Trainer:
     # -- one mini-batch / one validation pass ---------------------------------------------------------
     def train_batch(self, x_all, y_all, idx, lr, momentum, weight_decay):
         r = self.run
-        torch.index_select(x_all, 0, idx, out=r.act[0])
-        torch.index_select(y_all, 0, idx, out=r.labels)
+        s = torch.cuda.current_stream().cuda_stream
+        row_bytes = x_all[0].numel() * x_all.element_size()
+        cnnk.cnnk_gather_rows(self.batch, x_all.shape[0], row_bytes, x_all, idx, r.act[0], self.bad_index, s)
+        cnnk.cnnk_gather_rows(self.batch, y_all.shape[0], 4, y_all, idx, r.labels, self.bad_index, s)
         r.step(lr, momentum, weight_decay)
         self.step += 1
 
@@ -146,6 +146,8 @@ class Trainer:
                 self.train_batch(train_x, train_y, idx_all[b * self.batch:(b + 1) * self.batch], lrs[self.step],
                                  momentum, weight_decay)
                 losses[b:b + 1].copy_(r.loss)
+            if self.bad_index.item() != 0:
+                raise ValueError("an epoch's order names a sample outside the training set")
             acc, vloss = self.evaluate(val_x, val_y)
             history.append((float(losses.double().mean().item()), acc, vloss))
             self.epoch += 1

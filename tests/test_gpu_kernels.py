@@ -49,7 +49,8 @@ def conv_inputs(shape, dtype, seed):
 
 @pytest.mark.parametrize("shape", [s for s in CONV_SHAPES if s[3] < 8])
 def test_thin_input_fma_kernels(K, shape):
-    """The plain-FMA kernels for very thin inputs (normally superseded by the padded MFMA path)."""
+    """The direct (plain-FMA) kernels in bf16 storage for very thin inputs, which normally take the
+    first-layer or the padded MFMA path."""
     K.cnnk_tune(8, -1)
     try:
         test_conv_fwd_dgrad_wgrad(K, shape, "bf16")
@@ -136,17 +137,15 @@ WG_SHAPES = [(4, 8, 8, 64, 128), (3, 16, 16, 64, 64), (2, 32, 32, 128, 64), (18,
              (1, 32, 32, 64, 64)]
 
 
-@pytest.mark.parametrize("staging", [0, -1])
 @pytest.mark.parametrize("target", [1, 2, 3, 4, 0])   # 2, 3: fewer partials than the reduce has thread groups
 @pytest.mark.parametrize("shape", WG_SHAPES)
-def test_conv_wgrad_patch_kernel(K, shape, target, staging):
-    """3x3 stride-1 weight gradient through the LDS-patch kernels (tiles loaded straight into LDS,
-    and staged through registers): one workgroup per output tile (plain stores), a few (partial
-    sums), and the default split."""
+def test_conv_wgrad_patch_kernel(K, shape, target):
+    """3x3 stride-1 weight gradient through the LDS-patch kernel (tiles loaded straight into LDS):
+    one workgroup per output tile (plain stores), a few (partial sums), and the default split."""
     N, H, W, Cin, Cout = shape
     x, w, dy, pad = conv_inputs((N, H, W, Cin, Cout, 3, 1), "bf16", 17)
     d = K.conv_desc(N, H, W, Cin, Cout, 3, 3, 1, 1, K.BF16)
-    K.cnnk_tune(6, target); K.cnnk_tune(10, staging)
+    K.cnnk_tune(6, target)
     try:
         dw_ref = ref.conv2d_wgrad(x, dy, w.shape, 1, 1)
         gdw = torch.full(w.shape, 9.0, dtype=torch.float32, device="cuda:0")
@@ -155,7 +154,7 @@ def test_conv_wgrad_patch_kernel(K, shape, target, staging):
         torch.cuda.synchronize()
         assert max_rel_err(host(gdw), dw_ref) <= 1e-4
     finally:
-        K.cnnk_tune(6, 0); K.cnnk_tune(10, 0)
+        K.cnnk_tune(6, 0)
 
 
 PATCH_TILES = [(256, 128), (256, 64), (128, 128), (128, 64)]

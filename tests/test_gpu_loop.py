@@ -289,3 +289,64 @@ def test_profile_returns_layer_times_and_leaves_the_state_alone():
     assert sum(ms for _, ph, ms in rows if ph == "fwd") > 0.0
     after = tr.run.param + tr.run.mom + [t for t in tr.run.bn_running if t is not None]
     assert all(torch.equal(a, b) for a, b in zip(after, before))
+
+
+def test_batch_gather_and_bf16_rounding_match_the_definitions():
+    """cnnk_gather_rows against numpy indexing (bit exact; 16-byte, 4-byte and unaligned rows;
+    repeated and out-of-range indices), cnnk_round_bf16 against the oracle's rounding (bit exact)."""
+    from paper_2503_23186_amd import cnnk as K
+    from oracle import ops as ref
+    rng = np.random.default_rng(91)
+    for n_src, row_elems, dt in [(50, 32 * 32 * 3, torch.bfloat16), (33, 7, torch.float32), (9, 1, torch.int32),
+                                 (20, 10, torch.bfloat16)]:
+        if dt == torch.int32:
+            src = torch.from_numpy(rng.integers(0, 100, (n_src, row_elems)).astype(np.int32)).to("cuda:0")
+        else:
+            src = torch.from_numpy(rng.standard_normal((n_src, row_elems)).astype(np.float32)).to("cuda:0").to(dt)
+        idx = rng.integers(0, n_src, 24).astype(np.int64)
+        idx[3] = idx[4]                                            # a repeated sample
+        gidx = torch.from_numpy(idx).to("cuda:0")
+        dst = torch.full((24, row_elems), 7, dtype=dt, device="cuda:0")
+        bad = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+        K.cnnk_gather_rows(24, n_src, row_elems * src.element_size(), src, gidx, dst, bad)
+        torch.cuda.synchronize()
+        assert torch.equal(dst, src[gidx]) and bad.item() == 0
+        for wrong in (n_src, -1):
+            idx2 = idx.copy(); idx2[5] = wrong
+            K.cnnk_gather_rows(24, n_src, row_elems * src.element_size(), src, torch.from_numpy(idx2).to("cuda:0"), dst, bad)
+            torch.cuda.synchronize()
+            want = src[gidx].clone(); want[5] = 0
+            assert torch.equal(dst, want) and bad.item() == 1
+            bad.zero_()
+    for n in (1, 5, 1000, 4099, 1 << 20):
+        w = (rng.standard_normal(n) * 10.0 ** rng.integers(-3, 3, n)).astype(np.float32)
+        gw = torch.from_numpy(w).to("cuda:0")
+        glp = torch.zeros(n, dtype=torch.bfloat16, device="cuda:0")
+        K.cnnk_round_bf16(n, gw, glp)
+        torch.cuda.synchronize()
+        assert np.array_equal(glp.to(torch.float64).cpu().numpy(), ref.round_bf16(w.astype(np.float64)))
+
+
+def test_strategy_selection_from_a_measured_profile():
+    """Algorithm 1's "profile, estimate, solve" on a real profile: the per-call times of the HIP step
+    become components, and the solver's plan for four devices equals the oracle's brute-force
+    minimum of the same objective."""
+    from paper_2503_23186_amd.trainer import Trainer
+    from paper_2503_23186_amd import asa
+    from oracle import asa_ref
+    net = WL.mini_resnet(batch=32, dtype="bf16", size=16, widths=(32, 64))
+    inp = WL.make_inputs(net, 45)
+    tr = Trainer(net)
+    tr.load_state(inp["params"], inp["mom"])
+    tr.run.load(inp["x"], inp["labels"], inp["params"], inp["mom"])
+    rows = tr.profile(steps=3)
+    comps = asa.components_from_tape(net.layers, rows, net.dtype)
+    assert len(comps) == 7 and all(c.t > 0 for c in comps)
+    comps = comps[:6]                                   # 6^6 assignments for the brute force
+    as_dicts = [dict(t=c.t, G=c.G, O=c.O, S=c.S, A=c.A) for c in comps]
+    need = sum(c.S + c.A for c in comps)
+    for caps, bw in (([need] * 4, 100e9), ([need / 3] * 4, 100e9), ([need / 3] * 4, 1e9)):
+        plan = asa.solve(comps, asa.Cluster(K=4, mem=list(caps), bw=bw, lat=5e-6, d=2))
+        want_t, want_a = asa_ref.solve_brute_force(as_dicts, 4, 2, bw, 5e-6, caps)
+        assert want_a is not None and plan.time == pytest.approx(want_t, rel=1e-12)
+        assert asa_ref.feasible(as_dicts, plan.assignment, 4, 2, caps)
