@@ -26,7 +26,7 @@ sys.path.insert(0, ROOT)
 # below (a plain copy kernel of known size in the same run); commands, raw counter means and the
 # scale factors are in profiles/.  None for a class that was not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "conv3x3 s1 64->64 @32 fwd+dgrad (patch_kernel)": 66294 * 1024,
+    "conv3x3 s1 64->64 @32 fwd+dgrad (patch_kernel)": 86444077,   # profiles/bench_resnet18_b256_hbm_traffic.md
 }
 # Launches that exist to be found in a profiler's kernel trace (all through cnnk_grad_route, a plain
 # copy kernel of the library, whose grid is its element count / 2048): one copy of CAL_ELEMS bf16
@@ -173,9 +173,7 @@ def main():
             a = acc.setdefault(key, dict(ms=0.0, calls=0, flops=fl, bytes=by, op=L["op"]))
             a["ms"] += times[g]
             a["calls"] += 1
-    _cnnk.cnnk_grad_route(MARK_END_ELEMS, _cnnk.BF16, cal, cal[CAL_ELEMS:], 0, stream)
     torch.cuda.synchronize()
-    del cal
     run.enable_timing(False)
     # Every timed call sits between two event records of its own; the pair costs a few microseconds
     # even when empty.  That overhead, measured on the empty pairs of the same steps, is taken off
@@ -204,12 +202,17 @@ def main():
                          % (sum(r["ms_per_step"] for r in rows), conv_ms, conv_flops / conv_ms / 1e9 if conv_ms else 0,
                             ew_ms, ew_bytes / ew_ms / 1e6 if ew_ms else 0))
     dom = rows[0]
+    _cnnk.cnnk_grad_route(MARK_END_ELEMS, _cnnk.BF16, cal, cal[CAL_ELEMS:], 0, stream)
+    torch.cuda.synchronize()
+    del cal
     if dom["op"] == "conv":
         ach = dom["flops"] / dom["avg_ms"] / 1e9
         roof = dict(bound="mfma", kernel=dom["key"], achieved=round(ach, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                     frac=round(ach / PEAK_BF16_TFLOPS, 4),
                     traffic=MEASURED_TRAFFIC_BYTES.get(dom["key"]) if args.config == 3 and not args.batch else None,
                     avg_ms=round(dom["avg_ms"], 4),
+                    timing="HIP events on the launch stream around each of the class's %d calls in %d single-stream "
+                           "steps, less the cost of an empty event pair (%.4f ms)" % (dom["calls_per_step"] * nt, nt, ev_overhead),
                     calls_per_step=dom["calls_per_step"])
     else:
         ach = dom["bytes"] / dom["avg_ms"] / 1e6
