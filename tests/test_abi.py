@@ -19,8 +19,8 @@ def cnnk():
     return mod
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "cnnk.h")).read()
+def declared_functions(header="cnnk.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(cnnk_[a-z0-9_]+)\s*\(", text)))
 
@@ -32,6 +32,64 @@ def test_every_declared_symbol_is_exported(cnnk):
         assert hasattr(cnnk.lib, n), n
     assert sorted(cnnk.EXPORTS) == names
     assert "gfx950" in cnnk.version()
+
+
+def test_every_symbol_of_the_transformer_header_is_exported(cnnk):
+    from paper_2503_23186_amd import vit
+    names = declared_functions("cnnk_vit.h")
+    assert len(names) >= 15
+    for n in names:
+        assert hasattr(cnnk.lib, n), n
+    assert sorted(vit.EXPORTS) == names
+    assert C.sizeof(vit.LnDesc) == 24 and C.sizeof(vit.AttnDesc) == 20 and C.sizeof(vit.EmbedDesc) == 20
+    assert C.sizeof(vit.VitDesc) == 40 and C.sizeof(vit.VitBuffers) == 128
+
+
+def test_transformer_entry_points_reject_bad_arguments_on_the_host(cnnk):
+    from paper_2503_23186_amd import vit
+    ln = vit.ln_desc(8, 30, cnnk.F32)
+    with pytest.raises(cnnk.CnnkError) as e:
+        vit.cnnk_layernorm_fwd(ln, 256, 256, 256, 256, 256)
+    assert e.value.status == 3                              # C must be a multiple of 4
+    ln = vit.ln_desc(8, 32, cnnk.F32)
+    with pytest.raises(cnnk.CnnkError) as e:
+        vit.cnnk_layernorm_fwd(ln, 256, 256, 256, None, 256)
+    assert e.value.status == 1
+    with pytest.raises(cnnk.CnnkError) as e:
+        vit.cnnk_layernorm_bwd(ln, 256, 256, 256, 256, None, 256, 256, 256, None, 0)
+    assert e.value.status == 4
+    assert vit.cnnk_layernorm_workspace_bytes(ln) >= 2 * 32 * 4
+    with pytest.raises(cnnk.CnnkError) as e:
+        vit.cnnk_bias_act_fwd(4, 12, cnnk.BF16, vit.ACT_NONE, 256, 256, None, None, 256)
+    assert e.value.status == 3
+    with pytest.raises(cnnk.CnnkError) as e:
+        vit.cnnk_bias_act_fwd(4, 16, cnnk.BF16, vit.ACT_GELU, 256, 256, 256, 256, 256)
+    assert e.value.status == 3                              # no residual behind the activation
+    with pytest.raises(cnnk.CnnkError) as e:
+        vit.cnnk_attention_fwd(vit.attn_desc(1, 197, 12, 48, cnnk.BF16), 256, 256, 256)
+    assert e.value.status == 3
+    with pytest.raises(cnnk.CnnkError) as e:
+        vit.cnnk_attention_fwd(vit.attn_desc(1, 0, 12, 64, cnnk.BF16), 256, 256, 256)
+    assert e.value.status == 2
+    with pytest.raises(cnnk.CnnkError) as e:
+        vit.cnnk_vit_patchify(vit.embed_desc(1, 30, 8, 64, cnnk.F32), 256, 256)
+    assert e.value.status == 2                              # the image is not a whole number of patches
+    d = vit.vit_desc(64, 224, 16, 768, 12, 12, 3072, 100, cnnk.BF16)
+    assert vit.cnnk_vit_step_calls(d) == 3 + 12 * 11 + 2 + 2 + 12 * 15 + 2 + 1
+    assert vit.cnnk_vit_step_call_name(d, 0) == "embed.patchify"
+    assert vit.cnnk_vit_step_call_name(d, vit.cnnk_vit_step_calls(d) - 1) == "update"
+    off, nb = vit.cnnk_vit_tensor(d, vit.TENSOR_IDS.index("QKV"), 3)
+    assert nb == 64 * 197 * 2304 * 2 and off % 256 == 0
+    assert vit.cnnk_vit_arena_bytes(d) > 12 * 2 * nb
+    with pytest.raises(cnnk.CnnkError) as e:
+        vit.cnnk_vit_tensor(d, vit.TENSOR_IDS.index("QKV"), 12)
+    assert e.value.status == 2
+    bad = vit.vit_desc(64, 224, 16, 768, 10, 12, 3072, 100, cnnk.BF16)
+    assert vit.cnnk_vit_arena_bytes(bad) == 0               # 768 / 10 heads
+    b = vit.VitBuffers()
+    with pytest.raises(cnnk.CnnkError) as e:
+        vit.cnnk_vit_train_step(d, b, 0.1, 0.9, 0.0)
+    assert e.value.status == 1
 
 
 def test_struct_layouts_match_header(cnnk):
