@@ -1,6 +1,8 @@
 // Multi-head self-attention of the Vision Transformer step (Section IV-A's second model), forward
 // and backward, for sequences that fit one workgroup's LDS (a ViT-B/16 image is 197 tokens).
 //
+// These are the general kernels (any storage type, head sizes 16 / 32 / 64); bf16 storage with head
+// size 64 runs on the matrix cores instead (vit_attention_mfma.hip) unless cnnk_tune key 10 is -1.
 // fp32 arithmetic on the vector ALUs, whatever the storage type: one workgroup per (image, head)
 // holds the head's keys and values (or, for the key / value gradients, its queries and output
 // gradients) in LDS as floats; a thread owns one query (or one key) and walks the other index, every
@@ -8,6 +10,13 @@
 // forward pass keeps log-sum-exp per query and the backward pass recomputes exp(s - lse).
 #include "common.h"
 #include "../../include/cnnk_vit.h"
+
+// the matrix-core kernels (vit_attention_mfma.hip): bf16, head size 64, at most 256 tokens
+bool attn_mfma_supported(const cnnk_attn_desc* d);
+int attn_mfma_fwd(const cnnk_attn_desc* d, const void* qkv, void* o, float* lse, hipStream_t st);
+int attn_mfma_bwd(const cnnk_attn_desc* d, const void* qkv, const void* o, const void* d_o, const float* lse, void* dqkv,
+                  hipStream_t st);
+extern int g_cnnk_tune[16];
 
 namespace {
 constexpr int kT = 256;
@@ -223,6 +232,7 @@ extern "C" int cnnk_attention_fwd(const cnnk_attn_desc* d, const void* qkv, void
   if (!qkv || !o || !lse) return CNNK_ERR_NULL;
   if (!aligned16(qkv) || !aligned16(o)) return CNNK_ERR_UNSUPPORTED;
   hipStream_t st = (hipStream_t)stream;
+  if (attn_mfma_supported(d) && g_cnnk_tune[10] >= 0) return attn_mfma_fwd(d, qkv, o, lse, st);
   const bool bf = d->dtype == CNNK_BF16;
   switch (d->dh) {
     case 16: bf ? launch_fwd<bf16_t, 16>(d, qkv, o, lse, st) : launch_fwd<float, 16>(d, qkv, o, lse, st); break;
@@ -239,6 +249,7 @@ extern "C" int cnnk_attention_bwd(const cnnk_attn_desc* d, const void* qkv, cons
   if (!qkv || !o || !d_o || !lse || !dqkv) return CNNK_ERR_NULL;
   if (!aligned16(qkv) || !aligned16(o) || !aligned16(d_o) || !aligned16(dqkv)) return CNNK_ERR_UNSUPPORTED;
   hipStream_t st = (hipStream_t)stream;
+  if (attn_mfma_supported(d) && g_cnnk_tune[10] >= 0) return attn_mfma_bwd(d, qkv, o, d_o, lse, dqkv, st);
   const bool bf = d->dtype == CNNK_BF16;
   switch (d->dh) {
     case 16: bf ? launch_bwd<bf16_t, 16>(d, qkv, o, d_o, lse, dqkv, st) : launch_bwd<float, 16>(d, qkv, o, d_o, lse, dqkv, st); break;

@@ -147,9 +147,9 @@ struct Walk {
       return;
     }
     if (rc != CNNK_OK) { ++idx; return; }
-    if (events) hipEventRecord((hipEvent_t)events[2 * idx], st);
+    if (events) (void)hipEventRecord((hipEvent_t)events[2 * idx], st);
     rc = f();
-    if (events) hipEventRecord((hipEvent_t)events[2 * idx + 1], st);
+    if (events) (void)hipEventRecord((hipEvent_t)events[2 * idx + 1], st);
     ++idx;
   }
 };

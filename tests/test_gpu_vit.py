@@ -111,10 +111,26 @@ def test_bias_activation_residual(K, rows, C, dtype):
     assert (host(gz) == u).all()
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+# bf16 with head size 64 runs on the matrix cores (one 32-token block per wavefront: 17, 197, 256, 33
+# tokens = 1, 7, 8, 2 blocks with ragged and full last blocks); "bf16-valu" forces the general kernels
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "bf16-valu"])
 @pytest.mark.parametrize("B,T,heads,dh", [(2, 17, 2, 64), (1, 197, 3, 64), (2, 5, 2, 16), (1, 50, 4, 32), (1, 300, 1, 32),
-                                          (3, 1, 2, 16), (1, 256, 1, 64)])
+                                          (3, 1, 2, 16), (1, 256, 1, 64), (2, 33, 12, 64), (1, 1, 1, 64)])
 def test_attention(K, B, T, heads, dh, dtype):
+    from paper_2503_23186_amd import cnnk
+    if dtype == "bf16-valu":
+        if dh != 64:
+            pytest.skip("already on the general kernels")
+        cnnk.cnnk_tune(10, -1)
+        try:
+            _attention_case(K, B, T, heads, dh, "bf16")
+        finally:
+            cnnk.cnnk_tune(10, 0)
+    else:
+        _attention_case(K, B, T, heads, dh, dtype)
+
+
+def _attention_case(K, B, T, heads, dh, dtype):
     rng = np.random.default_rng(B * 7 + T * 13 + heads + dh)
     d = heads * dh
     qkv = rep(rng.standard_normal((B, T, 3 * d)) * 1.3, dtype)
