@@ -11,8 +11,6 @@
  *   tokens   X[b, 0] = cls + pos[0];  X[b, 1 + i] = patch_i(b) @ We^T + be + pos[1 + i]
  *   block    X += Attn(LN(X)) @ Wo^T + bo;   X += gelu(LN(X) @ W1^T + c1) @ W2^T + c2
  *   head     logits = LN(X[:, 0]) @ Wh^T + bh, mean softmax cross-entropy
- * The linear maps themselves are 1 x 1 convolutions over an [B, T, 1, C] tensor and go through
- * cnnk_conv2d_fwd / _dgrad / _wgrad of cnnk.h.
  */
 #ifndef CNNK_VIT_ABI_H_
 #define CNNK_VIT_ABI_H_
@@ -57,6 +55,23 @@ int cnnk_bias_act_fwd(long long rows, int C, int dtype, int act, const void* z, 
 size_t cnnk_bias_act_workspace_bytes(long long rows, int C);
 int cnnk_bias_act_bwd(long long rows, int C, int dtype, int act, const void* dy, const void* u,
                       void* dz, float* dbias, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- linear layers ---------------------------------------------------------------------------------------
+ * x [rows][K], w [N][K] (of dtype: in the bf16 mode the bf16 copy of the fp32 master), bias [N]
+ * float or NULL.  fwd: act = NONE: y = x w^T + bias;  act = GELU (bias required): u = x w^T + bias is
+ * stored and y = gelu(u as stored), as in cnnk_bias_act_fwd.  dgrad: dx [rows][K] = dy w.
+ * wgrad: dw [N][K] float = dy^T x (the bias gradient is cnnk_bias_act_bwd's column sum).
+ * K % 8 == 0, N % 8 == 0.  bf16 with rows, K, N multiples of 32 runs on dedicated matrix-core
+ * kernels (an output is rounded once, after bias); everything else on the 1 x 1 convolution kernels
+ * of cnnk.h followed by cnnk_bias_act_fwd (cnnk_tune key 15 = -1 forces that path).  The weight
+ * gradient is a fixed-order sum of per-row-range partials: reproducible bit for bit. */
+size_t cnnk_linear_workspace_bytes(long long rows, int K, int N, int dtype);
+int cnnk_linear_fwd(long long rows, int K, int N, int dtype, const void* x, const void* w,
+                    const float* bias, int act, void* u, void* y, void* ws, size_t ws_bytes, void* stream);
+int cnnk_linear_dgrad(long long rows, int K, int N, int dtype, const void* dy, const void* w, void* dx,
+                      void* ws, size_t ws_bytes, void* stream);
+int cnnk_linear_wgrad(long long rows, int K, int N, int dtype, const void* x, const void* dy, float* dw,
+                      void* ws, size_t ws_bytes, void* stream);
 
 /* ---- multi-head self-attention ------------------------------------------------------------------------
  * qkv [B][T][3 * heads * dh]: per token the queries of all heads, then the keys, then the values.

@@ -1,8 +1,8 @@
 // cnnk_vit_train_step: one training step of a pre-norm Vision Transformer classifier on one device
 // (Section IV-A's second model; Algorithm 1's inner loop: forward pass, loss, backward pass, update).
-// Host code: the order of the calls, the layout of the arena, the parameter table.  Every matrix
-// product is a 1 x 1 convolution over [B, T, 1, C] and goes through cnnk_conv2d_fwd / _dgrad /
-// _wgrad; everything else through the entry points of cnnk_vit.h.
+// Host code: the order of the calls, the layout of the arena, the parameter table.  Everything runs
+// through the entry points of cnnk_vit.h (and the classifier head and the residual sums through
+// cnnk_fc_softmax_xent / cnnk_add of cnnk.h).
 #include <stdio.h>
 #include <string.h>
 #include "common.h"
@@ -101,22 +101,13 @@ void layout(const Geo& g, Arena* a) {
   a->total = at;
 }
 
-cnnk_conv_desc gemm_desc(const Geo& g, int rows_per_image, int K, int N) {
-  cnnk_conv_desc c;
-  c.N = g.B; c.H = rows_per_image; c.W = 1; c.Cin = K; c.Cout = N; c.R = 1; c.S = 1; c.stride = 1; c.pad = 0;
-  c.dtype = g.dtype;
-  return c;
-}
-
 size_t max_sz(size_t a, size_t b) { return a > b ? a : b; }
 
 size_t workspace(const cnnk_vit_desc* v, const Geo& g) {
   size_t w = 0;
-  const int shapes[5][3] = {{g.n, g.K0, g.d}, {g.T, g.d, 3 * g.d}, {g.T, g.d, g.d}, {g.T, g.d, g.m}, {g.T, g.m, g.d}};
-  for (int i = 0; i < 5; ++i) {
-    const cnnk_conv_desc c = gemm_desc(g, shapes[i][0], shapes[i][1], shapes[i][2]);
-    for (int pass = 0; pass < 3; ++pass) w = max_sz(w, cnnk_conv2d_workspace_bytes(&c, pass));
-  }
+  const long long shapes[5][3] = {{(long long)g.B * g.n, g.K0, g.d}, {(long long)g.rows, g.d, 3 * g.d}, {(long long)g.rows, g.d, g.d},
+                                  {(long long)g.rows, g.d, g.m}, {(long long)g.rows, g.m, g.d}};
+  for (int i = 0; i < 5; ++i) w = max_sz(w, cnnk_linear_workspace_bytes(shapes[i][0], (int)shapes[i][1], (int)shapes[i][2], g.dtype));
   cnnk_ln_desc ln = {(int)g.rows, g.d, g.dtype, v->ln_eps, 0};
   w = max_sz(w, cnnk_layernorm_workspace_bytes(&ln));
   w = max_sz(w, cnnk_bias_act_workspace_bytes((long long)g.rows, 3 * g.d));
@@ -169,8 +160,8 @@ int walk(const cnnk_vit_desc* v, const Geo& g, const cnnk_vit_buffers* buf, floa
   const int d = g.d, m = g.m, T = g.T;
   const long long rows = (long long)g.rows;
   const cnnk_embed_desc ed = {g.B, v->image, v->patch, d, g.dtype};
-  const cnnk_conv_desc c_emb = gemm_desc(g, g.n, g.K0, d), c_qkv = gemm_desc(g, T, d, 3 * d), c_o = gemm_desc(g, T, d, d),
-                       c_1 = gemm_desc(g, T, d, m), c_2 = gemm_desc(g, T, m, d);
+  const long long prow = (long long)g.B * g.n;     // patch rows
+  const int dt = g.dtype;
   const cnnk_ln_desc ln = {(int)g.rows, d, g.dtype, v->ln_eps, 0};
   const cnnk_ln_desc ln_cls = {g.B, d, g.dtype, v->ln_eps, (long long)T * d};
   const cnnk_attn_desc ad = {g.B, T, v->heads, d / v->heads, g.dtype};
@@ -179,22 +170,20 @@ int walk(const cnnk_vit_desc* v, const Geo& g, const cnnk_vit_buffers* buf, floa
 
   // ---- forward ----
   w.call(-1, "embed.patchify", [&] { return cnnk_vit_patchify(&ed, buf->x, at(CNNK_VIT_PATCHES, 0), st); });
-  w.call(-1, "embed.gemm", [&] { return cnnk_conv2d_fwd(&c_emb, at(CNNK_VIT_PATCHES, 0), Wm(P_WE), at(X_Z0, 0), nullptr, nullptr, ws, wsb, st); });
+  w.call(-1, "embed.gemm", [&] { return cnnk_linear_fwd(prow, g.K0, d, dt, at(CNNK_VIT_PATCHES, 0), Wm(P_WE), nullptr, CNNK_ACT_NONE, nullptr, at(X_Z0, 0), ws, wsb, st); });
   w.call(-1, "embed.tokens", [&] { return cnnk_vit_embed_fwd(&ed, at(X_Z0, 0), P(P_BE), P(P_CLS), P(P_POS), at(CNNK_VIT_TOK, 0), st); });
   for (int l = 0; l < g.L; ++l) {
     const int p0 = P_BLOCK0 + B_COUNT * l;
     void* xin = l ? at(CNNK_VIT_XOUT, l - 1) : at(CNNK_VIT_TOK, 0);
     w.call(l, "ln1", [&] { return cnnk_layernorm_fwd(&ln, xin, P(p0 + B_G1), P(p0 + B_B1), at(CNNK_VIT_H, l), (float*)at(X_STATS1, l), st); });
-    w.call(l, "qkv.gemm", [&] { return cnnk_conv2d_fwd(&c_qkv, at(CNNK_VIT_H, l), Wm(p0 + B_WQKV), at(CNNK_VIT_QKV, l), nullptr, nullptr, ws, wsb, st); });
-    w.call(l, "qkv.bias", [&] { return cnnk_bias_act_fwd(rows, 3 * d, g.dtype, CNNK_ACT_NONE, at(CNNK_VIT_QKV, l), P(p0 + B_BQKV), nullptr, nullptr, at(CNNK_VIT_QKV, l), st); });
+    w.call(l, "qkv.gemm", [&] { return cnnk_linear_fwd(rows, d, 3 * d, dt, at(CNNK_VIT_H, l), Wm(p0 + B_WQKV), P(p0 + B_BQKV), CNNK_ACT_NONE, nullptr, at(CNNK_VIT_QKV, l), ws, wsb, st); });
     w.call(l, "attn", [&] { return cnnk_attention_fwd(&ad, at(CNNK_VIT_QKV, l), at(CNNK_VIT_O, l), (float*)at(X_LSE, l), st); });
-    w.call(l, "proj.gemm", [&] { return cnnk_conv2d_fwd(&c_o, at(CNNK_VIT_O, l), Wm(p0 + B_WO), at(X_ZTMP, 0), nullptr, nullptr, ws, wsb, st); });
-    w.call(l, "proj.bias_res", [&] { return cnnk_bias_act_fwd(rows, d, g.dtype, CNNK_ACT_NONE, at(X_ZTMP, 0), P(p0 + B_BO), xin, nullptr, at(CNNK_VIT_XMID, l), st); });
+    w.call(l, "proj.gemm", [&] { return cnnk_linear_fwd(rows, d, d, dt, at(CNNK_VIT_O, l), Wm(p0 + B_WO), P(p0 + B_BO), CNNK_ACT_NONE, nullptr, at(X_ZTMP, 0), ws, wsb, st); });
+    w.call(l, "proj.res", [&] { return cnnk_add((size_t)rows * d, dt, xin, at(X_ZTMP, 0), at(CNNK_VIT_XMID, l), st); });
     w.call(l, "ln2", [&] { return cnnk_layernorm_fwd(&ln, at(CNNK_VIT_XMID, l), P(p0 + B_G2), P(p0 + B_B2), at(CNNK_VIT_H2, l), (float*)at(X_STATS2, l), st); });
-    w.call(l, "fc1.gemm", [&] { return cnnk_conv2d_fwd(&c_1, at(CNNK_VIT_H2, l), Wm(p0 + B_W1), at(CNNK_VIT_U, l), nullptr, nullptr, ws, wsb, st); });
-    w.call(l, "fc1.bias_gelu", [&] { return cnnk_bias_act_fwd(rows, m, g.dtype, CNNK_ACT_GELU, at(CNNK_VIT_U, l), P(p0 + B_C1), nullptr, at(CNNK_VIT_U, l), at(CNNK_VIT_G, l), st); });
-    w.call(l, "fc2.gemm", [&] { return cnnk_conv2d_fwd(&c_2, at(CNNK_VIT_G, l), Wm(p0 + B_W2), at(X_ZTMP, 0), nullptr, nullptr, ws, wsb, st); });
-    w.call(l, "fc2.bias_res", [&] { return cnnk_bias_act_fwd(rows, d, g.dtype, CNNK_ACT_NONE, at(X_ZTMP, 0), P(p0 + B_C2), at(CNNK_VIT_XMID, l), nullptr, at(CNNK_VIT_XOUT, l), st); });
+    w.call(l, "fc1.gemm_gelu", [&] { return cnnk_linear_fwd(rows, d, m, dt, at(CNNK_VIT_H2, l), Wm(p0 + B_W1), P(p0 + B_C1), CNNK_ACT_GELU, at(CNNK_VIT_U, l), at(CNNK_VIT_G, l), ws, wsb, st); });
+    w.call(l, "fc2.gemm", [&] { return cnnk_linear_fwd(rows, m, d, dt, at(CNNK_VIT_G, l), Wm(p0 + B_W2), P(p0 + B_C2), CNNK_ACT_NONE, nullptr, at(X_ZTMP, 0), ws, wsb, st); });
+    w.call(l, "fc2.res", [&] { return cnnk_add((size_t)rows * d, dt, at(CNNK_VIT_XMID, l), at(X_ZTMP, 0), at(CNNK_VIT_XOUT, l), st); });
   }
   void* xlast = at(CNNK_VIT_XOUT, g.L - 1);
   w.call(-1, "head.ln", [&] { return cnnk_layernorm_fwd(&ln_cls, xlast, P(p_tail), P(p_tail + 1), at(CNNK_VIT_F, 0), (float*)at(X_STATSF, 0), st); });
@@ -215,30 +204,30 @@ int walk(const cnnk_vit_desc* v, const Geo& g, const cnnk_vit_buffers* buf, floa
     void* dxin = l ? at(CNNK_VIT_DXOUT, l - 1) : at(CNNK_VIT_DTOK, 0);
     void* dxo = at(CNNK_VIT_DXOUT, l);
     w.call(l, "fc2.dbias", [&] { return cnnk_bias_act_bwd(rows, d, g.dtype, CNNK_ACT_NONE, dxo, nullptr, nullptr, Gr(p0 + B_C2), ws, wsb, st); });
-    w.call(l, "fc2.wgrad", [&] { return cnnk_conv2d_wgrad(&c_2, at(CNNK_VIT_G, l), dxo, Gr(p0 + B_W2), ws, wsb, st); });
-    w.call(l, "fc2.dgrad", [&] { return cnnk_conv2d_dgrad(&c_2, dxo, Wm(p0 + B_W2), at(CNNK_VIT_DG, l), 0, ws, wsb, st); });
+    w.call(l, "fc2.wgrad", [&] { return cnnk_linear_wgrad(rows, m, d, dt, at(CNNK_VIT_G, l), dxo, Gr(p0 + B_W2), ws, wsb, st); });
+    w.call(l, "fc2.dgrad", [&] { return cnnk_linear_dgrad(rows, m, d, dt, dxo, Wm(p0 + B_W2), at(CNNK_VIT_DG, l), ws, wsb, st); });
     w.call(l, "fc1.gelu.bwd", [&] { return cnnk_bias_act_bwd(rows, m, g.dtype, CNNK_ACT_GELU, at(CNNK_VIT_DG, l), at(CNNK_VIT_U, l), at(CNNK_VIT_DU, l), Gr(p0 + B_C1), ws, wsb, st); });
-    w.call(l, "fc1.wgrad", [&] { return cnnk_conv2d_wgrad(&c_1, at(CNNK_VIT_H2, l), at(CNNK_VIT_DU, l), Gr(p0 + B_W1), ws, wsb, st); });
-    w.call(l, "fc1.dgrad", [&] { return cnnk_conv2d_dgrad(&c_1, at(CNNK_VIT_DU, l), Wm(p0 + B_W1), at(CNNK_VIT_DH2, l), 0, ws, wsb, st); });
+    w.call(l, "fc1.wgrad", [&] { return cnnk_linear_wgrad(rows, d, m, dt, at(CNNK_VIT_H2, l), at(CNNK_VIT_DU, l), Gr(p0 + B_W1), ws, wsb, st); });
+    w.call(l, "fc1.dgrad", [&] { return cnnk_linear_dgrad(rows, d, m, dt, at(CNNK_VIT_DU, l), Wm(p0 + B_W1), at(CNNK_VIT_DH2, l), ws, wsb, st); });
     w.call(l, "ln2.bwd", [&] {
       return cnnk_layernorm_bwd(&ln, at(CNNK_VIT_DH2, l), at(CNNK_VIT_XMID, l), P(p0 + B_G2), (const float*)at(X_STATS2, l), dxo,
                                 at(CNNK_VIT_DXMID, l), Gr(p0 + B_G2), Gr(p0 + B_B2), ws, wsb, st);
     });
     void* dxm = at(CNNK_VIT_DXMID, l);
     w.call(l, "proj.dbias", [&] { return cnnk_bias_act_bwd(rows, d, g.dtype, CNNK_ACT_NONE, dxm, nullptr, nullptr, Gr(p0 + B_BO), ws, wsb, st); });
-    w.call(l, "proj.wgrad", [&] { return cnnk_conv2d_wgrad(&c_o, at(CNNK_VIT_O, l), dxm, Gr(p0 + B_WO), ws, wsb, st); });
-    w.call(l, "proj.dgrad", [&] { return cnnk_conv2d_dgrad(&c_o, dxm, Wm(p0 + B_WO), at(CNNK_VIT_DO, l), 0, ws, wsb, st); });
+    w.call(l, "proj.wgrad", [&] { return cnnk_linear_wgrad(rows, d, d, dt, at(CNNK_VIT_O, l), dxm, Gr(p0 + B_WO), ws, wsb, st); });
+    w.call(l, "proj.dgrad", [&] { return cnnk_linear_dgrad(rows, d, d, dt, dxm, Wm(p0 + B_WO), at(CNNK_VIT_DO, l), ws, wsb, st); });
     w.call(l, "attn.bwd", [&] { return cnnk_attention_bwd(&ad, at(CNNK_VIT_QKV, l), at(CNNK_VIT_O, l), at(CNNK_VIT_DO, l), (const float*)at(X_LSE, l), at(CNNK_VIT_DQKV, l), st); });
     w.call(l, "qkv.dbias", [&] { return cnnk_bias_act_bwd(rows, 3 * d, g.dtype, CNNK_ACT_NONE, at(CNNK_VIT_DQKV, l), nullptr, nullptr, Gr(p0 + B_BQKV), ws, wsb, st); });
-    w.call(l, "qkv.wgrad", [&] { return cnnk_conv2d_wgrad(&c_qkv, at(CNNK_VIT_H, l), at(CNNK_VIT_DQKV, l), Gr(p0 + B_WQKV), ws, wsb, st); });
-    w.call(l, "qkv.dgrad", [&] { return cnnk_conv2d_dgrad(&c_qkv, at(CNNK_VIT_DQKV, l), Wm(p0 + B_WQKV), at(CNNK_VIT_DH, l), 0, ws, wsb, st); });
+    w.call(l, "qkv.wgrad", [&] { return cnnk_linear_wgrad(rows, d, 3 * d, dt, at(CNNK_VIT_H, l), at(CNNK_VIT_DQKV, l), Gr(p0 + B_WQKV), ws, wsb, st); });
+    w.call(l, "qkv.dgrad", [&] { return cnnk_linear_dgrad(rows, d, 3 * d, dt, at(CNNK_VIT_DQKV, l), Wm(p0 + B_WQKV), at(CNNK_VIT_DH, l), ws, wsb, st); });
     w.call(l, "ln1.bwd", [&] {
       return cnnk_layernorm_bwd(&ln, at(CNNK_VIT_DH, l), xin, P(p0 + B_G1), (const float*)at(X_STATS1, l), dxm, dxin, Gr(p0 + B_G1),
                                 Gr(p0 + B_B1), ws, wsb, st);
     });
   }
   w.call(-1, "embed.tokens.bwd", [&] { return cnnk_vit_embed_bwd(&ed, at(CNNK_VIT_DTOK, 0), at(X_DZ0, 0), Gr(P_BE), Gr(P_CLS), Gr(P_POS), st); });
-  w.call(-1, "embed.wgrad", [&] { return cnnk_conv2d_wgrad(&c_emb, at(CNNK_VIT_PATCHES, 0), at(X_DZ0, 0), Gr(P_WE), ws, wsb, st); });
+  w.call(-1, "embed.wgrad", [&] { return cnnk_linear_wgrad(prow, g.K0, d, dt, at(CNNK_VIT_PATCHES, 0), at(X_DZ0, 0), Gr(P_WE), ws, wsb, st); });
   // ---- update ----
   w.call(-1, "update", [&] {
     const int np = p_tail + 4;

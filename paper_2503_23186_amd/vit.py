@@ -8,7 +8,7 @@ import torch
 from . import cnnk
 from .cnnk import lib, ptr, _check, F32, BF16
 
-EXPORTS = ["cnnk_layernorm_fwd", "cnnk_layernorm_workspace_bytes", "cnnk_layernorm_bwd", "cnnk_bias_act_fwd",
+EXPORTS = ["cnnk_linear_workspace_bytes", "cnnk_linear_fwd", "cnnk_linear_dgrad", "cnnk_linear_wgrad", "cnnk_layernorm_fwd", "cnnk_layernorm_workspace_bytes", "cnnk_layernorm_bwd", "cnnk_bias_act_fwd",
            "cnnk_bias_act_workspace_bytes", "cnnk_bias_act_bwd", "cnnk_attention_fwd", "cnnk_attention_bwd",
            "cnnk_vit_patchify", "cnnk_vit_embed_fwd", "cnnk_vit_embed_bwd", "cnnk_vit_arena_bytes",
            "cnnk_vit_workspace_bytes", "cnnk_vit_tensor", "cnnk_vit_step_calls", "cnnk_vit_step_call_name",
@@ -55,6 +55,11 @@ def _declare():
     lib.cnnk_bias_act_workspace_bytes.restype = sz
     lib.cnnk_bias_act_workspace_bytes.argtypes = [ll, ci]
     lib.cnnk_bias_act_bwd.argtypes = [ll, ci, ci, ci, vp, vp, vp, vp, vp, sz, vp]
+    lib.cnnk_linear_workspace_bytes.restype = sz
+    lib.cnnk_linear_workspace_bytes.argtypes = [ll, ci, ci, ci]
+    lib.cnnk_linear_fwd.argtypes = [ll, ci, ci, ci, vp, vp, vp, ci, vp, vp, vp, sz, vp]
+    lib.cnnk_linear_dgrad.argtypes = [ll, ci, ci, ci, vp, vp, vp, vp, sz, vp]
+    lib.cnnk_linear_wgrad.argtypes = [ll, ci, ci, ci, vp, vp, vp, vp, sz, vp]
     lib.cnnk_attention_fwd.argtypes = [C.POINTER(AttnDesc), vp, vp, vp, vp]
     lib.cnnk_attention_bwd.argtypes = [C.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp]
     lib.cnnk_vit_patchify.argtypes = [C.POINTER(EmbedDesc), vp, vp, vp]
@@ -101,6 +106,23 @@ def cnnk_bias_act_workspace_bytes(rows, Cc):
 def cnnk_bias_act_bwd(rows, Cc, dtype, act, dy, u, dz, dbias, ws, ws_bytes, stream=0):
     _check(lib.cnnk_bias_act_bwd(rows, Cc, dtype, act, ptr(dy), ptr(u), ptr(dz), ptr(dbias), ptr(ws), ws_bytes, stream),
            "cnnk_bias_act_bwd")
+
+
+def cnnk_linear_workspace_bytes(rows, K, N, dtype):
+    return int(lib.cnnk_linear_workspace_bytes(rows, K, N, dtype))
+
+
+def cnnk_linear_fwd(rows, K, N, dtype, x, w, bias, act, u, y, ws=None, ws_bytes=0, stream=0):
+    _check(lib.cnnk_linear_fwd(rows, K, N, dtype, ptr(x), ptr(w), ptr(bias), act, ptr(u), ptr(y), ptr(ws), ws_bytes, stream),
+           "cnnk_linear_fwd")
+
+
+def cnnk_linear_dgrad(rows, K, N, dtype, dy, w, dx, ws=None, ws_bytes=0, stream=0):
+    _check(lib.cnnk_linear_dgrad(rows, K, N, dtype, ptr(dy), ptr(w), ptr(dx), ptr(ws), ws_bytes, stream), "cnnk_linear_dgrad")
+
+
+def cnnk_linear_wgrad(rows, K, N, dtype, x, dy, dw, ws=None, ws_bytes=0, stream=0):
+    _check(lib.cnnk_linear_wgrad(rows, K, N, dtype, ptr(x), ptr(dy), ptr(dw), ptr(ws), ws_bytes, stream), "cnnk_linear_wgrad")
 
 
 def attn_desc(B, T, heads, dh, dtype):

@@ -111,6 +111,67 @@ def test_bias_activation_residual(K, rows, C, dtype):
     assert (host(gz) == u).all()
 
 
+# bf16 with rows, K, N multiples of 32 runs on the dense matrix-core kernels (256 x 128 tiles: ragged
+# row and column tiles, one to many reduction stages, split and unsplit weight gradients); the rest,
+# and "bf16-conv", on the 1 x 1 convolution kernels.  The last shapes are ViT-B/16's at batch 64.
+LINEAR_SHAPES = [(64, 32, 32), (288, 64, 160), (1056, 768, 96), (68, 128, 256), (100, 40, 24), (512, 3072, 128),
+                 (12608, 768, 2304), (12608, 3072, 768), (12544, 768, 768)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "bf16-conv"])
+@pytest.mark.parametrize("rows,Kd,N", LINEAR_SHAPES)
+def test_linear_layers(K, rows, Kd, N, dtype):
+    from paper_2503_23186_amd import cnnk
+    if dtype == "f32" and rows > 2000:
+        pytest.skip("the fp32 mode is a small-shape validation mode")
+    if dtype == "bf16-conv":
+        if rows % 32 or Kd % 32 or N % 32 or rows > 2000:
+            pytest.skip("already on the convolution kernels / covered by the convolution tests")
+        cnnk.cnnk_tune(15, -1)
+    try:
+        _linear_case(K, rows, Kd, N, "bf16" if dtype == "bf16-conv" else dtype)
+    finally:
+        cnnk.cnnk_tune(15, 0)
+
+
+def _linear_case(K, rows, Kd, N, dtype):
+    rng = np.random.default_rng(rows + Kd + N)
+    x = rep(rng.standard_normal((rows, Kd)), dtype)
+    w = rep(rng.standard_normal((N, Kd)) / np.sqrt(Kd), dtype)
+    bias = rep(0.5 * rng.standard_normal(N), "f32")
+    dy = rep(rng.standard_normal((rows, N)), dtype)
+    dt = dt_of(K, dtype)
+    ws, nb = ws_for(K.cnnk_linear_workspace_bytes(rows, Kd, N, dt))
+    gx, gw, gdy = dev(x, dtype), dev(w, dtype), dev(dy, dtype)
+    tol = OUT_TOL[dtype] if dtype == "bf16" else 2e-5
+    z = x @ w.T
+    for b in (None, bias):
+        gy = dev(np.zeros((rows, N)), dtype)
+        K.cnnk_linear_fwd(rows, Kd, N, dt, gx, gw, None if b is None else dev_f32(b), K.ACT_NONE, None, gy, ws, nb)
+        torch.cuda.synchronize()
+        # convolution path in bf16: the product is rounded before the bias is added, and again after
+        assert max_rel_err(host(gy), z + (0.0 if b is None else b)) <= tol * (2 if (dtype == "bf16" and b is not None) else 1)
+    gu, gy = dev(np.zeros((rows, N)), dtype), dev(np.zeros((rows, N)), dtype)
+    K.cnnk_linear_fwd(rows, Kd, N, dt, gx, gw, dev_f32(bias), K.ACT_GELU, gu, gy, ws, nb)
+    torch.cuda.synchronize()
+    u = host(gu)
+    assert max_rel_err(u, z + bias) <= tol * (2 if dtype == "bf16" else 1)       # convolution path: z is rounded before the bias
+    assert max_rel_err(host(gy), V.gelu(u)) <= tol
+    gdx = dev(np.zeros((rows, Kd)), dtype)
+    K.cnnk_linear_dgrad(rows, Kd, N, dt, gdy, gw, gdx, ws, nb)
+    torch.cuda.synchronize()
+    assert max_rel_err(host(gdx), dy @ w) <= tol
+    gdw = torch.full((N, Kd), 3.0, device="cuda:0")
+    K.cnnk_linear_wgrad(rows, Kd, N, dt, gx, gdy, gdw, ws, nb)
+    torch.cuda.synchronize()
+    assert max_rel_err(host(gdw), dy.T @ x) <= 2e-5
+    # bit-reproducible
+    gdw2 = torch.zeros((N, Kd), device="cuda:0")
+    K.cnnk_linear_wgrad(rows, Kd, N, dt, gx, gdy, gdw2, ws, nb)
+    torch.cuda.synchronize()
+    assert torch.equal(gdw, gdw2)
+
+
 # bf16 with head size 64 runs on the matrix cores (one 32-token block per wavefront: 17, 197, 256, 33
 # tokens = 1, 7, 8, 2 blocks with ragged and full last blocks); "bf16-valu" forces the general kernels
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "bf16-valu"])
