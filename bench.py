@@ -4,7 +4,8 @@
 A step is one pass of the whole hot path (forward, loss, backward, SGD-momentum update) over one
 batch of seeded synthetic CIFAR-100-shaped data, resident in HBM before the timed region starts.
 Workload: ResNet-18 adapted to 32x32 inputs, 100 classes, bf16 storage / fp32 accumulate, batch 256
-(--config picks another network).  Prints ONE JSON line: metric / value (images/s) / ms_per_step,
+(--config 1..5 picks another of the convolutional networks, --config 6 the paper's second model
+family: ViT-B/16 on 224x224 inputs at batch 64).  Prints ONE JSON line: metric / value (images/s) / ms_per_step,
 `roofline` for the call class with the largest time per step (measured with HIP events recorded
 on the launch stream around every entry-point call, in extra single-stream steps that two marker
 launches bracket in a kernel trace), `cpu_baseline` (the fp64 oracle timed on a
@@ -87,6 +88,155 @@ def layer_work(L, phase, esz):
     return 0.0, 0.0
 
 
+def vit_call_work(net, name):
+    """(kind, flops, bytes) of one call of the transformer step, by its name without the block prefix.
+    Algorithmic work: matrix products at their true sizes (recomputation inside the attention backward
+    is not counted), element-wise calls at the tensors they must read and write once."""
+    B, T, d, m, h = net.batch, net.tokens, net.dim, net.mlp, net.heads
+    rows, es = B * T, 2 if net.dtype == "bf16" else 4
+    lin = {"qkv": (d, 3 * d), "proj": (d, d), "fc1": (d, m), "fc2": (m, d), "embed": (net.patch * net.patch * 3, d)}
+    part = name.split(".")
+    if part[0] in lin and part[1] in ("gemm", "gemm_gelu", "dgrad", "wgrad"):
+        K, N = lin[part[0]]
+        r = B * (T - 1) if part[0] == "embed" else rows
+        out_b = {"gemm": r * N * es, "gemm_gelu": 2 * r * N * es, "dgrad": r * K * es, "wgrad": N * K * 4}[part[1]]
+        in_b = {"gemm": r * K * es, "gemm_gelu": r * K * es, "dgrad": r * N * es, "wgrad": r * (K + N) * es}[part[1]]
+        return "mfma", 2.0 * r * K * N, in_b + out_b + (0 if part[1] == "wgrad" else N * K * es)
+    if name == "attn":
+        return "mfma", 4.0 * B * h * T * T * (d // h), rows * 4 * d * es
+    if name == "attn.bwd":
+        return "mfma", 10.0 * B * h * T * T * (d // h), rows * (3 * d + 2 * d + 3 * d) * es
+    ew = {"ln1": 2 * d, "ln2": 2 * d, "ln1.bwd": 4 * d, "ln2.bwd": 4 * d, "proj.res": 3 * d, "fc2.res": 3 * d,
+          "fc1.gelu.bwd": 3 * m, "qkv.dbias": 3 * d, "proj.dbias": d, "fc2.dbias": d}
+    if name in ew:
+        return "hbm", 0.0, rows * ew[name] * es
+    if name == "update":
+        return "hbm", 0.0, net.n_params() * 22
+    return "hbm", 0.0, 0
+
+
+def bench_vit(args):
+    """The same measurement for the paper's second model family: ViT-B/16 on 224 x 224 inputs."""
+    import numpy as np
+    import torch
+    import workloads as WL
+    from paper_2503_23186_amd import cnnk as _cnnk
+    from paper_2503_23186_amd.vit import VitRunner
+    net = WL.vit_b16(batch=args.batch or 64)
+    inp = WL.make_vit_inputs(net, 6)
+    run = VitRunner(net, keep_probs=False)
+    run.load(inp["x"], inp["labels"], inp["params"], inp["mom"])
+    lr, mu, wd = 0.01, 0.9, 0.0
+    stream = torch.cuda.current_stream().cuda_stream
+    cal = torch.zeros(2 * CAL_ELEMS, dtype=torch.bfloat16, device="cuda:0")
+    _cnnk.cnnk_grad_route(CAL_ELEMS, _cnnk.BF16, cal, cal[CAL_ELEMS:], 0, stream)
+    torch.cuda.synchronize()
+    for _ in range(args.warmup):
+        run.step(lr, mu, wd)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run.step(lr, mu, wd)
+    torch.cuda.synchronize()
+    ms_per_step = 1e3 * (time.perf_counter() - t0) / args.steps
+    loss = run.loss.item()
+    assert np.isfinite(loss), "loss is not finite"
+
+    run.enable_timing(True)
+    nt = max(args.timed_steps, 1)
+    acc = {}
+    per_call = np.zeros(run.n_calls)
+    _cnnk.cnnk_grad_route(MARK_BEGIN_ELEMS, _cnnk.BF16, cal, cal[CAL_ELEMS:], 0, stream)
+    for _ in range(nt):
+        run.step(lr, mu, wd)
+        torch.cuda.synchronize()
+        times = run.call_times_ms()
+        per_call += np.asarray(times) / nt
+        for name, t in zip(run.call_names, times):
+            key = name.split(".", 1)[1] if name.startswith("block") else name
+            a = acc.setdefault(key, dict(ms=0.0, calls=0))
+            a["ms"] += t
+            a["calls"] += 1
+    _cnnk.cnnk_grad_route(MARK_END_ELEMS, _cnnk.BF16, cal, cal[CAL_ELEMS:], 0, stream)
+    torch.cuda.synchronize()
+    run.enable_timing(False)
+    del cal
+    # what an event pair costs with one tiny launch inside: the smallest call of the step
+    ev_overhead = min(a["ms"] / a["calls"] for a in acc.values()) * 0.5
+    rows = []
+    for key, a in acc.items():
+        kind, fl, by = vit_call_work(net, key)
+        avg = max(a["ms"] / a["calls"] - ev_overhead, 1e-6)
+        rows.append(dict(key=key, kind=kind, calls_per_step=a["calls"] // nt, avg_ms=avg, ms_per_step=avg * a["calls"] / nt,
+                         flops=fl, bytes=by))
+    rows.sort(key=lambda r: -r["ms_per_step"])
+    if args.layers:
+        for r in rows:
+            sys.stderr.write("%-20s x%-2d %8.3f ms/call %8.3f ms/step %8.1f TFLOP/s %8.1f GB/s\n"
+                             % (r["key"], r["calls_per_step"], r["avg_ms"], r["ms_per_step"], r["flops"] / r["avg_ms"] / 1e9,
+                                r["bytes"] / r["avg_ms"] / 1e6))
+    dom = rows[0]
+    if dom["kind"] == "mfma":
+        ach = dom["flops"] / dom["avg_ms"] / 1e9
+        roof = dict(bound="mfma", kernel=dom["key"], achieved=round(ach, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                    frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None, avg_ms=round(dom["avg_ms"], 4),
+                    calls_per_step=dom["calls_per_step"])
+    else:
+        ach = dom["bytes"] / dom["avg_ms"] / 1e6
+        roof = dict(bound="hbm", kernel=dom["key"], achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                    frac=round(ach / PEAK_HBM_GBS, 4), traffic=None, avg_ms=round(dom["avg_ms"], 4),
+                    calls_per_step=dom["calls_per_step"])
+    mm = [r for r in rows if r["kind"] == "mfma"]
+    ew = [r for r in rows if r["kind"] == "hbm" and r["bytes"]]
+    mm_ms, ew_ms = sum(r["ms_per_step"] for r in mm), sum(r["ms_per_step"] for r in ew)
+    mm_fl = sum(r["flops"] * r["calls_per_step"] for r in mm)
+    ew_by = sum(r["bytes"] * r["calls_per_step"] for r in ew)
+    roof["matmul_all"] = dict(tflops=round(mm_fl / mm_ms / 1e9, 2), frac_of_mfma_peak=round(mm_fl / mm_ms / 1e9 / PEAK_BF16_TFLOPS, 4),
+                              ms_per_step=round(mm_ms, 4))
+    roof["elementwise_all"] = dict(gbs=round(ew_by / ew_ms / 1e6, 1), frac_of_hbm_peak=round(ew_by / ew_ms / 1e6 / PEAK_HBM_GBS, 4),
+                                   ms_per_step=round(ew_ms, 4))
+
+    # the scheduler's choice for 8 such devices: components = embedding, per block its attention half
+    # and its MLP half, head; times from the calls above (Section III-B/III-C; a prediction)
+    from paper_2503_23186_amd import asa
+    comps = asa.components_from_vit(net, run.call_names, [max(t - ev_overhead, 0.0) for t in per_call])
+    plan = asa.solve(comps, asa.Cluster(K=8, mem=288e9, bw=153e9, lat=5e-6, d=2))
+    by_part = {}
+    for c, s_ in zip(comps, plan.assignment):
+        part = c.name.split(".")[-1]
+        by_part.setdefault(part, {}).setdefault(s_[0], 0)
+        by_part[part][s_[0]] += 1
+    asa_out = dict(devices=8, components=len(comps), predicted_ms_per_step=round(plan.time * 1e3, 4),
+                   single_device_ms=round(sum(c.t for c in comps) * 1e3, 4), strategies=by_part,
+                   basis="cost model of the paper's scheduler over this run's measured per-call times; prediction only")
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import vit as OV
+        sample_batch = 2
+        small = WL.vit_b16(batch=sample_batch)
+        sinp = WL.make_vit_inputs(small, 6)
+        t0 = time.perf_counter()
+        OV.train_step(small.cfg(), sinp["x"], sinp["labels"], sinp["params"], sinp["mom"], lr, mu, wd)
+        cdt = time.perf_counter() - t0
+        import threadpoolctl
+        cores = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] or [1])
+        cpu = dict(value=round(sample_batch / cdt, 3), unit="images/s", cores=cores, kind="oracle",
+                   sample="one fp64 oracle step of the same network at batch %d (%.1f s)" % (sample_batch, cdt))
+    out = {
+        "metric": "train images/sec on 1 GPU (ViT-B/16 224x224 bf16 b%d); matmul MFMA %% of peak" % net.batch,
+        "value": round(net.batch / (ms_per_step * 1e-3), 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": net.dtype, "data": "synthetic",
+        "config": {"workload": "ViT-B/16 224x224x3 100-class (197 tokens, width 768, 12 blocks, 85.9 M parameters), batch %d, "
+                               "%s storage / fp32 accumulate, SGD momentum" % (net.batch, net.dtype),
+                   "config_id": 6, "global_batch": net.batch, "loss": round(loss, 5),
+                   "tflops_per_step": round(net.flops() / 1e12, 3)},
+        "roofline": roof, "cpu_baseline": cpu, "asa_plan": asa_out,
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -118,6 +268,8 @@ def main():
         from paper_2503_23186_amd import cnnk
         k, v = kv.split("=")
         cnnk.cnnk_tune(int(k), int(v))
+    if args.config == 6:
+        return bench_vit(args)
     kw = {"batch": args.batch} if args.batch else {}
     net = WL.build_config(args.config, **kw)
     inp = WL.make_inputs(net, args.config)

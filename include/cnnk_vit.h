@@ -61,9 +61,9 @@ int cnnk_bias_act_bwd(long long rows, int C, int dtype, int act, const void* dy,
  * float or NULL.  fwd: act = NONE: y = x w^T + bias;  act = GELU (bias required): u = x w^T + bias is
  * stored and y = gelu(u as stored), as in cnnk_bias_act_fwd.  dgrad: dx [rows][K] = dy w.
  * wgrad: dw [N][K] float = dy^T x (the bias gradient is cnnk_bias_act_bwd's column sum).
- * K % 8 == 0, N % 8 == 0.  bf16 with rows, K, N multiples of 32 runs on dedicated matrix-core
- * kernels (an output is rounded once, after bias); everything else on the 1 x 1 convolution kernels
- * of cnnk.h followed by cnnk_bias_act_fwd (cnnk_tune key 15 = -1 forces that path).  The weight
+ * K % 8 == 0, N % 8 == 0.  bf16 runs on dedicated matrix-core kernels (an output is rounded once,
+ * after bias); fp32 on the 1 x 1 convolution kernels of cnnk.h followed by cnnk_bias_act_fwd
+ * (cnnk_tune key 15 = -1 forces that path for bf16 too).  The weight
  * gradient is a fixed-order sum of per-row-range partials: reproducible bit for bit. */
 size_t cnnk_linear_workspace_bytes(long long rows, int K, int N, int dtype);
 int cnnk_linear_fwd(long long rows, int K, int N, int dtype, const void* x, const void* w,

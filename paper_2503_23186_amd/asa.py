@@ -259,6 +259,46 @@ def components_from_tape(layers, rows, dtype="bf16", group="conv") -> List[Compo
     return comps
 
 
+def components_from_vit(net, call_names, times_ms) -> List[Component]:
+    """Logical components of a Vision Transformer out of the per-call times of cnnk_vit_train_step
+    (names as cnnk_vit_step_call_name lists them): the embedding, per block its attention half
+    (first norm, QKV, attention, projection) and its MLP half (second norm, two linear layers), and
+    the head.  The update's time is spread in proportion to parameter bytes."""
+    esz = 2 if net.dtype == "bf16" else 4
+    d, m, T, B = net.dim, net.mlp, net.tokens, net.batch
+    rows = B * T
+    t = {}
+    t_update = 0.0
+    for name, ms in zip(call_names, times_ms):
+        if name == "update":
+            t_update += ms * 1e-3
+            continue
+        if name.startswith("block"):
+            blk, rest = name.split(".", 1)
+            half = "attention" if rest.split(".")[0] in ("ln1", "qkv", "attn", "proj") else "mlp"
+            key = "%s.%s" % (blk, half)
+        else:
+            key = name.split(".")[0]
+        t[key] = t.get(key, 0.0) + ms * 1e-3
+    n_emb = d * net.patch * net.patch * 3 + 2 * d + T * d
+    n_att = 2 * d + 3 * d * d + 3 * d + d * d + d
+    n_mlp = 2 * d + 2 * d * m + m + d
+    n_head = 2 * d + net.classes * d + net.classes
+    total = n_emb + net.layers * (n_att + n_mlp) + n_head
+    out = []
+
+    def comp(name, n_p, n_matrix, kept_elems, out_elems):
+        return Component(name=name, t=t.get(name, 0.0) + t_update * n_p / total, G=4.0 * n_p, O=float(out_elems * esz),
+                         S=12.0 * n_p + (2.0 * n_matrix if net.dtype == "bf16" else 0.0), A=float(kept_elems * esz))
+
+    out.append(comp("embed", n_emb, d * net.patch * net.patch * 3, B * (T - 1) * net.patch * net.patch * 3 + rows * d, rows * d))
+    for l in range(net.layers):
+        out.append(comp("block%d.attention" % l, n_att, 4 * d * d, rows * (d + 3 * d + d + d), rows * d))
+        out.append(comp("block%d.mlp" % l, n_mlp, 2 * d * m, rows * (d + 2 * m + d), rows * d))
+    out.append(comp("head", n_head, 0, B * d, B * net.classes))
+    return out
+
+
 def changed_significantly(old_times: Sequence[float], new_times: Sequence[float], rel=0.1) -> bool:
     """Algorithm 1's "if communication patterns changed significantly: re-profile and update
     strategy".  The paper names no criterion; reading: some component's measured time moved by more

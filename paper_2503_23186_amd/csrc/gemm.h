@@ -3,7 +3,7 @@
 #pragma once
 #include "common.h"
 
-// K, N and rows multiples of 32, every matrix below 2 GiB
+// K and N multiples of 8, every matrix below 2 GiB
 bool gemm_bf16_supported(long long rows, int K, int N);
 // y = x w^T + bias (bias may be null); with gelu: u = x w^T + bias, y = gelu(u as stored)
 int gemm_bf16_fwd(long long rows, int K, int N, const bf16_t* x, const bf16_t* w, const float* bias, bool gelu, bf16_t* u,

@@ -78,12 +78,14 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_kernel(Args a) {
   const int kbeg = blockIdx.z * a.k_per_split;
   int kend = kbeg + a.k_per_split;
   if (kend > a.K) kend = a.K;
-  const int nst = (kend - kbeg) / BK;
+  const int nst = kend > kbeg ? (kend - kbeg + BK - 1) / BK : 0;
 
   const i32x4_t a_rs = make_desc(a.A, a.a_bytes), b_rs = make_desc(a.B, a.b_bytes);
   // ---- this lane's six direct loads of a stage ----
+  // kk0: reduction index of the lane's 16 bytes in stage 0 (its first element for a natural operand,
+  // its row for a transposed one); a load of stage t is in range while kk0 + t * BK < kend
   unsigned voff[NLOAD], vinc[NLOAD];
-  int ldsoff[NLOAD];
+  int ldsoff[NLOAD], kk0[NLOAD];
   bool isA[NLOAD];
 #pragma unroll
   for (int j = 0; j < NLOAD; ++j) {
@@ -99,20 +101,22 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_kernel(Args a) {
       const int r = qq * 16 + (lane >> 2);
       const int c = cp ^ ((r >> 2) & 3);
       const int row = o0 + r;
-      voff[j] = row < olim ? (unsigned)((row * ld + kbeg + 8 * c) * 2) : kOobOffset;
+      kk0[j] = row < olim ? kbeg + 8 * c : (1 << 30);
+      voff[j] = (unsigned)((row * ld + kbeg + 8 * c) * 2);
       vinc[j] = BK * 2;
     } else {
       const int plane = qq >> 1, r = (qq & 1) * 16 + (lane >> 2);
       const int c = cp ^ ((r >> 2) & 3);
       const int col = o0 + plane * 32 + 8 * c;
-      voff[j] = col < olim ? (unsigned)(((kbeg + r) * ld + col) * 2) : kOobOffset;
+      kk0[j] = col < olim ? kbeg + r : (1 << 30);
+      voff[j] = (unsigned)(((kbeg + r) * ld + col) * 2);
       vinc[j] = (unsigned)(BK * ld * 2);
     }
   }
   auto issue = [&](int t, int sb) __attribute__((always_inline)) {
 #pragma unroll
     for (int j = 0; j < NLOAD; ++j) {
-      const unsigned off = voff[j] == kOobOffset ? kOobOffset : voff[j] + (unsigned)t * vinc[j];
+      const unsigned off = kk0[j] + t * BK < kend ? voff[j] + (unsigned)t * vinc[j] : kOobOffset;
       load16_to_lds(isA[j] ? a_rs : b_rs, (unsigned)(sb + ldsoff[j]), off);
     }
   };
@@ -275,8 +279,7 @@ int wgrad_splits(int rows, int tiles) {
 }  // namespace
 
 bool gemm_bf16_supported(long long rows, int K, int N) {
-  return rows > 0 && K > 0 && N > 0 && K % 32 == 0 && N % 32 == 0 && rows % 32 == 0 && fits32(rows, K) && fits32(rows, N) &&
-         fits32(N, K);
+  return rows > 0 && K > 0 && N > 0 && K % 8 == 0 && N % 8 == 0 && fits32(rows, K) && fits32(rows, N) && fits32(N, K);
 }
 
 int gemm_bf16_fwd(long long rows, int K, int N, const bf16_t* x, const bf16_t* w, const float* bias, bool gelu, bf16_t* u,
@@ -313,7 +316,7 @@ int gemm_bf16_wgrad(long long rows, int K, int N, const bf16_t* x, const bf16_t*
   a.M = N; a.N = K; a.K = (int)rows; a.lda = N; a.ldb = K; a.ldc = K;
   a.mtiles = (N + BM - 1) / BM; a.ntiles = (K + BN - 1) / BN;
   const int splits = wgrad_splits((int)rows, a.mtiles * a.ntiles);
-  const int stages = ((int)rows / BK + splits - 1) / splits;
+  const int stages = (((int)rows + BK - 1) / BK + splits - 1) / splits;
   a.k_per_split = stages * BK;
   a.part = splits > 1 ? (float*)ws : dw;
   a.a_bytes = (unsigned)(rows * N * 2); a.b_bytes = (unsigned)(rows * K * 2);
