@@ -71,72 +71,94 @@ __global__ void __launch_bounds__(kT) ln_fwd_kernel(const T* __restrict__ x, lon
   if (lane == 0) { stats[2 * (size_t)row] = mean; stats[2 * (size_t)row + 1] = rstd; }
 }
 
-// A wavefront walks rows row0, row0 + stride, ...; per row two wave reductions give the two
-// projections that the normalisation removes; the lane keeps its columns' contributions to
-// dgamma / dbeta in registers over all its rows.  The four wavefronts of a workgroup then add
-// theirs in LDS one after the other (fixed order) and the workgroup writes one partial row.
-template <typename T, int NQ>
+// A wavefront walks its rows two at a time (both rows' loads are in flight together); per row two
+// wave reductions give the two projections that the normalisation removes; the lane keeps its
+// columns' contributions to dgamma / dbeta in registers over all its rows.  The four wavefronts of a
+// workgroup then add theirs in LDS one after the other (fixed order) and the workgroup writes one
+// partial row.  VW elements per access (8 where C allows), NV vectors of the row per lane.
+template <int VW, typename T> __device__ __forceinline__ void loadv(const T* p, float* f) {
+  if (VW == 8) load8(p, f); else load4(p, f);
+}
+template <int VW, typename T> __device__ __forceinline__ void storev(T* p, const float* f) {
+  if (VW == 8) store8(p, f); else store4(p, f);
+}
+
+template <typename T, int NV, int VW>
 __global__ void __launch_bounds__(kT) ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x, long long xs,
                                                     const float* __restrict__ g, const float* __restrict__ stats,
                                                     const T* dres, T* dx, float* __restrict__ part, int rows, int C) {
   extern __shared__ float sm[];     // [2][C]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  float gg[NQ][4], ag[NQ][4], ab[NQ][4];
+  float gg[NV][VW], ag[NV][VW], ab[NV][VW];
 #pragma unroll
-  for (int i = 0; i < NQ; ++i) {
-    const int c = (i * 64 + lane) * 4;
+  for (int i = 0; i < NV; ++i) {
+    const int c = (i * 64 + lane) * VW;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) { ag[i][k] = 0.f; ab[i][k] = 0.f; gg[i][k] = 0.f; }
-    if (c < C) { const float4 t = *reinterpret_cast<const float4*>(g + c); gg[i][0] = t.x; gg[i][1] = t.y; gg[i][2] = t.z; gg[i][3] = t.w; }
+    for (int k = 0; k < VW; ++k) { ag[i][k] = 0.f; ab[i][k] = 0.f; gg[i][k] = 0.f; }
+    if (c < C) loadv<VW>(g + c, gg[i]);
   }
-  for (int row = blockIdx.x * (kT / 64) + wave; row < rows; row += gridDim.x * (kT / 64)) {
-    const float mean = stats[2 * (size_t)row], rstd = stats[2 * (size_t)row + 1];
-    float d[NQ][4], xh[NQ][4];
-    float s1 = 0.f, s2 = 0.f;
+  const int stride = gridDim.x * (kT / 64);
+  for (int row0 = blockIdx.x * (kT / 64) + wave; row0 < rows; row0 += 2 * stride) {
+    float d[2][NV][VW], xh[2][NV][VW], rr[2][NV][VW];
+    float mean[2], rstd[2];
 #pragma unroll
-    for (int i = 0; i < NQ; ++i) {
-      const int c = (i * 64 + lane) * 4;
-      if (c < C) {
-        load4(dy + (size_t)row * C + c, d[i]);
-        load4(x + (size_t)row * xs + c, xh[i]);
+    for (int u = 0; u < 2; ++u) {
+      const int row = row0 + u * stride;
+      const bool live = row < rows;
+      mean[u] = live ? stats[2 * (size_t)row] : 0.f;
+      rstd[u] = live ? stats[2 * (size_t)row + 1] : 0.f;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          xh[i][k] = (xh[i][k] - mean) * rstd;
-          ab[i][k] += d[i][k];
-          ag[i][k] += d[i][k] * xh[i][k];
-          d[i][k] *= gg[i][k];
-          s1 += d[i][k];
-          s2 += d[i][k] * xh[i][k];
+      for (int i = 0; i < NV; ++i) {
+        const int c = (i * 64 + lane) * VW;
+        if (live && c < C) {
+          loadv<VW>(dy + (size_t)row * C + c, d[u][i]);
+          loadv<VW>(x + (size_t)row * xs + c, xh[u][i]);
+          if (dres) loadv<VW>(dres + (size_t)row * xs + c, rr[u][i]);
+        } else {
+#pragma unroll
+          for (int k = 0; k < VW; ++k) { d[u][i][k] = 0.f; xh[u][i][k] = mean[u]; }
         }
       }
     }
-    s1 = wave_sum(s1) / (float)C;
-    s2 = wave_sum(s2) / (float)C;
 #pragma unroll
-    for (int i = 0; i < NQ; ++i) {
-      const int c = (i * 64 + lane) * 4;
-      if (c < C) {
-        float o[4];
+    for (int u = 0; u < 2; ++u) {
+      const int row = row0 + u * stride;
+      float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) o[k] = rstd * (d[i][k] - s1 - xh[i][k] * s2);
-        if (dres) {
-          float r[4];
-          load4(dres + (size_t)row * xs + c, r);
+      for (int i = 0; i < NV; ++i)
 #pragma unroll
-          for (int k = 0; k < 4; ++k) o[k] += r[k];
+        for (int k = 0; k < VW; ++k) {
+          xh[u][i][k] = (xh[u][i][k] - mean[u]) * rstd[u];
+          ab[i][k] += d[u][i][k];
+          ag[i][k] += d[u][i][k] * xh[u][i][k];
+          d[u][i][k] *= gg[i][k];
+          s1 += d[u][i][k];
+          s2 += d[u][i][k] * xh[u][i][k];
         }
-        store4(dx + (size_t)row * xs + c, o);
+      s1 = wave_sum(s1) / (float)C;
+      s2 = wave_sum(s2) / (float)C;
+      if (row < rows) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+          const int c = (i * 64 + lane) * VW;
+          if (c < C) {
+            float o[VW];
+#pragma unroll
+            for (int k = 0; k < VW; ++k) o[k] = rstd[u] * (d[u][i][k] - s1 - xh[u][i][k] * s2) + (dres ? rr[u][i][k] : 0.f);
+            storev<VW>(dx + (size_t)row * xs + c, o);
+          }
+        }
       }
     }
   }
   for (int w = 0; w < kT / 64; ++w) {
     if (wave == w) {
 #pragma unroll
-      for (int i = 0; i < NQ; ++i) {
-        const int c = (i * 64 + lane) * 4;
+      for (int i = 0; i < NV; ++i) {
+        const int c = (i * 64 + lane) * VW;
         if (c < C) {
 #pragma unroll
-          for (int k = 0; k < 4; ++k) {
+          for (int k = 0; k < VW; ++k) {
             sm[c + k] = (w ? sm[c + k] : 0.f) + ag[i][k];
             sm[C + c + k] = (w ? sm[C + c + k] : 0.f) + ab[i][k];
           }
@@ -148,22 +170,32 @@ __global__ void __launch_bounds__(kT) ln_bwd_kernel(const T* __restrict__ dy, co
   for (int c = threadIdx.x; c < 2 * C; c += kT) part[(size_t)blockIdx.x * 2 * C + c] = sm[c];
 }
 
-// out[c] = sum_b part[b][c], b ascending; columns [0, n0) go to out0, the rest to out1.
+// out[c] = sum_b part[b][c]; columns [0, n0) go to out0, the rest to out1.  A workgroup owns 64
+// columns; four threads per column each add every fourth partial (sixteen loads in flight), then the
+// four meet in LDS: a fixed order, so the sums are reproducible.
 __global__ void __launch_bounds__(kT) colsum_finalize_kernel(const float* __restrict__ part, int nb, int n, int n0,
                                                              float* __restrict__ out0, float* __restrict__ out1) {
-  const int c = blockIdx.x * kT + threadIdx.x;
-  if (c >= n) return;
+  __shared__ float sm[4][64];
+  const int cl = threadIdx.x & 63, pl = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cl;
   float s = 0.f;
-  int b = 0;
-  for (; b + 8 <= nb; b += 8) {
-    float t[8];
+  if (c < n) {
+    int b = pl;
+    for (; b + 60 < nb; b += 64) {
+      float t[16];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) t[k] = part[(size_t)(b + k) * n + c];
+      for (int k = 0; k < 16; ++k) t[k] = part[(size_t)(b + 4 * k) * n + c];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) s += t[k];
+      for (int k = 0; k < 16; ++k) s += t[k];
+    }
+    for (; b < nb; b += 4) s += part[(size_t)b * n + c];
   }
-  for (; b < nb; ++b) s += part[(size_t)b * n + c];
-  if (c < n0) out0[c] = s; else out1[c - n0] = s;
+  sm[pl][cl] = s;
+  __syncthreads();
+  if (pl == 0 && c < n) {
+    const float r = (sm[0][cl] + sm[1][cl]) + (sm[2][cl] + sm[3][cl]);
+    if (c < n0) out0[c] = r; else out1[c - n0] = r;
+  }
 }
 
 // ---- bias, GELU, residual ----------------------------------------------------------------------------
@@ -343,7 +375,7 @@ inline unsigned grid_for(size_t work_items, unsigned cap = 8192) {
   return (unsigned)(b < 1 ? 1 : (b > cap ? cap : b));
 }
 inline int ln_nq(int C) { return C <= 256 ? 1 : C <= 1024 ? 4 : 16; }
-inline int ln_bwd_blocks(int rows) { int b = (rows + 15) / 16; return b < 1 ? 1 : (b > 512 ? 512 : b); }
+inline int ln_bwd_blocks(int rows) { int b = (rows + 7) / 8; return b < 1 ? 1 : (b > 768 ? 768 : b); }
 inline bool aligned16(const void* p) { return (((size_t)p) & 15) == 0; }
 }  // namespace
 
@@ -389,11 +421,13 @@ template <typename T>
 static void launch_ln_bwd(const cnnk_ln_desc* d, long long xs, int nb, const void* dy, const void* x, const float* g,
                           const float* stats, const void* dres, void* dx, float* part, hipStream_t st) {
   const size_t lds = (size_t)2 * d->C * sizeof(float);
-  switch (ln_nq(d->C)) {
-    case 1: ln_bwd_kernel<T, 1><<<nb, kT, lds, st>>>((const T*)dy, (const T*)x, xs, g, stats, (const T*)dres, (T*)dx, part, d->rows, d->C); break;
-    case 4: ln_bwd_kernel<T, 4><<<nb, kT, lds, st>>>((const T*)dy, (const T*)x, xs, g, stats, (const T*)dres, (T*)dx, part, d->rows, d->C); break;
-    default: ln_bwd_kernel<T, 16><<<nb, kT, lds, st>>>((const T*)dy, (const T*)x, xs, g, stats, (const T*)dres, (T*)dx, part, d->rows, d->C); break;
+#define LN_BWD(NV, VW) ln_bwd_kernel<T, NV, VW><<<nb, kT, lds, st>>>((const T*)dy, (const T*)x, xs, g, stats, (const T*)dres, (T*)dx, part, d->rows, d->C)
+  if (d->C % 8 == 0 && xs % 8 == 0) {
+    if (d->C <= 512) LN_BWD(1, 8); else if (d->C <= 1024) LN_BWD(2, 8); else if (d->C <= 2048) LN_BWD(4, 8); else LN_BWD(8, 8);
+  } else {
+    if (d->C <= 256) LN_BWD(1, 4); else if (d->C <= 1024) LN_BWD(4, 4); else LN_BWD(16, 4);
   }
+#undef LN_BWD
 }
 
 extern "C" int cnnk_layernorm_bwd(const cnnk_ln_desc* d, const void* dy, const void* x, const float* gamma,
@@ -410,7 +444,7 @@ extern "C" int cnnk_layernorm_bwd(const cnnk_ln_desc* d, const void* dy, const v
   hipStream_t st = (hipStream_t)stream;
   if (d->dtype == CNNK_BF16) launch_ln_bwd<bf16_t>(d, xs, nb, dy, x, gamma, stats, dres, dx, (float*)ws, st);
   else launch_ln_bwd<float>(d, xs, nb, dy, x, gamma, stats, dres, dx, (float*)ws, st);
-  colsum_finalize_kernel<<<(2 * d->C + kT - 1) / kT, kT, 0, st>>>((const float*)ws, nb, 2 * d->C, d->C, dgamma, dbeta);
+  colsum_finalize_kernel<<<(2 * d->C + 63) / 64, kT, 0, st>>>((const float*)ws, nb, 2 * d->C, d->C, dgamma, dbeta);
   return launch_status();
 }
 
@@ -482,7 +516,7 @@ extern "C" int cnnk_bias_act_bwd(long long rows, int C, int dtype, int act, cons
     if (act == CNNK_ACT_GELU) bias_act_bwd_kernel<float, CNNK_ACT_GELU><<<grid, kT, 0, st>>>((const float*)dy, (const float*)u, (float*)dz, part, rows, C, rpc);
     else bias_act_bwd_kernel<float, CNNK_ACT_NONE><<<grid, kT, 0, st>>>((const float*)dy, nullptr, nullptr, part, rows, C, rpc);
   }
-  colsum_finalize_kernel<<<(C + kT - 1) / kT, kT, 0, st>>>(part, chunks, C, C, dbias, nullptr);
+  colsum_finalize_kernel<<<(C + 63) / 64, kT, 0, st>>>(part, chunks, C, C, dbias, nullptr);
   return launch_status();
 }
 
