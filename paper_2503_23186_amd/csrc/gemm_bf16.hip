@@ -70,9 +70,10 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_kernel(Args a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1, h = lane >> 5, g = lane >> 4, i16 = lane & 15;
   // workgroups that share an XCD's L2 (every 8th) walk consecutive tiles: same rows of A, all of B
-  int tile = blockIdx.x;
+  // (the grid is 8 * ceil(tiles / 8) workgroups; the few past the end leave at once)
   const int ntot = a.mtiles * a.ntiles;
-  if (ntot % 8 == 0) tile = (tile & 7) * (ntot >> 3) + (tile >> 3);
+  const int tile = (blockIdx.x & 7) * ((ntot + 7) >> 3) + (blockIdx.x >> 3);
+  if (tile >= ntot || (blockIdx.x >> 3) >= ((ntot + 7) >> 3)) return;
   const int mt = tile / a.ntiles, nt = tile - mt * a.ntiles;
   const int m0 = mt * BM, n0 = nt * BN;
   const int kbeg = blockIdx.z * a.k_per_split;
@@ -265,7 +266,7 @@ int launch(Kern kern, bool* raised, const Args& a, int splits, hipStream_t st) {
       return CNNK_ERR_HIP;
     *raised = true;
   }
-  hipLaunchKernelGGL(kern, dim3(a.mtiles * a.ntiles, 1, splits), dim3(kThreads), NST * STAGE_B, st, a);
+  hipLaunchKernelGGL(kern, dim3(8 * ((a.mtiles * a.ntiles + 7) / 8), 1, splits), dim3(kThreads), NST * STAGE_B, st, a);
   return launch_status();
 }
 
