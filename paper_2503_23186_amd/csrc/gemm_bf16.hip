@@ -80,11 +80,22 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_kernel(Args a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1, h = lane >> 5, g = lane >> 4, i16 = lane & 15;
   // workgroups that share an XCD's L2 (every 8th) walk consecutive tiles: same rows of A, all of B
-  // (the grid is 8 * ceil(tiles / 8) workgroups; the few past the end leave at once)
-  const int ntot = a.mtiles * a.ntiles;
-  const int tile = (blockIdx.x & 7) * ((ntot + 7) >> 3) + (blockIdx.x >> 3);
-  if (tile >= ntot || (blockIdx.x >> 3) >= ((ntot + 7) >> 3)) return;
-  const int mt = tile / a.ntiles, nt = tile - mt * a.ntiles;
+  // (the grid is 8 * ceil(tiles / 8) workgroups; the few past the end leave at once).  An XCD owns a
+  // contiguous range of the row-major tile list, i.e. a band of tile rows, and walks it column by
+  // column: the workgroups in flight on it then share the band's rows of A, which stay in its L2,
+  // while B streams through once per XCD.
+  const int ntot = a.mtiles * a.ntiles, chunk = (ntot + 7) >> 3;
+  const int c0 = (blockIdx.x & 7) * chunk, c1 = min(c0 + chunk, ntot);
+  int l = blockIdx.x >> 3;
+  if (c0 + l >= c1) return;
+  const int r0 = c0 / a.ntiles, s0 = c0 - r0 * a.ntiles, r1 = (c1 - 1) / a.ntiles, e1 = (c1 - 1) - r1 * a.ntiles + 1;
+  int mt = r0, nt = 0;
+  for (; nt < a.ntiles; ++nt) {
+    const int first = nt >= s0 ? 1 : 0;                 // the band's first row has this column
+    const int cnt = r0 == r1 ? ((nt >= s0 && nt < e1) ? 1 : 0) : (r1 - r0 - 1) + first + (nt < e1 ? 1 : 0);
+    if (l < cnt) { mt = r0 + l + (1 - first); break; }
+    l -= cnt;
+  }
   const int m0 = mt * BM, n0 = nt * BN;
   const int kbeg = blockIdx.z * a.k_per_split;
   int kend = kbeg + a.k_per_split;
