@@ -28,6 +28,7 @@ sys.path.insert(0, ROOT)
 # scale factors are in profiles/.  None for a class that was not measured.
 MEASURED_TRAFFIC_BYTES = {
     "conv3x3 s1 64->64 @32 fwd+dgrad (patch_kernel)": 86444077,   # profiles/bench_resnet18_b256_hbm_traffic.md
+    "fc1.gemm_gelu": 276733000,                                    # profiles/bench_vit_b16_b64_hbm_traffic.md (--config 6)
 }
 # Launches that exist to be found in a profiler's kernel trace (all through cnnk_grad_route, a plain
 # copy kernel of the library, whose grid is its element count / 2048): one copy of CAL_ELEMS bf16
@@ -179,7 +180,8 @@ def bench_vit(args):
     if dom["kind"] == "mfma":
         ach = dom["flops"] / dom["avg_ms"] / 1e9
         roof = dict(bound="mfma", kernel=dom["key"], achieved=round(ach, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                    frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None, avg_ms=round(dom["avg_ms"], 4),
+                    frac=round(ach / PEAK_BF16_TFLOPS, 4),
+                    traffic=MEASURED_TRAFFIC_BYTES.get(dom["key"]) if not args.batch else None, avg_ms=round(dom["avg_ms"], 4),
                     calls_per_step=dom["calls_per_step"])
     else:
         ach = dom["bytes"] / dom["avg_ms"] / 1e6
