@@ -2,7 +2,7 @@
 // cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation): y = x W^T (+ bias, + GELU), dx = dy W,
 // dW = dy^T x.  One kernel, three operand orientations.
 //
-// Workgroup tile 256 x 128, four wavefronts of 128 x 64 (0.75 KB of LDS operand reads per MFMA), 32
+// Workgroup tile 256 x 128 (or 192 x 128), four wavefronts of 128 x 64 (0.75 KB of LDS operand reads per MFMA), 32
 // reduction elements per stage, three LDS stage buffers filled straight from memory
 // (buffer_load ... lds, issued two stages ahead; out-of-range rows deposit zeros), one barrier per
 // stage, two workgroups per CU.  An operand whose reduction index is its contiguous one ("natural":
@@ -25,10 +25,15 @@ typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
 typedef int i32x4_t __attribute__((ext_vector_type(4)));
 
-constexpr int BM = 256, BN = 128, BK = 32, NST = 3;
-constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE_B = A_BYTES + B_BYTES;
+constexpr int BN = 128, BK = 32, NST = 3;
+constexpr int B_BYTES = BN * BK * 2;
 constexpr int kThreads = 256;
-constexpr int NLOAD = STAGE_B / 1024 / 4;      // direct loads per wavefront and stage (6)
+// TM: 32-row blocks of a wavefront's tile (4: workgroup tile 256 x 128, 3: 192 x 128, for shapes whose
+// tile count at 256 rows leaves much of the device idle in the last round of resident workgroups)
+template <int TM> struct Cfg {
+  static constexpr int BM = 64 * TM, A_BYTES = BM * BK * 2, STAGE_B = A_BYTES + B_BYTES;
+  static constexpr int NLOAD = STAGE_B / 1024 / 4;      // direct loads per wavefront and stage (TM + 2)
+};
 constexpr int SP = 72;                         // epilogue strip pitch (bytes per column)
 
 __device__ __forceinline__ i32x4_t make_desc(const void* p, unsigned bytes) {
@@ -73,8 +78,9 @@ __device__ __forceinline__ float gelu_f(float u) {
   return u >= 0.f ? u - u * q : u * q;
 }
 
-template <bool ATR, bool BTR, int EPI>
+template <bool ATR, bool BTR, int EPI, int TM>
 __global__ void __launch_bounds__(kThreads, 2) gemm_kernel(Args a) {
+  constexpr int BM = Cfg<TM>::BM, A_BYTES = Cfg<TM>::A_BYTES, STAGE_B = Cfg<TM>::STAGE_B, NLOAD = Cfg<TM>::NLOAD;
   extern __shared__ __align__(16) unsigned char smem[];   // NST stage buffers, nothing else: LDS address 0
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -147,13 +153,13 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_kernel(Args a) {
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks) {
     if (!ATR) {
-      const int row = wm * 128 + (lane & 31);
+      const int row = wm * (TM * 32) + (lane & 31);
       aoff[ks][0] = swz(row, ks * 2 + h);
       aoff[ks][1] = 0;
     } else {
       const int ch0 = (g & 1) * 16 + (i16 & 3) * 4, row = ks * 16 + h * 8 + (i16 >> 2);
-      aoff[ks][0] = wm * 4 * 2048 + swz(row, ch0 >> 3) + (ch0 & 7) * 2;
-      aoff[ks][1] = wm * 4 * 2048 + swz(row + 4, ch0 >> 3) + (ch0 & 7) * 2;
+      aoff[ks][0] = wm * TM * 2048 + swz(row, ch0 >> 3) + (ch0 & 7) * 2;
+      aoff[ks][1] = wm * TM * 2048 + swz(row + 4, ch0 >> 3) + (ch0 & 7) * 2;
     }
     if (!BTR) {
       const int row = wn * 64 + (lane & 31);
@@ -174,9 +180,9 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_kernel(Args a) {
     return __builtin_bit_cast(bf16x8_t, v);
   };
 
-  f32x16_t acc[4][2];
+  f32x16_t acc[TM][2];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -195,18 +201,18 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_kernel(Args a) {
       issue(t + 2, fill);
     }
     const unsigned char* sb = smem + cur;
-    bf16x8_t af[2][4], bfr[2][2];
+    bf16x8_t af[2][TM], bfr[2][2];
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) af[ks][i] = read_frag(sb, ATR, aoff[ks][0], aoff[ks][1], i);
+      for (int i = 0; i < TM; ++i) af[ks][i] = read_frag(sb, ATR, aoff[ks][0], aoff[ks][1], i);
 #pragma unroll
       for (int j = 0; j < 2; ++j) bfr[ks][j] = read_frag(sb, BTR, boff[ks][0], boff[ks][1], j);
     }
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][i], bfr[ks][j], acc[i][j], 0, 0, 0);
@@ -217,13 +223,13 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_kernel(Args a) {
   if (EPI == 2) {
     float* out = a.part + (size_t)blockIdx.z * a.M * a.ldc;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         const int col = n0 + wn * 64 + j * 32 + (lane & 31);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int row = m0 + wm * 128 + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+          const int row = m0 + wm * (TM * 32) + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
           if (row < a.M && col < a.N) out[(size_t)row * a.ldc + col] = acc[i][j][r];
         }
       }
@@ -243,13 +249,13 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_kernel(Args a) {
       const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(S + rd_off + rb * 32));
       const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(S + rd_off + 4 * SP + rb * 32));
       const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
-      const int row = m0 + wm * 128 + i * 32 + rb * 16 + i16, col = n0 + wn * 64 + j * 32 + g * 8;
+      const int row = m0 + wm * (TM * 32) + i * 32 + rb * 16 + i16, col = n0 + wn * 64 + j * 32 + g * 8;
       if (row < a.M && col < a.N) *reinterpret_cast<uint4*>(dst + (size_t)row * a.ldc + col) = uint4{l2.x, l2.y, h2.x, h2.y};
     }
     asm volatile("" ::: "memory");
   };
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int colv = n0 + wn * 64 + j * 32 + (lane & 31);
@@ -281,14 +287,28 @@ __global__ void __launch_bounds__(256) sum_partials_kernel(const float* __restri
 }
 
 template <typename Kern>
-int launch(Kern kern, bool* raised, const Args& a, int splits, hipStream_t st) {
+int launch(Kern kern, bool* raised, int stage_b, const Args& a, int splits, hipStream_t st) {
   if (!*raised) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, NST * STAGE_B) != hipSuccess)
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, NST * stage_b) != hipSuccess)
       return CNNK_ERR_HIP;
     *raised = true;
   }
-  hipLaunchKernelGGL(kern, dim3(8 * ((a.mtiles * a.ntiles + 7) / 8), 1, splits), dim3(kThreads), NST * STAGE_B, st, a);
+  hipLaunchKernelGGL(kern, dim3(8 * ((a.mtiles * a.ntiles + 7) / 8), 1, splits), dim3(kThreads), NST * stage_b, st, a);
   return launch_status();
+}
+// one launch of the orientation / epilogue at either tile height
+template <bool ATR, bool BTR, int EPI>
+int launch_tm(int tm, Args& a, int out_rows, int splits, hipStream_t st) {
+  static bool r4 = false, r3 = false;
+  a.mtiles = (out_rows + 64 * tm - 1) / (64 * tm);
+  if (tm == 3) return launch(gemm_kernel<ATR, BTR, EPI, 3>, &r3, Cfg<3>::STAGE_B, a, splits, st);
+  return launch(gemm_kernel<ATR, BTR, EPI, 4>, &r4, Cfg<4>::STAGE_B, a, splits, st);
+}
+// Rows per workgroup tile (in 64s): the device holds 512 workgroups at once; the cost of a launch is
+// about (rounds of resident workgroups) x (tile height).
+int pick_tm(int out_rows, int ntiles) {
+  auto cost = [&](int tm) { const int t = ((out_rows + 64 * tm - 1) / (64 * tm)) * ntiles; return ((t + 511) / 512) * tm; };
+  return cost(3) < cost(4) ? 3 : 4;
 }
 
 bool fits32(long long rows, long long cols) { return rows * cols * 2 < 2147483647LL; }
@@ -310,24 +330,23 @@ int gemm_bf16_fwd(long long rows, int K, int N, const bf16_t* x, const bf16_t* w
   a.A = x; a.B = w; a.bias = bias;
   a.C = gelu ? u : y; a.C2 = gelu ? y : nullptr;
   a.M = (int)rows; a.N = N; a.K = K; a.lda = K; a.ldb = K; a.ldc = N; a.k_per_split = K;
-  a.mtiles = (a.M + BM - 1) / BM; a.ntiles = (N + BN - 1) / BN;
+  a.ntiles = (N + BN - 1) / BN;
   a.a_bytes = (unsigned)(rows * K * 2); a.b_bytes = (unsigned)((long long)N * K * 2);
-  static bool r0 = false, r1 = false;
-  return gelu ? launch(gemm_kernel<false, false, 1>, &r1, a, 1, st) : launch(gemm_kernel<false, false, 0>, &r0, a, 1, st);
+  const int tm = pick_tm(a.M, a.ntiles);
+  return gelu ? launch_tm<false, false, 1>(tm, a, a.M, 1, st) : launch_tm<false, false, 0>(tm, a, a.M, 1, st);
 }
 
 int gemm_bf16_dgrad(long long rows, int K, int N, const bf16_t* dy, const bf16_t* w, bf16_t* dx, hipStream_t st) {
   Args a{};
   a.A = dy; a.B = w; a.C = dx;
   a.M = (int)rows; a.N = K; a.K = N; a.lda = N; a.ldb = K; a.ldc = K; a.k_per_split = N;
-  a.mtiles = (a.M + BM - 1) / BM; a.ntiles = (K + BN - 1) / BN;
+  a.ntiles = (K + BN - 1) / BN;
   a.a_bytes = (unsigned)(rows * N * 2); a.b_bytes = (unsigned)((long long)N * K * 2);
-  static bool r = false;
-  return launch(gemm_kernel<false, true, 0>, &r, a, 1, st);
+  return launch_tm<false, true, 0>(pick_tm(a.M, a.ntiles), a, a.M, 1, st);
 }
 
 size_t gemm_bf16_wgrad_ws(long long rows, int K, int N) {
-  const int tiles = ((N + BM - 1) / BM) * ((K + BN - 1) / BN);
+  const int tiles = ((N + 255) / 256) * ((K + BN - 1) / BN);
   const int s = wgrad_splits((int)rows, tiles);
   return s > 1 ? (size_t)s * N * K * sizeof(float) : 0;
 }
@@ -336,14 +355,13 @@ int gemm_bf16_wgrad(long long rows, int K, int N, const bf16_t* x, const bf16_t*
   Args a{};
   a.A = dy; a.B = x;
   a.M = N; a.N = K; a.K = (int)rows; a.lda = N; a.ldb = K; a.ldc = K;
-  a.mtiles = (N + BM - 1) / BM; a.ntiles = (K + BN - 1) / BN;
+  a.mtiles = (N + 255) / 256; a.ntiles = (K + BN - 1) / BN;
   const int splits = wgrad_splits((int)rows, a.mtiles * a.ntiles);
   const int stages = (((int)rows + BK - 1) / BK + splits - 1) / splits;
   a.k_per_split = stages * BK;
   a.part = splits > 1 ? (float*)ws : dw;
   a.a_bytes = (unsigned)(rows * N * 2); a.b_bytes = (unsigned)(rows * K * 2);
-  static bool r = false;
-  const int rc = launch(gemm_kernel<true, true, 2>, &r, a, splits, st);
+  const int rc = launch_tm<true, true, 2>(4, a, N, splits, st);
   if (rc != CNNK_OK || splits == 1) return rc;
   const size_t n = (size_t)N * K;
   size_t blocks = (n / 4 + 255) / 256;
