@@ -106,7 +106,14 @@ int cnnk_vit_embed_bwd(const cnnk_embed_desc* d, const void* dtok, void* dz, flo
  * (cnnk_vit_arena_bytes; cnnk_vit_tensor finds a tensor in it).  Nothing in it has to survive
  * between steps.  ws: scratch of the single calls (cnnk_vit_workspace_bytes).
  * events (optional): 2 * cnnk_vit_step_calls(d) hipEvent_t; the step records one pair around each
- * call it makes, in the order that cnnk_vit_step_call_name lists. */
+ * call it makes, in the order that cnnk_vit_step_call_name lists.
+ * aux_stream (optional, with the two events ev_fork and ev_join; default priority): a second stream
+ * for work that only the update waits for - the weight gradients of the linear layers and the bias
+ * gradients that are plain column sums.  They depend only on tensors that are final when the backward
+ * pass reaches them, so the step forks each onto aux_stream and joins before the update; beside the
+ * main stream they fill the compute units that its launches leave idle.  ws must then hold twice
+ * cnnk_vit_workspace_bytes (the forked calls use the upper half).  Ignored while `events` is set (a
+ * call's time is then its own).  Results are bit-identical with and without it. */
 typedef struct { int B, image, patch, dim, heads, layers, mlp, classes; int dtype; float ln_eps; } cnnk_vit_desc;
 typedef struct cnnk_vit_buffers {
   int n_params;
@@ -125,6 +132,9 @@ typedef struct cnnk_vit_buffers {
   size_t ws_bytes;
   void** events;
   int n_events;
+  void* aux_stream;       /* hipStream_t or NULL */
+  void* ev_fork;          /* hipEvent_t */
+  void* ev_join;          /* hipEvent_t */
 } cnnk_vit_buffers;
 
 /* tensors of the arena; `layer` is the block index (ignored for the first and last group).

@@ -150,9 +150,29 @@ int walk(const cnnk_vit_desc* v, const Geo& g, const cnnk_vit_buffers* buf, floa
   layout(g, &A);
   char* base = buf ? (char*)buf->arena : nullptr;
   auto at = [&](int id, int l) -> void* { return base ? base + A.off[id] + A.size[id] * (size_t)(per_layer(id) ? l : 0) : nullptr; };
-  void* ws = buf ? buf->ws : nullptr;
-  const size_t wsb = buf ? buf->ws_bytes : 0;
+  // Calls that only the update waits for go to the second stream when there is one: `st`, `ws` and
+  // `wsb` are what the call lambdas below read, and forked() points them at the second stream and the
+  // upper half of the workspace for the duration of one call.
+  const bool two = w.run && buf && buf->aux_stream && buf->ev_fork && buf->ev_join && !w.events;
+  void* const ws_main = buf ? buf->ws : nullptr;
+  const size_t wsb_main = buf ? (two ? buf->ws_bytes / 2 / 256 * 256 : buf->ws_bytes) : 0;
+  void* ws = ws_main;
+  size_t wsb = wsb_main;
   hipStream_t st = w.st;
+  auto forked = [&](int layer, const char* name, auto&& f) {
+    if (!two) { w.call(layer, name, f); return; }
+    if (w.rc != CNNK_OK) { ++w.idx; return; }
+    hipStream_t aux = (hipStream_t)buf->aux_stream;
+    if (hipEventRecord((hipEvent_t)buf->ev_fork, w.st) != hipSuccess || hipStreamWaitEvent(aux, (hipEvent_t)buf->ev_fork, 0) != hipSuccess) {
+      w.rc = CNNK_ERR_HIP;
+      ++w.idx;
+      return;
+    }
+    st = aux; ws = (char*)ws_main + wsb_main; wsb = wsb_main;
+    w.rc = f();
+    st = w.st; ws = ws_main; wsb = wsb_main;
+    ++w.idx;
+  };
   const bool bf = g.dtype == CNNK_BF16;
   auto P = [&](int k) -> float* { return buf ? (float*)buf->param[k] : nullptr; };
   auto Wm = [&](int k) -> const void* { return buf ? (bf ? buf->param_lp[k] : buf->param[k]) : nullptr; };
@@ -203,23 +223,23 @@ int walk(const cnnk_vit_desc* v, const Geo& g, const cnnk_vit_buffers* buf, floa
     void* xin = l ? at(CNNK_VIT_XOUT, l - 1) : at(CNNK_VIT_TOK, 0);
     void* dxin = l ? at(CNNK_VIT_DXOUT, l - 1) : at(CNNK_VIT_DTOK, 0);
     void* dxo = at(CNNK_VIT_DXOUT, l);
-    w.call(l, "fc2.dbias", [&] { return cnnk_bias_act_bwd(rows, d, g.dtype, CNNK_ACT_NONE, dxo, nullptr, nullptr, Gr(p0 + B_C2), ws, wsb, st); });
-    w.call(l, "fc2.wgrad", [&] { return cnnk_linear_wgrad(rows, m, d, dt, at(CNNK_VIT_G, l), dxo, Gr(p0 + B_W2), ws, wsb, st); });
+    forked(l, "fc2.dbias", [&] { return cnnk_bias_act_bwd(rows, d, g.dtype, CNNK_ACT_NONE, dxo, nullptr, nullptr, Gr(p0 + B_C2), ws, wsb, st); });
+    forked(l, "fc2.wgrad", [&] { return cnnk_linear_wgrad(rows, m, d, dt, at(CNNK_VIT_G, l), dxo, Gr(p0 + B_W2), ws, wsb, st); });
     w.call(l, "fc2.dgrad", [&] { return cnnk_linear_dgrad(rows, m, d, dt, dxo, Wm(p0 + B_W2), at(CNNK_VIT_DG, l), ws, wsb, st); });
     w.call(l, "fc1.gelu.bwd", [&] { return cnnk_bias_act_bwd(rows, m, g.dtype, CNNK_ACT_GELU, at(CNNK_VIT_DG, l), at(CNNK_VIT_U, l), at(CNNK_VIT_DU, l), Gr(p0 + B_C1), ws, wsb, st); });
-    w.call(l, "fc1.wgrad", [&] { return cnnk_linear_wgrad(rows, d, m, dt, at(CNNK_VIT_H2, l), at(CNNK_VIT_DU, l), Gr(p0 + B_W1), ws, wsb, st); });
+    forked(l, "fc1.wgrad", [&] { return cnnk_linear_wgrad(rows, d, m, dt, at(CNNK_VIT_H2, l), at(CNNK_VIT_DU, l), Gr(p0 + B_W1), ws, wsb, st); });
     w.call(l, "fc1.dgrad", [&] { return cnnk_linear_dgrad(rows, d, m, dt, at(CNNK_VIT_DU, l), Wm(p0 + B_W1), at(CNNK_VIT_DH2, l), ws, wsb, st); });
     w.call(l, "ln2.bwd", [&] {
       return cnnk_layernorm_bwd(&ln, at(CNNK_VIT_DH2, l), at(CNNK_VIT_XMID, l), P(p0 + B_G2), (const float*)at(X_STATS2, l), dxo,
                                 at(CNNK_VIT_DXMID, l), Gr(p0 + B_G2), Gr(p0 + B_B2), ws, wsb, st);
     });
     void* dxm = at(CNNK_VIT_DXMID, l);
-    w.call(l, "proj.dbias", [&] { return cnnk_bias_act_bwd(rows, d, g.dtype, CNNK_ACT_NONE, dxm, nullptr, nullptr, Gr(p0 + B_BO), ws, wsb, st); });
-    w.call(l, "proj.wgrad", [&] { return cnnk_linear_wgrad(rows, d, d, dt, at(CNNK_VIT_O, l), dxm, Gr(p0 + B_WO), ws, wsb, st); });
+    forked(l, "proj.dbias", [&] { return cnnk_bias_act_bwd(rows, d, g.dtype, CNNK_ACT_NONE, dxm, nullptr, nullptr, Gr(p0 + B_BO), ws, wsb, st); });
+    forked(l, "proj.wgrad", [&] { return cnnk_linear_wgrad(rows, d, d, dt, at(CNNK_VIT_O, l), dxm, Gr(p0 + B_WO), ws, wsb, st); });
     w.call(l, "proj.dgrad", [&] { return cnnk_linear_dgrad(rows, d, d, dt, dxm, Wm(p0 + B_WO), at(CNNK_VIT_DO, l), ws, wsb, st); });
     w.call(l, "attn.bwd", [&] { return cnnk_attention_bwd(&ad, at(CNNK_VIT_QKV, l), at(CNNK_VIT_O, l), at(CNNK_VIT_DO, l), (const float*)at(X_LSE, l), at(CNNK_VIT_DQKV, l), st); });
-    w.call(l, "qkv.dbias", [&] { return cnnk_bias_act_bwd(rows, 3 * d, g.dtype, CNNK_ACT_NONE, at(CNNK_VIT_DQKV, l), nullptr, nullptr, Gr(p0 + B_BQKV), ws, wsb, st); });
-    w.call(l, "qkv.wgrad", [&] { return cnnk_linear_wgrad(rows, d, 3 * d, dt, at(CNNK_VIT_H, l), at(CNNK_VIT_DQKV, l), Gr(p0 + B_WQKV), ws, wsb, st); });
+    forked(l, "qkv.dbias", [&] { return cnnk_bias_act_bwd(rows, 3 * d, g.dtype, CNNK_ACT_NONE, at(CNNK_VIT_DQKV, l), nullptr, nullptr, Gr(p0 + B_BQKV), ws, wsb, st); });
+    forked(l, "qkv.wgrad", [&] { return cnnk_linear_wgrad(rows, d, 3 * d, dt, at(CNNK_VIT_H, l), at(CNNK_VIT_DQKV, l), Gr(p0 + B_WQKV), ws, wsb, st); });
     w.call(l, "qkv.dgrad", [&] { return cnnk_linear_dgrad(rows, d, 3 * d, dt, at(CNNK_VIT_DQKV, l), Wm(p0 + B_WQKV), at(CNNK_VIT_DH, l), ws, wsb, st); });
     w.call(l, "ln1.bwd", [&] {
       return cnnk_layernorm_bwd(&ln, at(CNNK_VIT_DH, l), xin, P(p0 + B_G1), (const float*)at(X_STATS1, l), dxm, dxin, Gr(p0 + B_G1),
@@ -227,8 +247,13 @@ int walk(const cnnk_vit_desc* v, const Geo& g, const cnnk_vit_buffers* buf, floa
     });
   }
   w.call(-1, "embed.tokens.bwd", [&] { return cnnk_vit_embed_bwd(&ed, at(CNNK_VIT_DTOK, 0), at(X_DZ0, 0), Gr(P_BE), Gr(P_CLS), Gr(P_POS), st); });
-  w.call(-1, "embed.wgrad", [&] { return cnnk_linear_wgrad(prow, g.K0, d, dt, at(CNNK_VIT_PATCHES, 0), at(X_DZ0, 0), Gr(P_WE), ws, wsb, st); });
+  forked(-1, "embed.wgrad", [&] { return cnnk_linear_wgrad(prow, g.K0, d, dt, at(CNNK_VIT_PATCHES, 0), at(X_DZ0, 0), Gr(P_WE), ws, wsb, st); });
   // ---- update ----
+  if (two && w.rc == CNNK_OK) {
+    if (hipEventRecord((hipEvent_t)buf->ev_join, (hipStream_t)buf->aux_stream) != hipSuccess ||
+        hipStreamWaitEvent(w.st, (hipEvent_t)buf->ev_join, 0) != hipSuccess)
+      w.rc = CNNK_ERR_HIP;
+  }
   w.call(-1, "update", [&] {
     const int np = p_tail + 4;
     const size_t sizes_blk[B_COUNT] = {(size_t)d, (size_t)d, (size_t)3 * d * d, (size_t)3 * d, (size_t)d * d, (size_t)d, (size_t)d, (size_t)d,
@@ -321,7 +346,8 @@ extern "C" int cnnk_vit_train_step(const cnnk_vit_desc* v, const cnnk_vit_buffer
     if (bf && matrix && !buf->param_lp[k]) return CNNK_ERR_NULL;
   }
   if (buf->arena_bytes < cnnk_vit_arena_bytes(v)) return CNNK_ERR_WORKSPACE;
-  if (!buf->ws || buf->ws_bytes < workspace(v, g)) return CNNK_ERR_WORKSPACE;
+  const bool two_streams = buf->aux_stream && buf->ev_fork && buf->ev_join && !buf->events;
+  if (!buf->ws || buf->ws_bytes < workspace(v, g) * (two_streams ? 2 : 1)) return CNNK_ERR_WORKSPACE;
   if ((((size_t)buf->arena) & 255) != 0 || (((size_t)buf->ws) & 255) != 0) return CNNK_ERR_UNSUPPORTED;
   Walk w = {true, 0, -1, nullptr, 0, CNNK_OK, nullptr, (hipStream_t)stream};
   if (buf->events) {

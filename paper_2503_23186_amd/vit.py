@@ -42,7 +42,8 @@ class VitBuffers(C.Structure):
                 ("grad", C.POINTER(C.c_void_p)), ("mom", C.POINTER(C.c_void_p)), ("x", C.c_void_p),
                 ("labels", C.c_void_p), ("loss", C.c_void_p), ("pred", C.c_void_p), ("probs", C.c_void_p),
                 ("arena", C.c_void_p), ("arena_bytes", C.c_size_t), ("ws", C.c_void_p), ("ws_bytes", C.c_size_t),
-                ("events", C.POINTER(C.c_void_p)), ("n_events", C.c_int)]
+                ("events", C.POINTER(C.c_void_p)), ("n_events", C.c_int),
+                ("aux_stream", C.c_void_p), ("ev_fork", C.c_void_p), ("ev_join", C.c_void_p)]
 
 
 def _declare():
@@ -196,7 +197,7 @@ class VitRunner:
     """Device buffers of one ViT training step.  net: a workloads.ViT-style description (batch, image,
     patch, dim, heads, layers, mlp, classes, dtype, param_table())."""
 
-    def __init__(self, net, device="cuda:0", keep_probs=True):
+    def __init__(self, net, device="cuda:0", keep_probs=True, two_streams=True):
         self.net = net
         self.dev = torch.device(device)
         self.dt = BF16 if net.dtype == "bf16" else F32
@@ -221,7 +222,8 @@ class VitRunner:
         if self.arena_bytes == 0:
             raise ValueError("unsupported ViT configuration")
         self.arena = torch.zeros(self.arena_bytes, dtype=torch.uint8, device=self.dev)
-        self.ws = torch.zeros(max(self.ws_bytes, 256), dtype=torch.uint8, device=self.dev)
+        self.ws = torch.zeros(max(self.ws_bytes, 256) * (2 if two_streams else 1), dtype=torch.uint8, device=self.dev)
+        self.aux_stream = torch.cuda.Stream(device=self.dev) if two_streams else None
         n = len(table)
         arr = lambda ts: (C.c_void_p * n)(*[None if t is None else t.data_ptr() for t in ts])
         self._keep = [arr(self.param), arr(self.param_lp), arr(self.grad), arr(self.mom)]
@@ -229,7 +231,10 @@ class VitRunner:
         self.buffers = VitBuffers(n, cast(self._keep[0]), cast(self._keep[1]), cast(self._keep[2]), cast(self._keep[3]),
                                   self.x.data_ptr(), self.labels.data_ptr(), self.loss.data_ptr(), self.pred.data_ptr(),
                                   None if self.probs is None else self.probs.data_ptr(), self.arena.data_ptr(),
-                                  self.arena_bytes, self.ws.data_ptr(), self.ws.numel(), None, 0)
+                                  self.arena_bytes, self.ws.data_ptr(), self.ws.numel(), None, 0,
+                                  self.aux_stream.cuda_stream if two_streams else None,
+                                  cnnk.hip_event_create() if two_streams else None,
+                                  cnnk.hip_event_create() if two_streams else None)
         self.n_calls = cnnk_vit_step_calls(self.desc)
         self.call_names = [cnnk_vit_step_call_name(self.desc, i) for i in range(self.n_calls)]
         self._events = None

@@ -42,7 +42,7 @@ def test_every_symbol_of_the_transformer_header_is_exported(cnnk):
         assert hasattr(cnnk.lib, n), n
     assert sorted(vit.EXPORTS) == names
     assert C.sizeof(vit.LnDesc) == 24 and C.sizeof(vit.AttnDesc) == 20 and C.sizeof(vit.EmbedDesc) == 20
-    assert C.sizeof(vit.VitDesc) == 40 and C.sizeof(vit.VitBuffers) == 128
+    assert C.sizeof(vit.VitDesc) == 40 and C.sizeof(vit.VitBuffers) == 152
 
 
 def test_transformer_entry_points_reject_bad_arguments_on_the_host(cnnk):

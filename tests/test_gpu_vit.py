@@ -260,9 +260,9 @@ ACTS = {"TOK": "X0", "H": "H", "QKV": "QKV", "O": "O", "XMID": "Xmid", "H2": "H2
 DACTS = {"DH": "H", "DQKV": "QKV", "DO": "O", "DXMID": "Xmid", "DH2": "H2", "DU": "U", "DG": "G", "DF": "F"}
 
 
-def run_hip(net, inp, lr, momentum, wd):
+def run_hip(net, inp, lr, momentum, wd, two_streams=True):
     from paper_2503_23186_amd.vit import VitRunner
-    r = VitRunner(net)
+    r = VitRunner(net, two_streams=two_streams)
     r.load(inp["x"], inp["labels"], inp["params"], inp["mom"])
     r.step(lr, momentum, wd)
     torch.cuda.synchronize()
@@ -370,3 +370,21 @@ def test_step_bf16_against_the_ensemble_of_legal_walks(K, name):
     top2 = np.sort(logits, axis=1)[:, -2:]
     clear = (top2[:, 1] - top2[:, 0]) > 5e-2
     assert (host(r.pred)[clear] == exact["pred"][clear]).all()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_second_stream_changes_no_bit(K, dtype):
+    """The weight and bias gradients forked onto a second stream: same kernels, same order of every
+    sum, so two consecutive steps give bit-identical parameters, momentum buffers and gradients."""
+    net = WL.vit_mini(dtype=dtype, **STEP_NETS["mini"])
+    inp = WL.make_vit_inputs(net, config_id=64)
+    runs = []
+    for two in (False, True):
+        r = run_hip(net, inp, 0.05, 0.9, 1e-3, two_streams=two)
+        r.step(0.05, 0.9, 1e-3)
+        torch.cuda.synchronize()
+        runs.append(r)
+    a, b = runs
+    assert a.loss.item() == b.loss.item()
+    for k in range(len(a.names)):
+        assert torch.equal(a.param[k], b.param[k]) and torch.equal(a.mom[k], b.mom[k]) and torch.equal(a.grad[k], b.grad[k]), a.names[k]
