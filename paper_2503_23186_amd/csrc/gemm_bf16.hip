@@ -313,7 +313,7 @@ int pick_tm(int out_rows, int ntiles) {
 
 bool fits32(long long rows, long long cols) { return rows * cols * 2 < 2147483647LL; }
 int wgrad_splits(int rows, int tiles) {
-  int s = (256 + tiles - 1) / tiles;           // about one workgroup per CU
+  int s = (192 + tiles - 1) / tiles;           // workgroups of a launch: it runs beside the main stream's kernels (128-192 measured best)
   const int max_s = rows / (8 * BK);           // at least 8 stages each
   if (s > max_s) s = max_s;
   return s < 1 ? 1 : s;
