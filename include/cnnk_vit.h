@@ -158,6 +158,14 @@ int cnnk_vit_step_call_name(const cnnk_vit_desc* d, int i, char* buf, int n);
 int cnnk_vit_train_step(const cnnk_vit_desc* d, const cnnk_vit_buffers* buf, float lr, float momentum,
                         float weight_decay, void* stream);
 
+/* The validation pass of the epoch loop (Algorithm 1: "evaluate model on validation data"): the
+ * forward pass and the loss of the same model on buf->x / buf->labels; writes *loss, pred, probs (if
+ * not NULL) and, if n_correct is not NULL, adds the number of correct predictions to *n_correct
+ * (device int, as cnnk_count_correct).  The model has no batch statistics, so this is the training
+ * step's own forward pass; parameters, gradients and momentum buffers are not touched (grad and mom
+ * may be NULL).  One stream; events and aux_stream are ignored. */
+int cnnk_vit_eval_step(const cnnk_vit_desc* d, const cnnk_vit_buffers* buf, int* n_correct, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

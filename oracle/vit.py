@@ -233,3 +233,42 @@ def train_step(cfg, x, labels, P, V, lr=0.1, momentum=0.9, weight_decay=0.0, sto
         newV[k] = v
         newP[k] = P[k] - lr * v
     return dict(loss=loss, pred=c["pred"], probs=c["probs"], cache=c, dacts=dacts, grads=grads, params=newP, mom=newV)
+
+
+def evaluate(cfg, batch, xs, ys, P, storage=None):
+    """The validation pass (Algorithm 1: "evaluate model on validation data"): forward and loss over xs in
+    batches of `batch` (xs.shape[0] a multiple of it).  Returns (accuracy, mean loss over batches, predictions)."""
+    assert xs.shape[0] % batch == 0
+    correct, losses, preds = 0, [], []
+    for b in range(xs.shape[0] // batch):
+        yb = np.asarray(ys[b * batch:(b + 1) * batch])
+        loss, c = forward(cfg, xs[b * batch:(b + 1) * batch], yb, P, storage)
+        correct += int(np.sum(c["pred"] == yb))
+        losses.append(loss)
+        preds.append(c["pred"])
+    return correct / xs.shape[0], float(np.mean(losses)), np.concatenate(preds)
+
+
+def fit(cfg, batch, train_x, train_y, val_x, val_y, P, V, orders, lrs, momentum=0.9, weight_decay=0.0, storage=None):
+    """The epoch loop of Algorithm 1 on one device: per epoch one train_step per mini-batch (orders[e]:
+    the epoch's sample order, consecutive slices of `batch` are the mini-batches; lrs: the learning
+    rate of every step), then the validation metric and "save checkpoint if it improved".
+    Returns dict(params, mom, history, best): history[e] = (mean train loss, val accuracy, val loss)."""
+    P = {k: np.array(v, dtype=np.float64) for k, v in P.items()}
+    V = {k: np.array(v, dtype=np.float64) for k, v in V.items()}
+    history, best, k = [], None, 0
+    for e, order in enumerate(orders):
+        order = np.asarray(order)
+        assert order.size % batch == 0
+        losses = []
+        for b in range(order.size // batch):
+            idx = order[b * batch:(b + 1) * batch]
+            r = train_step(cfg, train_x[idx], train_y[idx], P, V, lrs[k], momentum, weight_decay, storage)
+            P, V = r["params"], r["mom"]
+            losses.append(r["loss"])
+            k += 1
+        acc, vloss, _ = evaluate(cfg, batch, val_x, val_y, P, storage)
+        history.append((float(np.mean(losses)), acc, vloss))
+        if best is None or acc > best["acc"]:
+            best = dict(epoch=e, acc=acc, params={n: a.copy() for n, a in P.items()}, mom={n: a.copy() for n, a in V.items()})
+    return dict(params=P, mom=V, history=history, best=best)

@@ -145,7 +145,8 @@ struct Walk {
   }
 };
 
-int walk(const cnnk_vit_desc* v, const Geo& g, const cnnk_vit_buffers* buf, float lr, float mu, float wd, Walk& w) {
+int walk(const cnnk_vit_desc* v, const Geo& g, const cnnk_vit_buffers* buf, float lr, float mu, float wd, Walk& w,
+         bool forward_only = false) {
   Arena A;
   layout(g, &A);
   char* base = buf ? (char*)buf->arena : nullptr;
@@ -207,6 +208,13 @@ int walk(const cnnk_vit_desc* v, const Geo& g, const cnnk_vit_buffers* buf, floa
   }
   void* xlast = at(CNNK_VIT_XOUT, g.L - 1);
   w.call(-1, "head.ln", [&] { return cnnk_layernorm_fwd(&ln_cls, xlast, P(p_tail), P(p_tail + 1), at(CNNK_VIT_F, 0), (float*)at(X_STATSF, 0), st); });
+  if (forward_only) {
+    w.call(-1, "head.loss", [&] {
+      return cnnk_fc_softmax_xent(&fc, at(CNNK_VIT_F, 0), P(p_tail + 2), P(p_tail + 3), buf->labels, buf->loss, buf->pred,
+                                  buf->probs, nullptr, nullptr, nullptr, ws, wsb, st);
+    });
+    return w.rc;
+  }
   w.call(-1, "head.loss", [&] {
     return cnnk_fc_softmax_xent(&fc, at(CNNK_VIT_F, 0), P(p_tail + 2), P(p_tail + 3), buf->labels, buf->loss, buf->pred, buf->probs,
                                 at(CNNK_VIT_DF, 0), Gr(p_tail + 2), Gr(p_tail + 3), ws, wsb, st);
@@ -328,24 +336,46 @@ extern "C" int cnnk_vit_step_call_name(const cnnk_vit_desc* v, int i, char* out,
   return (i >= 0 && i < w.idx) ? CNNK_OK : CNNK_ERR_SHAPE;
 }
 
-extern "C" int cnnk_vit_train_step(const cnnk_vit_desc* v, const cnnk_vit_buffers* buf, float lr, float momentum,
-                                   float weight_decay, void* stream) {
-  Geo g;
-  const int rc = validate(v, &g);
-  if (rc != CNNK_OK) return rc;
-  if (!buf || !buf->param || !buf->grad || !buf->mom || !buf->x || !buf->labels || !buf->loss || !buf->pred || !buf->arena)
-    return CNNK_ERR_NULL;
+static int check_buffers(const cnnk_vit_desc* v, const Geo& g, const cnnk_vit_buffers* buf, bool training) {
+  if (!buf || !buf->param || !buf->x || !buf->labels || !buf->loss || !buf->pred || !buf->arena) return CNNK_ERR_NULL;
+  if (training && (!buf->grad || !buf->mom)) return CNNK_ERR_NULL;
   const int np = P_BLOCK0 + B_COUNT * g.L + 4;
   if (buf->n_params != np) return CNNK_ERR_SHAPE;
   const bool bf = g.dtype == CNNK_BF16;
   if (bf && !buf->param_lp) return CNNK_ERR_NULL;
   for (int k = 0; k < np; ++k) {
-    if (!buf->param[k] || !buf->grad[k] || !buf->mom[k]) return CNNK_ERR_NULL;
+    if (!buf->param[k] || (training && (!buf->grad[k] || !buf->mom[k]))) return CNNK_ERR_NULL;
     const int r = k >= P_BLOCK0 && k < np - 4 ? (k - P_BLOCK0) % B_COUNT : -1;
     const bool matrix = k == P_WE || r == B_WQKV || r == B_WO || r == B_W1 || r == B_W2;
     if (bf && matrix && !buf->param_lp[k]) return CNNK_ERR_NULL;
   }
   if (buf->arena_bytes < cnnk_vit_arena_bytes(v)) return CNNK_ERR_WORKSPACE;
+  if ((((size_t)buf->arena) & 255) != 0 || (((size_t)buf->ws) & 255) != 0) return CNNK_ERR_UNSUPPORTED;
+  return CNNK_OK;
+}
+
+extern "C" int cnnk_vit_eval_step(const cnnk_vit_desc* v, const cnnk_vit_buffers* buf, int* n_correct, void* stream) {
+  Geo g;
+  int rc = validate(v, &g);
+  if (rc != CNNK_OK) return rc;
+  rc = check_buffers(v, g, buf, false);
+  if (rc != CNNK_OK) return rc;
+  if (!buf->ws || buf->ws_bytes < workspace(v, g)) return CNNK_ERR_WORKSPACE;
+  cnnk_vit_buffers b = *buf;          // one stream, no per-call events
+  b.events = nullptr; b.n_events = 0; b.aux_stream = nullptr;
+  Walk w = {true, 0, -1, nullptr, 0, CNNK_OK, nullptr, (hipStream_t)stream};
+  rc = walk(v, g, &b, 0.f, 0.f, 0.f, w, true);
+  if (rc != CNNK_OK || !n_correct) return rc;
+  return cnnk_count_correct(g.B, buf->pred, buf->labels, n_correct, stream);
+}
+
+extern "C" int cnnk_vit_train_step(const cnnk_vit_desc* v, const cnnk_vit_buffers* buf, float lr, float momentum,
+                                   float weight_decay, void* stream) {
+  Geo g;
+  const int rc = validate(v, &g);
+  if (rc != CNNK_OK) return rc;
+  const int rcb = check_buffers(v, g, buf, true);
+  if (rcb != CNNK_OK) return rcb;
   const bool two_streams = buf->aux_stream && buf->ev_fork && buf->ev_join && !buf->events;
   if (!buf->ws || buf->ws_bytes < workspace(v, g) * (two_streams ? 2 : 1)) return CNNK_ERR_WORKSPACE;
   if ((((size_t)buf->arena) & 255) != 0 || (((size_t)buf->ws) & 255) != 0) return CNNK_ERR_UNSUPPORTED;

@@ -214,3 +214,130 @@ class Trainer:
         torch.cuda.synchronize()
         med = np.median(np.asarray(acc), axis=0)
         return [(layer, phase, float(med[g])) for g, layer, phase in rows]
+
+
+class VitTrainer:
+    """The same epoch loop around cnnk_vit_train_step (the paper's second model family): one step per
+    mini-batch, cnnk_vit_eval_step over the validation set, best-so-far checkpoint (fp32 masters,
+    momentum buffers, counters).  net: a workloads.ViT-style description."""
+
+    def __init__(self, net, device="cuda:0", two_streams=True):
+        from .vit import VitRunner
+        self.net = net
+        self.run = VitRunner(net, device=device, keep_probs=False, two_streams=two_streams)
+        self.batch = net.batch
+        self.n_correct = torch.zeros(1, dtype=torch.int32, device=self.run.dev)
+        self.bad_index = torch.zeros(1, dtype=torch.int32, device=self.run.dev)
+        self.epoch = 0
+        self.step = 0
+        self.best_acc = -1.0
+        self.best_epoch = -1
+
+    def load_state(self, params, mom):
+        """params / mom: {name: host array} in the names of VitRunner.names."""
+        r = self.run
+        for k, name in enumerate(r.names):
+            r.param[k].copy_(torch.from_numpy(np.ascontiguousarray(params[name], dtype=np.float32)))
+            r.mom[k].copy_(torch.from_numpy(np.ascontiguousarray(mom[name], dtype=np.float32)))
+        r.refresh_low_precision()
+        torch.cuda.synchronize()
+
+    def to_device(self, x, y):
+        r = self.run
+        xt = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(r.dev).to(r.tdt).contiguous()
+        yt = torch.from_numpy(np.ascontiguousarray(y, dtype=np.int32)).to(r.dev)
+        return xt, yt
+
+    def train_batch(self, x_all, y_all, idx, lr, momentum, weight_decay):
+        r = self.run
+        s = torch.cuda.current_stream().cuda_stream
+        row_bytes = x_all[0].numel() * x_all.element_size()
+        cnnk.cnnk_gather_rows(self.batch, x_all.shape[0], row_bytes, x_all, idx, r.x, self.bad_index, s)
+        cnnk.cnnk_gather_rows(self.batch, y_all.shape[0], 4, y_all, idx, r.labels, self.bad_index, s)
+        r.step(lr, momentum, weight_decay)
+        self.step += 1
+
+    def evaluate(self, x_all, y_all):
+        from .vit import cnnk_vit_eval_step
+        r = self.run
+        n = x_all.shape[0]
+        if n % self.batch:
+            raise ValueError("validation set size must be a multiple of the batch size")
+        self.n_correct.zero_()
+        losses = torch.empty(n // self.batch, dtype=torch.float32, device=r.dev)
+        s = torch.cuda.current_stream().cuda_stream
+        for b in range(n // self.batch):
+            r.x.copy_(x_all[b * self.batch:(b + 1) * self.batch])
+            r.labels.copy_(y_all[b * self.batch:(b + 1) * self.batch])
+            cnnk_vit_eval_step(r.desc, r.buffers, self.n_correct, s)
+            losses[b:b + 1].copy_(r.loss)
+        torch.cuda.synchronize()
+        return self.n_correct.item() / n, float(losses.double().mean().item())
+
+    def fit(self, train_x, train_y, val_x, val_y, orders, lrs, momentum=0.9, weight_decay=0.0, ckpt_path=None):
+        r = self.run
+        history = []
+        for order in orders:
+            idx_all = torch.from_numpy(np.ascontiguousarray(order, dtype=np.int64)).to(r.dev)
+            nb = idx_all.numel() // self.batch
+            if nb * self.batch != idx_all.numel():
+                raise ValueError("an epoch's order must hold whole mini-batches")
+            losses = torch.empty(nb, dtype=torch.float32, device=r.dev)
+            for b in range(nb):
+                self.train_batch(train_x, train_y, idx_all[b * self.batch:(b + 1) * self.batch], lrs[self.step], momentum,
+                                 weight_decay)
+                losses[b:b + 1].copy_(r.loss)
+            if self.bad_index.item() != 0:
+                raise ValueError("an epoch's order names a sample outside the training set")
+            acc, vloss = self.evaluate(val_x, val_y)
+            history.append((float(losses.double().mean().item()), acc, vloss))
+            self.epoch += 1
+            if acc > self.best_acc:
+                self.best_acc, self.best_epoch = acc, self.epoch - 1
+                if ckpt_path is not None:
+                    self.save_checkpoint(ckpt_path)
+        return history
+
+    def save_checkpoint(self, path):
+        r = self.run
+        torch.cuda.synchronize()
+        t = {}
+        for k, name in enumerate(r.names):
+            t["param." + name] = r.param[k].cpu()
+            t["mom." + name] = r.mom[k].cpu()
+        write_checkpoint(path, t, dict(net=self.net.name, dtype=self.net.dtype, epoch=self.epoch, step=self.step,
+                                       best_acc=float(self.best_acc), best_epoch=self.best_epoch))
+
+    def load_checkpoint(self, path):
+        r = self.run
+        t, meta = read_checkpoint(path)
+        if meta.get("net") != self.net.name or meta.get("dtype") != self.net.dtype:
+            raise ValueError("checkpoint is for %s/%s" % (meta.get("net"), meta.get("dtype")))
+        for k, name in enumerate(r.names):
+            if tuple(t["param." + name].shape) != tuple(r.param[k].shape):
+                raise ValueError("checkpoint parameter %s has shape %s" % (name, tuple(t["param." + name].shape)))
+        for k, name in enumerate(r.names):
+            r.param[k].copy_(t["param." + name])
+            r.mom[k].copy_(t["mom." + name])
+        r.refresh_low_precision()
+        self.epoch, self.step = int(meta["epoch"]), int(meta["step"])
+        self.best_acc, self.best_epoch = float(meta["best_acc"]), int(meta["best_epoch"])
+        torch.cuda.synchronize()
+
+    def profile(self, steps=3):
+        """Median per-call times (ms) of `steps` timed steps as [(call name, ms)]; the steps run with a zero
+        learning rate and the momentum buffers are put back afterwards."""
+        r = self.run
+        keep_mom = [v.clone() for v in r.mom]
+        r.enable_timing(True)
+        acc = []
+        for _ in range(steps):
+            r.step(0.0, 0.0, 0.0)
+            torch.cuda.synchronize()
+            acc.append(r.call_times_ms())
+        r.enable_timing(False)
+        for v, k in zip(r.mom, keep_mom):
+            v.copy_(k)
+        torch.cuda.synchronize()
+        med = np.median(np.asarray(acc), axis=0)
+        return list(zip(r.call_names, [float(x) for x in med]))

@@ -12,7 +12,7 @@ EXPORTS = ["cnnk_linear_workspace_bytes", "cnnk_linear_fwd", "cnnk_linear_dgrad"
            "cnnk_bias_act_workspace_bytes", "cnnk_bias_act_bwd", "cnnk_attention_fwd", "cnnk_attention_bwd",
            "cnnk_vit_patchify", "cnnk_vit_embed_fwd", "cnnk_vit_embed_bwd", "cnnk_vit_arena_bytes",
            "cnnk_vit_workspace_bytes", "cnnk_vit_tensor", "cnnk_vit_step_calls", "cnnk_vit_step_call_name",
-           "cnnk_vit_train_step"]
+           "cnnk_vit_train_step", "cnnk_vit_eval_step"]
 
 ACT_NONE, ACT_GELU = 0, 1
 TENSOR_IDS = ["PATCHES", "TOK", "H", "QKV", "O", "XMID", "H2", "U", "G", "XOUT", "F",
@@ -74,6 +74,7 @@ def _declare():
     lib.cnnk_vit_step_calls.argtypes = [C.POINTER(VitDesc)]
     lib.cnnk_vit_step_call_name.argtypes = [C.POINTER(VitDesc), ci, C.c_char_p, ci]
     lib.cnnk_vit_train_step.argtypes = [C.POINTER(VitDesc), C.POINTER(VitBuffers), cf, cf, cf, vp]
+    lib.cnnk_vit_eval_step.argtypes = [C.POINTER(VitDesc), C.POINTER(VitBuffers), vp, vp]
 
 
 _declare()
@@ -184,6 +185,10 @@ def cnnk_vit_step_call_name(d, i):
 
 def cnnk_vit_train_step(d, buffers, lr, momentum, weight_decay, stream=0):
     _check(lib.cnnk_vit_train_step(C.byref(d), C.byref(buffers), lr, momentum, weight_decay, stream), "cnnk_vit_train_step")
+
+
+def cnnk_vit_eval_step(d, buffers, n_correct=None, stream=0):
+    _check(lib.cnnk_vit_eval_step(C.byref(d), C.byref(buffers), ptr(n_correct), stream), "cnnk_vit_eval_step")
 
 
 def param_names(layers):

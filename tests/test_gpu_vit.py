@@ -388,3 +388,91 @@ def test_second_stream_changes_no_bit(K, dtype):
     assert a.loss.item() == b.loss.item()
     for k in range(len(a.names)):
         assert torch.equal(a.param[k], b.param[k]) and torch.equal(a.mom[k], b.mom[k]) and torch.equal(a.grad[k], b.grad[k]), a.names[k]
+
+
+# ---- the epoch loop around the step ---------------------------------------------------------------------
+def _loop_case(dtype):
+    net = WL.vit_mini(batch=4, dtype=dtype, image=32, patch=8, dim=128, heads=2, layers=2, mlp=256, classes=10)
+    inp = WL.make_vit_inputs(net, config_id=66)
+    ds = WL.make_vit_dataset(net, 66, n_train=24, n_val=8, signal=1.0)
+    return net, inp, ds
+
+
+def test_eval_step_matches_the_oracle_and_touches_no_training_state(K):
+    from paper_2503_23186_amd.vit import VitRunner
+    for dtype in ("f32", "bf16"):
+        net, inp, ds = _loop_case(dtype)
+        r = VitRunner(net)
+        r.load(ds["val_x"][:4], ds["val_y"][:4], inp["params"], inp["mom"])
+        before = [t.clone() for t in r.param + r.mom + r.grad]
+        nc = torch.full((1,), 5, dtype=torch.int32, device="cuda:0")
+        K.cnnk_vit_eval_step(r.desc, r.buffers, nc)
+        torch.cuda.synchronize()
+        loss, c = V.forward(net.cfg(), ds["val_x"][:4], ds["val_y"][:4], inp["params"], storage=None)
+        tol = 1e-5 if dtype == "f32" else 2e-2
+        assert abs(r.loss.item() - loss) <= tol * max(1.0, abs(loss))
+        assert np.abs(host(r.probs) - c["probs"]).max() <= tol
+        top2 = np.sort(c["logits"], axis=1)[:, -2:]
+        clear = (top2[:, 1] - top2[:, 0]) > (1e-4 if dtype == "f32" else 5e-2)
+        assert (host(r.pred)[clear] == c["pred"][clear]).all()
+        assert nc.item() == 5 + int(np.sum(host(r.pred) == ds["val_y"][:4]))
+        assert all(torch.equal(a, b) for a, b in zip(before, r.param + r.mom + r.grad))
+
+
+def test_fit_matches_the_oracle_loop_fp32(K, tmp_path):
+    from paper_2503_23186_amd.trainer import VitTrainer, cosine_lr
+    net, inp, ds = _loop_case("f32")
+    epochs, nb = 3, 24 // 4
+    orders = WL.epoch_orders(66, 24, 4, epochs)
+    lrs = cosine_lr(0.05, epochs * nb, warmup_steps=3)
+    want = V.fit(net.cfg(), 4, ds["train_x"], ds["train_y"], ds["val_x"], ds["val_y"], inp["params"], inp["mom"], orders, lrs,
+                 momentum=0.9, weight_decay=1e-3)
+    t = VitTrainer(net)
+    t.load_state(inp["params"], inp["mom"])
+    tx, ty = t.to_device(ds["train_x"], ds["train_y"])
+    vx, vy = t.to_device(ds["val_x"], ds["val_y"])
+    ck = str(tmp_path / "best.safetensors")
+    hist = t.fit(tx, ty, vx, vy, orders, lrs, 0.9, 1e-3, ckpt_path=ck)
+    for (gl, ga, gv), (wl, wa, wv) in zip(hist, want["history"]):
+        assert abs(gl - wl) <= 1e-4 * abs(wl) and ga == wa and abs(gv - wv) <= 1e-4 * abs(wv)
+    for k, name in enumerate(t.run.names):
+        assert max_rel_err(host(t.run.param[k]), want["params"][name].reshape(t.run.param[k].shape)) <= 1e-4, name
+        assert max_rel_err(host(t.run.mom[k]), want["mom"][name].reshape(t.run.mom[k].shape)) <= 1e-4, name
+    assert t.best_epoch == want["best"]["epoch"] and t.best_acc == want["best"]["acc"]
+    # the checkpoint holds the best epoch's parameters and reproduces its accuracy
+    t2 = VitTrainer(net)
+    t2.load_checkpoint(ck)
+    assert t2.epoch == want["best"]["epoch"] + 1
+    for k, name in enumerate(t2.run.names):
+        assert max_rel_err(host(t2.run.param[k]), want["best"]["params"][name].reshape(t2.run.param[k].shape)) <= 1e-4, name
+    assert t2.evaluate(vx, vy)[0] == want["best"]["acc"]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_resume_from_checkpoint_is_bit_identical(K, tmp_path, dtype):
+    from paper_2503_23186_amd.trainer import VitTrainer, step_lr
+    net, inp, ds = _loop_case(dtype)
+    nb = 24 // 4
+    orders = WL.epoch_orders(67, 24, 4, 4)
+    lrs = step_lr(0.05, nb, 4, milestones=[2])
+    full = VitTrainer(net)
+    full.load_state(inp["params"], inp["mom"])
+    tx, ty = full.to_device(ds["train_x"], ds["train_y"])
+    vx, vy = full.to_device(ds["val_x"], ds["val_y"])
+    h_full = full.fit(tx, ty, vx, vy, orders, lrs, 0.9, 1e-3)
+    a = VitTrainer(net)
+    a.load_state(inp["params"], inp["mom"])
+    h_a = a.fit(tx, ty, vx, vy, orders[:2], lrs, 0.9, 1e-3)
+    ck = str(tmp_path / "mid.safetensors")
+    a.save_checkpoint(ck)
+    b = VitTrainer(net)
+    b.load_checkpoint(ck)
+    h_b = b.fit(tx, ty, vx, vy, orders[2:], lrs, 0.9, 1e-3)
+    assert h_a + h_b == h_full
+    for k in range(len(full.run.names)):
+        assert torch.equal(full.run.param[k], b.run.param[k]) and torch.equal(full.run.mom[k], b.run.mom[k])
+    # the per-call profile leaves the training state alone
+    before = [t.clone() for t in b.run.param + b.run.mom]
+    prof = b.profile(steps=2)
+    assert len(prof) == b.run.n_calls and all(ms >= 0 for _, ms in prof)
+    assert all(torch.equal(x, y) for x, y in zip(before, b.run.param + b.run.mom))

@@ -221,3 +221,36 @@ def test_bf16_storage_points():
     assert V.round_bf16(np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20])).tolist() == \
         [1.0, 1.0 + 2.0 ** -6, 1.0 + 2.0 ** -7]
     assert (V.round_bf16(np.array([0.1, -3.3])) == torch.tensor([0.1, -3.3]).to(torch.bfloat16).double().numpy()).all()
+
+
+def test_epoch_loop_chains_steps_and_keeps_the_best_checkpoint():
+    net = WL.vit_mini(batch=4, dtype="f32", image=16, patch=4, dim=32, heads=2, layers=1, mlp=48, classes=5)
+    cfg = net.cfg()
+    inp = WL.make_vit_inputs(net, config_id=65)
+    ds = WL.make_vit_dataset(net, 65, n_train=16, n_val=8, signal=1.0)
+    orders = WL.epoch_orders(65, 16, 4, 3)
+    lrs = [0.05] * 12
+    out = V.fit(cfg, 4, ds["train_x"], ds["train_y"], ds["val_x"], ds["val_y"], inp["params"], inp["mom"], orders, lrs)
+    # the loop is nothing but the step chained over the mini-batches in the given order
+    P, M = inp["params"], inp["mom"]
+    losses = []
+    for e in range(3):
+        for b in range(4):
+            idx = orders[e][4 * b:4 * b + 4]
+            r = V.train_step(cfg, ds["train_x"][idx], ds["train_y"][idx], P, M, 0.05, 0.9, 0.0)
+            P, M = r["params"], r["mom"]
+            losses.append(r["loss"])
+    assert all((out["params"][k] == P[k]).all() for k in P)
+    assert [h[0] for h in out["history"]] == [float(np.mean(losses[4 * e:4 * e + 4])) for e in range(3)]
+    # validation: accuracy is the fraction of the oracle's own predictions that match; best = first maximum
+    acc, vloss, pred = V.evaluate(cfg, 4, ds["val_x"], ds["val_y"], P)
+    assert acc == float(np.mean(pred == ds["val_y"])) and (acc, vloss) == out["history"][-1][1:]
+    accs = [h[1] for h in out["history"]]
+    assert out["best"]["epoch"] == int(np.argmax(accs)) and out["best"]["acc"] == max(accs)
+    # zero learning rate: parameters stay, every epoch validates the same
+    z = V.fit(cfg, 4, ds["train_x"], ds["train_y"], ds["val_x"], ds["val_y"], inp["params"], inp["mom"], orders[:2], [0.0] * 8)
+    assert all((z["params"][k] == inp["params"][k]).all() for k in inp["params"]) and z["history"][0][1:] == z["history"][1][1:]
+    # a set that can be learnt is learnt: the training loss falls over a few epochs
+    more = V.fit(cfg, 4, ds["train_x"], ds["train_y"], ds["val_x"], ds["val_y"], inp["params"], inp["mom"],
+                 WL.epoch_orders(65, 16, 4, 12), [0.05] * 48)
+    assert more["history"][-1][0] < 0.75 * more["history"][0][0]

@@ -99,3 +99,19 @@ def make_vit_inputs(net: ViT, config_id=6, zero_momentum=False):
         v = np.zeros(shape) if zero_momentum else 1e-3 * vr.standard_normal(shape)
         mom[name] = np.ascontiguousarray(v.astype(np.float32).astype(np.float64))
     return dict(x=np.ascontiguousarray(x), labels=labels, params=params, mom=mom)
+
+
+def make_vit_dataset(net: ViT, config_id, n_train, n_val, signal=0.5):
+    """A seeded synthetic train / validation set of the net's input shape: every class has a fixed N(0, 1)
+    template image, a sample is N(0, 1) noise plus `signal` times its class's template, labels uniform.
+    Returns dict(train_x, train_y, val_x, val_y) (float64 NHWC / int32)."""
+    shape = (net.image, net.image, 3)
+    templates = rng_for(config_id, 10).standard_normal((net.classes,) + shape)
+    out = {}
+    for name, n, sid in (("train", n_train, 11), ("val", n_val, 13)):
+        y = rng_for(config_id, sid).integers(0, net.classes, size=n).astype(np.int32)
+        x = rng_for(config_id, sid + 1).standard_normal((n,) + shape) + signal * templates[y]
+        x = to_bf16_representable(x) if net.dtype == "bf16" else x.astype(np.float32).astype(np.float64)
+        out[name + "_x"] = np.ascontiguousarray(x)
+        out[name + "_y"] = y
+    return out
