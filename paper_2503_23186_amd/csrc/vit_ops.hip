@@ -71,7 +71,8 @@ __global__ void __launch_bounds__(kT) ln_fwd_kernel(const T* __restrict__ x, lon
   if (lane == 0) { stats[2 * (size_t)row] = mean; stats[2 * (size_t)row + 1] = rstd; }
 }
 
-// A wavefront walks its rows two at a time (both rows' loads are in flight together); per row two
+// A wavefront walks its rows RU at a time (1 as launched: two rows in flight cost the registers that
+// a second resident workgroup needs, 40 against 27 us at ViT-B/16's shape); per row two
 // wave reductions give the two projections that the normalisation removes; the lane keeps its
 // columns' contributions to dgamma / dbeta in registers over all its rows.  The four wavefronts of a
 // workgroup then add theirs in LDS one after the other (fixed order) and the workgroup writes one
@@ -83,7 +84,7 @@ template <int VW, typename T> __device__ __forceinline__ void storev(T* p, const
   if (VW == 8) store8(p, f); else store4(p, f);
 }
 
-template <typename T, int NV, int VW>
+template <typename T, int NV, int VW, int RU>
 __global__ void __launch_bounds__(kT) ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x, long long xs,
                                                     const float* __restrict__ g, const float* __restrict__ stats,
                                                     const T* dres, T* dx, float* __restrict__ part, int rows, int C) {
@@ -98,11 +99,11 @@ __global__ void __launch_bounds__(kT) ln_bwd_kernel(const T* __restrict__ dy, co
     if (c < C) loadv<VW>(g + c, gg[i]);
   }
   const int stride = gridDim.x * (kT / 64);
-  for (int row0 = blockIdx.x * (kT / 64) + wave; row0 < rows; row0 += 2 * stride) {
-    float d[2][NV][VW], xh[2][NV][VW], rr[2][NV][VW];
-    float mean[2], rstd[2];
+  for (int row0 = blockIdx.x * (kT / 64) + wave; row0 < rows; row0 += RU * stride) {
+    float d[RU][NV][VW], xh[RU][NV][VW], rr[RU][NV][VW];
+    float mean[RU], rstd[RU];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < RU; ++u) {
       const int row = row0 + u * stride;
       const bool live = row < rows;
       mean[u] = live ? stats[2 * (size_t)row] : 0.f;
@@ -121,7 +122,7 @@ __global__ void __launch_bounds__(kT) ln_bwd_kernel(const T* __restrict__ dy, co
       }
     }
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < RU; ++u) {
       const int row = row0 + u * stride;
       float s1 = 0.f, s2 = 0.f;
 #pragma unroll
@@ -421,7 +422,7 @@ template <typename T>
 static void launch_ln_bwd(const cnnk_ln_desc* d, long long xs, int nb, const void* dy, const void* x, const float* g,
                           const float* stats, const void* dres, void* dx, float* part, hipStream_t st) {
   const size_t lds = (size_t)2 * d->C * sizeof(float);
-#define LN_BWD(NV, VW) ln_bwd_kernel<T, NV, VW><<<nb, kT, lds, st>>>((const T*)dy, (const T*)x, xs, g, stats, (const T*)dres, (T*)dx, part, d->rows, d->C)
+#define LN_BWD(NV, VW) ln_bwd_kernel<T, NV, VW, 1><<<nb, kT, lds, st>>>((const T*)dy, (const T*)x, xs, g, stats, (const T*)dres, (T*)dx, part, d->rows, d->C)
   if (d->C % 8 == 0 && xs % 8 == 0) {
     if (d->C <= 512) LN_BWD(1, 8); else if (d->C <= 1024) LN_BWD(2, 8); else if (d->C <= 2048) LN_BWD(4, 8); else LN_BWD(8, 8);
   } else {
