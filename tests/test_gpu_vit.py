@@ -319,13 +319,14 @@ def l2_rel(got, ref):
 
 STEP_NETS = {
     "b16": dict(batch=2, image=224, patch=16, dim=768, heads=12, layers=2, mlp=3072),  # ViT-B/16's geometry, two blocks
+    "b16-full-depth": dict(batch=8, image=224, patch=16, dim=768, heads=12, layers=12, mlp=3072),  # ViT-B/16 itself, batch 8
     "mini": dict(batch=4, image=32, patch=8, dim=128, heads=2, layers=2, mlp=256),
     "tall": dict(batch=2, image=64, patch=8, dim=64, heads=4, layers=3, mlp=192),     # 65 tokens, dh 16
     "wide": dict(batch=3, image=32, patch=16, dim=256, heads=4, layers=1, mlp=1024),  # 5 tokens, dh 64
 }
 
 
-@pytest.mark.parametrize("name", [n for n in STEP_NETS if n != "b16"])
+@pytest.mark.parametrize("name", [n for n in STEP_NETS if not n.startswith("b16")])
 def test_step_fp32(K, name):
     net = WL.vit_mini(dtype="f32", **STEP_NETS[name])
     inp = WL.make_vit_inputs(net, config_id=62)
