@@ -97,17 +97,18 @@ def vit_call_work(net, name):
     rows, es = B * T, 2 if net.dtype == "bf16" else 4
     lin = {"qkv": (d, 3 * d), "proj": (d, d), "fc1": (d, m), "fc2": (m, d), "embed": (net.patch * net.patch * 3, d)}
     part = name.split(".")
-    if part[0] in lin and part[1] in ("gemm", "gemm_gelu", "dgrad", "wgrad"):
+    if part[0] in lin and part[1] in ("gemm", "gemm_gelu", "gemm_res", "dgrad", "wgrad"):
         K, N = lin[part[0]]
         r = B * (T - 1) if part[0] == "embed" else rows
-        out_b = {"gemm": r * N * es, "gemm_gelu": 2 * r * N * es, "dgrad": r * K * es, "wgrad": N * K * 4}[part[1]]
-        in_b = {"gemm": r * K * es, "gemm_gelu": r * K * es, "dgrad": r * N * es, "wgrad": r * (K + N) * es}[part[1]]
+        out_b = {"gemm": r * N * es, "gemm_gelu": 2 * r * N * es, "gemm_res": r * N * es, "dgrad": r * K * es, "wgrad": N * K * 4}[part[1]]
+        in_b = {"gemm": r * K * es, "gemm_gelu": r * K * es, "gemm_res": r * (K + N) * es, "dgrad": r * N * es,
+                "wgrad": r * (K + N) * es}[part[1]]
         return "mfma", 2.0 * r * K * N, in_b + out_b + (0 if part[1] == "wgrad" else N * K * es)
     if name == "attn":
         return "mfma", 4.0 * B * h * T * T * (d // h), rows * 4 * d * es
     if name == "attn.bwd":
         return "mfma", 10.0 * B * h * T * T * (d // h), rows * (3 * d + 2 * d + 3 * d) * es
-    ew = {"ln1": 2 * d, "ln2": 2 * d, "ln1.bwd": 4 * d, "ln2.bwd": 4 * d, "proj.res": 3 * d, "fc2.res": 3 * d,
+    ew = {"ln1": 2 * d, "ln2": 2 * d, "ln1.bwd": 4 * d, "ln2.bwd": 4 * d,
           "fc1.gelu.bwd": 3 * m, "qkv.dbias": 3 * d, "proj.dbias": d, "fc2.dbias": d}
     if name in ew:
         return "hbm", 0.0, rows * ew[name] * es

@@ -58,8 +58,11 @@ int cnnk_bias_act_bwd(long long rows, int C, int dtype, int act, const void* dy,
 
 /* ---- linear layers ---------------------------------------------------------------------------------------
  * x [rows][K], w [N][K] (of dtype: in the bf16 mode the bf16 copy of the fp32 master), bias [N]
- * float or NULL.  fwd: act = NONE: y = x w^T + bias;  act = GELU (bias required): u = x w^T + bias is
- * stored and y = gelu(u as stored), as in cnnk_bias_act_fwd.  dgrad: dx [rows][K] = dy w.
+ * float or NULL.  fwd: act = NONE: y = x w^T + bias, and with res [rows][N] not NULL (a residual
+ * connection; y must not alias res) y = res + (x w^T + bias as stored: in bf16 storage the product is
+ * rounded before the sum and the sum again, whichever kernels run);  act = GELU (bias required, no
+ * res): u = x w^T + bias is stored and y = gelu(u as stored), as in cnnk_bias_act_fwd.
+ * dgrad: dx [rows][K] = dy w.
  * wgrad: dw [N][K] float = dy^T x (the bias gradient is cnnk_bias_act_bwd's column sum).
  * K % 8 == 0, N % 8 == 0.  bf16 runs on dedicated matrix-core kernels (an output is rounded once,
  * after bias); fp32 on the 1 x 1 convolution kernels of cnnk.h followed by cnnk_bias_act_fwd
@@ -67,7 +70,8 @@ int cnnk_bias_act_bwd(long long rows, int C, int dtype, int act, const void* dy,
  * gradient is a fixed-order sum of per-row-range partials: reproducible bit for bit. */
 size_t cnnk_linear_workspace_bytes(long long rows, int K, int N, int dtype);
 int cnnk_linear_fwd(long long rows, int K, int N, int dtype, const void* x, const void* w,
-                    const float* bias, int act, void* u, void* y, void* ws, size_t ws_bytes, void* stream);
+                    const float* bias, const void* res, int act, void* u, void* y, void* ws,
+                    size_t ws_bytes, void* stream);
 int cnnk_linear_dgrad(long long rows, int K, int N, int dtype, const void* dy, const void* w, void* dx,
                       void* ws, size_t ws_bytes, void* stream);
 int cnnk_linear_wgrad(long long rows, int K, int N, int dtype, const void* x, const void* dy, float* dw,

@@ -5,9 +5,10 @@
 
 // K and N multiples of 8, every matrix below 2 GiB
 bool gemm_bf16_supported(long long rows, int K, int N);
-// y = x w^T + bias (bias may be null); with gelu: u = x w^T + bias, y = gelu(u as stored)
-int gemm_bf16_fwd(long long rows, int K, int N, const bf16_t* x, const bf16_t* w, const float* bias, bool gelu, bf16_t* u,
-                  bf16_t* y, hipStream_t st);
+// y = x w^T + bias (bias may be null); with res (not with gelu): y = res + (x w^T + bias as stored);
+// with gelu: u = x w^T + bias, y = gelu(u as stored)
+int gemm_bf16_fwd(long long rows, int K, int N, const bf16_t* x, const bf16_t* w, const float* bias, const bf16_t* res, bool gelu,
+                  bf16_t* u, bf16_t* y, hipStream_t st);
 // dx = dy w
 int gemm_bf16_dgrad(long long rows, int K, int N, const bf16_t* dy, const bf16_t* w, bf16_t* dx, hipStream_t st);
 // dw = dy^T x (fp32); ws: gemm_bf16_wgrad_ws bytes of partial sums

@@ -59,6 +59,7 @@ struct Args {
   bf16_t* C2;         // EPI 1: gelu(C)
   float* part;        // EPI 2: fp32 partials [splits][M][N]
   const float* bias;  // [N] or null
+  const bf16_t* res;  // EPI 3: [M][N] added to the rounded output (a residual connection)
   int M, N, K;        // output rows, output columns, reduction length
   int lda, ldb, ldc;
   int k_per_split;    // reduction elements per blockIdx.z (a multiple of BK)
@@ -250,7 +251,18 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_kernel(Args a) {
       const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(S + rd_off + 4 * SP + rb * 32));
       const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
       const int row = m0 + wm * (TM * 32) + i * 32 + rb * 16 + i16, col = n0 + wn * 64 + j * 32 + g * 8;
-      if (row < a.M && col < a.N) *reinterpret_cast<uint4*>(dst + (size_t)row * a.ldc + col) = uint4{l2.x, l2.y, h2.x, h2.y};
+      if (row < a.M && col < a.N) {
+        uint4 out = uint4{l2.x, l2.y, h2.x, h2.y};
+        if (EPI == 3) {     // + residual: the sum of two stored values, rounded again
+          float x[8], r[8];
+          unpack8(out, x);
+          load8(a.res + (size_t)row * a.ldc + col, r);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) x[e] += r[e];
+          out = uint4{pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]), pack_bf16x2(x[4], x[5]), pack_bf16x2(x[6], x[7])};
+        }
+        *reinterpret_cast<uint4*>(dst + (size_t)row * a.ldc + col) = out;
+      }
     }
     asm volatile("" ::: "memory");
   };
@@ -324,15 +336,16 @@ bool gemm_bf16_supported(long long rows, int K, int N) {
   return rows > 0 && K > 0 && N > 0 && K % 8 == 0 && N % 8 == 0 && fits32(rows, K) && fits32(rows, N) && fits32(N, K);
 }
 
-int gemm_bf16_fwd(long long rows, int K, int N, const bf16_t* x, const bf16_t* w, const float* bias, bool gelu, bf16_t* u,
-                  bf16_t* y, hipStream_t st) {
+int gemm_bf16_fwd(long long rows, int K, int N, const bf16_t* x, const bf16_t* w, const float* bias, const bf16_t* res, bool gelu,
+                  bf16_t* u, bf16_t* y, hipStream_t st) {
   Args a{};
-  a.A = x; a.B = w; a.bias = bias;
+  a.A = x; a.B = w; a.bias = bias; a.res = res;
   a.C = gelu ? u : y; a.C2 = gelu ? y : nullptr;
   a.M = (int)rows; a.N = N; a.K = K; a.lda = K; a.ldb = K; a.ldc = N; a.k_per_split = K;
   a.ntiles = (N + BN - 1) / BN;
   a.a_bytes = (unsigned)(rows * K * 2); a.b_bytes = (unsigned)((long long)N * K * 2);
   const int tm = pick_tm(a.M, a.ntiles);
+  if (res) return launch_tm<false, false, 3>(tm, a, a.M, 1, st);
   return gelu ? launch_tm<false, false, 1>(tm, a, a.M, 1, st) : launch_tm<false, false, 0>(tm, a, a.M, 1, st);
 }
 

@@ -37,20 +37,23 @@ extern "C" size_t cnnk_linear_workspace_bytes(long long rows, int K, int N, int 
 }
 
 extern "C" int cnnk_linear_fwd(long long rows, int K, int N, int dtype, const void* x, const void* w, const float* bias,
-                               int act, void* u, void* y, void* ws, size_t ws_bytes, void* stream) {
+                               const void* res, int act, void* u, void* y, void* ws, size_t ws_bytes, void* stream) {
   const int rc = check(rows, K, N, dtype);
   if (rc != CNNK_OK) return rc;
   if (act != CNNK_ACT_NONE && act != CNNK_ACT_GELU) return CNNK_ERR_UNSUPPORTED;
   if (!x || !w || !y || (act == CNNK_ACT_GELU && (!u || !bias))) return CNNK_ERR_NULL;
-  if (((size_t)x | (size_t)w | (size_t)y | (size_t)u) & 15) return CNNK_ERR_UNSUPPORTED;
+  if ((act == CNNK_ACT_GELU && res) || (res && res == y)) return CNNK_ERR_UNSUPPORTED;
+  if (((size_t)x | (size_t)w | (size_t)y | (size_t)u | (size_t)res) & 15) return CNNK_ERR_UNSUPPORTED;
   hipStream_t st = (hipStream_t)stream;
   if (fast(rows, K, N, dtype))
-    return gemm_bf16_fwd(rows, K, N, (const bf16_t*)x, (const bf16_t*)w, bias, act == CNNK_ACT_GELU, (bf16_t*)u, (bf16_t*)y, st);
+    return gemm_bf16_fwd(rows, K, N, (const bf16_t*)x, (const bf16_t*)w, bias, (const bf16_t*)res, act == CNNK_ACT_GELU, (bf16_t*)u,
+                         (bf16_t*)y, st);
   const cnnk_conv_desc c = as_conv(rows, K, N, dtype);
   void* z = act == CNNK_ACT_GELU ? u : y;
-  const int r2 = cnnk_conv2d_fwd(&c, x, w, z, nullptr, nullptr, ws, ws_bytes, stream);
-  if (r2 != CNNK_OK || !bias) return r2;
-  return cnnk_bias_act_fwd(rows, N, dtype, act, z, bias, nullptr, u, y, stream);
+  int r2 = cnnk_conv2d_fwd(&c, x, w, z, nullptr, nullptr, ws, ws_bytes, stream);
+  if (r2 == CNNK_OK && bias) r2 = cnnk_bias_act_fwd(rows, N, dtype, act, z, bias, nullptr, u, y, stream);
+  if (r2 == CNNK_OK && res) r2 = cnnk_add((size_t)rows * N, dtype, res, y, y, stream);   // the same two roundings
+  return r2;
 }
 
 extern "C" int cnnk_linear_dgrad(long long rows, int K, int N, int dtype, const void* dy, const void* w, void* dx, void* ws,

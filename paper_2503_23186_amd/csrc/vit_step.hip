@@ -15,7 +15,7 @@ namespace {
 enum { P_WE = 0, P_BE, P_CLS, P_POS, P_BLOCK0 };                          // model parameters
 enum { B_G1 = 0, B_B1, B_WQKV, B_BQKV, B_WO, B_BO, B_G2, B_B2, B_W1, B_C1, B_W2, B_C2, B_COUNT };
 // internal tensors of the arena behind the public ones
-enum { X_Z0 = CNNK_VIT_TENSORS, X_DZ0, X_ZTMP, X_STATS1, X_STATS2, X_LSE, X_STATSF, X_TENSORS };
+enum { X_Z0 = CNNK_VIT_TENSORS, X_DZ0, X_STATS1, X_STATS2, X_LSE, X_STATSF, X_TENSORS };
 
 struct Geo {
   int B, n, T, d, m, K0, L, classes, dtype, heads;
@@ -67,7 +67,6 @@ size_t tensor_bytes(const Geo& g, int id) {
     case CNNK_VIT_U: case CNNK_VIT_G: case CNNK_VIT_DU: case CNNK_VIT_DG: return r * g.m * es;
     case CNNK_VIT_F: case CNNK_VIT_DF: return (size_t)g.B * g.d * es;
     case X_Z0: case X_DZ0: return (size_t)g.B * g.n * g.d * es;
-    case X_ZTMP: return r * g.d * es;
     case X_STATS1: case X_STATS2: return r * 2 * sizeof(float);
     case X_LSE: return (size_t)g.B * g.heads * g.T * sizeof(float);
     case X_STATSF: return (size_t)g.B * 2 * sizeof(float);
@@ -191,20 +190,18 @@ int walk(const cnnk_vit_desc* v, const Geo& g, const cnnk_vit_buffers* buf, floa
 
   // ---- forward ----
   w.call(-1, "embed.patchify", [&] { return cnnk_vit_patchify(&ed, buf->x, at(CNNK_VIT_PATCHES, 0), st); });
-  w.call(-1, "embed.gemm", [&] { return cnnk_linear_fwd(prow, g.K0, d, dt, at(CNNK_VIT_PATCHES, 0), Wm(P_WE), nullptr, CNNK_ACT_NONE, nullptr, at(X_Z0, 0), ws, wsb, st); });
+  w.call(-1, "embed.gemm", [&] { return cnnk_linear_fwd(prow, g.K0, d, dt, at(CNNK_VIT_PATCHES, 0), Wm(P_WE), nullptr, nullptr, CNNK_ACT_NONE, nullptr, at(X_Z0, 0), ws, wsb, st); });
   w.call(-1, "embed.tokens", [&] { return cnnk_vit_embed_fwd(&ed, at(X_Z0, 0), P(P_BE), P(P_CLS), P(P_POS), at(CNNK_VIT_TOK, 0), st); });
   for (int l = 0; l < g.L; ++l) {
     const int p0 = P_BLOCK0 + B_COUNT * l;
     void* xin = l ? at(CNNK_VIT_XOUT, l - 1) : at(CNNK_VIT_TOK, 0);
     w.call(l, "ln1", [&] { return cnnk_layernorm_fwd(&ln, xin, P(p0 + B_G1), P(p0 + B_B1), at(CNNK_VIT_H, l), (float*)at(X_STATS1, l), st); });
-    w.call(l, "qkv.gemm", [&] { return cnnk_linear_fwd(rows, d, 3 * d, dt, at(CNNK_VIT_H, l), Wm(p0 + B_WQKV), P(p0 + B_BQKV), CNNK_ACT_NONE, nullptr, at(CNNK_VIT_QKV, l), ws, wsb, st); });
+    w.call(l, "qkv.gemm", [&] { return cnnk_linear_fwd(rows, d, 3 * d, dt, at(CNNK_VIT_H, l), Wm(p0 + B_WQKV), P(p0 + B_BQKV), nullptr, CNNK_ACT_NONE, nullptr, at(CNNK_VIT_QKV, l), ws, wsb, st); });
     w.call(l, "attn", [&] { return cnnk_attention_fwd(&ad, at(CNNK_VIT_QKV, l), at(CNNK_VIT_O, l), (float*)at(X_LSE, l), st); });
-    w.call(l, "proj.gemm", [&] { return cnnk_linear_fwd(rows, d, d, dt, at(CNNK_VIT_O, l), Wm(p0 + B_WO), P(p0 + B_BO), CNNK_ACT_NONE, nullptr, at(X_ZTMP, 0), ws, wsb, st); });
-    w.call(l, "proj.res", [&] { return cnnk_add((size_t)rows * d, dt, xin, at(X_ZTMP, 0), at(CNNK_VIT_XMID, l), st); });
+    w.call(l, "proj.gemm_res", [&] { return cnnk_linear_fwd(rows, d, d, dt, at(CNNK_VIT_O, l), Wm(p0 + B_WO), P(p0 + B_BO), xin, CNNK_ACT_NONE, nullptr, at(CNNK_VIT_XMID, l), ws, wsb, st); });
     w.call(l, "ln2", [&] { return cnnk_layernorm_fwd(&ln, at(CNNK_VIT_XMID, l), P(p0 + B_G2), P(p0 + B_B2), at(CNNK_VIT_H2, l), (float*)at(X_STATS2, l), st); });
-    w.call(l, "fc1.gemm_gelu", [&] { return cnnk_linear_fwd(rows, d, m, dt, at(CNNK_VIT_H2, l), Wm(p0 + B_W1), P(p0 + B_C1), CNNK_ACT_GELU, at(CNNK_VIT_U, l), at(CNNK_VIT_G, l), ws, wsb, st); });
-    w.call(l, "fc2.gemm", [&] { return cnnk_linear_fwd(rows, m, d, dt, at(CNNK_VIT_G, l), Wm(p0 + B_W2), P(p0 + B_C2), CNNK_ACT_NONE, nullptr, at(X_ZTMP, 0), ws, wsb, st); });
-    w.call(l, "fc2.res", [&] { return cnnk_add((size_t)rows * d, dt, at(CNNK_VIT_XMID, l), at(X_ZTMP, 0), at(CNNK_VIT_XOUT, l), st); });
+    w.call(l, "fc1.gemm_gelu", [&] { return cnnk_linear_fwd(rows, d, m, dt, at(CNNK_VIT_H2, l), Wm(p0 + B_W1), P(p0 + B_C1), nullptr, CNNK_ACT_GELU, at(CNNK_VIT_U, l), at(CNNK_VIT_G, l), ws, wsb, st); });
+    w.call(l, "fc2.gemm_res", [&] { return cnnk_linear_fwd(rows, m, d, dt, at(CNNK_VIT_G, l), Wm(p0 + B_W2), P(p0 + B_C2), at(CNNK_VIT_XMID, l), CNNK_ACT_NONE, nullptr, at(CNNK_VIT_XOUT, l), ws, wsb, st); });
   }
   void* xlast = at(CNNK_VIT_XOUT, g.L - 1);
   w.call(-1, "head.ln", [&] { return cnnk_layernorm_fwd(&ln_cls, xlast, P(p_tail), P(p_tail + 1), at(CNNK_VIT_F, 0), (float*)at(X_STATSF, 0), st); });

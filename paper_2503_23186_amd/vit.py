@@ -58,7 +58,7 @@ def _declare():
     lib.cnnk_bias_act_bwd.argtypes = [ll, ci, ci, ci, vp, vp, vp, vp, vp, sz, vp]
     lib.cnnk_linear_workspace_bytes.restype = sz
     lib.cnnk_linear_workspace_bytes.argtypes = [ll, ci, ci, ci]
-    lib.cnnk_linear_fwd.argtypes = [ll, ci, ci, ci, vp, vp, vp, ci, vp, vp, vp, sz, vp]
+    lib.cnnk_linear_fwd.argtypes = [ll, ci, ci, ci, vp, vp, vp, vp, ci, vp, vp, vp, sz, vp]
     lib.cnnk_linear_dgrad.argtypes = [ll, ci, ci, ci, vp, vp, vp, vp, sz, vp]
     lib.cnnk_linear_wgrad.argtypes = [ll, ci, ci, ci, vp, vp, vp, vp, sz, vp]
     lib.cnnk_attention_fwd.argtypes = [C.POINTER(AttnDesc), vp, vp, vp, vp]
@@ -114,8 +114,8 @@ def cnnk_linear_workspace_bytes(rows, K, N, dtype):
     return int(lib.cnnk_linear_workspace_bytes(rows, K, N, dtype))
 
 
-def cnnk_linear_fwd(rows, K, N, dtype, x, w, bias, act, u, y, ws=None, ws_bytes=0, stream=0):
-    _check(lib.cnnk_linear_fwd(rows, K, N, dtype, ptr(x), ptr(w), ptr(bias), act, ptr(u), ptr(y), ptr(ws), ws_bytes, stream),
+def cnnk_linear_fwd(rows, K, N, dtype, x, w, bias, act, u, y, ws=None, ws_bytes=0, stream=0, res=None):
+    _check(lib.cnnk_linear_fwd(rows, K, N, dtype, ptr(x), ptr(w), ptr(bias), ptr(res), act, ptr(u), ptr(y), ptr(ws), ws_bytes, stream),
            "cnnk_linear_fwd")
 
 

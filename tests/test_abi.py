@@ -75,7 +75,7 @@ def test_transformer_entry_points_reject_bad_arguments_on_the_host(cnnk):
         vit.cnnk_vit_patchify(vit.embed_desc(1, 30, 8, 64, cnnk.F32), 256, 256)
     assert e.value.status == 2                              # the image is not a whole number of patches
     d = vit.vit_desc(64, 224, 16, 768, 12, 12, 3072, 100, cnnk.BF16)
-    assert vit.cnnk_vit_step_calls(d) == 3 + 12 * 9 + 2 + 2 + 12 * 15 + 2 + 1
+    assert vit.cnnk_vit_step_calls(d) == 3 + 12 * 7 + 2 + 2 + 12 * 15 + 2 + 1
     assert vit.cnnk_vit_step_call_name(d, 0) == "embed.patchify"
     assert vit.cnnk_vit_step_call_name(d, vit.cnnk_vit_step_calls(d) - 1) == "update"
     off, nb = vit.cnnk_vit_tensor(d, vit.TENSOR_IDS.index("QKV"), 3)

@@ -151,6 +151,12 @@ def _linear_case(K, rows, Kd, N, dtype):
         torch.cuda.synchronize()
         # convolution path in bf16: the product is rounded before the bias is added, and again after
         assert max_rel_err(host(gy), z + (0.0 if b is None else b)) <= tol * (2 if (dtype == "bf16" and b is not None) else 1)
+    # residual connection: the sum of the stored product and the residual
+    res = rep(rng.standard_normal((rows, N)), dtype)
+    gy = dev(np.zeros((rows, N)), dtype)
+    K.cnnk_linear_fwd(rows, Kd, N, dt, gx, gw, dev_f32(bias), K.ACT_NONE, None, gy, ws, nb, res=dev(res, dtype))
+    torch.cuda.synchronize()
+    assert max_rel_err(host(gy), z + bias + res) <= tol * (2 if dtype == "bf16" else 1)
     gu, gy = dev(np.zeros((rows, N)), dtype), dev(np.zeros((rows, N)), dtype)
     K.cnnk_linear_fwd(rows, Kd, N, dt, gx, gw, dev_f32(bias), K.ACT_GELU, gu, gy, ws, nb)
     torch.cuda.synchronize()
