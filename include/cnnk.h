@@ -64,7 +64,7 @@ const char* cnnk_version(void);
  * (unsupported combinations make the conv calls return CNNK_ERR_UNSUPPORTED); 3 = target
  * number of workgroups of the weight-gradient kernel; 4/5 = pixel / channel tile of the 3x3
  * stride-1 LDS-patch kernels (4 = -1 switches them off); 6 = target number of workgroups of
- * the 3x3 stride-1 weight-gradient kernel (-1 switches it off); 10 = -1 keeps cnnk_attention_fwd / _bwd (cnnk_vit.h) on the vector-ALU kernels, 15 = -1 keeps cnnk_linear_* on the 1 x 1 convolution kernels; 7 = -1 switches off the pixel
+ * the 3x3 stride-1 weight-gradient kernel (-1 switches it off); 10 = -1 keeps cnnk_attention_fwd / _bwd (cnnk_vit.h) on the vector-ALU kernels, 15 = -1 keeps cnnk_linear_* on the 1 x 1 convolution kernels, 1 / 2 keeps their matrix-core kernels on 64-byte / 128-byte operand rows in LDS whatever the shape; 7 = -1 switches off the pixel
  * permutation that keeps narrow images (W < 16) free of LDS bank conflicts; 8 = -1 keeps convolutions with
  * fewer than 8 input channels on the direct (plain-FMA) kernels; 11 = -1 keeps the first layer's forward
  * pass on the padded-input path; 9 = -1 makes cnnk_train_step hand y to

@@ -20,19 +20,28 @@
 #include "common.h"
 #include "gemm.h"
 
+extern int g_cnnk_tune[16];
+
 namespace {
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
 typedef int i32x4_t __attribute__((ext_vector_type(4)));
 
-constexpr int BN = 128, BK = 32, NST = 3;
-constexpr int B_BYTES = BN * BK * 2;
-constexpr int kThreads = 256;
-// TM: 32-row blocks of a wavefront's tile (4: workgroup tile 256 x 128, 3: 192 x 128, for shapes whose
-// tile count at 256 rows leaves much of the device idle in the last round of resident workgroups)
-template <int TM> struct Cfg {
-  static constexpr int BM = 64 * TM, A_BYTES = BM * BK * 2, STAGE_B = A_BYTES + B_BYTES;
-  static constexpr int NLOAD = STAGE_B / 1024 / 4;      // direct loads per wavefront and stage (TM + 2)
+// TM: 32-row blocks of a wavefront's tile (4: workgroup tile 256 x 128, 3: 192 x 128).
+// RB: bytes of an LDS row = bytes of an operand row that one group of lanes fetches.  The path from L2
+// into LDS moves a fixed number of requests per clock whatever their size up to a 128-byte line
+// (measured: 16 TB/s with 64-byte row segments, 32 TB/s with 128-byte ones), and with 64-byte rows that
+// path, not the matrix pipe, bounds the kernel.  128-byte rows of an operand whose reduction index is
+// the contiguous one mean 64 reduction elements per stage, and then only two stage buffers of a
+// 192 x 128 tile fit the 80 KB a workgroup may hold with two workgroups per CU; an operand read through
+// the transposing load takes 128-byte rows by widening its planes to 64 columns, at any stage depth.
+template <int TM, int BK_, int RB_> struct Cfg {
+  static constexpr int BK = BK_, RB = RB_;
+  static constexpr int NW = 4, THREADS = 64 * NW, BN = 128;   // four wavefronts, 2 x 2
+  static constexpr int NST = BK == 64 ? 2 : 3;           // stage buffers; loads run NST - 1 stages ahead
+  static constexpr int BM = 64 * TM, A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE_B = A_BYTES + B_BYTES;
+  static constexpr int NLOAD = STAGE_B / 1024 / NW;      // direct loads per wavefront and stage
+  static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "every load of a wavefront belongs to one operand");
 };
 constexpr int SP = 72;                         // epilogue strip pitch (bytes per column)
 
@@ -50,7 +59,17 @@ __device__ __forceinline__ void load16_to_lds(i32x4_t desc, unsigned lds_addr, u
                : "s"(lds_addr), "v"(voff), "s"(desc)
                : "memory");
 }
-__device__ __forceinline__ int swz(int row, int c16) { return row * 64 + ((c16 ^ ((row >> 2) & 3)) << 4); }
+// What the index of a 16-byte chunk is XORed with to give its position in the LDS row.  64-byte rows
+// read with 16-byte loads: row bits 2-3; read with the transposing load: nothing, four consecutive
+// rows are the 64 banks whatever the order inside a row.
+// 128-byte rows read with 16-byte loads (sixteen rows of one chunk per pass): with row bits 1-3, so that
+// the eight rows of either parity - a row's parity picks the half of the banks - sit on eight different
+// chunk positions.  128-byte rows read with the transposing load (four rows x 64 bytes per pass): the
+// two 64-byte halves swap on every second pair of rows, which puts the four rows on four bank quarters.
+template <int RB, bool TR> __device__ __forceinline__ int swz_of(int row) {
+  if (RB == 64) return TR ? 0 : (row >> 2) & 3;
+  return TR ? ((row >> 1) & 1) << 2 : (row >> 1) & 7;
+}
 
 struct Args {
   const bf16_t* A;
@@ -79,9 +98,17 @@ __device__ __forceinline__ float gelu_f(float u) {
   return u >= 0.f ? u - u * q : u * q;
 }
 
-template <bool ATR, bool BTR, int EPI, int TM>
-__global__ void __launch_bounds__(kThreads, 2) gemm_kernel(Args a) {
-  constexpr int BM = Cfg<TM>::BM, A_BYTES = Cfg<TM>::A_BYTES, STAGE_B = Cfg<TM>::STAGE_B, NLOAD = Cfg<TM>::NLOAD;
+template <bool ATR, bool BTR, int EPI, int TM, int BK, int RB>
+__global__ void __launch_bounds__(256, 2) gemm_kernel(Args a) {
+  using C = Cfg<TM, BK, RB>;
+  constexpr int NW = C::NW, BN = C::BN;
+  constexpr int BM = C::BM, A_BYTES = C::A_BYTES, STAGE_B = C::STAGE_B, NLOAD = C::NLOAD, NST = C::NST;
+  constexpr int LPR = RB / 16, RPL = 1024 / RB;       // lanes per LDS row, rows per direct load
+  constexpr int PC = RB / 2, PLANE_B = BK * RB;       // a transposed operand: planes of BK reduction rows x PC columns
+  constexpr int KS = BK / 16;                         // MFMA reduction steps per stage
+  static_assert((ATR || BK * 2 == RB) && (BTR || BK * 2 == RB), "a natural operand's LDS row is its BK reduction elements");
+  static_assert(BM % PC == 0 || !ATR, "whole planes");
+  static_assert(NST == 2 || NLOAD < 16, "the wait below encodes the load count in four bits");
   extern __shared__ __align__(16) unsigned char smem[];   // NST stage buffers, nothing else: LDS address 0
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -110,73 +137,77 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_kernel(Args a) {
   const int nst = kend > kbeg ? (kend - kbeg + BK - 1) / BK : 0;
 
   const i32x4_t a_rs = make_desc(a.A, a.a_bytes), b_rs = make_desc(a.B, a.b_bytes);
-  // ---- this lane's six direct loads of a stage ----
+  // ---- this lane's direct loads of a stage ----
+  // A load of the wavefront fills 1 KB of LDS: RPL rows of RB bytes, lane i the 16 bytes at 16 i, so
+  // the LPR lanes of a row ask for the (swizzled) chunks of one RB-byte segment of memory.
   // kk0: reduction index of the lane's 16 bytes in stage 0 (its first element for a natural operand,
   // its row for a transposed one); a load of stage t is in range while kk0 + t * BK < kend
-  unsigned voff[NLOAD], vinc[NLOAD];
-  int ldsoff[NLOAD], kk0[NLOAD];
-  bool isA[NLOAD];
+  unsigned voff[NLOAD];
+  int kk0[NLOAD];
+  const unsigned vinc_a = ATR ? (unsigned)(BK * a.lda * 2) : BK * 2, vinc_b = BTR ? (unsigned)(BK * a.ldb * 2) : BK * 2;
 #pragma unroll
   for (int j = 0; j < NLOAD; ++j) {
-    const int q = j * 4 + wave;
-    isA[j] = q < A_BYTES / 1024;
-    const int qq = isA[j] ? q : q - A_BYTES / 1024;
-    const bool tr = isA[j] ? ATR : BTR;
-    const int ld = isA[j] ? a.lda : a.ldb;
-    const int o0 = isA[j] ? m0 : n0, olim = isA[j] ? a.M : a.N;
-    ldsoff[j] = (isA[j] ? 0 : A_BYTES) + qq * 1024;
-    const int cp = lane & 3;
+    const bool isA = j * NW < A_BYTES / 1024;           // blocks j * NW + wave: a compile-time property
+    const int qq = j * NW + wave - (isA ? 0 : A_BYTES / 1024);
+    const bool tr = isA ? ATR : BTR;
+    const int ld = isA ? a.lda : a.ldb;
+    const int o0 = isA ? m0 : n0, olim = isA ? a.M : a.N;
+    const int p = lane % LPR;
     if (!tr) {
-      const int r = qq * 16 + (lane >> 2);
-      const int c = cp ^ ((r >> 2) & 3);
+      const int r = qq * RPL + lane / LPR;
+      const int c = p ^ swz_of<RB, false>(r);
       const int row = o0 + r;
       kk0[j] = row < olim ? kbeg + 8 * c : (1 << 30);
       voff[j] = (unsigned)((row * ld + kbeg + 8 * c) * 2);
-      vinc[j] = BK * 2;
     } else {
-      const int plane = qq >> 1, r = (qq & 1) * 16 + (lane >> 2);
-      const int c = cp ^ ((r >> 2) & 3);
-      const int col = o0 + plane * 32 + 8 * c;
+      const int plane = qq / (BK / RPL), r = (qq % (BK / RPL)) * RPL + lane / LPR;
+      const int c = p ^ swz_of<RB, true>(r);
+      const int col = o0 + plane * PC + 8 * c;
       kk0[j] = col < olim ? kbeg + r : (1 << 30);
       voff[j] = (unsigned)(((kbeg + r) * ld + col) * 2);
-      vinc[j] = (unsigned)(BK * ld * 2);
     }
   }
   auto issue = [&](int t, int sb) __attribute__((always_inline)) {
 #pragma unroll
     for (int j = 0; j < NLOAD; ++j) {
-      const unsigned off = kk0[j] + t * BK < kend ? voff[j] + (unsigned)t * vinc[j] : kOobOffset;
-      load16_to_lds(isA[j] ? a_rs : b_rs, (unsigned)(sb + ldsoff[j]), off);
+      const bool isA = j * NW < A_BYTES / 1024;
+      const unsigned off = kk0[j] + t * BK < kend ? voff[j] + (unsigned)t * (isA ? vinc_a : vinc_b) : kOobOffset;
+      load16_to_lds(isA ? a_rs : b_rs, (unsigned)(sb + (j * NW + wave) * 1024), off);
     }
   };
   // ---- fragment addresses (stage-relative) ----
-  int aoff[2][2], boff[2][2];     // [reduction step of the stage][first / second read of a transposing pair]
+  // natural: 16 bytes = reduction elements ks * 16 + h * 8 .. + 8 of row lane % 32 of a 32-row block;
+  // blocks lie 32 rows apart and the swizzle repeats every 16 rows.  The chunk index ks * 2 + h meets
+  // the swizzle in an XOR, so step ks is the address of step 0 XOR ks * 32 (128-byte rows) and the next
+  // row's 32 bytes on (64-byte rows).
+  // transposed: a pair of transposing reads, reduction rows ks * 16 + h * 8 + (lane % 16) / 4 and + 4,
+  // of 32-column block sub of the wavefront's tile.
+  int a_n0 = 0, b_n0 = 0;            // natural: address of step 0, block 0
+  int a_t0 = 0, b_t0 = 0;            // transposed: address of step 0 within a 32-column block at column 0
+  int a_sub[TM], b_sub[2];           // transposed: where block sub lies (plane, and half of a 128-byte row)
+  auto nat0 = [&](int row) { return row * RB + ((h ^ swz_of<RB, false>(row)) << 4); };
+  auto tr0 = [&]() {
+    const int ch0 = (g & 1) * 16 + (i16 & 3) * 4, row = h * 8 + (i16 >> 2);
+    return row * RB + ((ch0 >> 3) << 4) + (ch0 & 7) * 2;        // 128-byte rows: which half of the row is in a_sub / b_sub
+  };
+  auto tr_sub = [&](int cb) {        // cb: 32-column block of the operand's tile
+    if (RB == 64) return cb * PLANE_B;
+    const int sw = swz_of<128, true>(i16 >> 2) >> 2;            // the same for every row this lane reads
+    return (cb >> 1) * PLANE_B + (((cb & 1) ^ sw) << 6);
+  };
+  if (!ATR) a_n0 = nat0(wm * (TM * 32) + (lane & 31)); else a_t0 = tr0();
+  if (!BTR) b_n0 = A_BYTES + nat0(wn * 64 + (lane & 31)); else b_t0 = A_BYTES + tr0();
 #pragma unroll
-  for (int ks = 0; ks < 2; ++ks) {
-    if (!ATR) {
-      const int row = wm * (TM * 32) + (lane & 31);
-      aoff[ks][0] = swz(row, ks * 2 + h);
-      aoff[ks][1] = 0;
-    } else {
-      const int ch0 = (g & 1) * 16 + (i16 & 3) * 4, row = ks * 16 + h * 8 + (i16 >> 2);
-      aoff[ks][0] = wm * TM * 2048 + swz(row, ch0 >> 3) + (ch0 & 7) * 2;
-      aoff[ks][1] = wm * TM * 2048 + swz(row + 4, ch0 >> 3) + (ch0 & 7) * 2;
+  for (int i = 0; i < TM; ++i) a_sub[i] = ATR ? tr_sub(wm * TM + i) : i * 32 * RB;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) b_sub[j] = BTR ? tr_sub(wn * 2 + j) : j * 32 * RB;
+  auto read_frag = [&](const unsigned char* sb, bool tr, int n0a, int t0a, int subo, int ks) __attribute__((always_inline)) -> bf16x8_t {
+    if (!tr) {
+      return *reinterpret_cast<const bf16x8_t*>(sb + (n0a ^ (ks << 5)) + subo);
     }
-    if (!BTR) {
-      const int row = wn * 64 + (lane & 31);
-      boff[ks][0] = A_BYTES + swz(row, ks * 2 + h);
-      boff[ks][1] = 0;
-    } else {
-      const int ch0 = (g & 1) * 16 + (i16 & 3) * 4, row = ks * 16 + h * 8 + (i16 >> 2);
-      boff[ks][0] = A_BYTES + wn * 2 * 2048 + swz(row, ch0 >> 3) + (ch0 & 7) * 2;
-      boff[ks][1] = A_BYTES + wn * 2 * 2048 + swz(row + 4, ch0 >> 3) + (ch0 & 7) * 2;
-    }
-  }
-  auto read_frag = [&](const unsigned char* sb, bool tr, int o0, int o1, int sub) __attribute__((always_inline)) -> bf16x8_t {
-    // sub: 32-row (natural) or 32-column (transposing) block of the wave's tile: both 2048 bytes apart
-    if (!tr) return *reinterpret_cast<const bf16x8_t*>(sb + o0 + sub * 2048);
-    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(sb + o0 + sub * 2048));
-    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(sb + o1 + sub * 2048));
+    const unsigned char* q = sb + t0a + ks * 16 * RB + subo;
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)q);
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(q + 4 * RB));
     const s16x8_t v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     return __builtin_bit_cast(bf16x8_t, v);
   };
@@ -189,34 +220,39 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_kernel(Args a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  if (nst > 0) issue(0, 0);
-  if (nst > 1) issue(1, STAGE_B);
+#pragma unroll
+  for (int d = 0; d < NST - 1; ++d)
+    if (d < nst) issue(d, d * STAGE_B);
   int cur = 0;
   for (int t = 0; t < nst; ++t) {
-    if (t + 1 < nst) __builtin_amdgcn_s_waitcnt(0x0f70 | NLOAD);   // this wave's loads of stage t have landed
+    // this wave's loads of stage t have landed; those of the stages issued after it may stay in flight
+    if (NST == 3 && t + 1 < nst) __builtin_amdgcn_s_waitcnt(0x0f70 | NLOAD);
     else __builtin_amdgcn_s_waitcnt(0x0f70);
     __builtin_amdgcn_s_barrier();
-    if (t + 2 < nst) {
-      int fill = cur + 2 * STAGE_B;
+    if (t + NST - 1 < nst) {
+      int fill = cur + (NST - 1) * STAGE_B;
       if (fill >= NST * STAGE_B) fill -= NST * STAGE_B;
-      issue(t + 2, fill);
+      issue(t + NST - 1, fill);
     }
     const unsigned char* sb = smem + cur;
     bf16x8_t af[2][TM], bfr[2][2];
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
+    for (int kp = 0; kp < KS; kp += 2) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i) af[ks][i] = read_frag(sb, ATR, aoff[ks][0], aoff[ks][1], i);
+      for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
-      for (int j = 0; j < 2; ++j) bfr[ks][j] = read_frag(sb, BTR, boff[ks][0], boff[ks][1], j);
+        for (int i = 0; i < TM; ++i) af[ks][i] = read_frag(sb, ATR, a_n0, a_t0, a_sub[i], kp + ks);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) bfr[ks][j] = read_frag(sb, BTR, b_n0, b_t0, b_sub[j], kp + ks);
+      }
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][i], bfr[ks][j], acc[i][j], 0, 0, 0);
     }
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][i], bfr[ks][j], acc[i][j], 0, 0, 0);
     cur += STAGE_B;
     if (cur == NST * STAGE_B) cur = 0;
   }
@@ -299,22 +335,22 @@ __global__ void __launch_bounds__(256) sum_partials_kernel(const float* __restri
 }
 
 template <typename Kern>
-int launch(Kern kern, bool* raised, int stage_b, const Args& a, int splits, hipStream_t st) {
+int launch(Kern kern, bool* raised, int threads, int smem_bytes, const Args& a, int splits, hipStream_t st) {
   if (!*raised) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, NST * stage_b) != hipSuccess)
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes) != hipSuccess)
       return CNNK_ERR_HIP;
     *raised = true;
   }
-  hipLaunchKernelGGL(kern, dim3(8 * ((a.mtiles * a.ntiles + 7) / 8), 1, splits), dim3(kThreads), NST * stage_b, st, a);
+  hipLaunchKernelGGL(kern, dim3(8 * ((a.mtiles * a.ntiles + 7) / 8), 1, splits), dim3(threads), smem_bytes, st, a);
   return launch_status();
 }
-// one launch of the orientation / epilogue at either tile height
-template <bool ATR, bool BTR, int EPI>
-int launch_tm(int tm, Args& a, int out_rows, int splits, hipStream_t st) {
-  static bool r4 = false, r3 = false;
-  a.mtiles = (out_rows + 64 * tm - 1) / (64 * tm);
-  if (tm == 3) return launch(gemm_kernel<ATR, BTR, EPI, 3>, &r3, Cfg<3>::STAGE_B, a, splits, st);
-  return launch(gemm_kernel<ATR, BTR, EPI, 4>, &r4, Cfg<4>::STAGE_B, a, splits, st);
+template <bool ATR, bool BTR, int EPI, int TM, int BK, int RB>
+int launch_cfg(Args& a, int splits, hipStream_t st) {
+  static bool raised = false;
+  using C = Cfg<TM, BK, RB>;
+  a.mtiles = (a.M + C::BM - 1) / C::BM;
+  a.ntiles = (a.N + C::BN - 1) / C::BN;
+  return launch(gemm_kernel<ATR, BTR, EPI, TM, BK, RB>, &raised, C::THREADS, C::NST * C::STAGE_B, a, splits, st);
 }
 // Rows per workgroup tile (in 64s): the device holds 512 workgroups at once; the cost of a launch is
 // about (rounds of resident workgroups) x (tile height).
@@ -322,11 +358,22 @@ int pick_tm(int out_rows, int ntiles) {
   auto cost = [&](int tm) { const int t = ((out_rows + 64 * tm - 1) / (64 * tm)) * ntiles; return ((t + 511) / 512) * tm; };
   return cost(3) < cost(4) ? 3 : 4;
 }
+// One launch of an orientation with a natural operand.  128-byte rows (192 x 128 tiles, 64 reduction
+// elements per stage, loads one stage ahead) pay from a reduction length of 2048 on: -15 % on
+// 12608 x 3072 -> 768; shorter reductions run as fast or faster with 64-byte rows, three stage buffers
+// and the choice of tile heights (the tuning table forces either: 15 = 1 / 2).
+template <bool BTR, int EPI>
+int launch_nat(Args& a, hipStream_t st) {
+  const bool wide = g_cnnk_tune[15] == 2 || (g_cnnk_tune[15] != 1 && a.K >= 2048);
+  if (wide) return launch_cfg<false, BTR, EPI, 3, 64, 128>(a, 1, st);
+  if (pick_tm(a.M, (a.N + 127) / 128) == 3) return launch_cfg<false, BTR, EPI, 3, 32, 64>(a, 1, st);
+  return launch_cfg<false, BTR, EPI, 4, 32, 64>(a, 1, st);
+}
 
 bool fits32(long long rows, long long cols) { return rows * cols * 2 < 2147483647LL; }
 int wgrad_splits(int rows, int tiles) {
   int s = (192 + tiles - 1) / tiles;           // workgroups of a launch: it runs beside the main stream's kernels (128-192 measured best)
-  const int max_s = rows / (8 * BK);           // at least 8 stages each
+  const int max_s = rows / (8 * 32);           // at least 8 stages each
   if (s > max_s) s = max_s;
   return s < 1 ? 1 : s;
 }
@@ -342,24 +389,21 @@ int gemm_bf16_fwd(long long rows, int K, int N, const bf16_t* x, const bf16_t* w
   a.A = x; a.B = w; a.bias = bias; a.res = res;
   a.C = gelu ? u : y; a.C2 = gelu ? y : nullptr;
   a.M = (int)rows; a.N = N; a.K = K; a.lda = K; a.ldb = K; a.ldc = N; a.k_per_split = K;
-  a.ntiles = (N + BN - 1) / BN;
   a.a_bytes = (unsigned)(rows * K * 2); a.b_bytes = (unsigned)((long long)N * K * 2);
-  const int tm = pick_tm(a.M, a.ntiles);
-  if (res) return launch_tm<false, false, 3>(tm, a, a.M, 1, st);
-  return gelu ? launch_tm<false, false, 1>(tm, a, a.M, 1, st) : launch_tm<false, false, 0>(tm, a, a.M, 1, st);
+  if (res) return launch_nat<false, 3>(a, st);
+  return gelu ? launch_nat<false, 1>(a, st) : launch_nat<false, 0>(a, st);
 }
 
 int gemm_bf16_dgrad(long long rows, int K, int N, const bf16_t* dy, const bf16_t* w, bf16_t* dx, hipStream_t st) {
   Args a{};
   a.A = dy; a.B = w; a.C = dx;
   a.M = (int)rows; a.N = K; a.K = N; a.lda = N; a.ldb = K; a.ldc = K; a.k_per_split = N;
-  a.ntiles = (K + BN - 1) / BN;
   a.a_bytes = (unsigned)(rows * N * 2); a.b_bytes = (unsigned)((long long)N * K * 2);
-  return launch_tm<false, true, 0>(pick_tm(a.M, a.ntiles), a, a.M, 1, st);
+  return launch_nat<true, 0>(a, st);
 }
 
 size_t gemm_bf16_wgrad_ws(long long rows, int K, int N) {
-  const int tiles = ((N + 255) / 256) * ((K + BN - 1) / BN);
+  const int tiles = ((N + 255) / 256) * ((K + 127) / 128);
   const int s = wgrad_splits((int)rows, tiles);
   return s > 1 ? (size_t)s * N * K * sizeof(float) : 0;
 }
@@ -368,13 +412,14 @@ int gemm_bf16_wgrad(long long rows, int K, int N, const bf16_t* x, const bf16_t*
   Args a{};
   a.A = dy; a.B = x;
   a.M = N; a.N = K; a.K = (int)rows; a.lda = N; a.ldb = K; a.ldc = K;
-  a.mtiles = (N + 255) / 256; a.ntiles = (K + BN - 1) / BN;
+  a.mtiles = (N + 255) / 256; a.ntiles = (K + 127) / 128;
   const int splits = wgrad_splits((int)rows, a.mtiles * a.ntiles);
-  const int stages = (((int)rows + BK - 1) / BK + splits - 1) / splits;
-  a.k_per_split = stages * BK;
+  const int stages = (((int)rows + 31) / 32 + splits - 1) / splits;
+  a.k_per_split = stages * 32;
   a.part = splits > 1 ? (float*)ws : dw;
   a.a_bytes = (unsigned)(rows * N * 2); a.b_bytes = (unsigned)(rows * K * 2);
-  const int rc = launch_tm<true, true, 2>(4, a, N, splits, st);
+  // 64-column planes (128-byte rows) measured 5-10 % slower here than 32-column ones; kept selectable
+  const int rc = g_cnnk_tune[15] == 2 ? launch_cfg<true, true, 2, 4, 32, 128>(a, splits, st) : launch_cfg<true, true, 2, 4, 32, 64>(a, splits, st);
   if (rc != CNNK_OK || splits == 1) return rc;
   const size_t n = (size_t)N * K;
   size_t blocks = (n / 4 + 255) / 256;

@@ -118,7 +118,7 @@ LINEAR_SHAPES = [(64, 32, 32), (288, 64, 160), (1056, 768, 96), (68, 128, 256), 
                  (12608, 768, 2304), (12608, 3072, 768), (12544, 768, 768)]
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16", "bf16-conv"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "bf16-rows64", "bf16-rows128", "bf16-conv"])
 @pytest.mark.parametrize("rows,Kd,N", LINEAR_SHAPES)
 def test_linear_layers(K, rows, Kd, N, dtype):
     from paper_2503_23186_amd import cnnk
@@ -128,8 +128,11 @@ def test_linear_layers(K, rows, Kd, N, dtype):
         if rows > 2000:
             pytest.skip("covered by the convolution tests")
         cnnk.cnnk_tune(15, -1)
+    if dtype in ("bf16-rows64", "bf16-rows128"):
+        # the matrix-core kernels with 64-byte / 128-byte operand rows in LDS whatever the shape
+        cnnk.cnnk_tune(15, 1 if dtype == "bf16-rows64" else 2)
     try:
-        _linear_case(K, rows, Kd, N, "bf16" if dtype == "bf16-conv" else dtype)
+        _linear_case(K, rows, Kd, N, "bf16" if dtype.startswith("bf16-") else dtype)
     finally:
         cnnk.cnnk_tune(15, 0)
 
