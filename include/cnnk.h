@@ -71,7 +71,8 @@ const char* cnnk_version(void);
  * every batch-norm backward call (no mask recomputation); 12 = -1 keeps the weight transposes of
  * the data-gradient kernels on the main stream when cnnk_train_step has a second one; 14 = tiles that one workgroup of the
  * gathered implicit-GEMM kernels walks (0: as many as still fill every CU); 13 = pixel tiles that one workgroup of
- * the 3x3 stride-1 LDS-patch kernels walks (0: as many as still leave two workgroups per CU).
+ * the 3x3 stride-1 LDS-patch kernels walks (0: as many as still leave two workgroups per CU; -1: one, and no
+ * split of the reduction over two groups of wavefronts on grids of fewer than 512 workgroups).
  * Process-wide, not thread-safe. */
 int cnnk_tune(int key, int value);
 

@@ -79,8 +79,19 @@ __device__ __forceinline__ int tile_pixel(int rho, int perm) {
 // LDS reads per MFMA, 4 KB per 32 cycles and CU, against the ~180 B/clk that 16-byte LDS reads
 // sustain: the LDS pipe is ~70 % busy when the matrix pipe is full, so the two have to overlap
 // almost perfectly.  Measured: 45-65 % of the MFMA rate inside the main loop.
-template <int BM, int BN, int WM, int WN, int OCC, int PL>
-__global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
+//
+// KG = 2: two groups of four wavefronts share the output tile and split the reduction: group kg takes
+// the channel chunks kg, kg + 2, ... with patch and weight buffers of its own, and hands its
+// accumulators to group 0 through LDS at the end.  For the layers whose tile grid only gives every CU
+// one workgroup (few pixels, many channels: 8 x 8 and 4 x 4 images) this puts two wavefronts on every
+// SIMD without the second output tile per CU that the layer does not have.  The two groups fetch
+// together: eight lanes take the 128 bytes that the two chunks of a pair occupy side by side in a pixel
+// or weight row, and each lane stores its 16 bytes into the buffer of the group that owns the chunk.
+// The path from L2 into a CU moves a fixed number of requests per clock whatever their size up to a
+// 128-byte line, and a workgroup of these layers streams all 4.6 K reduction rows of its 64 filters
+// (590 KB with 512 channels): in 64-byte pieces that alone took longer than the MFMAs.
+template <int BM, int BN, int WM, int WN, int OCC, int PL, int KG>
+__global__ void __launch_bounds__(kThreads * KG, OCC) patch_kernel(PatchArgs a) {
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   constexpr int B_IT = (BN + 63) / 64;  // 64 weight rows per pass (4 chunks of 8 channels per row)
   constexpr int KK = CK / 16;
@@ -89,10 +100,14 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   const int PW = a.W + 2, PH = a.TH + 2;
   const int patch_px = a.TI * PH * PW;
   const int patch_bytes = max(patch_px * 64, 4 * 32 * 72);   // at least the epilogue's four transposition strips
-  unsigned char* Pb = smem_raw;                      // [2][patch_px][64 B]
-  unsigned char* Bb = smem_raw + 2 * patch_bytes;    // [2][3][BN][64 B]
+  // (group 1's buffers start an odd multiple of 128 bytes after group 0's, so that the two 64-byte
+  // halves of a staged 128-byte piece fall on different banks)
+  const int group_bytes = 2 * patch_bytes + 6 * BN * 64 + (KG == 2 && (patch_bytes & 64) == 0 ? 128 : 0);
+  const int kg = KG == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 8);   // reduction group
+  unsigned char* Pb = smem_raw + kg * group_bytes;   // [2][patch_px][64 B]
+  unsigned char* Bb = Pb + 2 * patch_bytes;          // [2][3][BN][64 B]
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x & (kThreads - 1), lane = tid & 63, wave = tid >> 6;   // within the group
   const int wm = wave % WM, wn = wave / WM;
   // The grid is (pixel-tile groups, channel tiles), walked as one linear index; the second
   // dimension only makes layers with the same number of workgroups tell apart in a kernel trace.
@@ -107,8 +122,15 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   const __amdgpu_buffer_rsrc_t src_rs = make_rsrc(a.src, (unsigned)M * a.Cs * 2u);
   const __amdgpu_buffer_rsrc_t wt_rs = make_rsrc(a.wt, (unsigned)a.Cd * 9u * a.Cs * 2u);
 
-  const int kc = tid & 3;
-  // Patch addressing.  What a thread loads for patch position pp = tid/4 + 64*j is the same for
+  // Staging: LPP lanes fetch one row (a patch position, or a filter's tap) of a 64-row pass.  One group:
+  // 4 lanes, the 64 bytes of the chunk.  Two groups: 8 lanes, the 128 bytes of a pair of chunks; group kg
+  // stages rows kg * 32 .. + 32 of the pass, and a lane's piece goes to group piece / 4.
+  constexpr int LPP = KG == 2 ? 8 : 4;
+  const int piece = tid & (LPP - 1), kc = piece & 3;
+  const int srow = KG == 2 ? kg * 32 + (tid >> 3) : tid >> 2;
+  unsigned char* Pst = KG == 2 ? smem_raw + (piece >> 2) * group_bytes : Pb;
+  unsigned char* Bst = Pst + 2 * patch_bytes;
+  // Patch addressing.  What a thread loads for patch position pp = srow + 64*j is the same for
   // every tile up to the tile's origin: a byte offset relative to the tile's first pixel (prel),
   // and whether the position is real data - never (padding column, or a padding row of a tile of
   // whole images), always (interior row), or only if the band of rows has a row above / below it
@@ -119,7 +141,7 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   unsigned pcls = 0;
 #pragma unroll
   for (int j = 0; j < PL; ++j) {
-    const int pp = (tid >> 2) + j * (kThreads / 4);
+    const int pp = srow + j * 64;
     int q, pw, ti, ph;
     a.dPW.divmod(pp, &q, &pw);
     a.dPH.divmod(q, &ti, &ph);
@@ -127,7 +149,7 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
       if (ph >= 1 && ph <= a.TH) pcls |= 1u << j;
       else if (a.TI == 1) pcls |= (ph == 0 ? 0x100u : 0x10000u) << j;
     }
-    prel[j] = (((ti * a.H + ph - 1) * a.W + pw - 1) * a.Cs + kc * 8) * 2;
+    prel[j] = (((ti * a.H + ph - 1) * a.W + pw - 1) * a.Cs + piece * 8) * 2;
   }
   // the positions that are real data in pixel tile `mtile` (bit j), and the byte offset of its origin
   auto tile_mask = [&](int mtile, unsigned* base) __attribute__((always_inline)) {
@@ -147,14 +169,14 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
     return (mask >> j) & 1u ? base + (unsigned)prel[j] : kOobOffset;
   };
   // its LDS byte offset inside a patch buffer is pst0 + j * 64 rows (the swizzle repeats every 16 rows)
-  const int pst0 = swz_off(tid >> 2, kc);
-  const int r0 = tid >> 2;  // weight row of this thread inside a 64-row pass
+  const int pst0 = swz_off(srow, kc);
+  const int r0 = srow;      // weight row of this thread inside a 64-row pass
   unsigned boff[B_IT];
   int bst[B_IT];
 #pragma unroll
   for (int it = 0; it < B_IT; ++it) {
     const int row = r0 + it * 64, ch = nt * BN + row;
-    boff[it] = (row < BN && ch < a.Cd) ? (unsigned)(ch * 9 * a.Cs + kc * 8) * 2u : kOobOffset;
+    boff[it] = (row < BN && ch < a.Cd) ? (unsigned)(ch * 9 * a.Cs + piece * 8) * 2u : kOobOffset;
     bst[it] = swz_off(row, kc);
   }
   // patch pixel (tap (0,0)) under each of this lane's output rows, and the weight-row offsets
@@ -180,7 +202,9 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int nchunks = a.Cs / CK;
+  const int nchunks = a.Cs / CK / KG;      // chunks of this group: kg, kg + KG, ...
+  // byte offset, in a pixel or weight row, of what is staged for chunk c: the chunk, or the pair
+  auto chunk_bytes = [&](int c) { return (unsigned)__builtin_amdgcn_readfirstlane(c * KG * (CK * 2)); };
   uint4 preg[PL];
   uint4 rb[2][3][B_IT];
 
@@ -188,7 +212,7 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   int c_in_tile = 0;
   auto load_next_patch = [&]() __attribute__((always_inline)) {
     const bool last = c_in_tile + 1 == nchunks;
-    const unsigned so = (unsigned)__builtin_amdgcn_readfirstlane(last ? 0 : (c_in_tile + 1) * (CK * 2));
+    const unsigned so = chunk_bytes(last ? 0 : c_in_tile + 1);
     const unsigned base = last ? nbase : cbase, mask = last ? nmask : cmask;
 #pragma unroll
     for (int j = 0; j < PL; ++j) preg[j] = buffer_load16(src_rs, patch_off(mask, base, j), so);
@@ -196,14 +220,14 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   auto store_patch = [&](int buf) {
 #pragma unroll
     for (int j = 0; j < PL; ++j)
-      if ((tid >> 2) + j * (kThreads / 4) < patch_px)
-        *reinterpret_cast<uint4*>(Pb + buf * patch_bytes + pst0 + j * (kThreads / 4) * 64) = preg[j];
+      if (srow + j * 64 < patch_px)
+        *reinterpret_cast<uint4*>(Pst + buf * patch_bytes + pst0 + j * 64 * 64) = preg[j];
   };
   auto load_w = [&](int chunk, auto ROW, auto SET) {   // the three taps of (chunk, filter row ROW) -> register set SET
     constexpr int row = decltype(ROW)::value, rs = decltype(SET)::value;
 #pragma unroll
     for (int s3 = 0; s3 < 3; ++s3) {
-      const unsigned so = (unsigned)(a.widx[row * 3 + s3] * a.Cs + chunk * CK) * 2u;
+      const unsigned so = (unsigned)(a.widx[row * 3 + s3] * a.Cs) * 2u + chunk_bytes(chunk);
 #pragma unroll
       for (int it = 0; it < B_IT; ++it) rb[rs][s3][it] = buffer_load16(wt_rs, boff[it], so);
     }
@@ -215,7 +239,7 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
 #pragma unroll
       for (int it = 0; it < B_IT; ++it)
         if (BN % 64 == 0 || r0 + it * 64 < BN)
-          *reinterpret_cast<uint4*>(Bb + (wb * 3 + s3) * (BN * 64) + bst[it]) = rb[rs][s3][it];
+          *reinterpret_cast<uint4*>(Bst + (wb * 3 + s3) * (BN * 64) + bst[it]) = rb[rs][s3][it];
   };
   bf16x8_t af[2][TM][KK], bfr[2][TN][KK];
   // MFMA operands of tap TAP from patch buffer `pbuf` and weight buffer WB into fragment set SET
@@ -391,6 +415,27 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
     step(PARC, std::integral_constant<int, 1>{});
     step(PARC, std::integral_constant<int, 2>{});
     if (c_in_tile + 1 == nchunks) {
+      if constexpr (KG == 2) {
+        // every wavefront is past the barrier behind its last operand read, and nothing refills the
+        // buffers of a workgroup's only tile: group 1's buffers take its accumulators
+        float* R = reinterpret_cast<float*>(smem_raw + group_bytes);
+        if (kg == 1) {
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+              for (int r = 0; r < 16; ++r) R[((i * TN + j) * 16 + r) * kThreads + tid] = acc[i][j][r];
+        }
+        __syncthreads();
+        if (kg == 1) return;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] += R[((i * TN + j) * 16 + r) * kThreads + tid];
+      }
       epilogue(mt, decltype(PARC)::value);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
@@ -408,7 +453,7 @@ __global__ void __launch_bounds__(kThreads, OCC) patch_kernel(PatchArgs a) {
   };
 
 #pragma unroll
-  for (int j = 0; j < PL; ++j) preg[j] = buffer_load16(src_rs, patch_off(cmask, cbase, j), 0u);
+  for (int j = 0; j < PL; ++j) preg[j] = buffer_load16(src_rs, patch_off(cmask, cbase, j), chunk_bytes(0));
   load_w(0, I0{}, I0{});
   load_w(0, I1{}, I1{});
   store_patch(0);
@@ -446,16 +491,24 @@ size_t patch_smem(int patch_px) {
   return (size_t)2 * (patch_px * 64 < 4 * 32 * 72 ? 4 * 32 * 72 : patch_px * 64) + (size_t)6 * BN * 64;
 }
 
-template <int BM, int BN, int WM, int WN, int OCC, int PL>
-int launch_patch(PatchArgs& a, hipStream_t st) {
-  auto kern = patch_kernel<BM, BN, WM, WN, OCC, PL>;
+template <int BM, int BN, int WM, int WN, int OCC, int PL, int KG>
+int launch_patch_kg(PatchArgs& a, hipStream_t st) {
+  auto kern = patch_kernel<BM, BN, WM, WN, KG == 1 ? OCC : 1, PL, KG>;
   static bool attr_done = false;
   if (!attr_done) {
+    const int most = KG * (int)patch_smem<BM, BN>(PL * kPxPerLoad) + 128;   // the largest patch the template takes
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)patch_smem<BM, BN>(PL * kPxPerLoad)) != hipSuccess)
+                            most < 160 * 1024 ? most : 160 * 1024) != hipSuccess)
       return CNNK_ERR_HIP;
     attr_done = true;
   }
+  const size_t smem = KG * patch_smem<BM, BN>(a.TI * (a.TH + 2) * (a.W + 2)) + (KG == 2 ? 128 : 0);
+  hipLaunchKernelGGL(kern, dim3((unsigned)(a.mtiles / a.tpb), (unsigned)a.ntiles), dim3(kThreads * KG), smem, st, a);
+  return launch_status();
+}
+
+template <int BM, int BN, int WM, int WN, int OCC, int PL>
+int launch_patch(PatchArgs& a, hipStream_t st) {
   const long M = (long)a.N * a.H * a.W;
   a.ntiles = (a.Cd + BN - 1) / BN;
   a.mtiles = (int)((M + BM - 1) / BM);
@@ -465,9 +518,11 @@ int launch_patch(PatchArgs& a, hipStream_t st) {
   for (int t = 2; t <= 8; t *= 2)
     if (a.mtiles % t == 0 && (long)a.ntiles * (a.mtiles / t) >= 512) a.tpb = t;
   if (g_cnnk_tune[13] > 0 && a.mtiles % g_cnnk_tune[13] == 0) a.tpb = g_cnnk_tune[13];
-  const size_t smem = patch_smem<BM, BN>(a.TI * (a.TH + 2) * (a.W + 2));
-  hipLaunchKernelGGL(kern, dim3((unsigned)(a.mtiles / a.tpb), (unsigned)a.ntiles), dim3(kThreads), smem, st, a);
-  return launch_status();
+  // Fewer than two workgroups per CU: two groups of wavefronts per workgroup split the reduction
+  // (an even number of channel chunks, both groups' buffers within the CU's 160 KB)
+  const bool split = a.tpb == 1 && (long)a.ntiles * a.mtiles < 512 && (a.Cs / CK) % 2 == 0 && g_cnnk_tune[13] >= 0 &&
+                     2 * patch_smem<BM, BN>(a.TI * (a.TH + 2) * (a.W + 2)) + 128 <= 160 * 1024;
+  return split ? launch_patch_kg<BM, BN, WM, WN, OCC, PL, 2>(a, st) : launch_patch_kg<BM, BN, WM, WN, OCC, PL, 1>(a, st);
 }
 
 bool plan_patch(const ConvGeom& g, int Cs, int Cd, PatchPlan* p) {
