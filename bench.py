@@ -27,7 +27,7 @@ sys.path.insert(0, ROOT)
 # below (a plain copy kernel of known size in the same run); commands, raw counter means and the
 # scale factors are in profiles/.  None for a class that was not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "conv3x3 s1 64->64 @32 fwd+dgrad (patch_kernel)": 86444077,   # profiles/bench_resnet18_b256_hbm_traffic.md
+    "conv3x3 s1 64->64 @32 fwd+dgrad (patch_kernel)": 86084197,   # profiles/bench_resnet18_b256_hbm_traffic.md
     "fc1.gemm_gelu": 276733000,                                    # profiles/bench_vit_b16_b64_hbm_traffic.md (--config 6)
 }
 # Launches that exist to be found in a profiler's kernel trace (all through cnnk_grad_route, a plain
