@@ -73,6 +73,11 @@ def _load():
     if not os.path.exists(LIB_PATH):
         raise RuntimeError("libcnnk.so is not built: run `python -m paper_2503_23186_amd.build` "
                            "(there is no CPU fallback)")
+    # The buffers and streams handed to the library come from torch, so both must run on one HIP
+    # runtime.  torch ships its own copy of libamdhip64 and the dynamic loader serves every later request
+    # for that name with whichever copy came first: with the library loaded before torch its kernels
+    # would be registered with another runtime than the one that owns the memory, and every launch fails.
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     vp, ci, cf, sz = C.c_void_p, C.c_int, C.c_float, C.c_size_t
     lib.cnnk_status_string.restype = C.c_char_p
