@@ -2,16 +2,18 @@
 // cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation): y = x W^T (+ bias, + GELU), dx = dy W,
 // dW = dy^T x.  One kernel, three operand orientations.
 //
-// Workgroup tile 256 x 128 (or 192 x 128), four wavefronts of 128 x 64 (0.75 KB of LDS operand reads per MFMA), 32
-// reduction elements per stage, three LDS stage buffers filled straight from memory
-// (buffer_load ... lds, issued two stages ahead; out-of-range rows deposit zeros), one barrier per
-// stage, two workgroups per CU.  An operand whose reduction index is its contiguous one ("natural":
-// x and W of the forward product, dy of the data gradient) lies in LDS as [row][32 reduction
-// elements] and is read with 16-byte loads; an operand whose reduction index is its row index (W of
-// the data gradient, both operands of the weight gradient) lies as planes of [32 reduction
-// rows][32 columns] and is read with the transposing load ds_read_b64_tr_b16, so no operand is ever
-// transposed in memory.  Rows are 64 bytes with the 16-byte chunks XOR-swizzled by row bits 2-3: both
-// kinds of read touch every bank once per pass.  Because the hardware fixes where a direct load's
+// Workgroup tile 256 x 128 (or 192 x 128), four wavefronts of 128 x 64 (0.75 KB of LDS operand reads per
+// MFMA), LDS stage buffers filled straight from memory (buffer_load ... lds; out-of-range rows deposit
+// zeros), one barrier per stage, two workgroups per CU.  Two configurations: 32 reduction elements per
+// stage in 64-byte LDS rows with three stage buffers (loads two stages ahead), or - for the long
+// reductions of an operand whose reduction index is the contiguous one - 64 elements per stage in
+// 128-byte rows with two buffers (see Cfg below for why).  An operand whose reduction index is its
+// contiguous one ("natural": x and W of the forward product, dy of the data gradient) lies in LDS as
+// [row][reduction elements of the stage] and is read with 16-byte loads; an operand whose reduction
+// index is its row index (W of the data gradient, both operands of the weight gradient) lies as planes
+// of [reduction rows][32 or 64 columns] and is read with the transposing load ds_read_b64_tr_b16, so no
+// operand is ever transposed in memory.  The 16-byte chunks of a row are XOR-swizzled so that both kinds
+// of read touch every bank once per pass (swz_of).  Because the hardware fixes where a direct load's
 // bytes land (lane i at base + 16 i), the layout is produced by which global bytes each lane asks for.
 // Epilogue per wavefront through a private LDS strip (accumulator quads in, transposing reads out):
 // 16-byte stores of 8 consecutive columns; bias and GELU are applied to the fp32 accumulator first, so
