@@ -63,14 +63,25 @@ __device__ __forceinline__ f32x16_t zero16() {
   for (int i = 0; i < 16; ++i) z[i] = 0.f;
   return z;
 }
-// rows [0, Tp) of a head's 64 features (global rows `ld` elements apart) into the two LDS planes;
-// rows >= T are zero.
-__device__ __forceinline__ void stage(const bf16_t* src, size_t ld, int T, int Tp, unsigned char* dst, int plane_b) {
-  for (int i = threadIdx.x; i < Tp * 8; i += blockDim.x) {
-    const int r = i >> 3, c8 = i & 7;
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (r < T) v = *reinterpret_cast<const uint4*>(src + (size_t)r * ld + c8 * 8);
-    *reinterpret_cast<uint4*>(dst + (c8 >> 2) * plane_b + chunk_off(r, c8 & 3)) = v;
+// Rows [0, Tp) of a head's 64 features (global rows `ld` elements apart) into the two LDS planes; rows
+// >= T are zero.  A workgroup has 64 threads per 32 rows, so every thread moves exactly four 16-byte
+// pieces of a matrix: fetch() issues the four loads, put() stores them - a caller fetches all its
+// matrices before it puts the first, so that a thread has all its loads in flight at once (as a loop of
+// load-then-store the sixteen loads of the backward pass ran one after the other, a third of the launch).
+struct Pieces { uint4 v[4]; };
+__device__ __forceinline__ void fetch(const bf16_t* src, size_t ld, int T, Pieces* p) {
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int i = threadIdx.x + k * blockDim.x, r = i >> 3, c8 = i & 7;
+    p->v[k] = make_uint4(0u, 0u, 0u, 0u);
+    if (r < T) p->v[k] = *reinterpret_cast<const uint4*>(src + (size_t)r * ld + c8 * 8);
+  }
+}
+__device__ __forceinline__ void put(const Pieces& p, unsigned char* dst, int plane_b) {
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int i = threadIdx.x + k * blockDim.x, r = i >> 3, c8 = i & 7;
+    *reinterpret_cast<uint4*>(dst + (c8 >> 2) * plane_b + chunk_off(r, c8 & 3)) = p.v[k];
   }
 }
 // a 32 x 32 tile of X Y^T over the 64 features: rows = tokens arow0.. of the LDS matrix `a`, columns =
@@ -101,8 +112,9 @@ __global__ void __launch_bounds__(512) attn_mfma_fwd_kernel(const bf16_t* __rest
   unsigned char* Vs = smem + 2 * plane_b;
   const int b = blockIdx.x / heads, head = blockIdx.x % heads, d = heads * kDH;
   const bf16_t* base = qkv + (size_t)b * T * 3 * d + head * kDH;
-  stage(base + d, 3 * (size_t)d, T, Tp, Ks, plane_b);
-  stage(base + 2 * d, 3 * (size_t)d, T, Tp, Vs, plane_b);
+  Pieces pk, pv;
+  fetch(base + d, 3 * (size_t)d, T, &pk);
+  fetch(base + 2 * d, 3 * (size_t)d, T, &pv);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 31, h = lane >> 5;
   const int q = wave * 32 + n;
   bf16x8_t bq[4];
@@ -112,44 +124,52 @@ __global__ void __launch_bounds__(512) attn_mfma_fwd_kernel(const bf16_t* __rest
     if (q < T) v = *reinterpret_cast<const uint4*>(base + (size_t)q * 3 * d + ks * 16 + h * 8);
     bq[ks] = __builtin_bit_cast(bf16x8_t, v);
   }
+  put(pk, Ks, plane_b);
+  put(pv, Vs, plane_b);
   __syncthreads();
-  const float scale = 0.125f;
-  // first walk over the keys: running maximum and sum of this lane's half of the keys
+  // exp(s / 8 - x) = exp2(s c - x c') with c = log2 e / 8: the scale rides in the multiply-add in front of
+  // the exponential.  Keys past T exist only in the last tile, so only that tile masks.
+  const float c2 = 0.125f * 1.44269504088896341f;
+  // first walk over the keys: running maximum (of the raw scores) and sum of this lane's half of the keys
   float m = -INFINITY, l = 0.f;
   for (int kt = 0; kt < NT; ++kt) {
-    const f32x16_t s = tile_nt(Ks, plane_b, kt * 32, bq, lane);
-    float tm = -INFINITY;
-    float sv[16];
+    f32x16_t s = tile_nt(Ks, plane_b, kt * 32, bq, lane);
+    if (kt == NT - 1) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int key = kt * 32 + (i >> 2) * 8 + h * 4 + (i & 3);
-      sv[i] = key < T ? s[i] * scale : -INFINITY;
-      tm = fmaxf(tm, sv[i]);
+      for (int i = 0; i < 16; ++i)
+        if (kt * 32 + (i >> 2) * 8 + h * 4 + (i & 3) >= T) s[i] = -INFINITY;
     }
+    float tm = s[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) tm = fmaxf(tm, s[i]);
     const float mn = fmaxf(m, tm);
     if (mn > -INFINITY) {
+      const float mc = mn * c2;
       float add = 0.f;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) add += __expf(sv[i] - mn);
-      l = l * __expf(m - mn) + add;
+      for (int i = 0; i < 16; ++i) add += __builtin_amdgcn_exp2f(fmaf(s[i], c2, -mc));
+      l = l * __builtin_amdgcn_exp2f(fmaf(m, c2, -mc)) + add;
       m = mn;
     }
   }
   {
     const float mo = __shfl_xor(m, 32, 64), lo = __shfl_xor(l, 32, 64);
     const float M = fmaxf(m, mo);
-    l = l * __expf(m - M) + lo * __expf(mo - M);
+    l = l * __builtin_amdgcn_exp2f((m - M) * c2) + lo * __builtin_amdgcn_exp2f((mo - M) * c2);
     m = M;
   }
-  const float L = m + __logf(l);
+  const float L2 = fmaf(m, c2, __builtin_amdgcn_logf(l));      // log2 of the sum of exp(s / 8)
+  const float L = L2 * 0.69314718055994531f;
   // second walk: probabilities, and o^T += v^T p^T
   f32x16_t oacc[2] = {zero16(), zero16()};
   for (int kt = 0; kt < NT; ++kt) {
     f32x16_t s = tile_nt(Ks, plane_b, kt * 32, bq, lane);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int key = kt * 32 + (i >> 2) * 8 + h * 4 + (i & 3);
-      s[i] = key < T ? __expf(s[i] * scale - L) : 0.f;
+    for (int i = 0; i < 16; ++i) s[i] = __builtin_amdgcn_exp2f(fmaf(s[i], c2, -L2));
+    if (kt == NT - 1) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        if (kt * 32 + (i >> 2) * 8 + h * 4 + (i & 3) >= T) s[i] = 0.f;
     }
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -181,10 +201,17 @@ __global__ void __launch_bounds__(512) attn_mfma_bwd_kernel(const bf16_t* __rest
   const bf16_t* gbase = d_o + (size_t)b * T * d + head * kDH;
   const bf16_t* obase = o + (size_t)b * T * d + head * kDH;
   bf16_t* dbase = dqkv + (size_t)b * T * 3 * d + head * kDH;
-  stage(base, 3 * (size_t)d, T, Tp, Qs, plane_b);
-  stage(base + d, 3 * (size_t)d, T, Tp, Ks, plane_b);
-  stage(base + 2 * d, 3 * (size_t)d, T, Tp, Vs, plane_b);
-  stage(gbase, (size_t)d, T, Tp, Gs, plane_b);
+  {
+    Pieces pq, pk, pv, pg;
+    fetch(base, 3 * (size_t)d, T, &pq);
+    fetch(base + d, 3 * (size_t)d, T, &pk);
+    fetch(base + 2 * d, 3 * (size_t)d, T, &pv);
+    fetch(gbase, (size_t)d, T, &pg);
+    put(pq, Qs, plane_b);
+    put(pk, Ks, plane_b);
+    put(pv, Vs, plane_b);
+    put(pg, Gs, plane_b);
+  }
   for (int t = threadIdx.x; t < Tp; t += blockDim.x) {
     float D = 0.f, L = 0.f;
     if (t < T) {
@@ -198,13 +225,19 @@ __global__ void __launch_bounds__(512) attn_mfma_bwd_kernel(const bf16_t* __rest
       }
       L = lse[((size_t)b * heads + head) * T + t];
     }
-    Ds[t] = D;
-    Ls[t] = L;
+    // stored as the walks use them: exp(s / 8 - L) = exp2(s c - L log2 e) with c = log2 e / 8, and
+    // ds = p (dp - D) / 8 = p (dp / 8 - D / 8)
+    Ds[t] = D * 0.125f;
+    Ls[t] = L * 1.44269504088896341f;
   }
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 31, h = lane >> 5;
-  const float scale = 0.125f;
+  const float scale = 0.125f, c2 = 0.125f * 1.44269504088896341f;
   const int own = wave * 32 + n;           // this lane's query (first walk) or key (second walk)
+  // No score is masked in either walk.  Tokens past T are rows of zeros in all four matrices, with
+  // L = D = 0: their probabilities are finite, and wherever one enters a sum it multiplies a zero row
+  // of the other operand (a key past T: its row of K in dq; a query past T: its rows of dO and Q in dv
+  // and dk), or lands in an output column that is not stored (the lane's own token past T).
 
   // ---- by query block: dq^T = k^T ds^T ----
   {
@@ -214,17 +247,13 @@ __global__ void __launch_bounds__(512) attn_mfma_bwd_kernel(const bf16_t* __rest
       bq[ks] = frag_read(Qs, plane_b, own, ks * 16 + h * 8);
       bg[ks] = frag_read(Gs, plane_b, own, ks * 16 + h * 8);
     }
-    const float L = Ls[own], D = Ds[own];
+    const float L2 = Ls[own], Dsc = Ds[own];
     f32x16_t acc[2] = {zero16(), zero16()};
     for (int kt = 0; kt < NT; ++kt) {
       const f32x16_t s = tile_nt(Ks, plane_b, kt * 32, bq, lane);     // [key][query]
       f32x16_t dp = tile_nt(Vs, plane_b, kt * 32, bg, lane);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int key = kt * 32 + (i >> 2) * 8 + h * 4 + (i & 3);
-        const float p = (key < T && own < T) ? __expf(s[i] * scale - L) : 0.f;
-        dp[i] = p * (dp[i] - D) * scale;
-      }
+      for (int i = 0; i < 16; ++i) dp[i] = __builtin_amdgcn_exp2f(fmaf(s[i], c2, -L2)) * fmaf(dp[i], scale, -Dsc);
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         const bf16x8_t dsb = pack_frag(dp, j);
@@ -256,9 +285,9 @@ __global__ void __launch_bounds__(512) attn_mfma_bwd_kernel(const bf16_t* __rest
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
           const int i = i4 * 4 + k;
-          const float pp = (r0 + k < T && own < T) ? __expf(p[i] * scale - Lr[k]) : 0.f;
+          const float pp = __builtin_amdgcn_exp2f(fmaf(p[i], c2, -Lr[k]));
           p[i] = pp;
-          dp[i] = pp * (dp[i] - Dr[k]) * scale;
+          dp[i] = pp * fmaf(dp[i], scale, -Dr[k]);
         }
       }
 #pragma unroll
